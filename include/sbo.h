@@ -1,0 +1,131 @@
+/*
+ * libsbo -- one Single Block Orthogonal (SBO) dictionary-learning iteration on
+ * one MI355X (gfx950): sparse coding, grouping, block accumulation and the
+ * batched SVD update Q_j = U V^T.
+ *
+ * Problem (Section 1, eq. (1)-(3)): signals Y in R^{p x m}, sparsity s0, a
+ * dictionary D = [Q_1 ... Q_K] of K orthonormal p x p blocks, Q_j^T Q_j = I.
+ *
+ * Conventions for every call
+ *   - Every array pointer is a DEVICE pointer owned by the caller.  The library
+ *     never frees or reallocates caller memory.  It owns only the workspace it
+ *     allocates in sbo_create and frees in sbo_destroy.
+ *   - Y    [m][p]     float : signal-major (row i = y_i; same bytes as a
+ *                             column-major p x m matrix with ld = p).  Read only.
+ *   - D    [K][p][p]  float : atom-major, D[j][k][:] = atom k of Q_j (same bytes
+ *                             as column-major Q_j).
+ *   - blk  [m]        int32 : block chosen for each signal, 0..K-1.
+ *   - supp [m][s0]    int32 : kept atom indices inside that block, ASCENDING.
+ *   - coef [m][s0]    float : coef[i][t] pairs with supp[i][t].
+ *   - err  [m]        float : ||y_i - Q_blk x_i||^2 (squared residual).
+ *   - All per-signal outputs are in the ORIGINAL signal order.
+ *   - Work is enqueued on the HIP stream given to sbo_create; calls return
+ *     without synchronising the host (exception: sbo_stage_ms).  Calls on one
+ *     context must not overlap.
+ *   - Return value: 0 on success, a negative SBO_E* code otherwise.  On error no
+ *     output is defined; no exception crosses this boundary.
+ *   - Supported shapes: p in {16, 32, 64}, 1 <= s0 <= min(p, 16), 1 <= K <= 1024
+ *     (K even when p = 16), 1 <= m <= m_max < 2^31 / max(p, s0).
+ */
+#ifndef SBO_H
+#define SBO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SBO_OK       0
+#define SBO_EINVAL  (-1)  /* bad or unsupported shape, NULL pointer, m > m_max */
+#define SBO_ENOMEM  (-2)  /* workspace allocation failed */
+#define SBO_EHIP    (-3)  /* a HIP call failed; text via sbo_strerror */
+
+typedef struct sbo_ctx sbo_ctx;   /* opaque: shapes, stream, device workspace */
+
+/* Stages timed by sbo_stage_ms, in this order. */
+enum {
+    SBO_STAGE_ENERGY = 0,  /* projection onto all K blocks + top-s0 energy + block argmax */
+    SBO_STAGE_GROUP  = 1,  /* counting-sort bucketing of signals by block */
+    SBO_STAGE_SELECT = 2,  /* support/coefficients/error in the winning block */
+    SBO_STAGE_ACCUM  = 3,  /* P_j = Y_j X_j^T */
+    SBO_STAGE_SVD    = 4,  /* Jacobi SVD of each P_j and Q_j = U V^T */
+    SBO_N_STAGES     = 5
+};
+
+/* Create a context for fixed (p, K, s0) and at most m_max signals per call.
+ * hip_stream: a hipStream_t (NULL = the default stream).  Allocates the device
+ * workspace (sbo_workspace_bytes).  *out is set only on success. */
+int sbo_create(sbo_ctx** out, int p, int K, int s0, int64_t m_max, void* hip_stream);
+
+/* Free the workspace and the context.  Synchronises the stream first. */
+int sbo_destroy(sbo_ctx* c);
+
+/* Device bytes sbo_create will allocate for these shapes; 0 if unsupported. */
+size_t sbo_workspace_bytes(int p, int K, int s0, int64_t m_max);
+
+/* Sparse coding of every signal with a single block (Section 2, eq. (4);
+ * Section 3.1; Algorithm 2 step 4).  For each signal and each block j:
+ * c = Q_j^T y, keep the s0 entries of largest magnitude (ties: lower atom index),
+ * E_j = sum of kept c^2; blk = argmax_j E_j (ties: lowest j).
+ * in : Y[m][p], D[K][p][p]          out: blk[m], supp[m][s0], coef[m][s0], err[m]
+ * The K*p x m projection is never written to memory. */
+int sbo_code(sbo_ctx* c, const float* Y, int64_t m, const float* D,
+             int32_t* blk, int32_t* supp, float* coef, float* err);
+
+/* Grouping of the signals by chosen block (Section 3.3, grouping before the
+ * training step): counts[K], offsets[K+1] (exclusive prefix sums) and perm[m],
+ * the signal ids listed block by block, original order inside a block (stable).
+ * in : blk[m]                        out: counts[K], offsets[K+1], perm[m]
+ * Any output pointer may be NULL (that output is then not copied out). */
+int sbo_group(sbo_ctx* c, const int32_t* blk, int64_t m,
+              int32_t* counts, int32_t* offsets, int32_t* perm);
+
+/* Block accumulation P_j = Y_j X_j^T for every block (Algorithm 1, step 5),
+ * atom-major: M[j][k][:] = sum over the block's signals of x_i[k] * y_i.
+ * Summation order is fixed: results are bitwise repeatable.  Blocks without
+ * signals give M[j] = 0.
+ * in : Y, blk, supp, coef            out: M[K][p][p] */
+int sbo_accumulate(sbo_ctx* c, const float* Y, int64_t m, const int32_t* blk,
+                   const int32_t* supp, const float* coef, float* M);
+
+/* Orthogonal factor of each M_j (Algorithm 1, steps 6-7): M_j = U S V^T by
+ * one-sided Jacobi, Q_j = U V^T written to D[j] (atom-major, same convention as
+ * M).  A block with counts[j] == 0 is left untouched (counts may be NULL = all
+ * blocks updated).  Rank-deficient M_j: the null directions are completed to an
+ * orthonormal basis (any completion is a valid U V^T).
+ * in : M[K][p][p], counts[K] or NULL in/out: D[K][p][p] */
+int sbo_polar(sbo_ctx* c, const float* M, const int32_t* counts, float* D);
+
+/* Train every orthobase over its own signals, one round (Algorithm 2 step 5 with
+ * R = 1; Algorithm 1 steps 5-7): grouping, accumulation, SVD, Q_j = U V^T, in
+ * place in D.  counts (device, [K]) may be NULL. */
+int sbo_update(sbo_ctx* c, const float* Y, int64_t m, const int32_t* blk,
+               const int32_t* supp, const float* coef, float* D, int32_t* counts);
+
+/* n_iter x (sbo_code; sbo_update) (Algorithm 2, steps 4-5).  blk/supp/coef/err
+ * hold the LAST coding pass (i.e. with respect to D before the last update).
+ * sqerr_per_iter: device double[n_iter] or NULL; entry t = sum_i err_i of coding
+ * pass t (RMSE = sqrt(sqerr / (p m)), Section 4). */
+int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter,
+                int32_t* blk, int32_t* supp, float* coef, float* err,
+                double* sqerr_per_iter);
+
+/* Per-stage timing with HIP events on the context's stream.  enable != 0 makes
+ * every later call record events around each stage it runs. */
+int sbo_set_timing(sbo_ctx* c, int enable);
+
+/* Synchronises the stream and writes, for the most recent timed call,
+ * milliseconds per stage into ms[SBO_N_STAGES] (HOST pointer); stages that call
+ * did not run read 0.  For sbo_iterate the times are summed over iterations. */
+int sbo_stage_ms(sbo_ctx* c, float* ms);
+
+/* Text for a return code; for SBO_EHIP the text of the last HIP error seen by
+ * this thread.  Never NULL; the pointer stays valid until the next call. */
+const char* sbo_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SBO_H */

@@ -1,0 +1,149 @@
+"""ctypes binding of libsbo: same names as the C entry points, argument
+marshalling only.  Tensors are torch CUDA tensors used as device memory; torch
+does no arithmetic here.  Fails loudly when the HIP library is missing."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "lib", "libsbo.so")
+
+SBO_OK, SBO_EINVAL, SBO_ENOMEM, SBO_EHIP = 0, -1, -2, -3
+STAGES = ("energy", "group", "select", "accum", "svd")
+
+EXPORTS = ("sbo_create", "sbo_destroy", "sbo_workspace_bytes", "sbo_code", "sbo_group",
+           "sbo_accumulate", "sbo_polar", "sbo_update", "sbo_iterate", "sbo_set_timing",
+           "sbo_stage_ms", "sbo_strerror")
+
+_lib = None
+
+
+class SboError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"libsbo error {code}: {text}")
+        self.code = code
+
+
+def lib() -> ctypes.CDLL:
+    """Load libsbo.so (built by paper_1412_4944_amd.build); no fallback exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_1412_4944_amd.build` "
+                           "(there is no CPU fallback)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+    L.sbo_create.argtypes = [ctypes.POINTER(vp), i32, i32, i32, i64, vp]
+    L.sbo_destroy.argtypes = [vp]
+    L.sbo_workspace_bytes.argtypes = [i32, i32, i32, i64]
+    L.sbo_workspace_bytes.restype = ctypes.c_size_t
+    L.sbo_code.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp]
+    L.sbo_group.argtypes = [vp, vp, i64, vp, vp, vp]
+    L.sbo_accumulate.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+    L.sbo_polar.argtypes = [vp, vp, vp, vp]
+    L.sbo_update.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp]
+    L.sbo_iterate.argtypes = [vp, vp, i64, vp, i32, vp, vp, vp, vp, vp]
+    L.sbo_set_timing.argtypes = [vp, i32]
+    L.sbo_stage_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+    L.sbo_strerror.argtypes = [i32]
+    L.sbo_strerror.restype = ctypes.c_char_p
+    for name in EXPORTS:
+        if name not in ("sbo_workspace_bytes", "sbo_strerror"):
+            getattr(L, name).restype = i32
+    _lib = L
+    return L
+
+
+def sbo_strerror(code: int) -> str:
+    return lib().sbo_strerror(code).decode()
+
+
+def _check(rc: int) -> None:
+    if rc != SBO_OK:
+        raise SboError(rc, sbo_strerror(rc))
+
+
+def _ptr(t, dtype=None, optional=False):
+    if t is None:
+        if optional:
+            return None
+        raise ValueError("required tensor is None")
+    import torch
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("libsbo takes contiguous device tensors")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected {dtype}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def sbo_workspace_bytes(p: int, K: int, s0: int, m_max: int) -> int:
+    return int(lib().sbo_workspace_bytes(p, K, s0, m_max))
+
+
+def sbo_create(p: int, K: int, s0: int, m_max: int, stream: int | None = None) -> ctypes.c_void_p:
+    """Returns an opaque context handle.  stream: a raw hipStream_t value; default =
+    torch's current stream."""
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    h = ctypes.c_void_p()
+    _check(lib().sbo_create(ctypes.byref(h), p, K, s0, m_max, ctypes.c_void_p(stream)))
+    return h
+
+
+def sbo_destroy(ctx) -> None:
+    _check(lib().sbo_destroy(ctx))
+
+
+def sbo_code(ctx, Y, D, blk, supp, coef, err) -> None:
+    import torch
+    _check(lib().sbo_code(ctx, _ptr(Y, torch.float32), Y.shape[0], _ptr(D, torch.float32),
+                          _ptr(blk, torch.int32), _ptr(supp, torch.int32),
+                          _ptr(coef, torch.float32), _ptr(err, torch.float32)))
+
+
+def sbo_group(ctx, blk, counts=None, offsets=None, perm=None) -> None:
+    import torch
+    _check(lib().sbo_group(ctx, _ptr(blk, torch.int32), blk.shape[0],
+                           _ptr(counts, torch.int32, True), _ptr(offsets, torch.int32, True),
+                           _ptr(perm, torch.int32, True)))
+
+
+def sbo_accumulate(ctx, Y, blk, supp, coef, M) -> None:
+    import torch
+    _check(lib().sbo_accumulate(ctx, _ptr(Y, torch.float32), Y.shape[0], _ptr(blk, torch.int32),
+                                _ptr(supp, torch.int32), _ptr(coef, torch.float32),
+                                _ptr(M, torch.float32)))
+
+
+def sbo_polar(ctx, M, counts, D) -> None:
+    import torch
+    _check(lib().sbo_polar(ctx, _ptr(M, torch.float32), _ptr(counts, torch.int32, True),
+                           _ptr(D, torch.float32)))
+
+
+def sbo_update(ctx, Y, blk, supp, coef, D, counts=None) -> None:
+    import torch
+    _check(lib().sbo_update(ctx, _ptr(Y, torch.float32), Y.shape[0], _ptr(blk, torch.int32),
+                            _ptr(supp, torch.int32), _ptr(coef, torch.float32),
+                            _ptr(D, torch.float32), _ptr(counts, torch.int32, True)))
+
+
+def sbo_iterate(ctx, Y, D, n_iter, blk, supp, coef, err, sqerr_per_iter=None) -> None:
+    import torch
+    _check(lib().sbo_iterate(ctx, _ptr(Y, torch.float32), Y.shape[0], _ptr(D, torch.float32),
+                             int(n_iter), _ptr(blk, torch.int32), _ptr(supp, torch.int32),
+                             _ptr(coef, torch.float32), _ptr(err, torch.float32),
+                             _ptr(sqerr_per_iter, torch.float64, True)))
+
+
+def sbo_set_timing(ctx, enable: bool) -> None:
+    _check(lib().sbo_set_timing(ctx, 1 if enable else 0))
+
+
+def sbo_stage_ms(ctx) -> dict:
+    buf = (ctypes.c_float * len(STAGES))()
+    _check(lib().sbo_stage_ms(ctx, buf))
+    return {name: float(buf[i]) for i, name in enumerate(STAGES)}

@@ -1,0 +1,224 @@
+// Sparse-coding stage 1: for every signal, the kept energy in every orthobase and
+// the block where it is largest (Section 2, eq. (4); Section 3.1).
+//
+// c = Q_j^T y is a dense contraction: fp32 MFMA 32x32x2 with atoms on the M axis
+// and signals on the N axis, so that the 32x32 accumulator tile leaves every
+// signal's coefficients in just two lanes (l and l^32).  The s0 largest squares
+// are then found in registers by compare-exchange networks, merged across the lane
+// pair, summed, and compared against the running best block.  The K*p x m
+// projection never leaves the register file.
+//
+// Dictionary rows (atom k of block j = row j*p + k, p floats) are streamed through
+// LDS in stages of 64 rows, double-buffered, in the exact per-lane order the MFMA
+// A operand wants, so every LDS read is one conflict-free 16-byte load per lane.
+#include "sbo_internal.h"
+#include "device_utils.h"
+
+namespace sbo {
+
+namespace {
+
+// Energy of the s0 largest entries among the squares held by this lane (x, NV of
+// them) and by its partner lane.  S = power of two >= s0, S <= 2 * NV.
+template <int NV, int S>
+__device__ __forceinline__ float pair_top_energy(const float (&x)[NV], int s0) {
+    constexpr int L = S < NV ? S : NV;
+    float a[L];
+    top_sorted<NV, L>(x, a);
+    float c[S];
+    if constexpr (L == S) {
+        float b[L];
+#pragma unroll
+        for (int i = 0; i < L; ++i) b[i] = other_half(a[i]);
+#pragma unroll
+        for (int i = 0; i < L; ++i) c[i] = fmaxf(a[i], b[L - 1 - i]);
+    } else {
+        static_assert(2 * L == S, "sort width exceeds the coefficients of a lane pair");
+#pragma unroll
+        for (int i = 0; i < L; ++i) {
+            c[i] = a[i];
+            c[S - 1 - i] = other_half(a[i]);
+        }
+    }
+    bitonic_merge_desc<S>(c);
+    float e = 0.f;
+#pragma unroll
+    for (int t = 0; t < S; ++t) e += (t < s0) ? c[t] : 0.f;
+    return e;
+}
+
+template <int P, int S, int NT>
+__global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y, int m,
+                                                     const float* __restrict__ D, int K, int s0,
+                                                     int32_t* __restrict__ blk,
+                                                     float* __restrict__ energy) {
+    constexpr int KS = P / 2;            // contraction steps (each lane half covers P/2 dims)
+    constexpr int QN = P / 8;            // 16-byte groups of steps per 32-row tile
+    constexpr int NB = 64 / P;           // blocks per 64-row stage
+    constexpr int NV = P / 2;            // coefficients per lane per block
+    constexpr int STAGE_F4 = 2 * QN * 64;
+    constexpr int FPT = STAGE_F4 / 256;  // 16-byte pieces each thread moves per stage
+    static_assert(P == 16 || P == 32 || P == 64, "unsupported p");
+
+    __shared__ f32x4 Qs[2][STAGE_F4];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int h = lane >> 5, n = lane & 31;
+    const int64_t sig0 = ((int64_t)blockIdx.x * 4 + wave) * (32 * NT);
+
+    // B operand: this lane's half of the dims of NT signals, kept for the whole kernel.
+    float yb[NT][KS];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int64_t i = sig0 + nt * 32 + n;
+        if (i < m) {
+            const f32x4* src = reinterpret_cast<const f32x4*>(Y + i * P + h * KS);
+#pragma unroll
+            for (int q = 0; q < QN; ++q) {
+                f32x4 v = src[q];
+                yb[nt][4 * q + 0] = v.x;
+                yb[nt][4 * q + 1] = v.y;
+                yb[nt][4 * q + 2] = v.z;
+                yb[nt][4 * q + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < KS; ++t) yb[nt][t] = 0.f;
+        }
+    }
+
+    const int rows = K * P;
+    const int n_stage = (rows + 63) / 64;
+    const f32x4* D4 = reinterpret_cast<const f32x4*>(D);
+
+    f32x4 pre[FPT];
+    auto fetch = [&](int s) {
+#pragma unroll
+        for (int r = 0; r < FPT; ++r) {
+            const int f = tid + 256 * r;
+            const int row = f / (P / 4), d4 = f % (P / 4);
+            const int grow = s * 64 + row;
+            pre[r] = grow < rows ? D4[(int64_t)grow * (P / 4) + d4] : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int r = 0; r < FPT; ++r) {
+            const int f = tid + 256 * r;
+            const int row = f / (P / 4), d4 = f % (P / 4);
+            const int hh = d4 / QN, q = d4 % QN;
+            const int mt = row >> 5, nn = row & 31;
+            Qs[buf][(mt * QN + q) * 64 + hh * 32 + nn] = pre[r];
+        }
+    };
+
+    fetch(0);
+    stash(0);
+    __syncthreads();
+
+    int best[NT];
+    float bestE[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        best[nt] = 0;
+        bestE[nt] = -1.f;
+    }
+
+    for (int s = 0; s < n_stage; ++s) {
+        const int cur = s & 1;
+        if (s + 1 < n_stage) fetch(s + 1);
+
+        f32x16 acc[NT][2];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[nt][mt][r] = 0.f;
+
+#pragma unroll
+        for (int q = 0; q < QN; ++q) {
+            f32x4 a[2];
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) a[mt] = Qs[cur][(mt * QN + q) * 64 + lane];
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                            a[mt][kk], yb[nt][4 * q + kk], acc[nt][mt], 0, 0, 0);
+        }
+
+        if (s + 1 < n_stage) stash(cur ^ 1);
+
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                float x[NV];
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+                    const int f = b * NV + v;          // flattened (tile, register)
+                    const float cval = acc[nt][f >> 4][f & 15];
+                    x[v] = cval * cval;
+                }
+                const float e = pair_top_energy<NV, S>(x, s0);
+                const int j = s * NB + b;
+                if (j < K && e > bestE[nt]) {
+                    bestE[nt] = e;
+                    best[nt] = j;
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    if (h == 0) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int64_t i = sig0 + nt * 32 + n;
+            if (i < m) {
+                blk[i] = best[nt];
+                energy[i] = bestE[nt];
+            }
+        }
+    }
+}
+
+template <int P, int S>
+hipError_t launch_ps(const float* Y, int64_t m, const float* D, int K, int s0, int32_t* blk,
+                     float* energy, hipStream_t st) {
+    constexpr int NT = 2;
+    const int per_wg = 4 * 32 * NT;
+    dim3 grid((unsigned)((m + per_wg - 1) / per_wg));
+    hipLaunchKernelGGL((energy_kernel<P, S, NT>), grid, dim3(256), 0, st, Y, (int)m, D, K, s0, blk,
+                       energy);
+    return hipGetLastError();
+}
+
+template <int P>
+hipError_t launch_p(int s0, const float* Y, int64_t m, const float* D, int K, int32_t* blk,
+                    float* energy, hipStream_t st) {
+    if (s0 <= 1) return launch_ps<P, 1>(Y, m, D, K, s0, blk, energy, st);
+    if (s0 <= 2) return launch_ps<P, 2>(Y, m, D, K, s0, blk, energy, st);
+    if (s0 <= 4) return launch_ps<P, 4>(Y, m, D, K, s0, blk, energy, st);
+    if (s0 <= 8) return launch_ps<P, 8>(Y, m, D, K, s0, blk, energy, st);
+    return launch_ps<P, 16>(Y, m, D, K, s0, blk, energy, st);
+}
+
+}  // namespace
+
+hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const float* D,
+                         int32_t* blk, float* energy, hipStream_t st) {
+    switch (p) {
+        case 16: return launch_p<16>(s0, Y, m, D, K, blk, energy, st);
+        case 32: return launch_p<32>(s0, Y, m, D, K, blk, energy, st);
+        case 64: return launch_p<64>(s0, Y, m, D, K, blk, energy, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace sbo

@@ -1,0 +1,223 @@
+// Sparse-coding stage 2: support, coefficients and residual of every signal in the
+// block that won the energy comparison (Section 2: x = Q_j^T y hard-thresholded to the
+// s0 entries of largest magnitude; Algorithm 1, steps 3-4).
+//
+// Signals arrive grouped by block (perm/offsets).  One wavefront takes a tile of up to
+// 32 signals of ONE block, so the projection is again one fp32 MFMA tile product with
+// atoms on M and signals on N; every signal's p coefficients then sit in two lanes.
+// The s0-th largest magnitude tau is found with the same compare-exchange networks as
+// in stage 1, and the support {|c| > tau} plus the lowest-index entries equal to tau is
+// written in ascending atom order.  Exact ties in magnitude beyond the trivial one are
+// resolved by a sequential per-signal pass (rare).
+#include "sbo_internal.h"
+#include "device_utils.h"
+
+namespace sbo {
+
+namespace {
+
+template <int P, int S>
+__global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ Y,
+                                                     const float* __restrict__ D, int K, int s0,
+                                                     const int32_t* __restrict__ offsets,
+                                                     const int32_t* __restrict__ perm,
+                                                     int32_t* __restrict__ supp,
+                                                     float* __restrict__ coef,
+                                                     float* __restrict__ err) {
+    constexpr int KS = P / 2;
+    constexpr int QN = P / 8;
+    constexpr int MT = P >= 32 ? P / 32 : 1;   // 32-row tiles per block
+    constexpr int NVL = MT * 16;               // accumulator values per lane
+    constexpr int LDC = P + 1;
+    static_assert(S <= NVL, "sort width exceeds the values of one lane");
+
+    extern __shared__ int lds[];               // tile_start[K+1] | tmp[16] | ctile[4][32][LDC]
+    int* tile_start = lds;
+    int* tmp = lds + (K + 1);
+    float* ctile_all = reinterpret_cast<float*>(tmp + 16);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int h = lane >> 5, n = lane & 31;
+
+    wg_exclusive_scan4([&](int j) { return (offsets[j + 1] - offsets[j] + 31) >> 5; }, K,
+                       tile_start, tmp);
+    const int wt = blockIdx.x * 4 + wave;
+    if (wt >= tile_start[K]) return;           // no workgroup barrier below this line
+
+    const int j = upper_slot(tile_start, K, wt);
+    const int pos0 = offsets[j] + (wt - tile_start[j]) * 32;
+    const int cnt = min(32, offsets[j + 1] - pos0);
+    const bool active = n < cnt;
+    const int64_t i = active ? perm[pos0 + n] : -1;
+
+    // B operand: this lane's half of the dims of signal i.
+    float yb[KS];
+    if (active) {
+        const f32x4* src = reinterpret_cast<const f32x4*>(Y + i * P + h * KS);
+#pragma unroll
+        for (int q = 0; q < QN; ++q) {
+            f32x4 v = src[q];
+            yb[4 * q + 0] = v.x;
+            yb[4 * q + 1] = v.y;
+            yb[4 * q + 2] = v.z;
+            yb[4 * q + 3] = v.w;
+        }
+    } else {
+#pragma unroll
+        for (int t = 0; t < KS; ++t) yb[t] = 0.f;
+    }
+
+    // Projection c = Q_j^T y for the tile.
+    f32x16 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
+        const int row = mt * 32 + n;           // atom fed by this lane into the A operand
+        const f32x4* arow =
+            reinterpret_cast<const f32x4*>(D + ((int64_t)j * P + (row < P ? row : 0)) * P + h * KS);
+#pragma unroll
+        for (int q = 0; q < QN; ++q) {
+            f32x4 a = arow[q];
+            if (row >= P) a = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[kk], yb[4 * q + kk], acc[mt], 0, 0, 0);
+        }
+    }
+
+    // Accumulator register r of tile mt in lane (h, n) is atom mt*32 + (r/4)*8 + h*4 + r%4
+    // of signal n.
+    float c[NVL], mag[NVL];
+#pragma unroll
+    for (int f = 0; f < NVL; ++f) {
+        const int r = f & 15;
+        const int atom = (f >> 4) * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+        c[f] = acc[f >> 4][r];
+        mag[f] = atom < P ? fabsf(c[f]) : -1.f;
+    }
+
+    // tau = s0-th largest magnitude of the signal.
+    float top[S], oth[S], mrg[S];
+    top_sorted<NVL, S>(mag, top);
+#pragma unroll
+    for (int t = 0; t < S; ++t) oth[t] = other_half(top[t]);
+#pragma unroll
+    for (int t = 0; t < S; ++t) mrg[t] = fmaxf(top[t], oth[S - 1 - t]);
+    bitonic_merge_desc<S>(mrg);
+    float tau = mrg[0];
+#pragma unroll
+    for (int t = 1; t < S; ++t) tau = (t == s0 - 1) ? mrg[t] : tau;
+
+    int gt = 0, eq = 0;
+#pragma unroll
+    for (int f = 0; f < NVL; ++f) {
+        gt += mag[f] > tau;
+        eq += mag[f] == tau;
+    }
+    gt += other_half(gt);
+    eq += other_half(eq);
+    const int need = s0 - gt;                  // entries equal to tau still to take (>= 1)
+    const bool simple = !active || eq == need;
+
+    if (__all(simple)) {
+        // Every entry with |c| >= tau is kept.  Emit in ascending atom order: 4-atom
+        // groups alternate between the two lanes of a signal.
+        int run = 0;
+        float dropped = 0.f;
+#pragma unroll
+        for (int g = 0; g < NVL / 4; ++g) {
+            int own = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) own += mag[4 * g + e] >= tau;
+            const int par = other_half(own);
+            int pos = run + (h ? par : 0);
+            run += own + par;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int f = 4 * g + e;
+                const int atom = (f >> 4) * 32 + ((f & 15) >> 2) * 8 + h * 4 + (f & 3);
+                if (mag[f] >= tau) {
+                    if (active) {
+                        supp[i * s0 + pos] = atom;
+                        coef[i * s0 + pos] = c[f];
+                    }
+                    ++pos;
+                } else if (atom < P) {
+                    dropped += c[f] * c[f];
+                }
+            }
+        }
+        dropped += other_half(dropped);
+        if (active && h == 0) err[i] = dropped;
+    } else {
+        // Exact magnitude ties: walk each signal's coefficients in atom order.
+        float* ct = ctile_all + wave * 32 * LDC;
+#pragma unroll
+        for (int f = 0; f < NVL; ++f) {
+            const int atom = (f >> 4) * 32 + ((f & 15) >> 2) * 8 + h * 4 + (f & 3);
+            if (atom < P) ct[n * LDC + atom] = c[f];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (active && h == 0) {
+            int pos = 0, taken_eq = 0;
+            float dropped = 0.f;
+            for (int k = 0; k < P; ++k) {
+                const float v = ct[n * LDC + k];
+                const float a = fabsf(v);
+                bool take = a > tau;
+                if (!take && a == tau && taken_eq < need) {
+                    take = true;
+                    ++taken_eq;
+                }
+                if (take && pos < s0) {
+                    supp[i * s0 + pos] = k;
+                    coef[i * s0 + pos] = v;
+                    ++pos;
+                } else {
+                    dropped += v * v;
+                }
+            }
+            err[i] = dropped;
+        }
+    }
+}
+
+template <int P, int S>
+hipError_t launch_ps(const float* Y, int64_t m, const float* D, int K, int s0, const Workspace& ws,
+                     int32_t* supp, float* coef, float* err, hipStream_t st) {
+    const int64_t max_tiles = (m + 31) / 32 + K;
+    dim3 grid((unsigned)((max_tiles + 3) / 4));
+    const size_t lds = (K + 1 + 16) * sizeof(int) + 4 * 32 * (P + 1) * sizeof(float);
+    hipLaunchKernelGGL((select_kernel<P, S>), grid, dim3(256), lds, st, Y, D, K, s0, ws.offsets,
+                       ws.perm, supp, coef, err);
+    return hipGetLastError();
+}
+
+template <int P>
+hipError_t launch_p(int s0, const float* Y, int64_t m, const float* D, int K, const Workspace& ws,
+                    int32_t* supp, float* coef, float* err, hipStream_t st) {
+    if (s0 <= 1) return launch_ps<P, 1>(Y, m, D, K, s0, ws, supp, coef, err, st);
+    if (s0 <= 2) return launch_ps<P, 2>(Y, m, D, K, s0, ws, supp, coef, err, st);
+    if (s0 <= 4) return launch_ps<P, 4>(Y, m, D, K, s0, ws, supp, coef, err, st);
+    if (s0 <= 8) return launch_ps<P, 8>(Y, m, D, K, s0, ws, supp, coef, err, st);
+    return launch_ps<P, 16>(Y, m, D, K, s0, ws, supp, coef, err, st);
+}
+
+}  // namespace
+
+hipError_t launch_select(int p, int K, int s0, const float* Y, int64_t m, const float* D,
+                         const Workspace& ws, int32_t* supp, float* coef, float* err,
+                         hipStream_t st) {
+    switch (p) {
+        case 16: return launch_p<16>(s0, Y, m, D, K, ws, supp, coef, err, st);
+        case 32: return launch_p<32>(s0, Y, m, D, K, ws, supp, coef, err, st);
+        case 64: return launch_p<64>(s0, Y, m, D, K, ws, supp, coef, err, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace sbo

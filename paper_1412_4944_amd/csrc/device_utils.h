@@ -1,0 +1,125 @@
+// Small device helpers shared by the libsbo kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sbo {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+// Value held by the lane 32 positions away (the other half of the wavefront).
+__device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32, 64); }
+__device__ __forceinline__ int other_half(int x) { return __shfl_xor(x, 32, 64); }
+
+// Workgroup-wide exclusive scan of n <= 4 * blockDim.x integers produced by f(idx).
+// out (LDS) receives n + 1 entries (out[n] = total); tmp (LDS) needs 16 ints.
+// Every thread of the workgroup must call this; ends with a barrier.
+template <class F>
+__device__ __forceinline__ void wg_exclusive_scan4(F f, int n, int* out, int* tmp) {
+    const int t = threadIdx.x;
+    const int lane = t & 63, wave = t >> 6;
+    const int nwaves = (blockDim.x + 63) >> 6;
+    int v[4];
+    int s = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        int idx = 4 * t + e;
+        v[e] = idx < n ? f(idx) : 0;
+        s += v[e];
+    }
+    int incl = s;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        int o = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += o;
+    }
+    if (lane == 63) tmp[wave] = incl;
+    __syncthreads();
+    int base = 0, total = 0;
+    for (int w = 0; w < nwaves; ++w) {
+        int x = tmp[w];
+        if (w < wave) base += x;
+        total += x;
+    }
+    int ex = base + incl - s;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        int idx = 4 * t + e;
+        if (idx < n) out[idx] = ex;
+        ex += v[e];
+    }
+    if (t == 0) out[n] = total;
+    __syncthreads();
+}
+
+// Largest j in [0, n) with start[j] <= x, for a non-decreasing start[0..n].
+__host__ __device__ __forceinline__ int upper_slot(const int* start, int n, int x) {
+    int lo = 0, hi = n;  // invariant: start[lo] <= x, answer in [lo, hi)
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (start[mid] <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// ---- compare-exchange networks on register arrays (descending order) ---------------
+__host__ __device__ __forceinline__ void cmpx_desc(float& a, float& b) {
+    float hi = fmaxf(a, b), lo = fminf(a, b);
+    a = hi;
+    b = lo;
+}
+
+// v is bitonic -> sorted descending.
+template <int N>
+__host__ __device__ __forceinline__ void bitonic_merge_desc(float (&v)[N]) {
+#pragma unroll
+    for (int half = N / 2; half >= 1; half >>= 1) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            if ((i & half) == 0) cmpx_desc(v[i], v[i + half]);
+        }
+    }
+}
+
+// Full bitonic sorting network, descending.
+template <int N>
+__host__ __device__ __forceinline__ void bitonic_sort_desc(float (&v)[N]) {
+#pragma unroll
+    for (int k = 2; k <= N; k <<= 1) {
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) {
+                int l = i ^ j;
+                if (l > i) {
+                    if ((i & k) == 0 || k == N) cmpx_desc(v[i], v[l]);
+                    else cmpx_desc(v[l], v[i]);
+                }
+            }
+        }
+    }
+}
+
+// The L largest of x[0..NV), sorted descending (NV and L powers of two, L <= NV).
+template <int NV, int L>
+__host__ __device__ __forceinline__ void top_sorted(const float (&x)[NV], float (&out)[L]) {
+#pragma unroll
+    for (int i = 0; i < L; ++i) out[i] = x[i];
+    bitonic_sort_desc<L>(out);
+#pragma unroll
+    for (int g = 1; g < NV / L; ++g) {
+        float t[L];
+#pragma unroll
+        for (int i = 0; i < L; ++i) t[i] = x[g * L + i];
+        bitonic_sort_desc<L>(t);
+#pragma unroll
+        for (int i = 0; i < L; ++i) out[i] = fmaxf(out[i], t[L - 1 - i]);
+        bitonic_merge_desc<L>(out);
+    }
+}
+
+}  // namespace sbo

@@ -1,0 +1,215 @@
+// Batched SVD update Q_j = U V^T (Algorithm 1, steps 6-7), one workgroup per block.
+//
+// One-sided (Hestenes) Jacobi: plane rotations applied from the right to the columns
+// of A = P_j and to V (starting at I) until all columns of A are mutually orthogonal;
+// then A = U diag(sigma) and P_j = U diag(sigma) V^T, so Q_j = sum_c (A_c / sigma_c) V_c^T.
+// A and V live in LDS for the whole decomposition.  p/2 disjoint column pairs (round-
+// robin tournament) are rotated concurrently, eight lanes per pair, with one barrier
+// per tournament round.  Columns whose norm vanishes (rank-deficient P_j) are replaced
+// by an orthonormal completion, which is a valid choice of U there.
+#include "sbo_internal.h"
+#include "device_utils.h"
+
+namespace sbo {
+
+namespace {
+
+constexpr int kMaxSweeps = 30;
+constexpr float kTol = 1e-6f;                  // |a_i . a_j| <= kTol |a_i| |a_j| for every pair
+
+template <int P>
+__global__ __launch_bounds__(4 * P) void polar_kernel(const float* __restrict__ M,
+                                                      const int32_t* __restrict__ counts,
+                                                      float* __restrict__ D) {
+    constexpr int LD = P + 4;
+    constexpr int NT = 4 * P;                  // threads
+    constexpr int RPT = P / 8;                 // rows per thread in a rotation
+    __shared__ __attribute__((aligned(16))) float A[P * LD];
+    __shared__ __attribute__((aligned(16))) float V[P * LD];
+    __shared__ float sig[P];
+    __shared__ float coefs[P];
+    __shared__ float vec[P];
+    __shared__ int isbad[P];
+    __shared__ int shared_i[2];
+
+    const int j = blockIdx.x;
+    if (counts != nullptr && counts[j] == 0) return;   // uniform: block keeps its basis
+    const int tid = threadIdx.x;
+
+    const float* Mj = M + (int64_t)j * P * P;
+    for (int e = tid; e < P * P; e += NT) {
+        const int c = e / P, r = e % P;
+        A[c * LD + r] = Mj[e];
+        V[c * LD + r] = (c == r) ? 1.f : 0.f;
+    }
+    __syncthreads();
+
+    const int pi = tid >> 3, sub = tid & 7;
+    for (int sweep = 0; sweep < kMaxSweeps; ++sweep) {
+        int rotated = 0;
+        for (int step = 0; step < P - 1; ++step) {
+            int ca, cb;
+            if (pi == 0) {
+                ca = P - 1;
+                cb = step;
+            } else {
+                ca = (step + pi) % (P - 1);
+                cb = (step + (P - 1) - pi) % (P - 1);
+            }
+            const int ci = min(ca, cb), cj = max(ca, cb);
+            float* ai = A + ci * LD;
+            float* aj = A + cj * LD;
+            float x[RPT], y[RPT];
+            float alpha = 0.f, beta = 0.f, gamma = 0.f;
+#pragma unroll
+            for (int t = 0; t < RPT; ++t) {
+                x[t] = ai[sub + 8 * t];
+                y[t] = aj[sub + 8 * t];
+                alpha += x[t] * x[t];
+                beta += y[t] * y[t];
+                gamma += x[t] * y[t];
+            }
+#pragma unroll
+            for (int o = 1; o < 8; o <<= 1) {
+                alpha += __shfl_xor(alpha, o, 64);
+                beta += __shfl_xor(beta, o, 64);
+                gamma += __shfl_xor(gamma, o, 64);
+            }
+            if (fabsf(gamma) > kTol * sqrtf(alpha * beta)) {
+                rotated = 1;
+                const float zeta = (beta - alpha) / (2.f * gamma);
+                const float t = copysignf(1.f, zeta) / (fabsf(zeta) + sqrtf(1.f + zeta * zeta));
+                const float cs = 1.f / sqrtf(1.f + t * t);
+                const float sn = cs * t;
+                float* vi = V + ci * LD;
+                float* vj = V + cj * LD;
+#pragma unroll
+                for (int t2 = 0; t2 < RPT; ++t2) {
+                    ai[sub + 8 * t2] = cs * x[t2] - sn * y[t2];
+                    aj[sub + 8 * t2] = sn * x[t2] + cs * y[t2];
+                    const float p_ = vi[sub + 8 * t2], q_ = vj[sub + 8 * t2];
+                    vi[sub + 8 * t2] = cs * p_ - sn * q_;
+                    vj[sub + 8 * t2] = sn * p_ + cs * q_;
+                }
+            }
+            __syncthreads();
+        }
+        if (!__syncthreads_or(rotated)) break;
+    }
+
+    // Singular values = column norms; U = A diag(1/sigma).
+    // The accumulated rotations leave V orthogonal but let its column norms drift by a few
+    // ulps per rotation; they are reset to one here.
+    if (tid < P) {
+        float s = 0.f, v = 0.f;
+        for (int r = 0; r < P; ++r) {
+            s += A[tid * LD + r] * A[tid * LD + r];
+            v += V[tid * LD + r] * V[tid * LD + r];
+        }
+        sig[tid] = sqrtf(s);
+        vec[tid] = 1.f / sqrtf(v);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        float mx = 0.f;
+        for (int c = 0; c < P; ++c) mx = fmaxf(mx, sig[c]);
+        int nb = 0;
+        const float thr = mx * (1e-6f);
+        for (int c = 0; c < P; ++c) {
+            isbad[c] = !(sig[c] > thr);
+            nb += isbad[c];
+        }
+        shared_i[0] = nb;
+    }
+    __syncthreads();
+    for (int e = tid; e < P * P; e += NT) {
+        const int c = e / P, r = e % P;
+        A[c * LD + r] = isbad[c] ? 0.f : A[c * LD + r] / sig[c];
+        V[c * LD + r] *= vec[c];
+    }
+    __syncthreads();
+
+    if (shared_i[0] > 0) {                     // uniform
+        for (int c = 0; c < P; ++c) {
+            if (!isbad[c]) continue;           // uniform
+            // the coordinate axis least covered by the columns accepted so far
+            if (tid < P) {
+                float s = 0.f;
+                for (int cc = 0; cc < P; ++cc) s += A[cc * LD + tid] * A[cc * LD + tid];
+                vec[tid] = s;
+            }
+            __syncthreads();
+            if (tid == 0) {
+                int best = 0;
+                for (int r = 1; r < P; ++r)
+                    if (vec[r] < vec[best]) best = r;
+                shared_i[1] = best;
+            }
+            __syncthreads();
+            const int rs = shared_i[1];
+            // two Gram-Schmidt passes of e_rs against the accepted columns
+            float w = 0.f;
+            if (tid < P) {
+                float s = (tid == rs) ? 1.f : 0.f;
+                for (int cc = 0; cc < P; ++cc) s -= A[cc * LD + rs] * A[cc * LD + tid];
+                w = s;
+                vec[tid] = s;
+            }
+            __syncthreads();
+            if (tid < P) {
+                float dsum = 0.f;
+                for (int r = 0; r < P; ++r) dsum += A[tid * LD + r] * vec[r];
+                coefs[tid] = dsum;
+            }
+            __syncthreads();
+            if (tid < P) {
+                for (int cc = 0; cc < P; ++cc) w -= coefs[cc] * A[cc * LD + tid];
+            }
+            __syncthreads();
+            if (tid < P) vec[tid] = w;
+            __syncthreads();
+            if (tid < P) {
+                float nrm = 0.f;
+                for (int r = 0; r < P; ++r) nrm += vec[r] * vec[r];
+                A[c * LD + tid] = w / sqrtf(nrm);
+            }
+            __syncthreads();
+        }
+    }
+
+    // Q = U V^T, written atom-major: D[j][k][r] = sum_c U[r][c] V[k][c].
+    constexpr int TILES = (P / 4) * (P / 4);
+    if (tid < TILES) {
+        const int r0 = 4 * (tid % (P / 4)), k0 = 4 * (tid / (P / 4));
+        float o[4][4] = {};
+        for (int c = 0; c < P; ++c) {
+            const f32x4 u = *reinterpret_cast<const f32x4*>(&A[c * LD + r0]);
+            const f32x4 v = *reinterpret_cast<const f32x4*>(&V[c * LD + k0]);
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) o[a][b] += v[a] * u[b];
+        }
+        float* Dj = D + (int64_t)j * P * P;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            f32x4 row = {o[a][0], o[a][1], o[a][2], o[a][3]};
+            *reinterpret_cast<f32x4*>(&Dj[(k0 + a) * P + r0]) = row;
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
+                        hipStream_t st) {
+    switch (p) {
+        case 16: hipLaunchKernelGGL((polar_kernel<16>), dim3(K), dim3(64), 0, st, M, counts, D); break;
+        case 32: hipLaunchKernelGGL((polar_kernel<32>), dim3(K), dim3(128), 0, st, M, counts, D); break;
+        case 64: hipLaunchKernelGGL((polar_kernel<64>), dim3(K), dim3(256), 0, st, M, counts, D); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace sbo

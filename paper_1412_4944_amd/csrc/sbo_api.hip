@@ -1,0 +1,292 @@
+// C-ABI of libsbo: argument checks, workspace, stage sequencing and timing.
+// All arithmetic is in the kernels; this file only enqueues them.
+#include "sbo_internal.h"
+
+#include <new>
+#include <string>
+
+namespace sbo {
+
+static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static int max_chunks() { return 1025; }
+
+static int max_pieces_bound(int64_t m_max, int K) {
+    int64_t a = (m_max + 2047) / 2048 + 1;
+    if (a < 513) a = 513;
+    return (int)a + K;
+}
+
+size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char* base) {
+    (void)s0;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char* ptr = base ? base + off : nullptr;
+        off += align_up(bytes);
+        return ptr;
+    };
+    Workspace w;
+    w.chunk_count = (int32_t*)take((size_t)max_chunks() * K * 4);
+    w.chunk_base = (int32_t*)take((size_t)max_chunks() * K * 4);
+    w.counts = (int32_t*)take((size_t)K * 4);
+    w.offsets = (int32_t*)take((size_t)(K + 1) * 4);
+    w.perm = (int32_t*)take((size_t)m_max * 4);
+    w.energy = (float*)take((size_t)m_max * 4);
+    w.partial = (float*)take((size_t)max_pieces_bound(m_max, K) * p * p * 4);
+    w.M = (float*)take((size_t)K * p * p * 4);
+    w.sq_partial = (double*)take((size_t)kSqBlocks * 8);
+    w.bytes = off;
+    if (ws) *ws = w;
+    return off;
+}
+
+static bool shape_ok(int p, int K, int s0, int64_t m_max) {
+    if (!(p == 16 || p == 32 || p == 64)) return false;
+    if (K < 1 || K > 1024) return false;
+    if (s0 < 1 || s0 > 16 || s0 > p) return false;
+    if (m_max < 1) return false;
+    const int64_t lim = ((int64_t)1 << 31) / (p > s0 ? p : s0);
+    if (m_max >= lim) return false;
+    return true;
+}
+
+static thread_local std::string g_hip_text = "no HIP error recorded";
+
+static int hip_fail(hipError_t e) {
+    g_hip_text = std::string("HIP error: ") + hipGetErrorString(e);
+    return SBO_EHIP;
+}
+
+#define SBO_HIP(expr)                                   \
+    do {                                                \
+        hipError_t e_ = (expr);                         \
+        if (e_ != hipSuccess) return sbo::hip_fail(e_); \
+    } while (0)
+
+// Records a begin event now and an end event at scope exit when timing is on.
+struct StageTimer {
+    sbo_ctx* c;
+    long idx;                                  // index into c->spans, -1 = not timing
+    StageTimer(sbo_ctx* ctx, int stage) : c(ctx), idx(-1) {
+        if (!c->timing) return;
+        if (c->n_spans == c->spans.size()) {
+            sbo_span s;
+            s.stage = stage;
+            if (hipEventCreate(&s.beg) != hipSuccess) return;
+            if (hipEventCreate(&s.end) != hipSuccess) {
+                (void)hipEventDestroy(s.beg);
+                return;
+            }
+            c->spans.push_back(s);
+        }
+        idx = (long)c->n_spans++;
+        c->spans[idx].stage = stage;
+        (void)hipEventRecord(c->spans[idx].beg, c->stream);
+    }
+    ~StageTimer() {
+        if (idx >= 0) (void)hipEventRecord(c->spans[idx].end, c->stream);
+    }
+};
+
+static int check_call(const sbo_ctx* c, int64_t m) {
+    if (!c) return SBO_EINVAL;
+    if (m < 1 || m > c->m_max) return SBO_EINVAL;
+    return SBO_OK;
+}
+
+static int run_group(sbo_ctx* c, const int32_t* blk, int64_t m) {
+    StageTimer t(c, SBO_STAGE_GROUP);
+    SBO_HIP(launch_group(c->K, blk, m, c->ws, c->stream));
+    return SBO_OK;
+}
+
+static int run_code(sbo_ctx* c, const float* Y, int64_t m, const float* D, int32_t* blk,
+                    int32_t* supp, float* coef, float* err) {
+    {
+        StageTimer t(c, SBO_STAGE_ENERGY);
+        SBO_HIP(launch_energy(c->p, c->K, c->s0, Y, m, D, blk, c->ws.energy, c->stream));
+    }
+    int rc = run_group(c, blk, m);
+    if (rc) return rc;
+    {
+        StageTimer t(c, SBO_STAGE_SELECT);
+        SBO_HIP(launch_select(c->p, c->K, c->s0, Y, m, D, c->ws, supp, coef, err, c->stream));
+    }
+    return SBO_OK;
+}
+
+// Accumulate + SVD for signals already grouped in the workspace.
+static int run_update_grouped(sbo_ctx* c, const float* Y, int64_t m, const int32_t* supp,
+                              const float* coef, float* D) {
+    {
+        StageTimer t(c, SBO_STAGE_ACCUM);
+        SBO_HIP(launch_accumulate(c->p, c->K, c->s0, Y, m, supp, coef, c->ws, c->ws.M, c->stream));
+    }
+    {
+        StageTimer t(c, SBO_STAGE_SVD);
+        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->stream));
+    }
+    return SBO_OK;
+}
+
+}  // namespace sbo
+
+using namespace sbo;
+
+extern "C" {
+
+size_t sbo_workspace_bytes(int p, int K, int s0, int64_t m_max) {
+    if (!shape_ok(p, K, s0, m_max)) return 0;
+    return workspace_layout(p, K, s0, m_max, nullptr, nullptr);
+}
+
+int sbo_create(sbo_ctx** out, int p, int K, int s0, int64_t m_max, void* hip_stream) {
+    if (!out || !shape_ok(p, K, s0, m_max)) return SBO_EINVAL;
+    sbo_ctx* c = new (std::nothrow) sbo_ctx();
+    if (!c) return SBO_ENOMEM;
+    c->p = p;
+    c->K = K;
+    c->s0 = s0;
+    c->m_max = m_max;
+    c->stream = (hipStream_t)hip_stream;
+    c->timing = 0;
+    c->n_spans = 0;
+    const size_t bytes = workspace_layout(p, K, s0, m_max, nullptr, nullptr);
+    void* base = nullptr;
+    hipError_t e = hipMalloc(&base, bytes);
+    if (e != hipSuccess) {
+        delete c;
+        if (e == hipErrorOutOfMemory) return SBO_ENOMEM;
+        return hip_fail(e);
+    }
+    c->ws_base = (char*)base;
+    workspace_layout(p, K, s0, m_max, &c->ws, c->ws_base);
+    *out = c;
+    return SBO_OK;
+}
+
+int sbo_destroy(sbo_ctx* c) {
+    if (!c) return SBO_EINVAL;
+    hipError_t e = hipStreamSynchronize(c->stream);
+    for (auto& s : c->spans) {
+        (void)hipEventDestroy(s.beg);
+        (void)hipEventDestroy(s.end);
+    }
+    hipError_t e2 = hipFree(c->ws_base);
+    delete c;
+    if (e != hipSuccess) return hip_fail(e);
+    if (e2 != hipSuccess) return hip_fail(e2);
+    return SBO_OK;
+}
+
+int sbo_code(sbo_ctx* c, const float* Y, int64_t m, const float* D, int32_t* blk, int32_t* supp,
+             float* coef, float* err) {
+    int rc = check_call(c, m);
+    if (rc) return rc;
+    if (!Y || !D || !blk || !supp || !coef || !err) return SBO_EINVAL;
+    c->n_spans = 0;
+    return run_code(c, Y, m, D, blk, supp, coef, err);
+}
+
+int sbo_group(sbo_ctx* c, const int32_t* blk, int64_t m, int32_t* counts, int32_t* offsets,
+              int32_t* perm) {
+    int rc = check_call(c, m);
+    if (rc) return rc;
+    if (!blk) return SBO_EINVAL;
+    c->n_spans = 0;
+    rc = run_group(c, blk, m);
+    if (rc) return rc;
+    if (counts)
+        SBO_HIP(hipMemcpyAsync(counts, c->ws.counts, (size_t)c->K * 4, hipMemcpyDeviceToDevice,
+                               c->stream));
+    if (offsets)
+        SBO_HIP(hipMemcpyAsync(offsets, c->ws.offsets, (size_t)(c->K + 1) * 4,
+                               hipMemcpyDeviceToDevice, c->stream));
+    if (perm)
+        SBO_HIP(hipMemcpyAsync(perm, c->ws.perm, (size_t)m * 4, hipMemcpyDeviceToDevice, c->stream));
+    return SBO_OK;
+}
+
+int sbo_accumulate(sbo_ctx* c, const float* Y, int64_t m, const int32_t* blk, const int32_t* supp,
+                   const float* coef, float* M) {
+    int rc = check_call(c, m);
+    if (rc) return rc;
+    if (!Y || !blk || !supp || !coef || !M) return SBO_EINVAL;
+    c->n_spans = 0;
+    rc = run_group(c, blk, m);
+    if (rc) return rc;
+    StageTimer t(c, SBO_STAGE_ACCUM);
+    SBO_HIP(launch_accumulate(c->p, c->K, c->s0, Y, m, supp, coef, c->ws, M, c->stream));
+    return SBO_OK;
+}
+
+int sbo_polar(sbo_ctx* c, const float* M, const int32_t* counts, float* D) {
+    if (!c || !M || !D) return SBO_EINVAL;
+    c->n_spans = 0;
+    StageTimer t(c, SBO_STAGE_SVD);
+    SBO_HIP(launch_polar(c->p, c->K, M, counts, D, c->stream));
+    return SBO_OK;
+}
+
+int sbo_update(sbo_ctx* c, const float* Y, int64_t m, const int32_t* blk, const int32_t* supp,
+               const float* coef, float* D, int32_t* counts) {
+    int rc = check_call(c, m);
+    if (rc) return rc;
+    if (!Y || !blk || !supp || !coef || !D) return SBO_EINVAL;
+    c->n_spans = 0;
+    rc = run_group(c, blk, m);
+    if (rc) return rc;
+    rc = run_update_grouped(c, Y, m, supp, coef, D);
+    if (rc) return rc;
+    if (counts)
+        SBO_HIP(hipMemcpyAsync(counts, c->ws.counts, (size_t)c->K * 4, hipMemcpyDeviceToDevice,
+                               c->stream));
+    return SBO_OK;
+}
+
+int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter, int32_t* blk,
+                int32_t* supp, float* coef, float* err, double* sqerr_per_iter) {
+    int rc = check_call(c, m);
+    if (rc) return rc;
+    if (!Y || !D || !blk || !supp || !coef || !err || n_iter < 1) return SBO_EINVAL;
+    c->n_spans = 0;
+    for (int it = 0; it < n_iter; ++it) {
+        rc = run_code(c, Y, m, D, blk, supp, coef, err);
+        if (rc) return rc;
+        if (sqerr_per_iter) SBO_HIP(launch_sqerr(err, m, c->ws, sqerr_per_iter + it, c->stream));
+        rc = run_update_grouped(c, Y, m, supp, coef, D);   // grouping of this coding pass is reused
+        if (rc) return rc;
+    }
+    return SBO_OK;
+}
+
+int sbo_set_timing(sbo_ctx* c, int enable) {
+    if (!c) return SBO_EINVAL;
+    c->timing = enable ? 1 : 0;
+    c->n_spans = 0;
+    return SBO_OK;
+}
+
+int sbo_stage_ms(sbo_ctx* c, float* ms) {
+    if (!c || !ms) return SBO_EINVAL;
+    for (int s = 0; s < SBO_N_STAGES; ++s) ms[s] = 0.f;
+    SBO_HIP(hipStreamSynchronize(c->stream));
+    for (size_t i = 0; i < c->n_spans; ++i) {
+        float t = 0.f;
+        SBO_HIP(hipEventElapsedTime(&t, c->spans[i].beg, c->spans[i].end));
+        ms[c->spans[i].stage] += t;
+    }
+    return SBO_OK;
+}
+
+const char* sbo_strerror(int code) {
+    switch (code) {
+        case SBO_OK: return "success";
+        case SBO_EINVAL: return "invalid argument or unsupported shape";
+        case SBO_ENOMEM: return "out of device memory";
+        case SBO_EHIP: return g_hip_text.c_str();
+        default: return "unknown error code";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,107 @@
+// Internal declarations shared by the libsbo translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <vector>
+
+#include "../../include/sbo.h"
+
+namespace sbo {
+
+constexpr int kWave = 64;
+
+// ---- grouping geometry -----------------------------------------------------
+// One wavefront owns one chunk of consecutive signals; a chunk is a multiple of
+// 64 signals, sized so that there are at most ~1024 chunks.
+struct GroupGeom {
+    int chunk;     // signals per chunk (multiple of 64)
+    int n_chunks;  // ceil(m / chunk)
+};
+inline GroupGeom group_geom(int64_t m) {
+    int64_t c = (m + 1023) / 1024;
+    c = ((c + 63) / 64) * 64;
+    if (c < 512) c = 512;
+    GroupGeom g;
+    g.chunk = (int)c;
+    g.n_chunks = (int)((m + c - 1) / c);
+    return g;
+}
+
+// ---- accumulation geometry ---------------------------------------------------
+// Each block's sorted signal list is cut into pieces of `piece` signals; one
+// workgroup reduces one piece into a partial p x p matrix.
+inline int accum_piece(int64_t m) {
+    int64_t c = m / 512;
+    c = ((c + 63) / 64) * 64;
+    if (c < 64) c = 64;
+    if (c > 2048) c = 2048;
+    return (int)c;
+}
+inline int accum_max_pieces(int64_t m, int K) {
+    int piece = accum_piece(m);
+    return (int)((m + piece - 1) / piece) + K;
+}
+
+// ---- device workspace layout ---------------------------------------------------
+struct Workspace {
+    // grouping
+    int32_t* chunk_count;  // [n_chunks_max][K]
+    int32_t* chunk_base;   // [n_chunks_max][K]
+    int32_t* counts;       // [K]
+    int32_t* offsets;      // [K+1]
+    int32_t* perm;         // [m_max]
+    // coding
+    float* energy;         // [m_max] kept energy in the winning block
+    // accumulation
+    float* partial;        // [max_pieces][p][p]
+    float* M;              // [K][p][p]
+    // iterate
+    double* sq_partial;    // [kSqBlocks]
+    size_t bytes;
+};
+constexpr int kSqBlocks = 256;
+
+size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char* base);
+
+}  // namespace sbo
+
+struct sbo_span {
+    int stage;
+    hipEvent_t beg, end;
+};
+
+struct sbo_ctx {
+    int p, K, s0;
+    int64_t m_max;
+    hipStream_t stream;
+    char* ws_base;
+    sbo::Workspace ws;
+    int timing;
+    std::vector<sbo_span> spans;     // event pool; the first n_spans are in use
+    size_t n_spans;
+};
+
+// ---- kernel launchers (each returns a hipError_t from the launch) ----------------
+namespace sbo {
+
+hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const float* D,
+                         int32_t* blk, float* energy, hipStream_t st);
+
+hipError_t launch_group(int K, const int32_t* blk, int64_t m, const Workspace& ws, hipStream_t st);
+
+hipError_t launch_select(int p, int K, int s0, const float* Y, int64_t m, const float* D,
+                         const Workspace& ws, int32_t* supp, float* coef, float* err,
+                         hipStream_t st);
+
+hipError_t launch_accumulate(int p, int K, int s0, const float* Y, int64_t m, const int32_t* supp,
+                             const float* coef, const Workspace& ws, float* M, hipStream_t st);
+
+hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
+                        hipStream_t st);
+
+hipError_t launch_sqerr(const float* err, int64_t m, const Workspace& ws, double* out,
+                        hipStream_t st);
+
+}  // namespace sbo

@@ -1,0 +1,205 @@
+"""GPU parity: the HIP path, called through the C-ABI, against the fp64 oracle on the
+same seeded inputs.  Tolerances are the ones stated in tests/gpu_util.py."""
+import numpy as np
+import pytest
+
+import sbo_synth as synth
+from oracle import sbo_oracle as orc
+from gpu_util import Sbo, compare_code, compare_Q
+
+pytestmark = pytest.mark.gpu
+
+
+def _problem(name, m=None, **kw):
+    if name in synth.CONFIGS:
+        return synth.generate(synth.CONFIGS[name], m=m)
+    return synth.generate(synth.custom(name, m=m, **kw))
+
+
+CODE_CASES = [
+    ("tiny", dict()),
+    ("patch8", dict(m=4096 + 77)),                       # several tiles + ragged tail
+    ("headline", dict(m=3000)),
+    ("p32", dict(p=32, K=6, m=1500, s0=4)),
+    ("p32_oddK", dict(p=32, K=5, m=700, s0=16)),
+    ("p16_oddK", dict(p=16, K=3, m=333, s0=2)),
+    ("p16_full", dict(p=16, K=2, m=200, s0=16)),
+    ("p16_s9", dict(p=16, K=4, m=257, s0=9)),
+    ("p64_s1", dict(p=64, K=3, m=129, s0=1)),
+    ("p64_s16", dict(p=64, K=4, m=640, s0=16)),
+    ("p64_s5", dict(p=64, K=7, m=1000, s0=5)),
+    ("K1", dict(p=64, K=1, m=100, s0=8)),
+    ("m1", dict(p=64, K=4, m=1, s0=3)),
+]
+
+
+@pytest.mark.parametrize("name,kw", CODE_CASES, ids=[c[0] for c in CODE_CASES])
+def test_code_matches_oracle(name, kw):
+    pr = _problem(name, **kw)
+    cfg = pr.cfg
+    print(f"case {name}: p={cfg.p} K={cfg.K} m={pr.Y.shape[0]} s0={cfg.s0}", flush=True)
+    with Sbo(cfg.p, cfg.K, cfg.s0, pr.Y.shape[0]) as g:
+        for D in (pr.D_init, pr.D_planted):
+            o = orc.o_code(pr.Y, D, cfg.s0)
+            out = g.code(pr.Y, D)
+            # s0 = p keeps everything: all blocks tie exactly, so every signal is exempt
+            frac = compare_code(pr.Y, D, cfg.s0, o, out,
+                                max_exempt_frac=1.0 if cfg.s0 == cfg.p else 0.01)
+            print(f"  exempt fraction {frac:.5f}", flush=True)
+
+
+def test_code_ties_zero_signal_and_duplicates():
+    # identical blocks (block tie -> lowest index), equal magnitudes (atom tie -> lowest
+    # index), an all-zero signal; every expected value follows from the tie rules alone
+    p, K, s0 = 16, 4, 3
+    rng = np.random.default_rng(3)
+    Q = synth.random_onb(rng, p).T.astype(np.float32)
+    D = np.stack([np.eye(p, dtype=np.float32), Q, np.eye(p, dtype=np.float32), Q])
+    Y = np.zeros((70, p), np.float32)
+    Y[0, [2, 5, 7, 9]] = [1.0, -1.0, 1.0, 1.0]          # four equal magnitudes, keep 2,5,7
+    Y[1] = 0.0
+    Y[2, [0, 15]] = [3.0, -3.0]                          # fewer non-zeros than s0
+    Y[3:] = rng.standard_normal((67, p)).astype(np.float32)
+    Y[40] = Y[39]                                        # duplicate signals
+    o = orc.o_code(Y, D, s0)
+    with Sbo(p, K, s0, 70) as g:
+        blk, supp, coef, err = g.code(Y, D)
+    assert blk[0] == 0 and supp[0].tolist() == [2, 5, 7] and coef[0].tolist() == [1.0, -1.0, 1.0]
+    assert err[0] == 1.0
+    assert blk[1] == 0 and supp[1].tolist() == [0, 1, 2] and (coef[1] == 0).all() and err[1] == 0
+    assert blk[2] == 0 and supp[2].tolist() == [0, 1, 15] and coef[2].tolist() == [3.0, 0.0, -3.0]
+    assert (blk[40], supp[40].tolist(), coef[40].tolist()) == (blk[39], supp[39].tolist(), coef[39].tolist())
+    assert (blk < 2).all()                               # blocks 2,3 duplicate 0,1: lowest index wins
+    compare_code(Y, D, s0, o, (blk, supp, coef, err), max_exempt_frac=0.05)
+
+
+@pytest.mark.parametrize("K,m", [(4, 1024), (32, 5000), (128, 70001), (1, 100), (1000, 3000), (7, 1)])
+def test_group_matches_oracle(K, m):
+    rng = np.random.default_rng(K * 1000 + m)
+    w = (np.arange(K) + 1.0) ** -1.1
+    blk = rng.choice(K, size=m, p=w / w.sum()).astype(np.int32)
+    if K > 3:
+        blk[blk == 2] = 1                                # an empty block
+    print(f"case K={K} m={m}", flush=True)
+    with Sbo(64, K, 4, m) as g:
+        counts, offsets, perm = g.group(blk)
+    oc, oo, op = orc.o_group(blk, K)
+    np.testing.assert_array_equal(counts, oc)
+    np.testing.assert_array_equal(offsets, oo)
+    np.testing.assert_array_equal(perm, op)
+
+
+UPDATE_CASES = [
+    ("tiny", dict()),
+    ("patch8", dict(m=4096 + 77)),
+    ("headline", dict(m=20000)),
+    ("p32", dict(p=32, K=6, m=3000, s0=4)),
+    ("p16_oddK", dict(p=16, K=3, m=999, s0=2)),
+]
+
+
+@pytest.mark.parametrize("name,kw", UPDATE_CASES, ids=[c[0] for c in UPDATE_CASES])
+def test_update_stages_match_oracle_teacher_forced(name, kw):
+    pr = _problem(name, **kw)
+    cfg = pr.cfg
+    print(f"case {name}: p={cfg.p} K={cfg.K} m={pr.Y.shape[0]} s0={cfg.s0}", flush=True)
+    blk, supp, coef, err, E = orc.o_code(pr.Y, pr.D_init, cfg.s0)
+    coef32 = coef.astype(np.float32)
+    Dn, M = orc.o_update(pr.Y, blk, supp, coef32, pr.D_init)
+    counts = np.bincount(blk, minlength=cfg.K)
+    with Sbo(cfg.p, cfg.K, cfg.s0, pr.Y.shape[0]) as g:
+        Mg = g.accumulate(pr.Y, blk, supp, coef32)
+        Mg2 = g.accumulate(pr.Y, blk, supp, coef32)
+        assert np.array_equal(Mg, Mg2), "accumulation not bitwise repeatable"
+        for j in range(cfg.K):
+            scale = np.abs(M[j]).max() + 1e-30
+            assert np.abs(Mg[j] - M[j]).max() <= 2e-5 * scale * max(1.0, np.sqrt(counts[j] / 64.0)), \
+                f"M[{j}] off by {np.abs(Mg[j] - M[j]).max() / scale} rel"
+        Dp = g.polar(M.astype(np.float32), pr.D_init, counts.astype(np.int32))
+        w1 = compare_Q(Dp, Dn, M, counts > 0)
+        Dg, cg = g.update(pr.Y, blk, supp, coef32, pr.D_init)
+        np.testing.assert_array_equal(cg, counts)
+        w2 = compare_Q(Dg, Dn, M, counts > 0)
+        Dg2, _ = g.update(pr.Y, blk, supp, coef32, pr.D_init)
+        assert np.array_equal(Dg, Dg2), "update not bitwise repeatable"
+        print(f"  worst |Q - Q_oracle|: polar {w1:.2e}, update {w2:.2e}", flush=True)
+
+
+def test_polar_rank_deficient_and_empty_blocks():
+    p, K = 64, 5
+    rng = np.random.default_rng(17)
+    M = rng.standard_normal((K, p, p))
+    M[1][:, :] = 0.0
+    M[1][:5] = rng.standard_normal((5, p))               # rank 5: most atoms never used
+    M[2][7] = 0.0                                        # one unused atom
+    M[3] = 0.0                                           # all-zero but counted as non-empty
+    u, s, vt = np.linalg.svd(M[4])
+    M[4] = (u * np.geomspace(1, 1e-6, p)) @ vt           # ill-conditioned but full rank
+    D_old = synth.random_dictionary(rng, K, p).astype(np.float32)
+    counts = np.array([10, 10, 10, 10, 10], np.int32)
+    counts0 = counts.copy()
+    counts0[0] = 0
+    with Sbo(p, K, 4, 16) as g:
+        Dg = g.polar(M.astype(np.float32), D_old, counts0)
+        np.testing.assert_array_equal(Dg[0], D_old[0])   # empty block keeps its basis
+        Dg = g.polar(M.astype(np.float32), D_old, None)
+    M32 = M.astype(np.float32).astype(np.float64)
+    Dn = np.stack([orc.o_polar(M32[j]) for j in range(K)])
+    compare_Q(Dg, Dn, M32, np.ones(K, bool))
+
+
+@pytest.mark.parametrize("name,kw,iters", [("tiny", dict(), 5), ("patch8", dict(m=8192), 6),
+                                           ("p32", dict(p=32, K=6, m=3000, s0=4), 4)])
+def test_iterate_free_running(name, kw, iters):
+    pr = _problem(name, **kw)
+    cfg = pr.cfg
+    print(f"case {name}: p={cfg.p} K={cfg.K} m={pr.Y.shape[0]} s0={cfg.s0}", flush=True)
+    Do, last, sq_o = orc.o_iterate(pr.Y, pr.D_init, cfg.s0, iters)
+    with Sbo(cfg.p, cfg.K, cfg.s0, pr.Y.shape[0]) as g:
+        Dg, blk, supp, coef, err, sq = g.iterate(pr.Y, pr.D_init, iters)
+        Dg2, *_rest, sq2 = g.iterate(pr.Y, pr.D_init, iters)
+    assert np.array_equal(Dg, Dg2) and np.array_equal(sq, sq2), "iteration not bitwise repeatable"
+    print("  oracle sqerr", sq_o, "\n  gpu    sqerr", sq, flush=True)
+    assert (np.diff(sq) <= 1e-6 * sq[0]).all(), "error increased"
+    np.testing.assert_allclose(sq, sq_o, rtol=1e-3)
+    assert abs(sq[-1] - err.astype(np.float64).sum()) <= 1e-6 * sq[-1] + 1e-12
+    for j in range(cfg.K):
+        Q = Dg[j].astype(np.float64)
+        assert np.abs(Q @ Q.T - np.eye(cfg.p)).max() <= 1e-5
+
+
+def test_teacher_forced_iterations_patch8():
+    """Each iteration: the GPU codes with the oracle's dictionary (rounded to fp32) and
+    updates from the oracle's code, so chaotic block flips do not compound."""
+    pr = _problem("patch8", m=4096)
+    cfg = pr.cfg
+    D = pr.D_init.astype(np.float64)
+    with Sbo(cfg.p, cfg.K, cfg.s0, pr.Y.shape[0]) as g:
+        for it in range(4):
+            D32 = D.astype(np.float32)
+            o = orc.o_code(pr.Y, D32, cfg.s0)
+            frac = compare_code(pr.Y, D32, cfg.s0, o, g.code(pr.Y, D32))
+            blk, supp, coef, err, E = o
+            coef32 = coef.astype(np.float32)
+            Dn, M = orc.o_update(pr.Y, blk, supp, coef32, D32)
+            Dg, _ = g.update(pr.Y, blk, supp, coef32, D32)
+            w = compare_Q(Dg, Dn, M, np.bincount(blk, minlength=cfg.K) > 0)
+            print(f"  iter {it}: exempt {frac:.5f}, worst dQ {w:.2e}", flush=True)
+            D = Dn
+
+
+def test_errors_are_reported_not_faulted():
+    import paper_1412_4944_amd as sbo
+    import torch
+    with Sbo(64, 4, 3, 128) as g:
+        Y = g.dev_f32(np.zeros((256, 64)))
+        D = g.dev_f32(np.zeros((4, 64, 64)))
+        blk, supp, coef, err = g.outputs(256)
+        with pytest.raises(sbo.SboError) as e:
+            sbo.sbo_code(g.ctx, Y, D, blk, supp, coef, err)      # m > m_max
+        assert e.value.code == sbo.binding.SBO_EINVAL
+        # out-of-range block ids are dropped by grouping, not dereferenced
+        b = np.array([0, 1, 99, -5, 3] + [2] * 100, np.int32)
+        counts, offsets, perm = g.group(b)
+        assert counts.tolist() == [1, 1, 100, 1] and offsets[-1] == 103
+        torch.cuda.synchronize()
