@@ -15,6 +15,28 @@ __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 __device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32, 64); }
 __device__ __forceinline__ int other_half(int x) { return __shfl_xor(x, 32, 64); }
 
+// ---- DPP lane exchanges (all lanes active, in-row patterns) ---------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float x) {
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7 - i inside each group of 8
+constexpr int kDppRowMirror = 0x140;  // lane i <-> 15 - i inside each row of 16
+
+// Sum over aligned groups of G = 8 or 16 lanes; every lane of the group receives the
+// bitwise identical total.
+template <int G>
+__device__ __forceinline__ float group_sum(float x) {
+    x += dpp_f<kDppXor1>(x);
+    x += dpp_f<kDppXor2>(x);
+    x += dpp_f<kDppHalfMirror>(x);
+    if constexpr (G == 16) x += dpp_f<kDppRowMirror>(x);
+    return x;
+}
+
 // Workgroup-wide exclusive scan of n <= 4 * blockDim.x integers produced by f(idx).
 // out (LDS) receives n + 1 entries (out[n] = total); tmp (LDS) needs 16 ints.
 // Every thread of the workgroup must call this; ends with a barrier.

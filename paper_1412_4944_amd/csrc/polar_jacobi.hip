@@ -17,13 +17,15 @@ namespace {
 constexpr int kMaxSweeps = 30;
 constexpr float kTol = 1e-6f;                  // |a_i . a_j| <= kTol |a_i| |a_j| for every pair
 
-template <int P>
-__global__ __launch_bounds__(4 * P) void polar_kernel(const float* __restrict__ M,
-                                                      const int32_t* __restrict__ counts,
-                                                      float* __restrict__ D) {
+template <int P, int TPP>
+__global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __restrict__ M,
+                                                             const int32_t* __restrict__ counts,
+                                                             float* __restrict__ D) {
     constexpr int LD = P + 4;
-    constexpr int NT = 4 * P;                  // threads
-    constexpr int RPT = P / 8;                 // rows per thread in a rotation
+    constexpr int NT = (P / 2) * TPP;          // threads: TPP lanes per column pair
+    constexpr int RPT = P / TPP;               // contiguous rows per lane in a rotation
+    static_assert(TPP == 8 || TPP == 16, "lanes per pair");
+    static_assert(RPT >= 1 && P % TPP == 0, "rows per lane");
     __shared__ __attribute__((aligned(16))) float A[P * LD];
     __shared__ __attribute__((aligned(16))) float V[P * LD];
     __shared__ float sig[P];
@@ -44,7 +46,8 @@ __global__ __launch_bounds__(4 * P) void polar_kernel(const float* __restrict__ 
     }
     __syncthreads();
 
-    const int pi = tid >> 3, sub = tid & 7;
+    const int pi = tid / TPP, sub = tid % TPP;
+    const int r0 = sub * RPT;
     for (int sweep = 0; sweep < kMaxSweeps; ++sweep) {
         int rotated = 0;
         for (int step = 0; step < P - 1; ++step) {
@@ -57,39 +60,44 @@ __global__ __launch_bounds__(4 * P) void polar_kernel(const float* __restrict__ 
                 cb = (step + (P - 1) - pi) % (P - 1);
             }
             const int ci = min(ca, cb), cj = max(ca, cb);
-            float* ai = A + ci * LD;
-            float* aj = A + cj * LD;
-            float x[RPT], y[RPT];
+            float* ai = A + ci * LD + r0;
+            float* aj = A + cj * LD + r0;
+            float* vi = V + ci * LD + r0;
+            float* vj = V + cj * LD + r0;
+            float x[RPT], y[RPT], vx[RPT], vy[RPT];
+#pragma unroll
+            for (int t = 0; t < RPT; ++t) {
+                x[t] = ai[t];
+                y[t] = aj[t];
+                vx[t] = vi[t];
+                vy[t] = vj[t];
+            }
             float alpha = 0.f, beta = 0.f, gamma = 0.f;
 #pragma unroll
             for (int t = 0; t < RPT; ++t) {
-                x[t] = ai[sub + 8 * t];
-                y[t] = aj[sub + 8 * t];
                 alpha += x[t] * x[t];
                 beta += y[t] * y[t];
                 gamma += x[t] * y[t];
             }
-#pragma unroll
-            for (int o = 1; o < 8; o <<= 1) {
-                alpha += __shfl_xor(alpha, o, 64);
-                beta += __shfl_xor(beta, o, 64);
-                gamma += __shfl_xor(gamma, o, 64);
-            }
-            if (fabsf(gamma) > kTol * sqrtf(alpha * beta)) {
+            alpha = group_sum<TPP>(alpha);
+            beta = group_sum<TPP>(beta);
+            gamma = group_sum<TPP>(gamma);
+            if (gamma * gamma > (kTol * kTol) * (alpha * beta)) {
                 rotated = 1;
-                const float zeta = (beta - alpha) / (2.f * gamma);
-                const float t = copysignf(1.f, zeta) / (fabsf(zeta) + sqrtf(1.f + zeta * zeta));
-                const float cs = 1.f / sqrtf(1.f + t * t);
+                // tan of the rotation angle that makes the two columns orthogonal; one-ulp
+                // reciprocal / square-root instructions suffice, the iteration corrects itself
+                float zeta = (beta - alpha) * __builtin_amdgcn_rcpf(2.f * gamma);
+                if (zeta != zeta) zeta = 0.f;
+                const float t = copysignf(
+                    __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.f + zeta * zeta)), zeta);
+                const float cs = __builtin_amdgcn_rsqf(1.f + t * t);
                 const float sn = cs * t;
-                float* vi = V + ci * LD;
-                float* vj = V + cj * LD;
 #pragma unroll
                 for (int t2 = 0; t2 < RPT; ++t2) {
-                    ai[sub + 8 * t2] = cs * x[t2] - sn * y[t2];
-                    aj[sub + 8 * t2] = sn * x[t2] + cs * y[t2];
-                    const float p_ = vi[sub + 8 * t2], q_ = vj[sub + 8 * t2];
-                    vi[sub + 8 * t2] = cs * p_ - sn * q_;
-                    vj[sub + 8 * t2] = sn * p_ + cs * q_;
+                    ai[t2] = cs * x[t2] - sn * y[t2];
+                    aj[t2] = sn * x[t2] + cs * y[t2];
+                    vi[t2] = cs * vx[t2] - sn * vy[t2];
+                    vj[t2] = sn * vx[t2] + cs * vy[t2];
                 }
             }
             __syncthreads();
@@ -203,10 +211,11 @@ __global__ __launch_bounds__(4 * P) void polar_kernel(const float* __restrict__ 
 
 hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
                         hipStream_t st) {
+    constexpr int TPP = 16;
     switch (p) {
-        case 16: hipLaunchKernelGGL((polar_kernel<16>), dim3(K), dim3(64), 0, st, M, counts, D); break;
-        case 32: hipLaunchKernelGGL((polar_kernel<32>), dim3(K), dim3(128), 0, st, M, counts, D); break;
-        case 64: hipLaunchKernelGGL((polar_kernel<64>), dim3(K), dim3(256), 0, st, M, counts, D); break;
+        case 16: hipLaunchKernelGGL((polar_kernel<16, TPP>), dim3(K), dim3(8 * TPP), 0, st, M, counts, D); break;
+        case 32: hipLaunchKernelGGL((polar_kernel<32, TPP>), dim3(K), dim3(16 * TPP), 0, st, M, counts, D); break;
+        case 64: hipLaunchKernelGGL((polar_kernel<64, TPP>), dim3(K), dim3(32 * TPP), 0, st, M, counts, D); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
