@@ -1,19 +1,20 @@
 // Block accumulation P_j = Y_j X_j^T (Algorithm 1, step 5), atom-major:
 // M[j][k][:] = sum over the signals of block j of x_i[k] * y_i.
 //
-// X is s0-sparse per signal, so this is s0 scaled row additions per signal and the
-// stage is bound by reading Y once.  Determinism comes from a two-level reduction with
-// a fixed order: the grouped signal list of every block is cut into pieces; one
-// workgroup reduces one piece (each wavefront walks its share of the piece in order
-// and owns a private p x p accumulator in LDS; the wave accumulators are then added in
-// wave order), and a second kernel adds the piece results of a block in piece order.
-// No floating-point atomics touch memory shared between wavefronts.
+// Determinism comes from a two-level reduction with a fixed order: the grouped signal
+// list of every block is cut into pieces; one workgroup reduces one piece (each wavefront
+// walks its share of the piece in order with private accumulators, which are then added
+// in wave order), and a second kernel adds the piece results of a block in piece order.
+// No floating-point atomics are used anywhere.
 //
-// Lane layout inside a wavefront: 64/p signals side by side ("slots"), lane % p = the
-// dimension d it owns.  Every 16-lane row also loads the signal's (atom, coefficient)
-// pairs, lane % 16 = t, so that the t-th pair reaches all lanes of the row with a DPP
-// row broadcast instead of a trip through scalar registers.  Several signals per slot
-// are kept in flight to cover HBM latency.
+// The piece kernel forms the product on the matrix cores: with atoms on the M axis, the
+// dimensions on the N axis and the signal index as the contraction index, one fp32 MFMA
+// 32x32x2 adds two signals to a 32x32 tile of P_j.  Its A operand is the dense x_i, which
+// each signal's s0 (atom, coefficient) pairs are scattered into through a 64-float row of
+// wave-private LDS (written, read back as the operand, cleared again); its B operand is
+// y_i straight from global memory in the lane order the instruction wants.  Accumulators
+// stay in registers, so no read-modify-write traffic exists at all, and the order of
+// additions is fixed by the program.
 #include "sbo_internal.h"
 #include "device_utils.h"
 
@@ -21,57 +22,7 @@ namespace sbo {
 
 namespace {
 
-constexpr int kInFlight = 8;                   // signals per slot loaded before any is used
-
-// Value of lane (row base + T) for every lane of each 16-lane row.
-template <int T>
-__device__ __forceinline__ int row_bcast(int v) {
-    return __builtin_amdgcn_update_dpp(0, v, 0x150 + T, 0xf, 0xf, true);
-}
-
-// acc_d[k_t * P] += c_t * y for the s0 (atom, coefficient) pairs of ONE signal per slot.
-// The LDS cells are read, updated and written back in three batches so that the reads
-// overlap; this needs the atoms of a signal to be distinct, which a support is.
-// (LDS floating-point atomics would also do, but they retire only a few lanes per
-// clock on this chip.)
-template <int T0>
-__device__ __forceinline__ int row_bcast_dyn(int v, int t) {   // t is a compile-time constant after unrolling
-    switch (T0 + t) {
-        case 0: return row_bcast<0>(v);
-        case 1: return row_bcast<1>(v);
-        case 2: return row_bcast<2>(v);
-        case 3: return row_bcast<3>(v);
-        case 4: return row_bcast<4>(v);
-        case 5: return row_bcast<5>(v);
-        case 6: return row_bcast<6>(v);
-        case 7: return row_bcast<7>(v);
-        case 8: return row_bcast<8>(v);
-        case 9: return row_bcast<9>(v);
-        case 10: return row_bcast<10>(v);
-        case 11: return row_bcast<11>(v);
-        case 12: return row_bcast<12>(v);
-        case 13: return row_bcast<13>(v);
-        case 14: return row_bcast<14>(v);
-        default: return row_bcast<15>(v);
-    }
-}
-
-template <int T0, int N>
-__device__ __forceinline__ void add_rows(float* acc_d, int koff, float cf, float y) {
-    int ko[N];
-    float c[N], v[N];
-#pragma unroll
-    for (int t = 0; t < N; ++t) {
-        ko[t] = row_bcast_dyn<T0>(koff, t);
-        c[t] = __builtin_bit_cast(float, row_bcast_dyn<T0>(__builtin_bit_cast(int, cf), t));
-    }
-#pragma unroll
-    for (int t = 0; t < N; ++t) v[t] = acc_d[ko[t]];
-#pragma unroll
-    for (int t = 0; t < N; ++t) v[t] = fmaf(c[t], y, v[t]);
-#pragma unroll
-    for (int t = 0; t < N; ++t) acc_d[ko[t]] = v[t];
-}
+constexpr int kPairs = 8;                      // signal pairs per wavefront loaded before use
 
 template <int P, int S0>
 __global__ __launch_bounds__(256) void accum_partial_kernel(const float* __restrict__ Y, int K,
@@ -81,18 +32,19 @@ __global__ __launch_bounds__(256) void accum_partial_kernel(const float* __restr
                                                             const int32_t* __restrict__ supp,
                                                             const float* __restrict__ coef,
                                                             float* __restrict__ partial) {
-    constexpr int SLOTS = 64 / P;              // signals one wavefront handles side by side
+    constexpr int MT = P >= 32 ? P / 32 : 1;   // 32-wide tiles per side of P_j
     constexpr int PP = P * P;
-    extern __shared__ int lds[];               // piece_start[K+1] | tmp[16] | acc[4][SLOTS][PP]
+    extern __shared__ int lds[];   // piece_start[K+1] | tmp[16] | xd[4][kPairs][2][64] | red[PP]
     int* piece_start = lds;
     int* tmp = lds + (K + 1);
-    float* accs = reinterpret_cast<float*>(tmp + 16);
+    float* xd_all = reinterpret_cast<float*>(tmp + 16);
+    float* red = xd_all + 4 * kPairs * 2 * 64;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int sl = lane / P, d = lane % P, t = lane & 15;
+    const int h = lane >> 5, n = lane & 31;
 
-    for (int e = tid; e < 4 * SLOTS * PP; e += 256) accs[e] = 0.f;
+    for (int e = tid; e < 4 * kPairs * 2 * 64; e += 256) xd_all[e] = 0.f;
     wg_exclusive_scan4([&](int j) { return (offsets[j + 1] - offsets[j] + piece - 1) / piece; }, K,
                        piece_start, tmp);
     const int id = blockIdx.x;
@@ -102,49 +54,82 @@ __global__ __launch_bounds__(256) void accum_partial_kernel(const float* __restr
     const int pos0 = offsets[j] + (id - piece_start[j]) * piece;
     const int cnt = min(piece, offsets[j + 1] - pos0);
 
-    float* acc_d = accs + (wave * SLOTS + sl) * PP + d;
-    constexpr int STRIDE = 4 * SLOTS;          // signals consumed per step by the workgroup
-    for (int q0 = 0; q0 < cnt; q0 += STRIDE * kInFlight) {
-        int64_t i[kInFlight];
+    f32x16 acc[MT][MT];
 #pragma unroll
-        for (int u = 0; u < kInFlight; ++u) {
-            const int q = q0 + u * STRIDE + wave * SLOTS + sl;
+    for (int a = 0; a < MT; ++a)
+#pragma unroll
+        for (int b = 0; b < MT; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    float* xd = xd_all + (wave * kPairs * 2 + h) * 64;   // + u * 128 for pair u
+    const int n_pairs = (cnt + 1) >> 1;
+    for (int g = wave; g < n_pairs; g += 4 * kPairs) {
+        int64_t i[kPairs];
+#pragma unroll
+        for (int u = 0; u < kPairs; ++u) {
+            const int q = 2 * (g + 4 * u) + h;           // lane half h takes the pair's h-th signal
             i[u] = q < cnt ? perm[pos0 + q] : -1;
         }
-        int koff[kInFlight];
-        float cf[kInFlight], y[kInFlight];
+        float yv[kPairs][MT], c[kPairs];
+        int k[kPairs];
 #pragma unroll
-        for (int u = 0; u < kInFlight; ++u) {
+        for (int u = 0; u < kPairs; ++u) {
             const bool on = i[u] >= 0;
-            y[u] = on ? Y[i[u] * P + d] : 0.f;
-            int k = 0;
-            float c = 0.f;
-            if (on && t < S0) {
-                k = supp[i[u] * S0 + t];
-                c = coef[i[u] * S0 + t];
+#pragma unroll
+            for (int nt = 0; nt < MT; ++nt)
+                yv[u][nt] = (on && nt * 32 + n < P) ? Y[i[u] * P + nt * 32 + n] : 0.f;
+            k[u] = -1;
+            c[u] = 0.f;
+            if (on && n < S0) {
+                k[u] = supp[i[u] * S0 + n];
+                c[u] = coef[i[u] * S0 + n];
             }
-            if ((unsigned)k >= (unsigned)P) {  // out-of-range atom ids contribute nothing
-                k = 0;
-                c = 0.f;
-            }
-            koff[u] = k * P;
-            cf[u] = c;
+            if ((unsigned)k[u] >= (unsigned)P) k[u] = -1;   // out-of-range atoms contribute nothing
         }
 #pragma unroll
-        for (int u = 0; u < kInFlight; ++u) {
-            constexpr int HEAD = S0 < 8 ? S0 : 8;
-            add_rows<0, HEAD>(acc_d, koff[u], cf[u], y[u]);
-            if constexpr (S0 > 8) add_rows<8, S0 - 8>(acc_d, koff[u], cf[u], y[u]);
-        }
+        for (int u = 0; u < kPairs; ++u)
+            if (k[u] >= 0) xd[u * 128 + k[u]] = c[u];
+        float a[kPairs][MT];
+#pragma unroll
+        for (int u = 0; u < kPairs; ++u)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) a[u][mt] = xd[u * 128 + mt * 32 + n];
+#pragma unroll
+        for (int u = 0; u < kPairs; ++u)
+            if (k[u] >= 0) xd[u * 128 + k[u]] = 0.f;
+#pragma unroll
+        for (int u = 0; u < kPairs; ++u)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < MT; ++nt)
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][mt], yv[u][nt],
+                                                                       acc[mt][nt], 0, 0, 0);
     }
-    __syncthreads();
+
+    // Wave accumulators are added in wave order.  Register r of tile (mt, nt) in lane
+    // (h, n) is atom mt*32 + (r/4)*8 + h*4 + r%4, dimension nt*32 + n.
+    for (int w = 0; w < 4; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < MT; ++nt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int atom = mt * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+                        const int dim = nt * 32 + n;
+                        if (atom < P && dim < P) {
+                            float* cell = red + atom * P + dim;
+                            *cell = (w == 0) ? acc[mt][nt][r] : *cell + acc[mt][nt][r];
+                        }
+                    }
+        }
+        __syncthreads();
+    }
     float* out = partial + (int64_t)id * PP;
-    for (int e = tid; e < PP; e += 256) {
-        float s = 0.f;
-#pragma unroll
-        for (int w = 0; w < 4 * SLOTS; ++w) s += accs[w * PP + e];
-        out[e] = s;
-    }
+    for (int e = tid; e < PP; e += 256) out[e] = red[e];
 }
 
 template <int P>
@@ -169,10 +154,10 @@ __global__ __launch_bounds__(256) void accum_reduce_kernel(int K, int piece,
 template <int P, int S0>
 hipError_t launch_ps(int K, const float* Y, int64_t m, const int32_t* supp, const float* coef,
                      const Workspace& ws, float* M, hipStream_t st) {
-    constexpr int SLOTS = 64 / P;
     const int piece = accum_piece(m);
     const int max_pieces = accum_max_pieces(m, K);
-    const size_t lds1 = (K + 1 + 16) * sizeof(int) + (size_t)4 * SLOTS * P * P * sizeof(float);
+    const size_t lds1 =
+        (K + 1 + 16) * sizeof(int) + ((size_t)4 * kPairs * 2 * 64 + (size_t)P * P) * sizeof(float);
     static bool raised = false;
     if (!raised) {
         hipError_t e =

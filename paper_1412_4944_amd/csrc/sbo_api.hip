@@ -12,9 +12,7 @@ static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 static int max_chunks() { return 1025; }
 
 static int max_pieces_bound(int64_t m_max, int K) {
-    int64_t a = (m_max + 2047) / 2048 + 1;
-    if (a < 513) a = 513;
-    return (int)a + K;
+    return (int)((m_max + 63) / 64) + K + 1;   // covers the smallest piece size (64 signals)
 }
 
 size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char* base) {

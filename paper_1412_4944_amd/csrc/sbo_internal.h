@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <stdlib.h>
 #include <vector>
 
 #include "../../include/sbo.h"
@@ -33,7 +34,11 @@ inline GroupGeom group_geom(int64_t m) {
 // Each block's sorted signal list is cut into pieces of `piece` signals; one
 // workgroup reduces one piece into a partial p x p matrix.
 inline int accum_piece(int64_t m) {
-    int64_t c = m / 512;
+    if (const char* e = getenv("SBO_ACCUM_PIECE")) {      // tuning override, multiple of 64
+        int v = atoi(e);
+        if (v >= 64 && v <= 2048 && v % 64 == 0) return v;
+    }
+    int64_t c = m / 700;                                   // ~2.7 workgroups per CU
     c = ((c + 63) / 64) * 64;
     if (c < 64) c = 64;
     if (c > 2048) c = 2048;
