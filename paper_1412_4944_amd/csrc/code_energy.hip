@@ -3,14 +3,16 @@
 //
 // c = Q_j^T y is a dense contraction: fp32 MFMA 32x32x2 with atoms on the M axis
 // and signals on the N axis, so that the 32x32 accumulator tile leaves every
-// signal's coefficients in just two lanes (l and l^32).  The s0 largest squares
+// signal's coefficients in just two lanes (l and l^32).  The s0 largest magnitudes
 // are then found in registers by compare-exchange networks, merged across the lane
-// pair, summed, and compared against the running best block.  The K*p x m
+// pair, squared and summed, and compared against the running best block.  The K*p x m
 // projection never leaves the register file.
 //
 // Dictionary rows (atom k of block j = row j*p + k, p floats) are streamed through
 // LDS in stages of 64 rows, double-buffered, in the exact per-lane order the MFMA
-// A operand wants, so every LDS read is one conflict-free 16-byte load per lane.
+// A operand wants, so every LDS read is one conflict-free 16-byte load per lane.  A
+// small kernel first rewrites D into that order (zero-padded to whole stages), which
+// makes the per-stage copy global -> registers -> LDS linear on both sides.
 #include "sbo_internal.h"
 #include "device_utils.h"
 
@@ -18,38 +20,110 @@ namespace sbo {
 
 namespace {
 
-// Energy of the s0 largest entries among the squares held by this lane (x, NV of
-// them) and by its partner lane.  S = power of two >= s0, S <= 2 * NV.
-template <int NV, int S>
-__device__ __forceinline__ float pair_top_energy(const float (&x)[NV], int s0) {
+// Both halves of a register pair after v_permlane32_swap(x, z):
+//   first  = [x.lo, z.lo]   second = [x.hi, z.hi]   (lo/hi = lanes 0-31 / 32-63)
+struct SwapPair {
+    float first, second;
+};
+__device__ __forceinline__ SwapPair swap32(float x, float z) {
+    auto r = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, x),
+                                              __builtin_bit_cast(unsigned, z), false, false);
+    const unsigned u0 = r[0], u1 = r[1];   // copy out first: a bit_cast applied to a vector
+                                           // element expression reads element 0 for both
+    return {__builtin_bit_cast(float, u0), __builtin_bit_cast(float, u1)};
+}
+
+// Sum of squares of the S largest magnitudes of the union of two sorted (descending)
+// S-lists, one per lane of a lane pair; valid and bitwise equal in both lanes.  The S
+// largest of the union are max(a_i(lo), a_{S-1-i}(hi)); the high lane reverses its list
+// so that both operands of one maximum sit in the same register, and one swap serves
+// two maxima.
+template <int S>
+__device__ __forceinline__ float pair_fold_energy(const float (&a)[S], bool hi) {
+    if constexpr (S == 1) {
+        SwapPair t = swap32(a[0], a[0]);
+        const float m = fmaxf(t.first, t.second);
+        return m * m;
+    } else {
+        // r_i = hi ? a_{S-1-i} : a_i as one bit-select per element (written with integer
+        // masks so that it is not rewritten into a lane-dependent index into a[])
+        const unsigned msk = hi ? 0xffffffffu : 0u;
+        float r[S];
+#pragma unroll
+        for (int i = 0; i < S; ++i) {
+            const unsigned fwd = __builtin_bit_cast(unsigned, a[i]);
+            const unsigned rev = __builtin_bit_cast(unsigned, a[S - 1 - i]);
+            r[i] = __builtin_bit_cast(float, (rev & msk) | (fwd & ~msk));
+        }
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < S; i += 2) {
+            SwapPair t = swap32(r[i], r[i + 1]);
+            const float m = fmaxf(t.first, t.second);   // low lanes: maximum i, high: i+1
+            sum = fmaf(m, m, sum);
+        }
+        SwapPair t = swap32(sum, sum);
+        return t.first + t.second;
+    }
+}
+
+// Energy (sum of squares) of the s0 largest magnitudes among the NV coefficients held
+// by this lane (x = |c|) and the NV held by its partner lane.  S = power of two >= s0,
+// S <= 2 * NV.  EXACT means s0 == S.
+template <int NV, int S, bool EXACT>
+__device__ __forceinline__ float pair_top_energy(const float (&x)[NV], int s0, bool hi) {
     constexpr int L = S < NV ? S : NV;
     float a[L];
     top_sorted<NV, L>(x, a);
-    float c[S];
-    if constexpr (L == S) {
-        float b[L];
-#pragma unroll
-        for (int i = 0; i < L; ++i) b[i] = other_half(a[i]);
-#pragma unroll
-        for (int i = 0; i < L; ++i) c[i] = fmaxf(a[i], b[L - 1 - i]);
+    if constexpr (L == S && EXACT) {
+        return pair_fold_energy<S>(a, hi);
     } else {
-        static_assert(2 * L == S, "sort width exceeds the coefficients of a lane pair");
+        float c[S];
+        if constexpr (L == S) {
+            float b[L];
 #pragma unroll
-        for (int i = 0; i < L; ++i) {
-            c[i] = a[i];
-            c[S - 1 - i] = other_half(a[i]);
+            for (int i = 0; i < L; ++i) b[i] = other_half(a[i]);
+#pragma unroll
+            for (int i = 0; i < L; ++i) c[i] = fmaxf(a[i], b[L - 1 - i]);
+        } else {
+            static_assert(2 * L == S, "sort width exceeds the coefficients of a lane pair");
+#pragma unroll
+            for (int i = 0; i < L; ++i) {
+                c[i] = a[i];
+                c[S - 1 - i] = other_half(a[i]);
+            }
         }
-    }
-    bitonic_merge_desc<S>(c);
-    float e = 0.f;
+        bitonic_merge_desc<S>(c);
+        float e = 0.f;
 #pragma unroll
-    for (int t = 0; t < S; ++t) e += (t < s0) ? c[t] : 0.f;
-    return e;
+        for (int t = 0; t < S; ++t) e += (t < s0) ? c[t] * c[t] : 0.f;
+        return e;
+    }
 }
 
-template <int P, int S, int NT>
+// Dsw[stage][(mt*QN + q)*64 + hh*32 + nn] = dims hh*P/2 + 4q .. +3 of row stage*64 + mt*32 + nn
+// (rows past K*P are zero): the order in which a wavefront's lanes consume the A operand.
+template <int P>
+__global__ __launch_bounds__(256) void dict_swizzle_kernel(const float* __restrict__ D, int K,
+                                                           f32x4* __restrict__ Dsw) {
+    constexpr int QN = P / 8;
+    constexpr int STAGE_F4 = 2 * QN * 64;
+    const f32x4* D4 = reinterpret_cast<const f32x4*>(D);
+    const int rows = K * P;
+    const int s = blockIdx.x;
+    for (int f = threadIdx.x; f < STAGE_F4; f += 256) {
+        const int nn = f & 31, hh = (f >> 5) & 1, mq = f >> 6;
+        const int q = mq % QN, mt = mq / QN;
+        const int grow = s * 64 + mt * 32 + nn;
+        const int d4 = hh * QN + q;
+        Dsw[(int64_t)s * STAGE_F4 + f] =
+            grow < rows ? D4[(int64_t)grow * (P / 4) + d4] : f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+}
+
+template <int P, int S, int NT, bool EXACT>
 __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y, int m,
-                                                     const float* __restrict__ D, int K, int s0,
+                                                     const f32x4* __restrict__ Dsw, int K, int s0,
                                                      int32_t* __restrict__ blk,
                                                      float* __restrict__ energy) {
     constexpr int KS = P / 2;            // contraction steps (each lane half covers P/2 dims)
@@ -88,29 +162,16 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
         }
     }
 
-    const int rows = K * P;
-    const int n_stage = (rows + 63) / 64;
-    const f32x4* D4 = reinterpret_cast<const f32x4*>(D);
+    const int n_stage = (K * P + 63) / 64;
 
     f32x4 pre[FPT];
     auto fetch = [&](int s) {
 #pragma unroll
-        for (int r = 0; r < FPT; ++r) {
-            const int f = tid + 256 * r;
-            const int row = f / (P / 4), d4 = f % (P / 4);
-            const int grow = s * 64 + row;
-            pre[r] = grow < rows ? D4[(int64_t)grow * (P / 4) + d4] : f32x4{0.f, 0.f, 0.f, 0.f};
-        }
+        for (int r = 0; r < FPT; ++r) pre[r] = Dsw[(int64_t)s * STAGE_F4 + tid + 256 * r];
     };
     auto stash = [&](int buf) {
 #pragma unroll
-        for (int r = 0; r < FPT; ++r) {
-            const int f = tid + 256 * r;
-            const int row = f / (P / 4), d4 = f % (P / 4);
-            const int hh = d4 / QN, q = d4 % QN;
-            const int mt = row >> 5, nn = row & 31;
-            Qs[buf][(mt * QN + q) * 64 + hh * 32 + nn] = pre[r];
-        }
+        for (int r = 0; r < FPT; ++r) Qs[buf][tid + 256 * r] = pre[r];
     };
 
     fetch(0);
@@ -130,13 +191,8 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
         if (s + 1 < n_stage) fetch(s + 1);
 
         f32x16 acc[NT][2];
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[nt][mt][r] = 0.f;
-
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
+                             0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int q = 0; q < QN; ++q) {
             f32x4 a[2];
@@ -149,7 +205,8 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt)
                         acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(
-                            a[mt][kk], yb[nt][4 * q + kk], acc[nt][mt], 0, 0, 0);
+                            a[mt][kk], yb[nt][4 * q + kk], (q == 0 && kk == 0) ? zero : acc[nt][mt],
+                            0, 0, 0);
         }
 
         if (s + 1 < n_stage) stash(cur ^ 1);
@@ -162,10 +219,9 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
 #pragma unroll
                 for (int v = 0; v < NV; ++v) {
                     const int f = b * NV + v;          // flattened (tile, register)
-                    const float cval = acc[nt][f >> 4][f & 15];
-                    x[v] = cval * cval;
+                    x[v] = fabsf(acc[nt][f >> 4][f & 15]);
                 }
-                const float e = pair_top_energy<NV, S>(x, s0);
+                const float e = pair_top_energy<NV, S, EXACT>(x, s0, h != 0);
                 const int j = s * NB + b;
                 if (j < K && e > bestE[nt]) {
                     bestE[nt] = e;
@@ -189,34 +245,51 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
 }
 
 template <int P, int S>
-hipError_t launch_ps(const float* Y, int64_t m, const float* D, int K, int s0, int32_t* blk,
-                     float* energy, hipStream_t st) {
+hipError_t launch_ps(const float* Y, int64_t m, int K, int s0, int32_t* blk, float* energy,
+                     const float* dsw, hipStream_t st) {
     constexpr int NT = 2;
+    const f32x4* Dsw = reinterpret_cast<const f32x4*>(dsw);
     const int per_wg = 4 * 32 * NT;
     dim3 grid((unsigned)((m + per_wg - 1) / per_wg));
-    hipLaunchKernelGGL((energy_kernel<P, S, NT>), grid, dim3(256), 0, st, Y, (int)m, D, K, s0, blk,
-                       energy);
+    if (s0 == S)
+        hipLaunchKernelGGL((energy_kernel<P, S, NT, true>), grid, dim3(256), 0, st, Y, (int)m, Dsw, K,
+                           s0, blk, energy);
+    else
+        hipLaunchKernelGGL((energy_kernel<P, S, NT, false>), grid, dim3(256), 0, st, Y, (int)m, Dsw,
+                           K, s0, blk, energy);
     return hipGetLastError();
 }
 
 template <int P>
-hipError_t launch_p(int s0, const float* Y, int64_t m, const float* D, int K, int32_t* blk,
-                    float* energy, hipStream_t st) {
-    if (s0 <= 1) return launch_ps<P, 1>(Y, m, D, K, s0, blk, energy, st);
-    if (s0 <= 2) return launch_ps<P, 2>(Y, m, D, K, s0, blk, energy, st);
-    if (s0 <= 4) return launch_ps<P, 4>(Y, m, D, K, s0, blk, energy, st);
-    if (s0 <= 8) return launch_ps<P, 8>(Y, m, D, K, s0, blk, energy, st);
-    return launch_ps<P, 16>(Y, m, D, K, s0, blk, energy, st);
+hipError_t launch_p(int s0, const float* Y, int64_t m, int K, int32_t* blk, float* energy,
+                    const float* dsw, hipStream_t st) {
+    if (s0 <= 1) return launch_ps<P, 1>(Y, m, K, s0, blk, energy, dsw, st);
+    if (s0 <= 2) return launch_ps<P, 2>(Y, m, K, s0, blk, energy, dsw, st);
+    if (s0 <= 4) return launch_ps<P, 4>(Y, m, K, s0, blk, energy, dsw, st);
+    if (s0 <= 8) return launch_ps<P, 8>(Y, m, K, s0, blk, energy, dsw, st);
+    return launch_ps<P, 16>(Y, m, K, s0, blk, energy, dsw, st);
 }
 
 }  // namespace
 
-hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const float* D,
+hipError_t launch_dict_swizzle(int p, int K, const float* D, float* dsw, hipStream_t st) {
+    f32x4* out = reinterpret_cast<f32x4*>(dsw);
+    const dim3 grid((K * p + 63) / 64);
+    switch (p) {
+        case 16: hipLaunchKernelGGL((dict_swizzle_kernel<16>), grid, dim3(256), 0, st, D, K, out); break;
+        case 32: hipLaunchKernelGGL((dict_swizzle_kernel<32>), grid, dim3(256), 0, st, D, K, out); break;
+        case 64: hipLaunchKernelGGL((dict_swizzle_kernel<64>), grid, dim3(256), 0, st, D, K, out); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const float* dsw,
                          int32_t* blk, float* energy, hipStream_t st) {
     switch (p) {
-        case 16: return launch_p<16>(s0, Y, m, D, K, blk, energy, st);
-        case 32: return launch_p<32>(s0, Y, m, D, K, blk, energy, st);
-        case 64: return launch_p<64>(s0, Y, m, D, K, blk, energy, st);
+        case 16: return launch_p<16>(s0, Y, m, K, blk, energy, dsw, st);
+        case 32: return launch_p<32>(s0, Y, m, K, blk, energy, dsw, st);
+        case 64: return launch_p<64>(s0, Y, m, K, blk, energy, dsw, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -26,13 +26,13 @@ constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
 constexpr int kDppHalfMirror = 0x141; // lane i <-> 7 - i inside each group of 8
 constexpr int kDppRowMirror = 0x140;  // lane i <-> 15 - i inside each row of 16
 
-// Sum over aligned groups of G = 8 or 16 lanes; every lane of the group receives the
+// Sum over aligned groups of G = 4, 8 or 16 lanes; every lane of the group receives the
 // bitwise identical total.
 template <int G>
 __device__ __forceinline__ float group_sum(float x) {
     x += dpp_f<kDppXor1>(x);
     x += dpp_f<kDppXor2>(x);
-    x += dpp_f<kDppHalfMirror>(x);
+    if constexpr (G >= 8) x += dpp_f<kDppHalfMirror>(x);
     if constexpr (G == 16) x += dpp_f<kDppRowMirror>(x);
     return x;
 }
@@ -126,18 +126,34 @@ __host__ __device__ __forceinline__ void bitonic_sort_desc(float (&v)[N]) {
     }
 }
 
+// 19-comparator sorting network for 8 keys (descending).
+__host__ __device__ __forceinline__ void sort8_desc(float (&v)[8]) {
+    cmpx_desc(v[0], v[2]); cmpx_desc(v[1], v[3]); cmpx_desc(v[4], v[6]); cmpx_desc(v[5], v[7]);
+    cmpx_desc(v[0], v[4]); cmpx_desc(v[1], v[5]); cmpx_desc(v[2], v[6]); cmpx_desc(v[3], v[7]);
+    cmpx_desc(v[0], v[1]); cmpx_desc(v[2], v[3]); cmpx_desc(v[4], v[5]); cmpx_desc(v[6], v[7]);
+    cmpx_desc(v[2], v[4]); cmpx_desc(v[3], v[5]);
+    cmpx_desc(v[1], v[4]); cmpx_desc(v[3], v[6]);
+    cmpx_desc(v[1], v[2]); cmpx_desc(v[3], v[4]); cmpx_desc(v[5], v[6]);
+}
+
+template <int N>
+__host__ __device__ __forceinline__ void sort_desc(float (&v)[N]) {
+    if constexpr (N == 8) sort8_desc(v);
+    else bitonic_sort_desc<N>(v);
+}
+
 // The L largest of x[0..NV), sorted descending (NV and L powers of two, L <= NV).
 template <int NV, int L>
 __host__ __device__ __forceinline__ void top_sorted(const float (&x)[NV], float (&out)[L]) {
 #pragma unroll
     for (int i = 0; i < L; ++i) out[i] = x[i];
-    bitonic_sort_desc<L>(out);
+    sort_desc<L>(out);
 #pragma unroll
     for (int g = 1; g < NV / L; ++g) {
         float t[L];
 #pragma unroll
         for (int i = 0; i < L; ++i) t[i] = x[g * L + i];
-        bitonic_sort_desc<L>(t);
+        sort_desc<L>(t);
 #pragma unroll
         for (int i = 0; i < L; ++i) out[i] = fmaxf(out[i], t[L - 1 - i]);
         bitonic_merge_desc<L>(out);

@@ -24,7 +24,7 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
     constexpr int LD = P + 4;
     constexpr int NT = (P / 2) * TPP;          // threads: TPP lanes per column pair
     constexpr int RPT = P / TPP;               // contiguous rows per lane in a rotation
-    static_assert(TPP == 8 || TPP == 16, "lanes per pair");
+    static_assert(TPP == 4 || TPP == 8 || TPP == 16, "lanes per pair");
     static_assert(RPT >= 1 && P % TPP == 0, "rows per lane");
     __shared__ __attribute__((aligned(16))) float A[P * LD];
     __shared__ __attribute__((aligned(16))) float V[P * LD];
@@ -38,27 +38,35 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
     if (counts != nullptr && counts[j] == 0) return;   // uniform: block keeps its basis
     const int tid = threadIdx.x;
 
+    // Load P_j scaled by 1 / max|entry| (the orthogonal factor does not depend on scale;
+    // this keeps the squared norms below well inside the fp32 range).
     const float* Mj = M + (int64_t)j * P * P;
+    float mx = 0.f;
+    for (int e = tid; e < P * P; e += NT) mx = fmaxf(mx, fabsf(Mj[e]));
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    if ((tid & 63) == 0) vec[tid >> 6] = mx;
+    __syncthreads();
+    mx = 0.f;
+    for (int w = 0; w < (NT + 63) / 64; ++w) mx = fmaxf(mx, vec[w]);
+    const float scale = mx > 0.f ? 1.f / mx : 0.f;
+    __syncthreads();
     for (int e = tid; e < P * P; e += NT) {
         const int c = e / P, r = e % P;
-        A[c * LD + r] = Mj[e];
+        A[c * LD + r] = Mj[e] * scale;
         V[c * LD + r] = (c == r) ? 1.f : 0.f;
     }
     __syncthreads();
 
+    // Round-robin tournament on P players: player P-1 stays, the others rotate; group pi
+    // meets columns ca, cb, which advance by one (mod P-1) every round.
     const int pi = tid / TPP, sub = tid % TPP;
     const int r0 = sub * RPT;
     for (int sweep = 0; sweep < kMaxSweeps; ++sweep) {
         int rotated = 0;
+        int ca = pi == 0 ? P - 1 : pi;
+        int cb = pi == 0 ? 0 : P - 1 - pi;
         for (int step = 0; step < P - 1; ++step) {
-            int ca, cb;
-            if (pi == 0) {
-                ca = P - 1;
-                cb = step;
-            } else {
-                ca = (step + pi) % (P - 1);
-                cb = (step + (P - 1) - pi) % (P - 1);
-            }
             const int ci = min(ca, cb), cj = max(ca, cb);
             float* ai = A + ci * LD + r0;
             float* aj = A + cj * LD + r0;
@@ -82,16 +90,18 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
             alpha = group_sum<TPP>(alpha);
             beta = group_sum<TPP>(beta);
             gamma = group_sum<TPP>(gamma);
-            if (gamma * gamma > (kTol * kTol) * (alpha * beta)) {
+            // Rotation by theta with tan(2 theta) = 2 gamma / (beta - alpha), |theta| <= pi/4,
+            // from cos(2 theta) = |d| / hypot(d, 2 gamma).  One-ulp reciprocal square roots
+            // suffice: the iteration corrects itself.
+            const float d = beta - alpha, g2 = 2.f * gamma;
+            const float hh = d * d + g2 * g2;
+            if (gamma * gamma > (kTol * kTol) * (alpha * beta) && hh > 1e-36f) {
                 rotated = 1;
-                // tan of the rotation angle that makes the two columns orthogonal; one-ulp
-                // reciprocal / square-root instructions suffice, the iteration corrects itself
-                float zeta = (beta - alpha) * __builtin_amdgcn_rcpf(2.f * gamma);
-                if (zeta != zeta) zeta = 0.f;
-                const float t = copysignf(
-                    __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.f + zeta * zeta)), zeta);
-                const float cs = __builtin_amdgcn_rsqf(1.f + t * t);
-                const float sn = cs * t;
+                const float r = __builtin_amdgcn_rsqf(hh);
+                const float w = 0.5f + 0.5f * (fabsf(d) * r);
+                const float rc = __builtin_amdgcn_rsqf(w);
+                const float cs = w * rc;
+                const float sn = copysignf(0.5f * rc * r, d) * g2;
 #pragma unroll
                 for (int t2 = 0; t2 < RPT; ++t2) {
                     ai[t2] = cs * x[t2] - sn * y[t2];
@@ -99,6 +109,12 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
                     vi[t2] = cs * vx[t2] - sn * vy[t2];
                     vj[t2] = sn * vx[t2] + cs * vy[t2];
                 }
+            }
+            if (pi == 0) {
+                cb = cb + 1;                   // 0, 1, ..., P-2
+            } else {
+                ca = ca + 1 == P - 1 ? 0 : ca + 1;
+                cb = cb + 1 == P - 1 ? 0 : cb + 1;
             }
             __syncthreads();
         }
@@ -187,31 +203,30 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
 
     // Q = U V^T, written atom-major: D[j][k][r] = sum_c U[r][c] V[k][c].
     constexpr int TILES = (P / 4) * (P / 4);
-    if (tid < TILES) {
-        const int r0 = 4 * (tid % (P / 4)), k0 = 4 * (tid / (P / 4));
+    float* Dj = D + (int64_t)j * P * P;
+    for (int tile = tid; tile < TILES; tile += NT) {
+        const int q0 = 4 * (tile % (P / 4)), k0 = 4 * (tile / (P / 4));
         float o[4][4] = {};
         for (int c = 0; c < P; ++c) {
-            const f32x4 u = *reinterpret_cast<const f32x4*>(&A[c * LD + r0]);
+            const f32x4 u = *reinterpret_cast<const f32x4*>(&A[c * LD + q0]);
             const f32x4 v = *reinterpret_cast<const f32x4*>(&V[c * LD + k0]);
 #pragma unroll
             for (int a = 0; a < 4; ++a)
 #pragma unroll
                 for (int b = 0; b < 4; ++b) o[a][b] += v[a] * u[b];
         }
-        float* Dj = D + (int64_t)j * P * P;
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
             f32x4 row = {o[a][0], o[a][1], o[a][2], o[a][3]};
-            *reinterpret_cast<f32x4*>(&Dj[(k0 + a) * P + r0]) = row;
+            *reinterpret_cast<f32x4*>(&Dj[(k0 + a) * P + q0]) = row;
         }
     }
 }
 
 }  // namespace
 
-hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
-                        hipStream_t st) {
-    constexpr int TPP = 16;
+template <int TPP>
+hipError_t launch_tpp(int p, int K, const float* M, const int32_t* counts, float* D, hipStream_t st) {
     switch (p) {
         case 16: hipLaunchKernelGGL((polar_kernel<16, TPP>), dim3(K), dim3(8 * TPP), 0, st, M, counts, D); break;
         case 32: hipLaunchKernelGGL((polar_kernel<32, TPP>), dim3(K), dim3(16 * TPP), 0, st, M, counts, D); break;
@@ -219,6 +234,15 @@ hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, flo
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
+}
+
+hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
+                        hipStream_t st) {
+    int tpp = 8;
+    if (const char* e = getenv("SBO_POLAR_TPP")) tpp = atoi(e);   // tuning override
+    if (tpp == 4) return launch_tpp<4>(p, K, M, counts, D, st);
+    if (tpp == 16) return launch_tpp<16>(p, K, M, counts, D, st);
+    return launch_tpp<8>(p, K, M, counts, D, st);
 }
 
 }  // namespace sbo

@@ -30,6 +30,7 @@ size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char
     w.offsets = (int32_t*)take((size_t)(K + 1) * 4);
     w.perm = (int32_t*)take((size_t)m_max * 4);
     w.energy = (float*)take((size_t)m_max * 4);
+    w.dsw = (float*)take((size_t)((K * p + 63) / 64) * 64 * p * 4);
     w.partial = (float*)take((size_t)max_pieces_bound(m_max, K) * p * p * 4);
     w.M = (float*)take((size_t)K * p * p * 4);
     w.sq_partial = (double*)take((size_t)kSqBlocks * 8);
@@ -100,9 +101,10 @@ static int run_group(sbo_ctx* c, const int32_t* blk, int64_t m) {
 
 static int run_code(sbo_ctx* c, const float* Y, int64_t m, const float* D, int32_t* blk,
                     int32_t* supp, float* coef, float* err) {
+    SBO_HIP(launch_dict_swizzle(c->p, c->K, D, c->ws.dsw, c->stream));   // tiny; outside the stages
     {
         StageTimer t(c, SBO_STAGE_ENERGY);
-        SBO_HIP(launch_energy(c->p, c->K, c->s0, Y, m, D, blk, c->ws.energy, c->stream));
+        SBO_HIP(launch_energy(c->p, c->K, c->s0, Y, m, c->ws.dsw, blk, c->ws.energy, c->stream));
     }
     int rc = run_group(c, blk, m);
     if (rc) return rc;

@@ -59,6 +59,7 @@ struct Workspace {
     int32_t* perm;         // [m_max]
     // coding
     float* energy;         // [m_max] kept energy in the winning block
+    float* dsw;            // [ceil(K*p/64)*64][p] dictionary in MFMA operand order
     // accumulation
     float* partial;        // [max_pieces][p][p]
     float* M;              // [K][p][p]
@@ -91,7 +92,9 @@ struct sbo_ctx {
 // ---- kernel launchers (each returns a hipError_t from the launch) ----------------
 namespace sbo {
 
-hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const float* D,
+// dsw = D rewritten by launch_dict_swizzle into the energy kernel's operand order.
+hipError_t launch_dict_swizzle(int p, int K, const float* D, float* dsw, hipStream_t st);
+hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const float* dsw,
                          int32_t* blk, float* energy, hipStream_t st);
 
 hipError_t launch_group(int K, const int32_t* blk, int64_t m, const Workspace& ws, hipStream_t st);

@@ -33,6 +33,15 @@ template <int N> static void test_sort() {
     }
 }
 
+static void test_sort8() {
+    for (unsigned b = 0; b < 256; ++b) {
+        float v[8];
+        for (int i = 0; i < 8; ++i) v[i] = (b >> i) & 1;
+        sort8_desc(v);
+        for (int i = 1; i < 8; ++i) CHECK(v[i - 1] >= v[i]);
+    }
+}
+
 template <int N> static void test_merge() {
     std::mt19937 g(100 + N);
     std::normal_distribution<float> d;
@@ -94,6 +103,7 @@ static void test_slot() {
 }
 
 int main() {
+    test_sort8();
     test_sort<1>(); test_sort<2>(); test_sort<4>(); test_sort<8>(); test_sort<16>(); test_sort<32>();
     test_merge<1>(); test_merge<2>(); test_merge<4>(); test_merge<8>(); test_merge<16>();
     test_top<8, 1>(); test_top<8, 2>(); test_top<8, 4>(); test_top<8, 8>();
