@@ -15,12 +15,17 @@ namespace sbo {
 namespace {
 
 constexpr int kMaxSweeps = 30;
-constexpr float kTol = 1e-6f;                  // |a_i . a_j| <= kTol |a_i| |a_j| for every pair
+// A pair is rotated while |a_i . a_j| > kTol |a_i| |a_j|.  Convergence is quadratic: a
+// sweep in which every pair already had a cosine below kDone leaves cosines of the order
+// of kDone^2 behind, so it is the last one and no sweep is spent on verifying.
+constexpr float kTol = 1e-6f;
+constexpr float kDone = 1e-4f;
 
 template <int P, int TPP>
 __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __restrict__ M,
                                                              const int32_t* __restrict__ counts,
-                                                             float* __restrict__ D) {
+                                                             float* __restrict__ D,
+                                                             float* __restrict__ Vstate, int warm) {
     constexpr int LD = P + 4;
     constexpr int NT = (P / 2) * TPP;          // threads: TPP lanes per column pair
     constexpr int RPT = P / TPP;               // contiguous rows per lane in a rotation
@@ -28,6 +33,7 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
     static_assert(RPT >= 1 && P % TPP == 0, "rows per lane");
     __shared__ __attribute__((aligned(16))) float A[P * LD];
     __shared__ __attribute__((aligned(16))) float V[P * LD];
+    __shared__ __attribute__((aligned(16))) float B[P * LD];   // warm start only
     __shared__ float sig[P];
     __shared__ float coefs[P];
     __shared__ float vec[P];
@@ -35,8 +41,13 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
     __shared__ int shared_i[2];
 
     const int j = blockIdx.x;
-    if (counts != nullptr && counts[j] == 0) return;   // uniform: block keeps its basis
     const int tid = threadIdx.x;
+    if (counts != nullptr && counts[j] == 0) {          // uniform: block keeps its basis
+        if (Vstate != nullptr && !warm)                 // a cold pass defines every block's V
+            for (int e = tid; e < P * P; e += NT)
+                Vstate[(int64_t)j * P * P + e] = (e / P == e % P) ? 1.f : 0.f;
+        return;
+    }
 
     // Load P_j scaled by 1 / max|entry| (the orthogonal factor does not depend on scale;
     // this keeps the squared norms below well inside the fp32 range).
@@ -58,6 +69,30 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
     }
     __syncthreads();
 
+    // Warm start: begin from the V of this block's previous decomposition.  Any orthogonal
+    // start is valid (P_j V is decomposed instead of P_j and the products are accumulated
+    // into the same V); one close to the answer saves sweeps.
+    if (Vstate != nullptr && warm) {
+        const float* Vj = Vstate + (int64_t)j * P * P;
+        for (int e = tid; e < P * P; e += NT) {
+            const int c = e / P, r = e % P;
+            B[c * LD + r] = A[c * LD + r];
+            V[c * LD + r] = Vj[e];
+        }
+        __syncthreads();
+        for (int o = tid; o < P * P / 4; o += NT) {
+            const int c = o / (P / 4), r4 = (o % (P / 4)) * 4;
+            f32x4 s4 = {0.f, 0.f, 0.f, 0.f};
+            for (int k = 0; k < P; ++k) {
+                const f32x4 b4 = *reinterpret_cast<const f32x4*>(&B[k * LD + r4]);
+                const float v = V[c * LD + k];
+                s4 += b4 * v;
+            }
+            *reinterpret_cast<f32x4*>(&A[c * LD + r4]) = s4;
+        }
+        __syncthreads();
+    }
+
     // Round-robin tournament on P players: player P-1 stays, the others rotate; group pi
     // meets columns ca, cb, which advance by one (mod P-1) every round.
     const int pi = tid / TPP, sub = tid % TPP;
@@ -73,12 +108,29 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
             float* vi = V + ci * LD + r0;
             float* vj = V + cj * LD + r0;
             float x[RPT], y[RPT], vx[RPT], vy[RPT];
+            if constexpr (RPT % 4 == 0) {
 #pragma unroll
-            for (int t = 0; t < RPT; ++t) {
-                x[t] = ai[t];
-                y[t] = aj[t];
-                vx[t] = vi[t];
-                vy[t] = vj[t];
+                for (int t = 0; t < RPT; t += 4) {
+                    const f32x4 a4 = *reinterpret_cast<const f32x4*>(ai + t);
+                    const f32x4 b4 = *reinterpret_cast<const f32x4*>(aj + t);
+                    const f32x4 c4 = *reinterpret_cast<const f32x4*>(vi + t);
+                    const f32x4 d4 = *reinterpret_cast<const f32x4*>(vj + t);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        x[t + e] = a4[e];
+                        y[t + e] = b4[e];
+                        vx[t + e] = c4[e];
+                        vy[t + e] = d4[e];
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int t = 0; t < RPT; ++t) {
+                    x[t] = ai[t];
+                    y[t] = aj[t];
+                    vx[t] = vi[t];
+                    vy[t] = vj[t];
+                }
             }
             float alpha = 0.f, beta = 0.f, gamma = 0.f;
 #pragma unroll
@@ -95,19 +147,41 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
             // suffice: the iteration corrects itself.
             const float d = beta - alpha, g2 = 2.f * gamma;
             const float hh = d * d + g2 * g2;
-            if (gamma * gamma > (kTol * kTol) * (alpha * beta) && hh > 1e-36f) {
-                rotated = 1;
+            // keep the V loads issued together with the A loads, ahead of the decision
+#pragma unroll
+            for (int t = 0; t < RPT; ++t) asm volatile("" : "+v"(vx[t]), "+v"(vy[t]));
+            const float g2ab = gamma * gamma, ab = alpha * beta;
+            if (g2ab > (kDone * kDone) * ab) rotated = 1;          // another sweep is needed
+            if (g2ab > (kTol * kTol) * ab && hh > 1e-36f) {
                 const float r = __builtin_amdgcn_rsqf(hh);
                 const float w = 0.5f + 0.5f * (fabsf(d) * r);
                 const float rc = __builtin_amdgcn_rsqf(w);
                 const float cs = w * rc;
                 const float sn = copysignf(0.5f * rc * r, d) * g2;
+                float nx[RPT], ny[RPT], nvx[RPT], nvy[RPT];
 #pragma unroll
                 for (int t2 = 0; t2 < RPT; ++t2) {
-                    ai[t2] = cs * x[t2] - sn * y[t2];
-                    aj[t2] = sn * x[t2] + cs * y[t2];
-                    vi[t2] = cs * vx[t2] - sn * vy[t2];
-                    vj[t2] = sn * vx[t2] + cs * vy[t2];
+                    nx[t2] = cs * x[t2] - sn * y[t2];
+                    ny[t2] = sn * x[t2] + cs * y[t2];
+                    nvx[t2] = cs * vx[t2] - sn * vy[t2];
+                    nvy[t2] = sn * vx[t2] + cs * vy[t2];
+                }
+                if constexpr (RPT % 4 == 0) {
+#pragma unroll
+                    for (int t = 0; t < RPT; t += 4) {
+                        *reinterpret_cast<f32x4*>(ai + t) = f32x4{nx[t], nx[t + 1], nx[t + 2], nx[t + 3]};
+                        *reinterpret_cast<f32x4*>(aj + t) = f32x4{ny[t], ny[t + 1], ny[t + 2], ny[t + 3]};
+                        *reinterpret_cast<f32x4*>(vi + t) = f32x4{nvx[t], nvx[t + 1], nvx[t + 2], nvx[t + 3]};
+                        *reinterpret_cast<f32x4*>(vj + t) = f32x4{nvy[t], nvy[t + 1], nvy[t + 2], nvy[t + 3]};
+                    }
+                } else {
+#pragma unroll
+                    for (int t2 = 0; t2 < RPT; ++t2) {
+                        ai[t2] = nx[t2];
+                        aj[t2] = ny[t2];
+                        vi[t2] = nvx[t2];
+                        vj[t2] = nvy[t2];
+                    }
                 }
             }
             if (pi == 0) {
@@ -152,6 +226,11 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
         V[c * LD + r] *= vec[c];
     }
     __syncthreads();
+
+    if (Vstate != nullptr) {
+        float* Vj = Vstate + (int64_t)j * P * P;
+        for (int e = tid; e < P * P; e += NT) Vj[e] = V[(e / P) * LD + (e % P)];
+    }
 
     if (shared_i[0] > 0) {                     // uniform
         for (int c = 0; c < P; ++c) {
@@ -226,23 +305,24 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
 }  // namespace
 
 template <int TPP>
-hipError_t launch_tpp(int p, int K, const float* M, const int32_t* counts, float* D, hipStream_t st) {
+hipError_t launch_tpp(int p, int K, const float* M, const int32_t* counts, float* D, float* vstate,
+                      int warm, hipStream_t st) {
     switch (p) {
-        case 16: hipLaunchKernelGGL((polar_kernel<16, TPP>), dim3(K), dim3(8 * TPP), 0, st, M, counts, D); break;
-        case 32: hipLaunchKernelGGL((polar_kernel<32, TPP>), dim3(K), dim3(16 * TPP), 0, st, M, counts, D); break;
-        case 64: hipLaunchKernelGGL((polar_kernel<64, TPP>), dim3(K), dim3(32 * TPP), 0, st, M, counts, D); break;
+        case 16: hipLaunchKernelGGL((polar_kernel<16, TPP>), dim3(K), dim3(8 * TPP), 0, st, M, counts, D, vstate, warm); break;
+        case 32: hipLaunchKernelGGL((polar_kernel<32, TPP>), dim3(K), dim3(16 * TPP), 0, st, M, counts, D, vstate, warm); break;
+        case 64: hipLaunchKernelGGL((polar_kernel<64, TPP>), dim3(K), dim3(32 * TPP), 0, st, M, counts, D, vstate, warm); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
 hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
-                        hipStream_t st) {
-    int tpp = 8;
+                        float* vstate, int warm, hipStream_t st) {
+    int tpp = 16;
     if (const char* e = getenv("SBO_POLAR_TPP")) tpp = atoi(e);   // tuning override
-    if (tpp == 4) return launch_tpp<4>(p, K, M, counts, D, st);
-    if (tpp == 16) return launch_tpp<16>(p, K, M, counts, D, st);
-    return launch_tpp<8>(p, K, M, counts, D, st);
+    if (tpp == 4) return launch_tpp<4>(p, K, M, counts, D, vstate, warm, st);
+    if (tpp == 8) return launch_tpp<8>(p, K, M, counts, D, vstate, warm, st);
+    return launch_tpp<16>(p, K, M, counts, D, vstate, warm, st);
 }
 
 }  // namespace sbo

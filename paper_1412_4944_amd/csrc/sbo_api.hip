@@ -33,6 +33,7 @@ size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char
     w.dsw = (float*)take((size_t)((K * p + 63) / 64) * 64 * p * 4);
     w.partial = (float*)take((size_t)max_pieces_bound(m_max, K) * p * p * 4);
     w.M = (float*)take((size_t)K * p * p * 4);
+    w.vstate = (float*)take((size_t)K * p * p * 4);
     w.sq_partial = (double*)take((size_t)kSqBlocks * 8);
     w.bytes = off;
     if (ws) *ws = w;
@@ -117,14 +118,14 @@ static int run_code(sbo_ctx* c, const float* Y, int64_t m, const float* D, int32
 
 // Accumulate + SVD for signals already grouped in the workspace.
 static int run_update_grouped(sbo_ctx* c, const float* Y, int64_t m, const int32_t* supp,
-                              const float* coef, float* D) {
+                              const float* coef, float* D, float* vstate, int warm) {
     {
         StageTimer t(c, SBO_STAGE_ACCUM);
         SBO_HIP(launch_accumulate(c->p, c->K, c->s0, Y, m, supp, coef, c->ws, c->ws.M, c->stream));
     }
     {
         StageTimer t(c, SBO_STAGE_SVD);
-        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->stream));
+        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, vstate, warm, c->stream));
     }
     return SBO_OK;
 }
@@ -224,7 +225,7 @@ int sbo_polar(sbo_ctx* c, const float* M, const int32_t* counts, float* D) {
     if (!c || !M || !D) return SBO_EINVAL;
     c->n_spans = 0;
     StageTimer t(c, SBO_STAGE_SVD);
-    SBO_HIP(launch_polar(c->p, c->K, M, counts, D, c->stream));
+    SBO_HIP(launch_polar(c->p, c->K, M, counts, D, nullptr, 0, c->stream));
     return SBO_OK;
 }
 
@@ -236,7 +237,7 @@ int sbo_update(sbo_ctx* c, const float* Y, int64_t m, const int32_t* blk, const 
     c->n_spans = 0;
     rc = run_group(c, blk, m);
     if (rc) return rc;
-    rc = run_update_grouped(c, Y, m, supp, coef, D);
+    rc = run_update_grouped(c, Y, m, supp, coef, D, nullptr, 0);
     if (rc) return rc;
     if (counts)
         SBO_HIP(hipMemcpyAsync(counts, c->ws.counts, (size_t)c->K * 4, hipMemcpyDeviceToDevice,
@@ -254,7 +255,10 @@ int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter, int
         rc = run_code(c, Y, m, D, blk, supp, coef, err);
         if (rc) return rc;
         if (sqerr_per_iter) SBO_HIP(launch_sqerr(err, m, c->ws, sqerr_per_iter + it, c->stream));
-        rc = run_update_grouped(c, Y, m, supp, coef, D);   // grouping of this coding pass is reused
+        // The grouping of this coding pass is reused.  Within one call the Jacobi SVD of
+        // every block starts from the previous iteration's V (restarted from the identity
+        // every 8th iteration to bound the accumulated rounding in V).
+        rc = run_update_grouped(c, Y, m, supp, coef, D, c->ws.vstate, it % 8 != 0);
         if (rc) return rc;
     }
     return SBO_OK;

@@ -63,6 +63,7 @@ struct Workspace {
     // accumulation
     float* partial;        // [max_pieces][p][p]
     float* M;              // [K][p][p]
+    float* vstate;         // [K][p][p] V of the previous decomposition (sbo_iterate only)
     // iterate
     double* sq_partial;    // [kSqBlocks]
     size_t bytes;
@@ -106,8 +107,10 @@ hipError_t launch_select(int p, int K, int s0, const float* Y, int64_t m, const 
 hipError_t launch_accumulate(int p, int K, int s0, const float* Y, int64_t m, const int32_t* supp,
                              const float* coef, const Workspace& ws, float* M, hipStream_t st);
 
+// vstate: [K][p][p] right singular vectors kept between calls (nullptr = none); warm != 0
+// starts the decomposition from them.
 hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
-                        hipStream_t st);
+                        float* vstate, int warm, hipStream_t st);
 
 hipError_t launch_sqerr(const float* err, int64_t m, const Workspace& ws, double* out,
                         hipStream_t st);
