@@ -24,6 +24,11 @@ if ROOT not in sys.path:
 PEAK_MFMA_F32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per launch of the roofline kernel, from the two rocprofv3 --pmc runs summarised in
+# profiles/headline_hbm_traffic_pmc.txt (FETCH_SIZE x 2.000 KiB + WRITE_SIZE x 1.000 KiB, factors
+# from a 256 MiB plain copy).  Only known for the workload those runs used.
+MEASURED_TRAFFIC_BYTES = {"headline": (70.29 + 2.00) * 1024 * 1024}
+
 
 def cpu_baseline(pr, sample_m: int) -> dict:
     """The fp64 oracle as it stands, one iteration (coding + update) on the first
@@ -57,6 +62,9 @@ def main() -> int:
     ap.add_argument("--workload", default="headline")
     ap.add_argument("--cpu-sample", type=int, default=262144)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--copy-calib", action="store_true",
+                    help="also run one plain 256 MiB device copy (a dispatch of known HBM traffic, used "
+                         "to scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU (one MI355X); run with --gpus 1", file=sys.stderr)
@@ -83,6 +91,13 @@ def main() -> int:
     coef = torch.empty((m, s0), dtype=torch.float32, device=dev)
     err = torch.empty(m, dtype=torch.float32, device=dev)
     sq = torch.zeros(max(args.steps, 1), dtype=torch.float64, device=dev)
+
+    if args.copy_calib:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)     # 256 MiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     ctx = sbo.sbo_create(p, K, s0, m)
     sbo.sbo_set_timing(ctx, True)
@@ -130,7 +145,8 @@ def main() -> int:
                    "p": p, "K": K, "m": m, "s0": s0},
         "roofline": {"kernel": "energy_kernel (fused Q^T y MFMA + top-s0 energy + block argmax)",
                      "bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_F32_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_MFMA_F32_TFLOPS, "traffic": None},
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_MFMA_F32_TFLOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name)},
         "stage_ms": stage_ms,
         "update_hbm": {"stages": "group+accum", "algorithmic_bytes": upd_bytes,
                        "achieved_GBps": upd_bytes / t_upd / 1e9, "peak_GBps": PEAK_HBM_GBS,
