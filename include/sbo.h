@@ -24,8 +24,10 @@
  *     context must not overlap.
  *   - Return value: 0 on success, a negative SBO_E* code otherwise.  On error no
  *     output is defined; no exception crosses this boundary.
- *   - Supported shapes: p in {16, 32, 64}, 1 <= s0 <= min(p, 16), 1 <= K <= 1024
- *     (K even when p = 16), 1 <= m <= m_max < 2^31 / max(p, s0).
+ *   - Supported shapes: p in {16, 32, 64, 256}, 1 <= s0 <= min(p, 16), 1 <= K <= 1024,
+ *     1 <= m <= m_max < 2^31 / max(p, s0).
+ *   - Signals or atoms holding NaN give unspecified results.  The atoms in one signal's
+ *     supp row must be distinct; block or atom ids outside their range are ignored.
  */
 #ifndef SBO_H
 #define SBO_H

@@ -67,31 +67,42 @@ __device__ __forceinline__ float pair_fold_energy(const float (&a)[S], bool hi) 
     }
 }
 
-// Energy (sum of squares) of the s0 largest magnitudes among the NV coefficients held
-// by this lane (x = |c|) and the NV held by its partner lane.  S = power of two >= s0,
-// S <= 2 * NV.  EXACT means s0 == S.
+// Energy (sum of squares) of the s0 largest magnitudes in the union of two sorted
+// (descending) S-lists of magnitudes, one per lane of a lane pair.  EXACT means s0 == S.
+template <int S, bool EXACT>
+__device__ __forceinline__ float pair_list_energy(const float (&a)[S], int s0, bool hi) {
+    if constexpr (EXACT) {
+        return pair_fold_energy<S>(a, hi);
+    } else {
+        float b[S], c[S];
+#pragma unroll
+        for (int i = 0; i < S; ++i) b[i] = other_half(a[i]);
+#pragma unroll
+        for (int i = 0; i < S; ++i) c[i] = fmaxf(a[i], b[S - 1 - i]);
+        bitonic_merge_desc<S>(c);
+        float e = 0.f;
+#pragma unroll
+        for (int t = 0; t < S; ++t) e += (t < s0) ? c[t] * c[t] : 0.f;
+        return e;
+    }
+}
+
+// The same for the NV magnitudes x held by this lane and the NV held by its partner
+// (one block's coefficients of one signal).  S = power of two >= s0, S <= 2 * NV.
 template <int NV, int S, bool EXACT>
 __device__ __forceinline__ float pair_top_energy(const float (&x)[NV], int s0, bool hi) {
     constexpr int L = S < NV ? S : NV;
     float a[L];
     top_sorted<NV, L>(x, a);
-    if constexpr (L == S && EXACT) {
-        return pair_fold_energy<S>(a, hi);
+    if constexpr (L == S) {
+        return pair_list_energy<S, EXACT>(a, s0, hi);
     } else {
+        static_assert(2 * L == S, "sort width exceeds the coefficients of a lane pair");
         float c[S];
-        if constexpr (L == S) {
-            float b[L];
 #pragma unroll
-            for (int i = 0; i < L; ++i) b[i] = other_half(a[i]);
-#pragma unroll
-            for (int i = 0; i < L; ++i) c[i] = fmaxf(a[i], b[L - 1 - i]);
-        } else {
-            static_assert(2 * L == S, "sort width exceeds the coefficients of a lane pair");
-#pragma unroll
-            for (int i = 0; i < L; ++i) {
-                c[i] = a[i];
-                c[S - 1 - i] = other_half(a[i]);
-            }
+        for (int i = 0; i < L; ++i) {
+            c[i] = a[i];
+            c[S - 1 - i] = other_half(a[i]);
         }
         bitonic_merge_desc<S>(c);
         float e = 0.f;
@@ -128,13 +139,16 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
                                                      float* __restrict__ energy) {
     constexpr int KS = P / 2;            // contraction steps (each lane half covers P/2 dims)
     constexpr int QN = P / 8;            // 16-byte groups of steps per 32-row tile
-    constexpr int NB = 64 / P;           // blocks per 64-row stage
-    constexpr int NV = P / 2;            // coefficients per lane per block
+    constexpr int NB = P <= 64 ? 64 / P : 1;   // blocks per 64-row stage (p <= 64)
+    constexpr int SPB = P <= 64 ? 1 : P / 64;  // 64-row stages per block (p > 64)
+    constexpr int NV = P <= 64 ? P / 2 : 32;   // coefficients per lane per block and stage
     constexpr int STAGE_F4 = 2 * QN * 64;
     constexpr int FPT = STAGE_F4 / 256;  // 16-byte pieces each thread moves per stage
-    static_assert(P == 16 || P == 32 || P == 64, "unsupported p");
+    static_assert(P == 16 || P == 32 || P == 64 || P == 256, "unsupported p");
+    static_assert(P <= 64 || S <= 32, "sort width");
 
-    __shared__ f32x4 Qs[2][STAGE_F4];
+    extern __shared__ f32x4 Qs_raw[];    // [2][STAGE_F4]
+    f32x4(*Qs)[STAGE_F4] = reinterpret_cast<f32x4(*)[STAGE_F4]>(Qs_raw);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -180,10 +194,13 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
 
     int best[NT];
     float bestE[NT];
+    float run[NT][S];                    // p > 64: lane's top-S magnitudes of the current block
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         best[nt] = 0;
         bestE[nt] = -1.f;
+#pragma unroll
+        for (int i = 0; i < S; ++i) run[nt][i] = 0.f;
     }
 
     for (int s = 0; s < n_stage; ++s) {
@@ -211,21 +228,50 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
 
         if (s + 1 < n_stage) stash(cur ^ 1);
 
+        if constexpr (P <= 64) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
+            for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                float x[NV];
+                for (int b = 0; b < NB; ++b) {
+                    float x[NV];
 #pragma unroll
-                for (int v = 0; v < NV; ++v) {
-                    const int f = b * NV + v;          // flattened (tile, register)
-                    x[v] = fabsf(acc[nt][f >> 4][f & 15]);
+                    for (int v = 0; v < NV; ++v) {
+                        const int f = b * NV + v;      // flattened (tile, register)
+                        x[v] = fabsf(acc[nt][f >> 4][f & 15]);
+                    }
+                    const float e = pair_top_energy<NV, S, EXACT>(x, s0, h != 0);
+                    const int j = s * NB + b;
+                    if (j < K && e > bestE[nt]) {
+                        bestE[nt] = e;
+                        best[nt] = j;
+                    }
                 }
-                const float e = pair_top_energy<NV, S, EXACT>(x, s0, h != 0);
-                const int j = s * NB + b;
-                if (j < K && e > bestE[nt]) {
-                    bestE[nt] = e;
-                    best[nt] = j;
+            }
+        } else {
+            // A block spans SPB stages: keep the lane's sorted top-S across them and
+            // combine the lane pair after the block's last stage.
+            const int part = s % SPB;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                float x[32], a[S];
+#pragma unroll
+                for (int f = 0; f < 32; ++f) x[f] = fabsf(acc[nt][f >> 4][f & 15]);
+                top_sorted<32, S>(x, a);
+                if (part == 0) {
+#pragma unroll
+                    for (int i = 0; i < S; ++i) run[nt][i] = a[i];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < S; ++i) run[nt][i] = fmaxf(run[nt][i], a[S - 1 - i]);
+                    bitonic_merge_desc<S>(run[nt]);
+                }
+                if (part == SPB - 1) {
+                    const float e = pair_list_energy<S, EXACT>(run[nt], s0, h != 0);
+                    const int j = s / SPB;
+                    if (j < K && e > bestE[nt]) {
+                        bestE[nt] = e;
+                        best[nt] = j;
+                    }
                 }
             }
         }
@@ -244,20 +290,35 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
     }
 }
 
+template <int P, int S, bool EXACT>
+hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, float* energy,
+                      const f32x4* Dsw, hipStream_t st) {
+    constexpr int NT = P <= 64 ? 2 : 1;
+    constexpr int QN = P / 8;
+    constexpr size_t lds = (size_t)2 * (2 * QN * 64) * sizeof(f32x4);
+    const int per_wg = 4 * 32 * NT;
+    dim3 grid((unsigned)((m + per_wg - 1) / per_wg));
+    if (lds > 64 * 1024) {
+        static bool raised = false;
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute(
+                reinterpret_cast<const void*>(&energy_kernel<P, S, NT, EXACT>),
+                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
+    hipLaunchKernelGGL((energy_kernel<P, S, NT, EXACT>), grid, dim3(256), lds, st, Y, (int)m, Dsw, K,
+                       s0, blk, energy);
+    return hipGetLastError();
+}
+
 template <int P, int S>
 hipError_t launch_ps(const float* Y, int64_t m, int K, int s0, int32_t* blk, float* energy,
                      const float* dsw, hipStream_t st) {
-    constexpr int NT = 2;
     const f32x4* Dsw = reinterpret_cast<const f32x4*>(dsw);
-    const int per_wg = 4 * 32 * NT;
-    dim3 grid((unsigned)((m + per_wg - 1) / per_wg));
-    if (s0 == S)
-        hipLaunchKernelGGL((energy_kernel<P, S, NT, true>), grid, dim3(256), 0, st, Y, (int)m, Dsw, K,
-                           s0, blk, energy);
-    else
-        hipLaunchKernelGGL((energy_kernel<P, S, NT, false>), grid, dim3(256), 0, st, Y, (int)m, Dsw,
-                           K, s0, blk, energy);
-    return hipGetLastError();
+    if (s0 == S) return launch_pse<P, S, true>(Y, m, K, s0, blk, energy, Dsw, st);
+    return launch_pse<P, S, false>(Y, m, K, s0, blk, energy, Dsw, st);
 }
 
 template <int P>
@@ -279,6 +340,7 @@ hipError_t launch_dict_swizzle(int p, int K, const float* D, float* dsw, hipStre
         case 16: hipLaunchKernelGGL((dict_swizzle_kernel<16>), grid, dim3(256), 0, st, D, K, out); break;
         case 32: hipLaunchKernelGGL((dict_swizzle_kernel<32>), grid, dim3(256), 0, st, D, K, out); break;
         case 64: hipLaunchKernelGGL((dict_swizzle_kernel<64>), grid, dim3(256), 0, st, D, K, out); break;
+        case 256: hipLaunchKernelGGL((dict_swizzle_kernel<256>), grid, dim3(256), 0, st, D, K, out); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -290,6 +352,7 @@ hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const 
         case 16: return launch_p<16>(s0, Y, m, K, blk, energy, dsw, st);
         case 32: return launch_p<32>(s0, Y, m, K, blk, energy, dsw, st);
         case 64: return launch_p<64>(s0, Y, m, K, blk, energy, dsw, st);
+        case 256: return launch_p<256>(s0, Y, m, K, blk, energy, dsw, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -186,6 +186,185 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ Y
     }
 }
 
+// Variant for p > 64.  The p coefficients of a signal no longer fit the registers of a
+// lane pair next to the signal itself, so the projection is produced 32 atoms at a time,
+// written to a wave-private LDS tile [signal][atom] while the lane keeps a running sorted
+// top-S of the magnitudes; the support is then emitted from the tile, each lane of a pair
+// walking one half of the atoms in index order (which resolves magnitude ties directly).
+template <int P, int S>
+__global__ __launch_bounds__(256) void select_wide_kernel(const float* __restrict__ Y,
+                                                          const float* __restrict__ D, int K, int s0,
+                                                          const int32_t* __restrict__ offsets,
+                                                          const int32_t* __restrict__ perm,
+                                                          int32_t* __restrict__ supp,
+                                                          float* __restrict__ coef,
+                                                          float* __restrict__ err) {
+    constexpr int KS = P / 2;
+    constexpr int QN = P / 8;
+    constexpr int MT = P / 32;
+    constexpr int LDC = P + 1;
+    constexpr int QCH = 8;                     // operand groups loaded ahead of their MFMAs
+    static_assert(S <= 16 && QN % QCH == 0, "shape");
+
+    extern __shared__ int lds[];               // tile_start[K+1] | tmp[16] | ctile[4][32][LDC]
+    int* tile_start = lds;
+    int* tmp = lds + (K + 1);
+    float* ctile_all = reinterpret_cast<float*>(tmp + 16);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int h = lane >> 5, n = lane & 31;
+
+    wg_exclusive_scan4([&](int j) { return (offsets[j + 1] - offsets[j] + 31) >> 5; }, K,
+                       tile_start, tmp);
+    const int wt = blockIdx.x * 4 + wave;
+    if (wt >= tile_start[K]) return;           // no workgroup barrier below this line
+
+    const int j = upper_slot(tile_start, K, wt);
+    const int pos0 = offsets[j] + (wt - tile_start[j]) * 32;
+    const int cnt = min(32, offsets[j + 1] - pos0);
+    const bool active = n < cnt;
+    const int64_t i = active ? perm[pos0 + n] : -1;
+
+    float yb[KS];
+    if (active) {
+        const f32x4* src = reinterpret_cast<const f32x4*>(Y + i * P + h * KS);
+#pragma unroll
+        for (int q = 0; q < QN; ++q) {
+            f32x4 v = src[q];
+            yb[4 * q + 0] = v.x;
+            yb[4 * q + 1] = v.y;
+            yb[4 * q + 2] = v.z;
+            yb[4 * q + 3] = v.w;
+        }
+    } else {
+#pragma unroll
+        for (int t = 0; t < KS; ++t) yb[t] = 0.f;
+    }
+
+    float* ct = ctile_all + wave * 32 * LDC + n * LDC;     // this lane's signal row
+    float run[S];
+#pragma unroll
+    for (int t = 0; t < S; ++t) run[t] = 0.f;
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
+                         0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+    for (int mt = 0; mt < MT; ++mt) {
+        const f32x4* arow =
+            reinterpret_cast<const f32x4*>(D + ((int64_t)j * P + mt * 32 + n) * P + h * KS);
+        f32x16 acc = zero;
+#pragma unroll
+        for (int q0 = 0; q0 < QN; q0 += QCH) {
+            f32x4 a[QCH];
+#pragma unroll
+            for (int q = 0; q < QCH; ++q) a[q] = arow[q0 + q];
+#pragma unroll
+            for (int q = 0; q < QCH; ++q)
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q][kk], yb[4 * (q0 + q) + kk], acc, 0,
+                                                               0, 0);
+        }
+        float x[16], top[S];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int atom = mt * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+            ct[atom] = acc[r];
+            x[r] = fabsf(acc[r]);
+        }
+        top_sorted<16, S>(x, top);
+        if (mt == 0) {
+#pragma unroll
+            for (int t = 0; t < S; ++t) run[t] = top[t];
+        } else {
+#pragma unroll
+            for (int t = 0; t < S; ++t) run[t] = fmaxf(run[t], top[S - 1 - t]);
+            bitonic_merge_desc<S>(run);
+        }
+    }
+
+    // tau = s0-th largest magnitude of the signal
+    float oth[S], mrg[S];
+#pragma unroll
+    for (int t = 0; t < S; ++t) oth[t] = other_half(run[t]);
+#pragma unroll
+    for (int t = 0; t < S; ++t) mrg[t] = fmaxf(run[t], oth[S - 1 - t]);
+    bitonic_merge_desc<S>(mrg);
+    float tau = mrg[0];
+#pragma unroll
+    for (int t = 1; t < S; ++t) tau = (t == s0 - 1) ? mrg[t] : tau;
+
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // lane h of a pair owns atoms [h*P/2, (h+1)*P/2) of its signal
+    const float* mine = ct + h * (P / 2);
+    int gt_own = 0, eq_own = 0;
+    for (int k = 0; k < P / 2; ++k) {
+        const float a = fabsf(mine[k]);
+        gt_own += a > tau;
+        eq_own += a == tau;
+    }
+    const int gt_oth = other_half(gt_own), eq_oth = other_half(eq_own);
+    const int need = s0 - (gt_own + gt_oth);   // entries equal to tau to take, lowest index first
+    const int gt_lo = h ? gt_oth : gt_own, eq_lo = h ? eq_oth : eq_own;
+    const int eq_lo_taken = min(eq_lo, need);
+    int pos = h ? gt_lo + eq_lo_taken : 0;
+    int eq_taken = h ? eq_lo_taken : 0;
+    float dropped = 0.f;
+    for (int k = 0; k < P / 2; ++k) {
+        const float v = mine[k];
+        const float a = fabsf(v);
+        bool take = a > tau;
+        if (!take && a == tau && eq_taken < need) {
+            take = true;
+            ++eq_taken;
+        }
+        if (take) {
+            if (active && pos < s0) {
+                supp[i * s0 + pos] = h * (P / 2) + k;
+                coef[i * s0 + pos] = v;
+            }
+            ++pos;
+        } else {
+            dropped += v * v;
+        }
+    }
+    dropped += other_half(dropped);
+    if (active && h == 0) err[i] = dropped;
+}
+
+template <int P, int S>
+hipError_t launch_wide_ps(const float* Y, int64_t m, const float* D, int K, int s0,
+                          const Workspace& ws, int32_t* supp, float* coef, float* err,
+                          hipStream_t st) {
+    const int64_t max_tiles = (m + 31) / 32 + K;
+    dim3 grid((unsigned)((max_tiles + 3) / 4));
+    const size_t lds = (K + 1 + 16) * sizeof(int) + 4 * 32 * (P + 1) * sizeof(float);
+    static bool raised = false;
+    if (!raised) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_wide_kernel<P, S>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    hipLaunchKernelGGL((select_wide_kernel<P, S>), grid, dim3(256), lds, st, Y, D, K, s0,
+                       ws.offsets, ws.perm, supp, coef, err);
+    return hipGetLastError();
+}
+
+template <int P>
+hipError_t launch_wide_p(int s0, const float* Y, int64_t m, const float* D, int K,
+                         const Workspace& ws, int32_t* supp, float* coef, float* err,
+                         hipStream_t st) {
+    if (s0 <= 1) return launch_wide_ps<P, 1>(Y, m, D, K, s0, ws, supp, coef, err, st);
+    if (s0 <= 2) return launch_wide_ps<P, 2>(Y, m, D, K, s0, ws, supp, coef, err, st);
+    if (s0 <= 4) return launch_wide_ps<P, 4>(Y, m, D, K, s0, ws, supp, coef, err, st);
+    if (s0 <= 8) return launch_wide_ps<P, 8>(Y, m, D, K, s0, ws, supp, coef, err, st);
+    return launch_wide_ps<P, 16>(Y, m, D, K, s0, ws, supp, coef, err, st);
+}
+
 template <int P, int S>
 hipError_t launch_ps(const float* Y, int64_t m, const float* D, int K, int s0, const Workspace& ws,
                      int32_t* supp, float* coef, float* err, hipStream_t st) {
@@ -216,6 +395,7 @@ hipError_t launch_select(int p, int K, int s0, const float* Y, int64_t m, const 
         case 16: return launch_p<16>(s0, Y, m, D, K, ws, supp, coef, err, st);
         case 32: return launch_p<32>(s0, Y, m, D, K, ws, supp, coef, err, st);
         case 64: return launch_p<64>(s0, Y, m, D, K, ws, supp, coef, err, st);
+        case 256: return launch_wide_p<256>(s0, Y, m, D, K, ws, supp, coef, err, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -317,7 +317,8 @@ hipError_t launch_tpp(int p, int K, const float* M, const int32_t* counts, float
 }
 
 hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
-                        float* vstate, int warm, hipStream_t st) {
+                        float* vstate, int warm, float* jac_a, hipStream_t st) {
+    if (p == 256) return launch_polar_wide(K, M, counts, D, vstate, warm, jac_a, st);
     int tpp = 16;
     if (const char* e = getenv("SBO_POLAR_TPP")) tpp = atoi(e);   // tuning override
     if (tpp == 4) return launch_tpp<4>(p, K, M, counts, D, vstate, warm, st);

@@ -11,8 +11,9 @@ static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 static int max_chunks() { return 1025; }
 
-static int max_pieces_bound(int64_t m_max, int K) {
-    return (int)((m_max + 63) / 64) + K + 1;   // covers the smallest piece size (64 signals)
+static int max_pieces_bound(int64_t m_max, int K, int p) {
+    const int min_piece = p <= 64 ? 64 : 256;  // smallest piece size accum_piece() can return
+    return (int)((m_max + min_piece - 1) / min_piece) + K + 1;
 }
 
 size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char* base) {
@@ -31,9 +32,10 @@ size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char
     w.perm = (int32_t*)take((size_t)m_max * 4);
     w.energy = (float*)take((size_t)m_max * 4);
     w.dsw = (float*)take((size_t)((K * p + 63) / 64) * 64 * p * 4);
-    w.partial = (float*)take((size_t)max_pieces_bound(m_max, K) * p * p * 4);
+    w.partial = (float*)take((size_t)max_pieces_bound(m_max, K, p) * p * p * 4);
     w.M = (float*)take((size_t)K * p * p * 4);
     w.vstate = (float*)take((size_t)K * p * p * 4);
+    w.jac_a = (float*)take(p > 64 ? (size_t)K * p * p * 4 : 0);
     w.sq_partial = (double*)take((size_t)kSqBlocks * 8);
     w.bytes = off;
     if (ws) *ws = w;
@@ -41,7 +43,7 @@ size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char
 }
 
 static bool shape_ok(int p, int K, int s0, int64_t m_max) {
-    if (!(p == 16 || p == 32 || p == 64)) return false;
+    if (!(p == 16 || p == 32 || p == 64 || p == 256)) return false;
     if (K < 1 || K > 1024) return false;
     if (s0 < 1 || s0 > 16 || s0 > p) return false;
     if (m_max < 1) return false;
@@ -125,7 +127,7 @@ static int run_update_grouped(sbo_ctx* c, const float* Y, int64_t m, const int32
     }
     {
         StageTimer t(c, SBO_STAGE_SVD);
-        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, vstate, warm, c->stream));
+        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, vstate, warm, c->ws.jac_a, c->stream));
     }
     return SBO_OK;
 }
@@ -225,7 +227,8 @@ int sbo_polar(sbo_ctx* c, const float* M, const int32_t* counts, float* D) {
     if (!c || !M || !D) return SBO_EINVAL;
     c->n_spans = 0;
     StageTimer t(c, SBO_STAGE_SVD);
-    SBO_HIP(launch_polar(c->p, c->K, M, counts, D, nullptr, 0, c->stream));
+    SBO_HIP(launch_polar(c->p, c->K, M, counts, D, c->p > 64 ? c->ws.vstate : nullptr, 0, c->ws.jac_a,
+                         c->stream));
     return SBO_OK;
 }
 
@@ -237,7 +240,7 @@ int sbo_update(sbo_ctx* c, const float* Y, int64_t m, const int32_t* blk, const 
     c->n_spans = 0;
     rc = run_group(c, blk, m);
     if (rc) return rc;
-    rc = run_update_grouped(c, Y, m, supp, coef, D, nullptr, 0);
+    rc = run_update_grouped(c, Y, m, supp, coef, D, c->p > 64 ? c->ws.vstate : nullptr, 0);
     if (rc) return rc;
     if (counts)
         SBO_HIP(hipMemcpyAsync(counts, c->ws.counts, (size_t)c->K * 4, hipMemcpyDeviceToDevice,

@@ -33,19 +33,20 @@ inline GroupGeom group_geom(int64_t m) {
 // ---- accumulation geometry ---------------------------------------------------
 // Each block's sorted signal list is cut into pieces of `piece` signals; one
 // workgroup reduces one piece into a partial p x p matrix.
-inline int accum_piece(int64_t m) {
+inline int accum_piece(int64_t m, int p) {
     if (const char* e = getenv("SBO_ACCUM_PIECE")) {      // tuning override, multiple of 64
         int v = atoi(e);
-        if (v >= 64 && v <= 2048 && v % 64 == 0) return v;
+        if (v >= (p <= 64 ? 64 : 256) && v <= 4096 && v % 64 == 0) return v;
     }
-    int64_t c = m / 700;                                   // ~2.7 workgroups per CU
+    // ~2.7 workgroups per CU; at p = 256 a piece result is 256 KiB, so fewer, larger pieces
+    int64_t c = p <= 64 ? m / 700 : m / 300;
     c = ((c + 63) / 64) * 64;
-    if (c < 64) c = 64;
-    if (c > 2048) c = 2048;
+    if (c < (p <= 64 ? 64 : 256)) c = p <= 64 ? 64 : 256;
+    if (c > 4096) c = 4096;
     return (int)c;
 }
-inline int accum_max_pieces(int64_t m, int K) {
-    int piece = accum_piece(m);
+inline int accum_max_pieces(int64_t m, int K, int p) {
+    int piece = accum_piece(m, p);
     return (int)((m + piece - 1) / piece) + K;
 }
 
@@ -64,6 +65,7 @@ struct Workspace {
     float* partial;        // [max_pieces][p][p]
     float* M;              // [K][p][p]
     float* vstate;         // [K][p][p] V of the previous decomposition (sbo_iterate only)
+    float* jac_a;          // [K][p][p] p > 64 only: Jacobi working copy of P_j (global memory)
     // iterate
     double* sq_partial;    // [kSqBlocks]
     size_t bytes;
@@ -109,8 +111,14 @@ hipError_t launch_accumulate(int p, int K, int s0, const float* Y, int64_t m, co
 
 // vstate: [K][p][p] right singular vectors kept between calls (nullptr = none); warm != 0
 // starts the decomposition from them.
+// jac_a: [K][p][p] scratch, used when p > 64 (the working matrices then live in global
+// memory; vstate doubles as the V working copy and must not be nullptr).
 hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
-                        float* vstate, int warm, hipStream_t st);
+                        float* vstate, int warm, float* jac_a, hipStream_t st);
+
+// p = 256 variant of launch_polar (polar_wide.hip).
+hipError_t launch_polar_wide(int K, const float* M, const int32_t* counts, float* D, float* vstate,
+                             int warm, float* jac_a, hipStream_t st);
 
 hipError_t launch_sqerr(const float* err, int64_t m, const Workspace& ws, double* out,
                         hipStream_t st);

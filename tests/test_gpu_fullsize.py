@@ -19,7 +19,7 @@ def _sample_ids(m, n, seed):
     return ids
 
 
-@pytest.mark.parametrize("name,n_sample", [("headline", 6000), ("skew", 3000)])
+@pytest.mark.parametrize("name,n_sample", [("headline", 6000), ("skew", 3000), ("patch16", 1500)])
 def test_full_size_iteration_against_oracle(name, n_sample):
     cfg = synth.CONFIGS[name]
     print(f"case {name}: p={cfg.p} K={cfg.K} m={cfg.m} s0={cfg.s0}: generating", flush=True)

@@ -30,6 +30,9 @@ CODE_CASES = [
     ("p64_s5", dict(p=64, K=7, m=1000, s0=5)),
     ("K1", dict(p=64, K=1, m=100, s0=8)),
     ("m1", dict(p=64, K=4, m=1, s0=3)),
+    ("p256", dict(p=256, K=3, m=333, s0=12, snr_db=25.0)),
+    ("p256_s8", dict(p=256, K=2, m=150, s0=8, snr_db=25.0)),
+    ("p256_s1", dict(p=256, K=2, m=70, s0=1, snr_db=25.0)),
 ]
 
 
@@ -95,6 +98,7 @@ UPDATE_CASES = [
     ("headline", dict(m=20000)),
     ("p32", dict(p=32, K=6, m=3000, s0=4)),
     ("p16_oddK", dict(p=16, K=3, m=999, s0=2)),
+    ("p256", dict(p=256, K=2, m=2500, s0=12, snr_db=25.0)),
 ]
 
 
@@ -149,7 +153,8 @@ def test_polar_rank_deficient_and_empty_blocks():
 
 
 @pytest.mark.parametrize("name,kw,iters", [("tiny", dict(), 5), ("patch8", dict(m=8192), 6),
-                                           ("p32", dict(p=32, K=6, m=3000, s0=4), 4)])
+                                           ("p32", dict(p=32, K=6, m=3000, s0=4), 4),
+                                           ("p256", dict(p=256, K=2, m=2500, s0=12, snr_db=25.0), 3)])
 def test_iterate_free_running(name, kw, iters):
     pr = _problem(name, **kw)
     cfg = pr.cfg
