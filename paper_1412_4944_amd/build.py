@@ -16,7 +16,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB_DIR = os.path.join(HERE, "lib")
 LIB = os.path.join(LIB_DIR, "libsbo.so")
 
-SOURCES = ["sbo_api.hip", "code_energy.hip", "code_select.hip", "group.hip", "accumulate.hip",
+SOURCES = ["sbo_api.hip", "code_energy.hip", "code_select.hip", "select_accum.hip", "group.hip", "accumulate.hip",
            "polar_jacobi.hip", "polar_wide.hip", "reduce.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -320,6 +320,22 @@ hipError_t launch_p(int K, int s0, const float* Y, int64_t m, const int32_t* sup
 
 }  // namespace
 
+// M[j] = sum of the piece results of block j in ws.partial, in piece order.
+hipError_t launch_accum_reduce(int p, int K, int64_t m, const Workspace& ws, float* M,
+                               hipStream_t st) {
+    const int piece = accum_piece(m, p);
+    const size_t lds = (K + 1 + 16) * sizeof(int);
+    const dim3 grid(K, (p * p + 255) / 256);
+    switch (p) {
+        case 16: hipLaunchKernelGGL((accum_reduce_kernel<16>), grid, dim3(256), lds, st, K, piece, ws.offsets, ws.partial, M); break;
+        case 32: hipLaunchKernelGGL((accum_reduce_kernel<32>), grid, dim3(256), lds, st, K, piece, ws.offsets, ws.partial, M); break;
+        case 64: hipLaunchKernelGGL((accum_reduce_kernel<64>), grid, dim3(256), lds, st, K, piece, ws.offsets, ws.partial, M); break;
+        case 256: hipLaunchKernelGGL((accum_reduce_kernel<256>), grid, dim3(256), lds, st, K, piece, ws.offsets, ws.partial, M); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_accumulate(int p, int K, int s0, const float* Y, int64_t m, const int32_t* supp,
                              const float* coef, const Workspace& ws, float* M, hipStream_t st) {
     switch (p) {

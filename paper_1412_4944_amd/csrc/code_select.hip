@@ -11,6 +11,7 @@
 // resolved by a sequential per-signal pass (rare).
 #include "sbo_internal.h"
 #include "device_utils.h"
+#include "select_tile.h"
 
 namespace sbo {
 
@@ -31,10 +32,12 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ Y
     constexpr int LDC = P + 1;
     static_assert(S <= NVL, "sort width exceeds the values of one lane");
 
-    extern __shared__ int lds[];               // tile_start[K+1] | tmp[16] | ctile[4][32][LDC]
+    extern __shared__ int lds[];   // tile_start[K+1] | tmp[16] | pad | stage[4][...] | ctile[4][32][LDC]
     int* tile_start = lds;
     int* tmp = lds + (K + 1);
-    float* ctile_all = reinterpret_cast<float*>(tmp + 16);
+    const int head = ((K + 1 + 16) + 3) & ~3;
+    int* stage_all = lds + head;
+    float* ctile_all = reinterpret_cast<float*>(stage_all + 4 * kSelectStageWords);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -87,103 +90,8 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ Y
         }
     }
 
-    // Accumulator register r of tile mt in lane (h, n) is atom mt*32 + (r/4)*8 + h*4 + r%4
-    // of signal n.
-    float c[NVL], mag[NVL];
-#pragma unroll
-    for (int f = 0; f < NVL; ++f) {
-        const int r = f & 15;
-        const int atom = (f >> 4) * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
-        c[f] = acc[f >> 4][r];
-        mag[f] = atom < P ? fabsf(c[f]) : -1.f;
-    }
-
-    // tau = s0-th largest magnitude of the signal.
-    float top[S], oth[S], mrg[S];
-    top_sorted<NVL, S>(mag, top);
-#pragma unroll
-    for (int t = 0; t < S; ++t) oth[t] = other_half(top[t]);
-#pragma unroll
-    for (int t = 0; t < S; ++t) mrg[t] = fmaxf(top[t], oth[S - 1 - t]);
-    bitonic_merge_desc<S>(mrg);
-    float tau = mrg[0];
-#pragma unroll
-    for (int t = 1; t < S; ++t) tau = (t == s0 - 1) ? mrg[t] : tau;
-
-    int gt = 0, eq = 0;
-#pragma unroll
-    for (int f = 0; f < NVL; ++f) {
-        gt += mag[f] > tau;
-        eq += mag[f] == tau;
-    }
-    gt += other_half(gt);
-    eq += other_half(eq);
-    const int need = s0 - gt;                  // entries equal to tau still to take (>= 1)
-    const bool simple = !active || eq == need;
-
-    if (__all(simple)) {
-        // Every entry with |c| >= tau is kept.  Emit in ascending atom order: 4-atom
-        // groups alternate between the two lanes of a signal.
-        int run = 0;
-        float dropped = 0.f;
-#pragma unroll
-        for (int g = 0; g < NVL / 4; ++g) {
-            int own = 0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) own += mag[4 * g + e] >= tau;
-            const int par = other_half(own);
-            int pos = run + (h ? par : 0);
-            run += own + par;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int f = 4 * g + e;
-                const int atom = (f >> 4) * 32 + ((f & 15) >> 2) * 8 + h * 4 + (f & 3);
-                if (mag[f] >= tau) {
-                    if (active) {
-                        supp[i * s0 + pos] = atom;
-                        coef[i * s0 + pos] = c[f];
-                    }
-                    ++pos;
-                } else if (atom < P) {
-                    dropped += c[f] * c[f];
-                }
-            }
-        }
-        dropped += other_half(dropped);
-        if (active && h == 0) err[i] = dropped;
-    } else {
-        // Exact magnitude ties: walk each signal's coefficients in atom order.
-        float* ct = ctile_all + wave * 32 * LDC;
-#pragma unroll
-        for (int f = 0; f < NVL; ++f) {
-            const int atom = (f >> 4) * 32 + ((f & 15) >> 2) * 8 + h * 4 + (f & 3);
-            if (atom < P) ct[n * LDC + atom] = c[f];
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        if (active && h == 0) {
-            int pos = 0, taken_eq = 0;
-            float dropped = 0.f;
-            for (int k = 0; k < P; ++k) {
-                const float v = ct[n * LDC + k];
-                const float a = fabsf(v);
-                bool take = a > tau;
-                if (!take && a == tau && taken_eq < need) {
-                    take = true;
-                    ++taken_eq;
-                }
-                if (take && pos < s0) {
-                    supp[i * s0 + pos] = k;
-                    coef[i * s0 + pos] = v;
-                    ++pos;
-                } else {
-                    dropped += v * v;
-                }
-            }
-            err[i] = dropped;
-        }
-    }
+    tile_select<P, S, false>(acc, h, n, active, i, s0, ctile_all + wave * 32 * LDC,
+                             stage_all + wave * kSelectStageWords, supp, coef, err);
 }
 
 // Variant for p > 64.  The p coefficients of a signal no longer fit the registers of a
@@ -370,7 +278,8 @@ hipError_t launch_ps(const float* Y, int64_t m, const float* D, int K, int s0, c
                      int32_t* supp, float* coef, float* err, hipStream_t st) {
     const int64_t max_tiles = (m + 31) / 32 + K;
     dim3 grid((unsigned)((max_tiles + 3) / 4));
-    const size_t lds = (K + 1 + 16) * sizeof(int) + 4 * 32 * (P + 1) * sizeof(float);
+    const size_t lds = ((((K + 1 + 16) + 3) & ~3) + 4 * kSelectStageWords) * sizeof(int) +
+                       4 * 32 * (P + 1) * sizeof(float);
     hipLaunchKernelGGL((select_kernel<P, S>), grid, dim3(256), lds, st, Y, D, K, s0, ws.offsets,
                        ws.perm, supp, coef, err);
     return hipGetLastError();

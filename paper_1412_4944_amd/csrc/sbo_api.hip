@@ -254,15 +254,41 @@ int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter, int
     if (rc) return rc;
     if (!Y || !D || !blk || !supp || !coef || !err || n_iter < 1) return SBO_EINVAL;
     c->n_spans = 0;
+    const bool fused = c->p <= 64;             // select and accumulate share one pass over Y
     for (int it = 0; it < n_iter; ++it) {
-        rc = run_code(c, Y, m, D, blk, supp, coef, err);
+        // Within one call the Jacobi SVD of every block starts from the previous
+        // iteration's V (restarted from the identity every 8th iteration to bound the
+        // accumulated rounding in V).
+        const int warm = it % 8 != 0;
+        if (!fused) {
+            rc = run_code(c, Y, m, D, blk, supp, coef, err);
+            if (rc) return rc;
+            if (sqerr_per_iter) SBO_HIP(launch_sqerr(err, m, c->ws, sqerr_per_iter + it, c->stream));
+            rc = run_update_grouped(c, Y, m, supp, coef, D, c->ws.vstate, warm);  // grouping reused
+            if (rc) return rc;
+            continue;
+        }
+        SBO_HIP(launch_dict_swizzle(c->p, c->K, D, c->ws.dsw, c->stream));
+        {
+            StageTimer t(c, SBO_STAGE_ENERGY);
+            SBO_HIP(launch_energy(c->p, c->K, c->s0, Y, m, c->ws.dsw, blk, c->ws.energy, c->stream));
+        }
+        rc = run_group(c, blk, m);
         if (rc) return rc;
+        {
+            StageTimer t(c, SBO_STAGE_SELECT);  // includes the per-piece accumulation
+            SBO_HIP(launch_select_accum(c->p, c->K, c->s0, Y, m, D, c->ws, supp, coef, err, c->stream));
+        }
         if (sqerr_per_iter) SBO_HIP(launch_sqerr(err, m, c->ws, sqerr_per_iter + it, c->stream));
-        // The grouping of this coding pass is reused.  Within one call the Jacobi SVD of
-        // every block starts from the previous iteration's V (restarted from the identity
-        // every 8th iteration to bound the accumulated rounding in V).
-        rc = run_update_grouped(c, Y, m, supp, coef, D, c->ws.vstate, it % 8 != 0);
-        if (rc) return rc;
+        {
+            StageTimer t(c, SBO_STAGE_ACCUM);   // only the sum over pieces remains
+            SBO_HIP(launch_accum_reduce(c->p, c->K, m, c->ws, c->ws.M, c->stream));
+        }
+        {
+            StageTimer t(c, SBO_STAGE_SVD);
+            SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws.vstate, warm,
+                                 c->ws.jac_a, c->stream));
+        }
     }
     return SBO_OK;
 }

@@ -113,6 +113,14 @@ hipError_t launch_accumulate(int p, int K, int s0, const float* Y, int64_t m, co
 // starts the decomposition from them.
 // jac_a: [K][p][p] scratch, used when p > 64 (the working matrices then live in global
 // memory; vstate doubles as the V working copy and must not be nullptr).
+// Fused select + per-piece accumulation (p <= 64); the piece results land in ws.partial
+// and launch_accum_reduce sums them into M.
+hipError_t launch_select_accum(int p, int K, int s0, const float* Y, int64_t m, const float* D,
+                               const Workspace& ws, int32_t* supp, float* coef, float* err,
+                               hipStream_t st);
+hipError_t launch_accum_reduce(int p, int K, int64_t m, const Workspace& ws, float* M,
+                               hipStream_t st);
+
 hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
                         float* vstate, int warm, float* jac_a, hipStream_t st);
 

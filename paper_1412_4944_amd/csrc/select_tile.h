@@ -1,0 +1,154 @@
+// Per-tile support selection shared by the select kernels (p <= 64).
+#pragma once
+
+#include "device_utils.h"
+
+namespace sbo {
+
+// One wavefront holds, in MFMA accumulator layout, the projections c = Q_j^T y of a tile
+// of up to 32 signals onto ONE block: register r of tile mt in lane (h, n) is atom
+// mt*32 + (r/4)*8 + h*4 + r%4 of signal n.  Finds the s0-th largest magnitude tau of every
+// signal with the compare-exchange networks, then writes the support {|c| > tau} plus the
+// lowest-index entries equal to tau in ascending atom order, the coefficients and the
+// residual (sum of the dropped c^2) of signal i (original index; active = lane has a
+// signal).  Exact magnitude ties beyond the trivial one are resolved by a sequential
+// per-signal pass through the wave-private LDS tile ct[32][P+1].  The (atom, coefficient)
+// rows are first compacted in the wave-private LDS area stage[32][2][16] (words) and then
+// written with one or a few wide stores per lane (lane half 0: supp row, half 1: coef row),
+// because scattered 4-byte stores to rows in original signal order are what this step
+// would otherwise wait on.
+// KEEP_X: on return ct[n][atom] holds the sparse code x of every signal of the tile
+// (kept coefficients, zeros elsewhere).
+constexpr int kSelectStageWords = 32 * 2 * 16;
+
+template <int P, int S, bool KEEP_X>
+__device__ __forceinline__ void tile_select(const f32x16* acc, int h, int n, bool active, int64_t i,
+                                            int s0, float* ct, int* stage,
+                                            int32_t* __restrict__ supp, float* __restrict__ coef,
+                                            float* __restrict__ err) {
+    constexpr int MT = P >= 32 ? P / 32 : 1;
+    constexpr int NVL = MT * 16;
+    constexpr int LDC = P + 1;
+    static_assert(S <= NVL, "sort width exceeds the values of one lane");
+    float c[NVL], mag[NVL];
+#pragma unroll
+    for (int f = 0; f < NVL; ++f) {
+        const int r = f & 15;
+        const int atom = (f >> 4) * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+        c[f] = acc[f >> 4][r];
+        mag[f] = atom < P ? fabsf(c[f]) : -1.f;
+    }
+
+    // tau = s0-th largest magnitude of the signal.
+    float top[S], oth[S], mrg[S];
+    top_sorted<NVL, S>(mag, top);
+#pragma unroll
+    for (int t = 0; t < S; ++t) oth[t] = other_half(top[t]);
+#pragma unroll
+    for (int t = 0; t < S; ++t) mrg[t] = fmaxf(top[t], oth[S - 1 - t]);
+    bitonic_merge_desc<S>(mrg);
+    float tau = mrg[0];
+#pragma unroll
+    for (int t = 1; t < S; ++t) tau = (t == s0 - 1) ? mrg[t] : tau;
+
+    int gt = 0, eq = 0;
+#pragma unroll
+    for (int f = 0; f < NVL; ++f) {
+        gt += mag[f] > tau;
+        eq += mag[f] == tau;
+    }
+    gt += other_half(gt);
+    eq += other_half(eq);
+    const int need = s0 - gt;                  // entries equal to tau still to take (>= 1)
+    const bool simple = !active || eq == need;
+
+    if (__all(simple)) {
+        // Every entry with |c| >= tau is kept.  Emit in ascending atom order: 4-atom
+        // groups alternate between the two lanes of a signal.
+        int run = 0;
+        float dropped = 0.f;
+#pragma unroll
+        for (int g = 0; g < NVL / 4; ++g) {
+            int own = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) own += mag[4 * g + e] >= tau;
+            const int par = other_half(own);
+            int pos = run + (h ? par : 0);
+            run += own + par;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int f = 4 * g + e;
+                const int atom = (f >> 4) * 32 + ((f & 15) >> 2) * 8 + h * 4 + (f & 3);
+                if (mag[f] >= tau) {
+                    if (active) {             // (a lane without a signal keeps "everything")
+                        stage[n * 32 + pos] = atom;
+                        stage[n * 32 + 16 + pos] = __builtin_bit_cast(int, c[f]);
+                    }
+                    ++pos;
+                } else if (atom < P) {
+                    dropped += c[f] * c[f];
+                }
+                if constexpr (KEEP_X)
+                    if (atom < P) ct[n * LDC + atom] = mag[f] >= tau ? c[f] : 0.f;
+            }
+        }
+        dropped += other_half(dropped);
+        if (active && h == 0) err[i] = dropped;
+    } else {
+        // Exact magnitude ties: walk each signal's coefficients in atom order.
+#pragma unroll
+        for (int f = 0; f < NVL; ++f) {
+            const int atom = (f >> 4) * 32 + ((f & 15) >> 2) * 8 + h * 4 + (f & 3);
+            if (atom < P) ct[n * LDC + atom] = c[f];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (active && h == 0) {
+            int pos = 0, taken_eq = 0;
+            float dropped = 0.f;
+            for (int k = 0; k < P; ++k) {
+                const float v = ct[n * LDC + k];
+                const float a = fabsf(v);
+                bool take = a > tau;
+                if (!take && a == tau && taken_eq < need) {
+                    take = true;
+                    ++taken_eq;
+                }
+                if (take && pos < s0) {
+                    stage[n * 32 + pos] = k;
+                    stage[n * 32 + 16 + pos] = __builtin_bit_cast(int, v);
+                    ++pos;
+                } else {
+                    dropped += v * v;
+                    if constexpr (KEEP_X) ct[n * LDC + k] = 0.f;
+                }
+            }
+            err[i] = dropped;
+        }
+    }
+
+    // compact rows -> global memory
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (active) {
+        const int* src = stage + n * 32 + h * 16;
+        int* dst = (h ? reinterpret_cast<int*>(coef) : supp) + i * s0;
+        typedef int i32x4 __attribute__((ext_vector_type(4)));
+        typedef int i32x2 __attribute__((ext_vector_type(2)));
+        if ((s0 & 3) == 0) {
+            for (int t = 0; t < s0; t += 4)
+                *reinterpret_cast<i32x4*>(dst + t) = *reinterpret_cast<const i32x4*>(src + t);
+        } else if ((s0 & 1) == 0) {
+            for (int t = 0; t < s0; t += 2)
+                *reinterpret_cast<i32x2*>(dst + t) = *reinterpret_cast<const i32x2*>(src + t);
+        } else {
+            for (int t = 0; t < s0; ++t) dst[t] = src[t];
+        }
+    }
+    __builtin_amdgcn_wave_barrier();           // stage is reused by the caller's next tile
+
+}
+
+}  // namespace sbo

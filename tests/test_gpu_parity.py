@@ -173,6 +173,29 @@ def test_iterate_free_running(name, kw, iters):
         assert np.abs(Q @ Q.T - np.eye(cfg.p)).max() <= 1e-5
 
 
+@pytest.mark.parametrize("name,kw", [("tiny", dict()), ("patch8", dict(m=5000)), ("p32", dict(p=32, K=6, m=3000, s0=4)),
+                                     ("p64_s5", dict(p=64, K=7, m=2100, s0=5)),
+                                     ("p256", dict(p=256, K=2, m=1500, s0=12, snr_db=25.0))])
+def test_iterate_one_step_matches_oracle(name, kw):
+    """sbo_iterate(1) (which fuses select and accumulate for p <= 64) against the oracle:
+    the coding outputs element by element, the updated dictionary teacher-forced."""
+    pr = _problem(name, **kw)
+    cfg = pr.cfg
+    print(f"case {name}: p={cfg.p} K={cfg.K} m={pr.Y.shape[0]} s0={cfg.s0}", flush=True)
+    o = orc.o_code(pr.Y, pr.D_init, cfg.s0)
+    with Sbo(cfg.p, cfg.K, cfg.s0, pr.Y.shape[0]) as g:
+        Dg, blk, supp, coef, err, sq = g.iterate(pr.Y, pr.D_init, 1)
+        frac = compare_code(pr.Y, pr.D_init, cfg.s0, o, (blk, supp, coef, err))
+        # the update the GPU made from ITS code, against the oracle's update from the same code
+        Dn, M = orc.o_update(pr.Y, blk, supp, coef, pr.D_init)
+        w = compare_Q(Dg, Dn, M, np.bincount(blk, minlength=cfg.K) > 0)
+        b2, s2, c2, e2 = g.code(pr.Y, pr.D_init)
+    assert np.array_equal(blk, b2) and np.array_equal(supp, s2)
+    np.testing.assert_allclose(coef, c2, rtol=0, atol=1e-6 * np.abs(c2).max())
+    assert abs(sq[0] - err.astype(np.float64).sum()) <= 1e-6 * sq[0] + 1e-12
+    print(f"  exempt {frac:.5f}, worst dQ {w:.2e}", flush=True)
+
+
 def test_teacher_forced_iterations_patch8():
     """Each iteration: the GPU codes with the oracle's dictionary (rounded to fp32) and
     updates from the oracle's code, so chaotic block flips do not compound."""
