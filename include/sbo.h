@@ -106,6 +106,16 @@ int sbo_polar(sbo_ctx* c, const float* M, const int32_t* counts, float* D);
 int sbo_update(sbo_ctx* c, const float* Y, int64_t m, const int32_t* blk,
                const int32_t* supp, const float* coef, float* D, int32_t* counts);
 
+/* R rounds of single-orthobase training per block with the block assignment frozen
+ * (Algorithm 1 with R rounds, as used by Algorithm 2 step 5): for every block j over the
+ * signals with blk == j, repeat R times { x = Q_j^T y hard-thresholded to its s0 largest
+ * magnitudes; P_j = Y_j X_j^T; Q_j = U V^T }.  D is updated in place R times; supp, coef
+ * and err receive the codes of the LAST round (i.e. with respect to D before the last
+ * update).  R = 1 with blk from sbo_code equals sbo_code's code followed by sbo_update.
+ * in : Y, blk[m], R >= 1     in/out: D     out: supp[m][s0], coef[m][s0], err[m] */
+int sbo_train_rounds(sbo_ctx* c, const float* Y, int64_t m, const int32_t* blk, float* D, int R,
+                     int32_t* supp, float* coef, float* err);
+
 /* n_iter x (sbo_code; sbo_update) (Algorithm 2, steps 4-5).  blk/supp/coef/err
  * hold the LAST coding pass (i.e. with respect to D before the last update).
  * sqerr_per_iter: device double[n_iter] or NULL; entry t = sum_i err_i of coding

@@ -13,7 +13,8 @@ Layouts (same as the GPU boundary, cast to fp64 on entry)
 Pins (tests/test_oracle_pins.py): Parseval, brute-force best s0-term fit,
 closed-form error, brute-force block argmax, planted recovery, hand-worked 2-D
 example, grouping invariants, dense Y_j X_j^T identity, scipy polar factor,
-nuclear-norm maximality, Procrustes decrease, fixed point, monotone iteration.
+nuclear-norm maximality, Procrustes decrease, fixed point, monotone iteration and
+monotone frozen-assignment rounds.
 No function here is "parity unpinned".
 """
 from __future__ import annotations
@@ -116,6 +117,34 @@ def o_update(Y, blk, supp, coef, D):
         if counts[j] > 0:
             Dn[j] = o_polar(M[j])
     return Dn, M
+
+
+def o_train_rounds(Y, blk, D, s0, R, round_f32=True):
+    """R rounds of single-orthobase training with the block assignment frozen (Algorithm 1
+    run for R rounds on every block over its own signals; Algorithm 2, step 5): per block
+    and round, X = SELECT(Q^T Y_j, s0), P = Y_j X^T, Q = U V^T.  Returns the final D, the
+    codes of the last round and the total squared error of every round's code."""
+    Y = np.asarray(Y, dtype=np.float64)
+    D = np.asarray(D, dtype=np.float64).copy()
+    blk = np.asarray(blk)
+    m, p = Y.shape
+    K = D.shape[0]
+    supp = np.zeros((m, s0), np.int32)
+    coef = np.zeros((m, s0), np.float64)
+    err = np.zeros(m, np.float64)
+    sq = []
+    for _ in range(R):
+        for j in range(K):
+            ids = np.nonzero(blk == j)[0]
+            if ids.size == 0:
+                continue
+            _b, S, x, e, _E = o_code(Y[ids], D[j:j + 1], s0)   # one block: plain SELECT
+            supp[ids], coef[ids], err[ids] = S, x, e
+        sq.append(err.sum())
+        D, _M = o_update(Y, blk, supp, coef, D)
+        if round_f32:
+            D = D.astype(np.float32).astype(np.float64)
+    return D, (supp, coef, err), np.array(sq)
 
 
 def o_iterate(Y, D, s0, n_iter, round_f32=True):

@@ -13,7 +13,7 @@ SBO_OK, SBO_EINVAL, SBO_ENOMEM, SBO_EHIP = 0, -1, -2, -3
 STAGES = ("energy", "group", "select", "accum", "svd")
 
 EXPORTS = ("sbo_create", "sbo_destroy", "sbo_workspace_bytes", "sbo_code", "sbo_group",
-           "sbo_accumulate", "sbo_polar", "sbo_update", "sbo_iterate", "sbo_set_timing",
+           "sbo_accumulate", "sbo_polar", "sbo_update", "sbo_train_rounds", "sbo_iterate", "sbo_set_timing",
            "sbo_stage_ms", "sbo_strerror")
 
 _lib = None
@@ -44,6 +44,7 @@ def lib() -> ctypes.CDLL:
     L.sbo_accumulate.argtypes = [vp, vp, i64, vp, vp, vp, vp]
     L.sbo_polar.argtypes = [vp, vp, vp, vp]
     L.sbo_update.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp]
+    L.sbo_train_rounds.argtypes = [vp, vp, i64, vp, vp, i32, vp, vp, vp]
     L.sbo_iterate.argtypes = [vp, vp, i64, vp, i32, vp, vp, vp, vp, vp]
     L.sbo_set_timing.argtypes = [vp, i32]
     L.sbo_stage_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
@@ -129,6 +130,13 @@ def sbo_update(ctx, Y, blk, supp, coef, D, counts=None) -> None:
     _check(lib().sbo_update(ctx, _ptr(Y, torch.float32), Y.shape[0], _ptr(blk, torch.int32),
                             _ptr(supp, torch.int32), _ptr(coef, torch.float32),
                             _ptr(D, torch.float32), _ptr(counts, torch.int32, True)))
+
+
+def sbo_train_rounds(ctx, Y, blk, D, R, supp, coef, err) -> None:
+    import torch
+    _check(lib().sbo_train_rounds(ctx, _ptr(Y, torch.float32), Y.shape[0], _ptr(blk, torch.int32),
+                                  _ptr(D, torch.float32), int(R), _ptr(supp, torch.int32),
+                                  _ptr(coef, torch.float32), _ptr(err, torch.float32)))
 
 
 def sbo_iterate(ctx, Y, D, n_iter, blk, supp, coef, err, sqerr_per_iter=None) -> None:

@@ -293,6 +293,39 @@ int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter, int
     return SBO_OK;
 }
 
+int sbo_train_rounds(sbo_ctx* c, const float* Y, int64_t m, const int32_t* blk, float* D, int R,
+                     int32_t* supp, float* coef, float* err) {
+    int rc = check_call(c, m);
+    if (rc) return rc;
+    if (!Y || !blk || !D || !supp || !coef || !err || R < 1) return SBO_EINVAL;
+    c->n_spans = 0;
+    rc = run_group(c, blk, m);                 // the assignment, hence the grouping, is fixed
+    if (rc) return rc;
+    for (int r = 0; r < R; ++r) {
+        const int warm = r % 8 != 0;           // later rounds start Jacobi from the last V
+        if (c->p <= 64) {
+            {
+                StageTimer t(c, SBO_STAGE_SELECT);
+                SBO_HIP(launch_select_accum(c->p, c->K, c->s0, Y, m, D, c->ws, supp, coef, err,
+                                            c->stream));
+            }
+            StageTimer t(c, SBO_STAGE_ACCUM);
+            SBO_HIP(launch_accum_reduce(c->p, c->K, m, c->ws, c->ws.M, c->stream));
+        } else {
+            {
+                StageTimer t(c, SBO_STAGE_SELECT);
+                SBO_HIP(launch_select(c->p, c->K, c->s0, Y, m, D, c->ws, supp, coef, err, c->stream));
+            }
+            StageTimer t(c, SBO_STAGE_ACCUM);
+            SBO_HIP(launch_accumulate(c->p, c->K, c->s0, Y, m, supp, coef, c->ws, c->ws.M, c->stream));
+        }
+        StageTimer t(c, SBO_STAGE_SVD);
+        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws.vstate, warm, c->ws.jac_a,
+                             c->stream));
+    }
+    return SBO_OK;
+}
+
 int sbo_set_timing(sbo_ctx* c, int enable) {
     if (!c) return SBO_EINVAL;
     c->timing = enable ? 1 : 0;

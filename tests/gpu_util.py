@@ -88,6 +88,13 @@ class Sbo:
         t.cuda.synchronize()
         return Dd.cpu().numpy(), counts.cpu().numpy()
 
+    def train_rounds(self, Y, blk, D, R):
+        Yd, Dd = self.dev_f32(Y), self.dev_f32(D)
+        _b, supp, coef, err = self.outputs(Y.shape[0])
+        sbo.sbo_train_rounds(self.ctx, Yd, self.dev_i32(blk), Dd, R, supp, coef, err)
+        self.torch.cuda.synchronize()
+        return Dd.cpu().numpy(), supp.cpu().numpy(), coef.cpu().numpy(), err.cpu().numpy()
+
     def iterate(self, Y, D, n_iter):
         t = self.torch
         Yd, Dd = self.dev_f32(Y), self.dev_f32(D)

@@ -196,6 +196,52 @@ def test_iterate_one_step_matches_oracle(name, kw):
     print(f"  exempt {frac:.5f}, worst dQ {w:.2e}", flush=True)
 
 
+@pytest.mark.parametrize("name,kw,R", [("tiny", dict(), 4), ("patch8", dict(m=6000), 3),
+                                       ("p256", dict(p=256, K=2, m=1500, s0=12, snr_db=25.0), 2)])
+def test_train_rounds_frozen_assignment(name, kw, R):
+    """R rounds of 1ONB per block with the assignment frozen.  Every round is compared with
+    the oracle teacher-forced (the GPU starts the round from the oracle's dictionary, so a
+    near-tie support flip cannot compound); the R-round call is then compared with the
+    chain of single-round calls."""
+    pr = _problem(name, **kw)
+    cfg = pr.cfg
+    m = pr.Y.shape[0]
+    print(f"case {name}: p={cfg.p} K={cfg.K} m={m} s0={cfg.s0} R={R}", flush=True)
+    blk = orc.o_code(pr.Y, pr.D_init, cfg.s0)[0]
+    counts = np.bincount(blk, minlength=cfg.K)
+    n2 = (pr.Y.astype(np.float64) ** 2).sum(1)
+    D = pr.D_init.astype(np.float64)
+    with Sbo(cfg.p, cfg.K, cfg.s0, m) as g:
+        chain = pr.D_init
+        for r in range(R):
+            D32 = D.astype(np.float32)
+            # oracle round from D32: SELECT in the assigned block, then the update
+            so, co, eo = orc.o_train_rounds(pr.Y, blk, D32, cfg.s0, 1)[1]
+            Dg, sg, cg, eg = g.train_rounds(pr.Y, blk, D32, 1)
+            bad = (sg != so).any(axis=1)
+            assert bad.mean() <= 0.001, f"round {r}: {bad.sum()} supports differ"
+            ok = ~bad
+            assert (np.abs(cg[ok] - co[ok]) <= 1e-4 * np.sqrt(n2[ok, None]) + 1e-30).all()
+            assert (np.abs(eg[ok] - eo[ok]) <= 1e-4 * n2[ok] + 1e-30).all()
+            Dn, M = orc.o_update(pr.Y, blk, sg, cg, D32)       # from the GPU's own code
+            w = compare_Q(Dg, Dn, M, counts > 0)
+            print(f"  round {r}: {bad.sum()} near-tie supports, worst dQ {w:.2e}, sqerr {eg.astype(np.float64).sum():.6f}",
+                  flush=True)
+            D = orc.o_train_rounds(pr.Y, blk, D32, cfg.s0, 1)[0]
+            chain, s_ch, c_ch, e_ch = g.train_rounds(pr.Y, blk, chain, 1)
+        DR, sR, cR, eR = g.train_rounds(pr.Y, blk, pr.D_init, R)
+        DR2, *_ = g.train_rounds(pr.Y, blk, pr.D_init, R)
+        D1, s1, c1, e1 = g.train_rounds(pr.Y, blk, pr.D_init, 1)
+    assert np.array_equal(DR, DR2), "rounds not bitwise repeatable"
+    # one call with R rounds = R calls with one round (up to Jacobi's starting point)
+    assert abs(eR.astype(np.float64).sum() - e_ch.astype(np.float64).sum()) <= 1e-5 * e_ch.astype(np.float64).sum()
+    assert (sR == s_ch).all(axis=1).mean() >= 0.999
+    assert eR.astype(np.float64).sum() <= e1.astype(np.float64).sum() * (1 + 1e-6), "error increased over rounds"
+    for j in range(cfg.K):
+        Q = DR[j].astype(np.float64)
+        assert np.abs(Q @ Q.T - np.eye(cfg.p)).max() <= 1e-5
+
+
 def test_teacher_forced_iterations_patch8():
     """Each iteration: the GPU codes with the oracle's dictionary (rounded to fp32) and
     updates from the oracle's code, so chaotic block flips do not compound."""

@@ -240,6 +240,28 @@ def test_iteration_error_non_increasing(name, m):
         assert np.abs(D[j] @ D[j].T - np.eye(pr.cfg.p)).max() < 1e-12
 
 
+def test_frozen_assignment_rounds_monotone_and_consistent():
+    pr = synth.generate(synth.CONFIGS["patch8"], m=3000)
+    D0 = pr.D_init.astype(np.float64)
+    blk = orc.o_code(pr.Y, D0, pr.cfg.s0)[0]
+    D3, (supp, coef, err), sq = orc.o_train_rounds(pr.Y, blk, D0, pr.cfg.s0, 4, round_f32=False)
+    # SELECT is the best s0-term code for the current basis and Q = U V^T the best basis for
+    # the current code, so the error cannot increase from one round to the next
+    assert (np.diff(sq) <= 1e-9 * sq[0]).all() and sq[-1] < sq[0]
+    for j in range(pr.cfg.K):
+        assert np.abs(D3[j] @ D3[j].T - np.eye(pr.cfg.p)).max() < 1e-12
+    # one round from the coding pass's assignment = coding + update
+    b, s_, c_, e_, _ = orc.o_code(pr.Y, D0, pr.cfg.s0)
+    D1a, _ = orc.o_update(pr.Y, b, s_, c_, D0)
+    D1b, (s2, c2, e2), sq1 = orc.o_train_rounds(pr.Y, b, D0, pr.cfg.s0, 1, round_f32=False)
+    np.testing.assert_allclose(D1a, D1b, atol=1e-12)
+    assert (s2 == s_).all() and np.allclose(c2, c_) and np.allclose(e2, e_)
+    # per-round error recomputed from a dense reconstruction of the last round's code
+    Y = pr.Y.astype(np.float64)
+    rec = np.einsum("nt,ntd->nd", coef, D3[blk[:, None], supp])   # not the basis the code was made for
+    assert ((Y - rec) ** 2).sum() <= sq[-1] + 1e-9                 # the later update only helps
+
+
 def test_rmse_definition_against_dense_reconstruction():
     pr = _tiny()
     D = pr.D_init.astype(np.float64)
