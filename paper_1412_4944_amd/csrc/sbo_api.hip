@@ -35,7 +35,7 @@ size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char
     w.partial = (float*)take((size_t)max_pieces_bound(m_max, K, p) * p * p * 4);
     w.M = (float*)take((size_t)K * p * p * 4);
     w.vstate = (float*)take((size_t)K * p * p * 4);
-    w.jac_a = (float*)take(p > 64 ? (size_t)K * p * p * 4 : 0);
+    w.jac_a = (float*)take(p > 64 ? polar_wide_scratch_bytes(K) : 0);
     w.sq_partial = (double*)take((size_t)kSqBlocks * 8);
     w.bytes = off;
     if (ws) *ws = w;

@@ -65,7 +65,7 @@ struct Workspace {
     float* partial;        // [max_pieces][p][p]
     float* M;              // [K][p][p]
     float* vstate;         // [K][p][p] V of the previous decomposition (sbo_iterate only)
-    float* jac_a;          // [K][p][p] p > 64 only: Jacobi working copy of P_j (global memory)
+    float* jac_a;          // p > 64 only: scratch of the wide Jacobi (polar_wide_scratch_bytes)
     // iterate
     double* sq_partial;    // [kSqBlocks]
     size_t bytes;
@@ -111,8 +111,8 @@ hipError_t launch_accumulate(int p, int K, int s0, const float* Y, int64_t m, co
 
 // vstate: [K][p][p] right singular vectors kept between calls (nullptr = none); warm != 0
 // starts the decomposition from them.
-// jac_a: [K][p][p] scratch, used when p > 64 (the working matrices then live in global
-// memory; vstate doubles as the V working copy and must not be nullptr).
+// jac_a: scratch of polar_wide_scratch_bytes(K) bytes, used when p > 64 (vstate then doubles
+// as the V working copy and must not be nullptr).
 // Fused select + per-piece accumulation (p <= 64); the piece results land in ws.partial
 // and launch_accum_reduce sums them into M.
 hipError_t launch_select_accum(int p, int K, int s0, const float* Y, int64_t m, const float* D,
@@ -124,7 +124,9 @@ hipError_t launch_accum_reduce(int p, int K, int64_t m, const Workspace& ws, flo
 hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
                         float* vstate, int warm, float* jac_a, hipStream_t st);
 
-// p = 256 variant of launch_polar (polar_wide.hip).
+// p = 256 variant of launch_polar (polar_wide.hip) and the size of its scratch (working
+// copy of P_j, rotation log, sweep counts).
+size_t polar_wide_scratch_bytes(int K);
 hipError_t launch_polar_wide(int K, const float* M, const int32_t* counts, float* D, float* vstate,
                              int warm, float* jac_a, hipStream_t st);
 
