@@ -4,10 +4,11 @@
 // Determinism comes from a two-level reduction with a fixed order: the grouped signal
 // list of every block is cut into pieces; one workgroup reduces one piece (each wavefront
 // walks its share of the piece in order with private accumulators, which are then added
-// in wave order), and a second kernel adds the piece results of a block in piece order.
+// pairwise in a fixed order), and a second kernel adds the piece results of a block in piece order.
 // No floating-point atomics are used anywhere.
 //
-// The piece kernel forms the product on the matrix cores: with atoms on the M axis, the
+// The piece kernel (p <= 64: one workgroup of 8 wavefronts per piece, about one piece per
+// CU, each wavefront keeping the operands of several steps in flight) forms the product on the matrix cores: with atoms on the M axis, the
 // dimensions on the N axis and the signal index as the contraction index, one fp32 MFMA
 // 32x32x2 adds two signals to a 32x32 tile of P_j.  Its A operand is the dense x_i, which
 // each signal's s0 (atom, coefficient) pairs are scattered into through a 64-float row of
@@ -22,29 +23,38 @@ namespace sbo {
 
 namespace {
 
-constexpr int kPairs = 8;                      // signal pairs per wavefront loaded before use
+constexpr int kTallWaves = 8;                  // wavefronts per workgroup (one workgroup per CU)
+constexpr int kPairs = 4;                      // signal pairs per step of a wavefront
+constexpr int kDepth = 6;                      // steps whose operands are in flight per wavefront
 
 template <int P, int S0>
-__global__ __launch_bounds__(256) void accum_partial_kernel(const float* __restrict__ Y, int K,
-                                                            int piece,
-                                                            const int32_t* __restrict__ offsets,
-                                                            const int32_t* __restrict__ perm,
-                                                            const int32_t* __restrict__ supp,
-                                                            const float* __restrict__ coef,
-                                                            float* __restrict__ partial) {
+__global__ __launch_bounds__(64 * kTallWaves) void accum_piece_kernel(
+    const float* __restrict__ Y, int K, int piece, const int32_t* __restrict__ offsets,
+    const int32_t* __restrict__ perm, const int32_t* __restrict__ supp,
+    const float* __restrict__ coef, float* __restrict__ partial) {
     constexpr int MT = P >= 32 ? P / 32 : 1;   // 32-wide tiles per side of P_j
     constexpr int PP = P * P;
-    extern __shared__ int lds[];   // piece_start[K+1] | tmp[16] | xd[4][kPairs][2][64] | red[PP]
+    constexpr int NW = kTallWaves;
+    constexpr int SPS = 2 * kPairs;            // signals per step
+    constexpr int ACC_F4 = MT * MT * 4 * 64;   // one wavefront's accumulators, 16-byte units
+    // one lane per (signal, support entry) when the sparse codes of a step are fetched
+    constexpr int EPS = S0 <= 1 ? 1 : S0 <= 2 ? 2 : S0 <= 4 ? 4 : S0 <= 8 ? 8 : 16;
+    constexpr int SPI = 64 / EPS;              // signals covered by one such fetch
+    constexpr int NI = (SPS + SPI - 1) / SPI;  // fetches per step
+    // piece_start[K+1] | tmp[16] | pad | ids[kTallMaxPiece] | buf: xd[NW][SPS][64] while the
+    // piece is walked, then [NW/2][ACC_F4] 16-byte units while the wavefronts are summed
+    extern __shared__ int lds[];
     int* piece_start = lds;
     int* tmp = lds + (K + 1);
-    float* xd_all = reinterpret_cast<float*>(tmp + 16);
-    float* red = xd_all + 4 * kPairs * 2 * 64;
+    const int head = ((K + 1 + 16) + 3) & ~3;
+    int* ids = lds + head;
+    float* buf = reinterpret_cast<float*>(ids + kTallMaxPiece);
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int h = lane >> 5, n = lane & 31;
 
-    for (int e = tid; e < 4 * kPairs * 2 * 64; e += 256) xd_all[e] = 0.f;
+    for (int e = tid; e < NW * SPS * 64; e += 64 * NW) buf[e] = 0.f;
     wg_exclusive_scan4([&](int j) { return (offsets[j + 1] - offsets[j] + piece - 1) / piece; }, K,
                        piece_start, tmp);
     const int id = blockIdx.x;
@@ -52,7 +62,10 @@ __global__ __launch_bounds__(256) void accum_partial_kernel(const float* __restr
 
     const int j = upper_slot(piece_start, K, id);
     const int pos0 = offsets[j] + (id - piece_start[j]) * piece;
-    const int cnt = min(piece, offsets[j + 1] - pos0);
+    const int cnt = min(piece, offsets[j + 1] - pos0);   // <= kTallMaxPiece (launcher)
+
+    for (int q = tid; q < cnt; q += 64 * NW) ids[q] = perm[pos0 + q];
+    __syncthreads();
 
     f32x16 acc[MT][MT];
 #pragma unroll
@@ -62,74 +75,135 @@ __global__ __launch_bounds__(256) void accum_partial_kernel(const float* __restr
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    float* xd = xd_all + (wave * kPairs * 2 + h) * 64;   // + u * 128 for pair u
-    const int n_pairs = (cnt + 1) >> 1;
-    for (int g = wave; g < n_pairs; g += 4 * kPairs) {
-        int64_t i[kPairs];
+    // Step G covers signals G*SPS .. G*SPS+SPS-1 of the piece; a wavefront takes steps
+    // wave, wave + NW, ...  The operands of kDepth steps are in flight at any time: the ring
+    // below lives in registers (every index into it is a compile-time constant).
+    struct Operands {
+        float yv[kPairs][MT];                  // B operand: lane (h, n) holds dim nt*32+n of signal 2u+h
+        float c[NI];                           // one (atom, coefficient) of one signal per lane
+        int k[NI];
+    };
+    // Loads are unconditional (positions past the end of the piece are clamped to its last
+    // signal, columns past P to the last one): a signal past the end gets no (atom,
+    // coefficient) pair in consume(), so whatever y was loaded for it is multiplied by zero,
+    // and columns past P are never stored.
+    const int ncol = n < P ? n : P - 1;
+    const int sl_lane = lane / EPS, t_lane = lane % EPS < S0 ? lane % EPS : S0 - 1;
+    auto fetch = [&](Operands& o, int G) {
 #pragma unroll
         for (int u = 0; u < kPairs; ++u) {
-            const int q = 2 * (g + 4 * u) + h;           // lane half h takes the pair's h-th signal
-            i[u] = q < cnt ? perm[pos0 + q] : -1;
-        }
-        float yv[kPairs][MT], c[kPairs];
-        int k[kPairs];
+            const int64_t i = ids[min(G * SPS + 2 * u + h, cnt - 1)];
 #pragma unroll
-        for (int u = 0; u < kPairs; ++u) {
-            const bool on = i[u] >= 0;
-#pragma unroll
-            for (int nt = 0; nt < MT; ++nt)
-                yv[u][nt] = (on && nt * 32 + n < P) ? Y[i[u] * P + nt * 32 + n] : 0.f;
-            k[u] = -1;
-            c[u] = 0.f;
-            if (on && n < S0) {
-                k[u] = supp[i[u] * S0 + n];
-                c[u] = coef[i[u] * S0 + n];
-            }
-            if ((unsigned)k[u] >= (unsigned)P) k[u] = -1;   // out-of-range atoms contribute nothing
+            for (int nt = 0; nt < MT; ++nt) o.yv[u][nt] = Y[i * P + (MT > 1 ? nt * 32 + n : ncol)];
         }
 #pragma unroll
-        for (int u = 0; u < kPairs; ++u)
-            if (k[u] >= 0) xd[u * 128 + k[u]] = c[u];
+        for (int e = 0; e < NI; ++e) {
+            const int64_t i = ids[min(G * SPS + e * SPI + sl_lane, cnt - 1)];
+            o.k[e] = supp[i * S0 + t_lane];
+            o.c[e] = coef[i * S0 + t_lane];
+        }
+    };
+
+    float* xd = buf + wave * SPS * 64;         // dense x of the step's signals, one 64-float row each
+    auto consume = [&](const Operands& o, int G) {
+        int k[NI];
+#pragma unroll
+        for (int e = 0; e < NI; ++e) {
+            const int sl = e * SPI + sl_lane;
+            const bool valid = sl < SPS && lane % EPS < S0 && G * SPS + sl < cnt &&
+                               (unsigned)o.k[e] < (unsigned)P;   // out-of-range atoms contribute nothing
+            k[e] = valid ? sl * 64 + o.k[e] : -1;
+        }
+#pragma unroll
+        for (int e = 0; e < NI; ++e)
+            if (k[e] >= 0) xd[k[e]] = o.c[e];
         float a[kPairs][MT];
 #pragma unroll
         for (int u = 0; u < kPairs; ++u)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) a[u][mt] = xd[u * 128 + mt * 32 + n];
+            for (int mt = 0; mt < MT; ++mt) a[u][mt] = xd[(2 * u + h) * 64 + mt * 32 + n];
 #pragma unroll
-        for (int u = 0; u < kPairs; ++u)
-            if (k[u] >= 0) xd[u * 128 + k[u]] = 0.f;
+        for (int e = 0; e < NI; ++e)
+            if (k[e] >= 0) xd[k[e]] = 0.f;
 #pragma unroll
         for (int u = 0; u < kPairs; ++u)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int nt = 0; nt < MT; ++nt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][mt], yv[u][nt],
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][mt], o.yv[u][nt],
                                                                        acc[mt][nt], 0, 0, 0);
-    }
+    };
 
-    // Wave accumulators are added in wave order.  Register r of tile (mt, nt) in lane
-    // (h, n) is atom mt*32 + (r/4)*8 + h*4 + r%4, dimension nt*32 + n.
-    for (int w = 0; w < 4; ++w) {
-        if (wave == w) {
+    // Full rounds of kDepth steps run without any condition (so that the operands of the
+    // other kDepth-1 slots stay in flight while one is consumed); fetches that reach past
+    // the end of the piece are clamped and never consumed.
+    const int n_steps = (cnt + SPS - 1) / SPS;
+    Operands ring[kDepth];
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) fetch(ring[d], wave + NW * d);
+    int G = wave;
+    for (; G + NW * (kDepth - 1) < n_steps; G += NW * kDepth) {
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+            consume(ring[d], G + NW * d);
+            fetch(ring[d], G + NW * (d + kDepth));
+        }
+    }
+#pragma unroll
+    for (int d = 0; d < kDepth - 1; ++d)
+        if (G + NW * d < n_steps) consume(ring[d], G + NW * d);   // uniform over the wavefront
+    __syncthreads();                           // xd is dead; buf becomes the exchange area
+
+    // Pairwise sum over the wavefronts in a fixed order: wavefront w adds w + half.
+    f32x4* xch = reinterpret_cast<f32x4*>(buf);
+    for (int half = NW / 2; half >= 1; half >>= 1) {
+        if (wave >= half && wave < 2 * half) {
+            f32x4* dst = xch + (wave - half) * ACC_F4;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int nt = 0; nt < MT; ++nt)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int atom = mt * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
-                        const int dim = nt * 32 + n;
-                        if (atom < P && dim < P) {
-                            float* cell = red + atom * P + dim;
-                            *cell = (w == 0) ? acc[mt][nt][r] : *cell + acc[mt][nt][r];
-                        }
+                    for (int r4 = 0; r4 < 4; ++r4)
+                        dst[((mt * MT + nt) * 4 + r4) * 64 + lane] =
+                            f32x4{acc[mt][nt][4 * r4], acc[mt][nt][4 * r4 + 1],
+                                  acc[mt][nt][4 * r4 + 2], acc[mt][nt][4 * r4 + 3]};
+        }
+        __syncthreads();
+        if (wave < half) {
+            const f32x4* src = xch + wave * ACC_F4;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < MT; ++nt)
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        const f32x4 v = src[((mt * MT + nt) * 4 + r4) * 64 + lane];
+                        acc[mt][nt][4 * r4] += v.x;
+                        acc[mt][nt][4 * r4 + 1] += v.y;
+                        acc[mt][nt][4 * r4 + 2] += v.z;
+                        acc[mt][nt][4 * r4 + 3] += v.w;
                     }
         }
         __syncthreads();
     }
-    float* out = partial + (int64_t)id * PP;
-    for (int e = tid; e < PP; e += 256) out[e] = red[e];
+
+    // Register r of tile (mt, nt) in lane (h, n) is atom mt*32 + (r/4)*8 + h*4 + r%4,
+    // dimension nt*32 + n.
+    if (wave == 0) {
+        float* out = partial + (int64_t)id * PP;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < MT; ++nt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int atom = mt * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+                    const int dim = nt * 32 + n;
+                    if (atom < P && dim < P) out[atom * P + dim] = acc[mt][nt][r];
+                }
+    }
 }
 
 // Variant for p = 256: a p x p accumulator (64 tiles) does not fit one wavefront, so the
@@ -256,20 +330,23 @@ __global__ __launch_bounds__(256) void accum_reduce_kernel(int K, int piece,
 template <int P, int S0>
 hipError_t launch_ps(int K, const float* Y, int64_t m, const int32_t* supp, const float* coef,
                      const Workspace& ws, float* M, hipStream_t st) {
-    const int piece = accum_piece(m, P);
-    const int max_pieces = accum_max_pieces(m, K, P);
-    const size_t lds1 =
-        (K + 1 + 16) * sizeof(int) + ((size_t)4 * kPairs * 2 * 64 + (size_t)P * P) * sizeof(float);
+    constexpr int MT = P >= 32 ? P / 32 : 1;
+    const int piece = accum_tall_piece(m, K);
+    const int max_pieces = (int)((m + piece - 1) / piece) + K;
+    const size_t head = ((size_t)(K + 1 + 16) + 3) & ~(size_t)3;
+    const size_t walk = (size_t)kTallWaves * 2 * kPairs * 64;
+    const size_t xch = (size_t)(kTallWaves / 2) * MT * MT * 16 * 64;
+    const size_t lds1 = (head + kTallMaxPiece + (walk > xch ? walk : xch)) * 4;
     static bool raised = false;
     if (!raised) {
         hipError_t e =
-            hipFuncSetAttribute(reinterpret_cast<const void*>(&accum_partial_kernel<P, S0>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+            hipFuncSetAttribute(reinterpret_cast<const void*>(&accum_piece_kernel<P, S0>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL((accum_partial_kernel<P, S0>), dim3(max_pieces), dim3(256), lds1, st, Y, K,
-                       piece, ws.offsets, ws.perm, supp, coef, ws.partial);
+    hipLaunchKernelGGL((accum_piece_kernel<P, S0>), dim3(max_pieces), dim3(64 * kTallWaves), lds1, st,
+                       Y, K, piece, ws.offsets, ws.perm, supp, coef, ws.partial);
     const size_t lds2 = (K + 1 + 16) * sizeof(int);
     hipLaunchKernelGGL((accum_reduce_kernel<P>), dim3(K, (P * P + 255) / 256), dim3(256), lds2, st,
                        K, piece, ws.offsets, ws.partial, M);
@@ -280,7 +357,7 @@ template <int S0>
 hipError_t launch_wide_s(int K, const float* Y, int64_t m, const int32_t* supp, const float* coef,
                          const Workspace& ws, float* M, hipStream_t st) {
     constexpr int P = 256;
-    const int piece = accum_piece(m, P);
+    const int piece = accum_piece(m, K, P);
     const int max_pieces = accum_max_pieces(m, K, P);
     const size_t lds1 = (K + 1 + 16) * sizeof(int) + (size_t)4 * kWidePairs * 2 * 64 * sizeof(float);
     hipLaunchKernelGGL((accum_wide_kernel<S0>), dim3(max_pieces), dim3(256), lds1, st, Y, K, piece,
@@ -323,7 +400,7 @@ hipError_t launch_p(int K, int s0, const float* Y, int64_t m, const int32_t* sup
 // M[j] = sum of the piece results of block j in ws.partial, in piece order.
 hipError_t launch_accum_reduce(int p, int K, int64_t m, const Workspace& ws, float* M,
                                hipStream_t st) {
-    const int piece = accum_piece(m, p);
+    const int piece = accum_piece(m, K, p);
     const size_t lds = (K + 1 + 16) * sizeof(int);
     const dim3 grid(K, (p * p + 255) / 256);
     switch (p) {

@@ -33,20 +33,36 @@ inline GroupGeom group_geom(int64_t m) {
 // ---- accumulation geometry ---------------------------------------------------
 // Each block's sorted signal list is cut into pieces of `piece` signals; one
 // workgroup reduces one piece into a partial p x p matrix.
-inline int accum_piece(int64_t m, int p) {
+constexpr int kNumCU = 256;
+inline int accum_piece(int64_t m, int K, int p) {
     if (const char* e = getenv("SBO_ACCUM_PIECE")) {      // tuning override, multiple of 64
         int v = atoi(e);
         if (v >= (p <= 64 ? 64 : 256) && v <= 4096 && v % 64 == 0) return v;
     }
-    // ~2.7 workgroups per CU; at p = 256 a piece result is 256 KiB, so fewer, larger pieces
-    int64_t c = p <= 64 ? m / 700 : m / 300;
+    // p <= 64: two workgroups fit a CU, and all pieces should be resident in one round
+    // (pieces <= 2 * CUs where K allows); at p = 256 a piece result is 256 KiB, so fewer,
+    // larger pieces
+    const int slots = 2 * kNumCU;
+    const int target = K < slots / 2 ? slots - K : slots / 2;
+    int64_t c = p <= 64 ? (m + target - 1) / target : m / 300;
     c = ((c + 63) / 64) * 64;
     if (c < (p <= 64 ? 64 : 256)) c = p <= 64 ? 64 : 256;
     if (c > 4096) c = 4096;
     return (int)c;
 }
+// Piece size of the stand-alone accumulation for p <= 64, whose workgroups fill a whole CU:
+// as few pieces as keep every CU busy in a single round (pieces <= CUs where K allows), capped
+// because the kernel keeps a piece's signal ids in LDS.
+constexpr int kTallMaxPiece = 4096;
+inline int accum_tall_piece(int64_t m, int K) {
+    const int target = K < kNumCU / 2 ? kNumCU - K : kNumCU / 2;
+    int64_t c = (m + target - 1) / target;
+    c = ((c + 63) / 64) * 64;
+    if (c > kTallMaxPiece) c = kTallMaxPiece;
+    return (int)(c < 64 ? 64 : c);
+}
 inline int accum_max_pieces(int64_t m, int K, int p) {
-    int piece = accum_piece(m, p);
+    int piece = accum_piece(m, K, p);
     return (int)((m + piece - 1) / piece) + K;
 }
 

@@ -84,32 +84,35 @@ __global__ __launch_bounds__(256) void select_accum_kernel(const float* __restri
     float* xt = tile_all + wave * TILE_WORDS;
     int* stage = stage_all + wave * kSelectStageWords;
     const int n_tiles = (cnt + 31) >> 5;
-    int64_t i_next = (wave < n_tiles && n < min(32, cnt - wave * 32)) ? perm[pos0 + wave * 32 + n] : -1;
-    for (int tile = wave; tile < n_tiles; tile += 4) {
-        const int64_t i = i_next;
-        const bool active = i >= 0;
-        {
-            const int nx = tile + 4;
-            i_next = (nx < n_tiles && n < min(32, cnt - nx * 32)) ? perm[pos0 + nx * 32 + n] : -1;
+    // Signal ids are fetched two tiles ahead and the rows of Y one tile ahead: the loads of
+    // the next tile are issued as soon as the projection has consumed the current rows, and
+    // land while the selection and the product run.  The loads are unconditional (lanes past
+    // the end of the piece read the row of signal 0 and are zeroed when consumed).
+    auto tile_id = [&](int t) -> int {
+        return (t < n_tiles && n < min(32, cnt - t * 32)) ? perm[pos0 + t * 32 + n] : -1;
+    };
+    float yb[KS];
+    auto load_rows = [&](int id) {
+        const f32x4* src = reinterpret_cast<const f32x4*>(Y + (int64_t)max(id, 0) * P + h * KS);
+#pragma unroll
+        for (int q = 0; q < QN; ++q) {
+            const f32x4 v = src[q];
+            yb[4 * q + 0] = v.x;
+            yb[4 * q + 1] = v.y;
+            yb[4 * q + 2] = v.z;
+            yb[4 * q + 3] = v.w;
         }
+    };
+    int i_cur = tile_id(wave), i_next = tile_id(wave + 4);
+    load_rows(i_cur);
+    for (int tile = wave; tile < n_tiles; tile += 4) {
+        const int64_t i = i_cur;
+        const bool active = i >= 0;
 
         // y: this lane's half row, for the projection (registers) and, transposed through
         // LDS, for the product
-        float yb[KS];
-        if (active) {
-            const f32x4* src = reinterpret_cast<const f32x4*>(Y + i * P + h * KS);
 #pragma unroll
-            for (int q = 0; q < QN; ++q) {
-                f32x4 v = src[q];
-                yb[4 * q + 0] = v.x;
-                yb[4 * q + 1] = v.y;
-                yb[4 * q + 2] = v.z;
-                yb[4 * q + 3] = v.w;
-            }
-        } else {
-#pragma unroll
-            for (int t = 0; t < KS; ++t) yb[t] = 0.f;
-        }
+        for (int t = 0; t < KS; ++t) yb[t] = active ? yb[t] : 0.f;
 #pragma unroll
         for (int q = 0; q < QN; ++q)
             *reinterpret_cast<f32x4*>(&xt[n * LDY + h * KS + 4 * q]) =
@@ -129,6 +132,9 @@ __global__ __launch_bounds__(256) void select_accum_kernel(const float* __restri
                                                                    0, 0);
             }
         }
+        i_cur = i_next;
+        i_next = tile_id(tile + 8);
+        load_rows(i_cur);                      // rows of the next tile
 
         // B operand of the product: lane (h, n) takes dimension nt*32 + n of signal 2*sp + h
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -195,7 +201,7 @@ template <int P, int S>
 hipError_t launch_ps(const float* Y, int64_t m, const float* D, int K, int s0, const Workspace& ws,
                      int32_t* supp, float* coef, float* err, hipStream_t st) {
     constexpr int MT = P >= 32 ? P / 32 : 1;
-    const int piece = accum_piece(m, P);
+    const int piece = accum_piece(m, K, P);
     const int max_pieces = accum_max_pieces(m, K, P);
     const int head = ((K + 1 + 16) + 3) & ~3;
     const size_t lds = (size_t)head * sizeof(int) + (size_t)MT * (P / 8) * 64 * sizeof(f32x4) +

@@ -51,30 +51,27 @@ __device__ __forceinline__ void tile_select(const f32x16* acc, int h, int n, boo
 #pragma unroll
     for (int t = 1; t < S; ++t) tau = (t == s0 - 1) ? mrg[t] : tau;
 
-    int gt = 0, eq = 0;
+    // Entries with |c| >= tau, per group of 4 consecutive atoms (the groups alternate
+    // between the two lanes of a signal).  Exactly s0 of them: no tie at tau to break.
+    int own[NVL / 4], par[NVL / 4], total = 0;
 #pragma unroll
-    for (int f = 0; f < NVL; ++f) {
-        gt += mag[f] > tau;
-        eq += mag[f] == tau;
+    for (int g = 0; g < NVL / 4; ++g) {
+        own[g] = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) own[g] += mag[4 * g + e] >= tau;
+        par[g] = other_half(own[g]);
+        total += own[g] + par[g];
     }
-    gt += other_half(gt);
-    eq += other_half(eq);
-    const int need = s0 - gt;                  // entries equal to tau still to take (>= 1)
-    const bool simple = !active || eq == need;
+    const bool simple = !active || total == s0;
 
     if (__all(simple)) {
-        // Every entry with |c| >= tau is kept.  Emit in ascending atom order: 4-atom
-        // groups alternate between the two lanes of a signal.
+        // Every entry with |c| >= tau is kept.  Emit in ascending atom order.
         int run = 0;
         float dropped = 0.f;
 #pragma unroll
         for (int g = 0; g < NVL / 4; ++g) {
-            int own = 0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) own += mag[4 * g + e] >= tau;
-            const int par = other_half(own);
-            int pos = run + (h ? par : 0);
-            run += own + par;
+            int pos = run + (h ? par[g] : 0);
+            run += own[g] + par[g];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int f = 4 * g + e;
@@ -104,6 +101,11 @@ __device__ __forceinline__ void tile_select(const f32x16* acc, int h, int n, boo
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        int gt = 0;
+#pragma unroll
+        for (int f = 0; f < NVL; ++f) gt += mag[f] > tau;
+        gt += other_half(gt);
+        const int need = s0 - gt;              // entries equal to tau still to take (>= 1)
         if (active && h == 0) {
             int pos = 0, taken_eq = 0;
             float dropped = 0.f;
