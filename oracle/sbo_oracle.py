@@ -14,7 +14,10 @@ Pins (tests/test_oracle_pins.py): Parseval, brute-force best s0-term fit,
 closed-form error, brute-force block argmax, planted recovery, hand-worked 2-D
 example, grouping invariants, dense Y_j X_j^T identity, scipy polar factor,
 nuclear-norm maximality, Procrustes decrease, fixed point, monotone iteration and
-monotone frozen-assignment rounds.
+monotone frozen-assignment rounds; worst-W set against its defining inequalities;
+base initialisation against the eigen-decomposition of the Gram matrix, a rank-one
+case, a hand-worked diagonal case and a planted factorisation; new-base training
+against monotone error and the planted fixed point.
 No function here is "parity unpinned".
 """
 from __future__ import annotations
@@ -163,6 +166,46 @@ def o_iterate(Y, D, s0, n_iter, round_f32=True):
             D = D.astype(np.float32).astype(np.float64)
         last = (blk, supp, coef, err)
     return D, last, np.array(sq)
+
+
+def o_worst(err, W):
+    """The W worst represented signals (Algorithm 2, step 3): the W largest squared
+    residuals; among equal residuals the lower signal index is taken first.  Returns the
+    chosen signal ids in ascending order."""
+    err = np.asarray(err, dtype=np.float64)
+    assert 0 <= W <= err.size
+    order = np.argsort(-err, kind="stable")      # descending error, ties by index
+    return np.sort(order[:W]).astype(np.int32)
+
+
+def o_init_base(Y, ids):
+    """Starting orthobase for a set of signals (eq. (5)): Y_sub = U S V^T, Q_0 = U.
+    Returns (Q0, sv): Q0 atom-major (row k = left singular vector k, singular values in
+    descending order; the sign of a row is not determined) and the p singular values
+    (zeros appended when the set has fewer than p signals)."""
+    Y = np.asarray(Y, dtype=np.float64)
+    sub = Y[np.asarray(ids, dtype=np.int64)].T       # p x n
+    U, sv, _ = np.linalg.svd(sub, full_matrices=True)
+    p = sub.shape[0]
+    full = np.zeros(p)
+    full[:sv.size] = sv
+    return U.T.copy(), full
+
+
+def o_new_base(Y, ids, s0, R, Q0=None, round_f32=True):
+    """A new orthobase trained on a set of signals (Algorithm 2, steps 1 and 3): start
+    from eq. (5) unless Q0 is given, then R rounds of Algorithm 1 on those signals.
+    Returns (Q, sq): Q atom-major and the total squared error of every round's code."""
+    Y = np.asarray(Y, dtype=np.float64)
+    ids = np.asarray(ids, dtype=np.int64)
+    if Q0 is None:
+        Q0, _ = o_init_base(Y, ids)
+        if round_f32:
+            Q0 = Q0.astype(np.float32).astype(np.float64)
+    sub = Y[ids]
+    D, _codes, sq = o_train_rounds(sub, np.zeros(ids.size, np.int32), Q0[None], s0, R,
+                                   round_f32=round_f32)
+    return D[0], sq
 
 
 def rmse(sqerr_total, p, m):

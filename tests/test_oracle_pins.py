@@ -274,3 +274,84 @@ def test_rmse_definition_against_dense_reconstruction():
     fro = np.linalg.norm(pr.Y.T.astype(np.float64) - Dfull @ X)
     assert orc.rmse(err.sum(), p, pr.Y.shape[0]) == pytest.approx(fro / np.sqrt(pr.Y.size), rel=1e-12)
     assert (np.count_nonzero(X, axis=0) <= pr.cfg.s0).all()
+
+
+# ------------------------------------------- worst-W set, base initialisation, new base
+def test_worst_set_defining_inequalities_and_ties():
+    rng = np.random.default_rng(31)
+    err = rng.random(500)
+    err[[7, 70, 170, 270]] = 0.5                      # exact ties at a value inside the range
+    for W in (0, 1, 17, 250, 500):
+        ids = orc.o_worst(err, W)
+        assert ids.size == W and (np.diff(ids) > 0).all()
+        rest = np.setdiff1d(np.arange(500), ids)
+        if W and rest.size:
+            assert err[ids].min() >= err[rest].max()
+    # ties: with k of the four equal values to take, the k lowest indices are taken
+    above = int((err > 0.5).sum())
+    for k in (1, 2, 3):
+        ids = orc.o_worst(err, above + k)
+        tied = [i for i in (7, 70, 170, 270) if i in set(ids.tolist())]
+        assert tied == [7, 70, 170, 270][:k]
+    # brute force on a tiny case: exhaustive check of "no outsider beats an insider"
+    e = np.array([0.1, 0.9, 0.9, 0.3, 0.0, 0.9])
+    assert orc.o_worst(e, 2).tolist() == [1, 2]
+    assert orc.o_worst(e, 4).tolist() == [1, 2, 3, 5]
+
+
+def test_init_base_hand_worked_diagonal_and_rank_one():
+    # Y_sub = diag(3, 1) padded with a zero signal: U = I (up to sign), sv = (3, 1)
+    Y = np.array([[3.0, 0.0], [0.0, 1.0], [0.0, 0.0]])
+    Q0, sv = orc.o_init_base(Y, [0, 1, 2])
+    assert np.allclose(np.abs(Q0), np.eye(2), atol=1e-14) and np.allclose(sv, [3, 1])
+    # order of the rows follows the singular values, not the input order
+    Q0, sv = orc.o_init_base(Y, [1, 0])
+    assert np.allclose(sv, [3, 1]) and np.allclose(np.abs(Q0), np.eye(2), atol=1e-14)
+    # rank one: first atom = +-y/||y||, the rest an orthonormal completion
+    y = np.array([[1.0, 2.0, 2.0]])
+    Q0, sv = orc.o_init_base(np.repeat(y, 4, axis=0), [0, 1, 2, 3])
+    assert np.allclose(np.abs(Q0[0]), y[0] / 3.0, atol=1e-14)
+    assert np.allclose(sv, [6.0, 0, 0], atol=1e-12)
+    assert np.abs(Q0 @ Q0.T - np.eye(3)).max() < 1e-12
+
+
+def test_init_base_diagonalises_gram_and_recovers_planted_factor():
+    rng = np.random.default_rng(32)
+    p, n = 16, 200
+    U = synth.random_onb(rng, p)
+    s = np.linspace(5.0, 0.5, p)                      # distinct, descending
+    W, _ = np.linalg.qr(rng.standard_normal((n, p)))
+    Ysub = (U * s) @ W.T                              # p x n with known SVD
+    Y = np.vstack([rng.standard_normal((50, p)), Ysub.T])   # the set sits at rows 50..249
+    ids = np.arange(50, 250)
+    Q0, sv = orc.o_init_base(Y, ids)
+    assert np.allclose(sv, s, rtol=1e-12)
+    assert np.abs(np.abs(Q0 @ U) - np.eye(p)).max() < 1e-10         # rows = +-columns of U, in order
+    # independent route: eigen-decomposition of the Gram matrix (routine the oracle does not call)
+    G = Ysub @ Ysub.T
+    lam, E = np.linalg.eigh(G)
+    assert np.allclose(lam[::-1], sv ** 2, rtol=1e-10)
+    assert np.abs(np.abs(Q0 @ E[:, ::-1]) - np.eye(p)).max() < 1e-8
+    assert np.abs(Q0 @ G @ Q0.T - np.diag(sv ** 2)).max() < 1e-10 * lam.max()
+    # fewer signals than dimensions: still a complete orthobase
+    Q0, sv = orc.o_init_base(Y, ids[:5])
+    assert np.abs(Q0 @ Q0.T - np.eye(p)).max() < 1e-12 and (sv[5:] == 0).all()
+
+
+def test_new_base_error_monotone_and_planted_fixed_point():
+    pr = synth.generate(synth.custom("nb", p=16, K=1, m=600, s0=3, snr_db=None), keep_fp64=True)
+    ids = np.arange(100, 500)
+    # eq. (5) start, then rounds: the error of the codes never increases
+    Q, sq = orc.o_new_base(pr.Y64, ids, 3, 6, round_f32=False)
+    assert np.abs(Q @ Q.T - np.eye(16)).max() < 1e-12
+    assert (np.diff(sq) <= 1e-12 * sq[0]).all()
+    # started at the planted orthobase of noiseless data, training stays there with zero error
+    Q, sq = orc.o_new_base(pr.Y64, ids, 3, 3, Q0=pr.D_planted64[0], round_f32=False)
+    assert np.abs(Q - pr.D_planted64[0]).max() < 1e-10 and sq.max() < 1e-20 * (pr.Y64[ids] ** 2).sum()
+    # the rounds are Algorithm 1 on the set alone: same as coding + update on the extracted signals
+    sub = pr.Y64[ids]
+    Q0, _ = orc.o_init_base(pr.Y64, ids)
+    blk, supp, coef, err, _ = orc.o_code(sub, Q0[None], 3)
+    Q1, _M = orc.o_update(sub, blk, supp, coef, Q0[None])
+    Qa, sqa = orc.o_new_base(pr.Y64, ids, 3, 1, round_f32=False)
+    assert np.abs(Qa - Q1[0]).max() < 1e-12 and abs(sqa[0] - err.sum()) <= 1e-12 * err.sum()
