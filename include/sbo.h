@@ -124,6 +124,40 @@ int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter,
                 int32_t* blk, int32_t* supp, float* coef, float* err,
                 double* sqerr_per_iter);
 
+/* Total squared representation error sum_i err[i] (numerator of the RMSE of Section 4;
+ * the stopping rule of Algorithm 2 compares it, or the number of orthobases, with a
+ * target on the host).  Fixed-order sum in double precision.
+ * in : err[m] (device)      out: out (device double[1]) */
+int sbo_sqerr(sbo_ctx* c, const float* err, int64_t m, double* out);
+
+/* The W worst represented signals (Algorithm 2, step 3, first half): the W largest
+ * err[i]; among equal values the lower signal index is taken first.  ids (device,
+ * int32[W]) receives the chosen signal indices in ascending order.  1 <= W <= m, else
+ * SBO_EINVAL.  NaN entries are ordered by their bit pattern (unspecified position). */
+int sbo_worst(sbo_ctx* c, const float* err, int64_t m, int64_t W, int32_t* ids);
+
+/* Starting orthobase for a set of signals (eq. (5)): Y_sub = U S V^T, Q_0 = U, computed as
+ * the eigenvectors of the set's Gram matrix sum_i y_i y_i^T.
+ * in : Y[m][p], ids[n] (device, signal indices; values outside [0, m) are clamped into it),
+ *      1 <= n <= m
+ * out: Q[p][p] atom-major, atom k = left singular vector of the k-th largest singular value
+ *      (sign not determined; directions of vanishing singular values are an arbitrary
+ *      orthonormal completion); sv[p] (device, may be NULL) = the singular values, descending.
+ * Uses the context's workspace (K may be anything; the set is treated as one block). */
+int sbo_init_base(sbo_ctx* c, const float* Y, int64_t m, const int32_t* ids, int64_t n,
+                  float* Q, float* sv);
+
+/* A new orthobase trained on a set of signals (Algorithm 2, steps 1 and 3): unless
+ * have_q0 != 0 start from sbo_init_base, then R rounds of Algorithm 1 on the set
+ * { x = Q^T y hard-thresholded to s0 entries; P = Y_sub X^T; Q = U V^T }.
+ * in : Y, ids[n] (as for sbo_init_base), R >= 0      in/out: Q[p][p] (input only if have_q0)
+ * out: rows ids[.] of supp[m][s0], coef[m][s0], err[m] receive the codes of the set's signals
+ *      in the last round (other rows are not touched; not written when R == 0);
+ *      sqerr_per_round (device double[R], may be NULL): total squared error of each round's codes. */
+int sbo_new_base(sbo_ctx* c, const float* Y, int64_t m, const int32_t* ids, int64_t n, int R,
+                 int have_q0, float* Q, int32_t* supp, float* coef, float* err,
+                 double* sqerr_per_round);
+
 /* Per-stage timing with HIP events on the context's stream.  enable != 0 makes
  * every later call record events around each stage it runs. */
 int sbo_set_timing(sbo_ctx* c, int enable);

@@ -13,8 +13,8 @@ SBO_OK, SBO_EINVAL, SBO_ENOMEM, SBO_EHIP = 0, -1, -2, -3
 STAGES = ("energy", "group", "select", "accum", "svd")
 
 EXPORTS = ("sbo_create", "sbo_destroy", "sbo_workspace_bytes", "sbo_code", "sbo_group",
-           "sbo_accumulate", "sbo_polar", "sbo_update", "sbo_train_rounds", "sbo_iterate", "sbo_set_timing",
-           "sbo_stage_ms", "sbo_strerror")
+           "sbo_accumulate", "sbo_polar", "sbo_update", "sbo_train_rounds", "sbo_iterate", "sbo_sqerr",
+           "sbo_worst", "sbo_init_base", "sbo_new_base", "sbo_set_timing", "sbo_stage_ms", "sbo_strerror")
 
 _lib = None
 
@@ -46,6 +46,10 @@ def lib() -> ctypes.CDLL:
     L.sbo_update.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp]
     L.sbo_train_rounds.argtypes = [vp, vp, i64, vp, vp, i32, vp, vp, vp]
     L.sbo_iterate.argtypes = [vp, vp, i64, vp, i32, vp, vp, vp, vp, vp]
+    L.sbo_sqerr.argtypes = [vp, vp, i64, vp]
+    L.sbo_worst.argtypes = [vp, vp, i64, i64, vp]
+    L.sbo_init_base.argtypes = [vp, vp, i64, vp, i64, vp, vp]
+    L.sbo_new_base.argtypes = [vp, vp, i64, vp, i64, i32, i32, vp, vp, vp, vp, vp]
     L.sbo_set_timing.argtypes = [vp, i32]
     L.sbo_stage_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     L.sbo_strerror.argtypes = [i32]
@@ -145,6 +149,30 @@ def sbo_iterate(ctx, Y, D, n_iter, blk, supp, coef, err, sqerr_per_iter=None) ->
                              int(n_iter), _ptr(blk, torch.int32), _ptr(supp, torch.int32),
                              _ptr(coef, torch.float32), _ptr(err, torch.float32),
                              _ptr(sqerr_per_iter, torch.float64, True)))
+
+
+def sbo_sqerr(ctx, err, out) -> None:
+    import torch
+    _check(lib().sbo_sqerr(ctx, _ptr(err, torch.float32), err.shape[0], _ptr(out, torch.float64)))
+
+
+def sbo_worst(ctx, err, W, ids) -> None:
+    import torch
+    _check(lib().sbo_worst(ctx, _ptr(err, torch.float32), err.shape[0], int(W), _ptr(ids, torch.int32)))
+
+
+def sbo_init_base(ctx, Y, ids, Q, sv=None) -> None:
+    import torch
+    _check(lib().sbo_init_base(ctx, _ptr(Y, torch.float32), Y.shape[0], _ptr(ids, torch.int32),
+                               ids.shape[0], _ptr(Q, torch.float32), _ptr(sv, torch.float32, True)))
+
+
+def sbo_new_base(ctx, Y, ids, R, have_q0, Q, supp, coef, err, sqerr_per_round=None) -> None:
+    import torch
+    _check(lib().sbo_new_base(ctx, _ptr(Y, torch.float32), Y.shape[0], _ptr(ids, torch.int32),
+                              ids.shape[0], int(R), 1 if have_q0 else 0, _ptr(Q, torch.float32),
+                              _ptr(supp, torch.int32), _ptr(coef, torch.float32),
+                              _ptr(err, torch.float32), _ptr(sqerr_per_round, torch.float64, True)))
 
 
 def sbo_set_timing(ctx, enable: bool) -> None:

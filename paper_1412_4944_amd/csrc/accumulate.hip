@@ -27,7 +27,8 @@ constexpr int kTallWaves = 8;                  // wavefronts per workgroup (one 
 constexpr int kPairs = 4;                      // signal pairs per step of a wavefront
 constexpr int kDepth = 6;                      // steps whose operands are in flight per wavefront
 
-template <int P, int S0>
+// GRAM: the A operand is y itself (S0 is not used): the piece's share of sum_i y_i y_i^T.
+template <int P, int S0, bool GRAM>
 __global__ __launch_bounds__(64 * kTallWaves) void accum_piece_kernel(
     const float* __restrict__ Y, int K, int piece, const int32_t* __restrict__ offsets,
     const int32_t* __restrict__ perm, const int32_t* __restrict__ supp,
@@ -96,16 +97,31 @@ __global__ __launch_bounds__(64 * kTallWaves) void accum_piece_kernel(
 #pragma unroll
             for (int nt = 0; nt < MT; ++nt) o.yv[u][nt] = Y[i * P + (MT > 1 ? nt * 32 + n : ncol)];
         }
+        if constexpr (!GRAM) {
 #pragma unroll
-        for (int e = 0; e < NI; ++e) {
-            const int64_t i = ids[min(G * SPS + e * SPI + sl_lane, cnt - 1)];
-            o.k[e] = supp[i * S0 + t_lane];
-            o.c[e] = coef[i * S0 + t_lane];
+            for (int e = 0; e < NI; ++e) {
+                const int64_t i = ids[min(G * SPS + e * SPI + sl_lane, cnt - 1)];
+                o.k[e] = supp[i * S0 + t_lane];
+                o.c[e] = coef[i * S0 + t_lane];
+            }
         }
     };
 
     float* xd = buf + wave * SPS * 64;         // dense x of the step's signals, one 64-float row each
     auto consume = [&](const Operands& o, int G) {
+        if constexpr (GRAM) {
+#pragma unroll
+            for (int u = 0; u < kPairs; ++u) {
+                const bool on = G * SPS + 2 * u + h < cnt;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < MT; ++nt)
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                            on ? o.yv[u][mt] : 0.f, o.yv[u][nt], acc[mt][nt], 0, 0, 0);
+            }
+            return;
+        }
         int k[NI];
 #pragma unroll
         for (int e = 0; e < NI; ++e) {
@@ -213,7 +229,7 @@ __global__ __launch_bounds__(64 * kTallWaves) void accum_piece_kernel(
 // the piece's partial matrix, so no cross-wave reduction is needed.
 constexpr int kWidePairs = 4;
 
-template <int S0>
+template <int S0, bool GRAM>
 __global__ __launch_bounds__(256) void accum_wide_kernel(const float* __restrict__ Y, int K,
                                                          int piece,
                                                          const int32_t* __restrict__ offsets,
@@ -269,23 +285,37 @@ __global__ __launch_bounds__(256) void accum_wide_kernel(const float* __restrict
             for (int nt = 0; nt < NTL; ++nt) yv[u][nt] = on ? Y[i[u] * P + nt * 32 + n] : 0.f;
             k[u] = -1;
             c[u] = 0.f;
-            if (on && n < S0) {
-                k[u] = supp[i[u] * S0 + n] - atom0;
-                c[u] = coef[i[u] * S0 + n];
+            if constexpr (!GRAM) {
+                if (on && n < S0) {
+                    k[u] = supp[i[u] * S0 + n] - atom0;
+                    c[u] = coef[i[u] * S0 + n];
+                }
+                if ((unsigned)k[u] >= 64u) k[u] = -1;      // another wavefront's atom, or invalid
             }
-            if ((unsigned)k[u] >= 64u) k[u] = -1;          // another wavefront's atom, or invalid
         }
-#pragma unroll
-        for (int u = 0; u < kWidePairs; ++u)
-            if (k[u] >= 0) xd[u * 128 + k[u]] = c[u];
         float a[kWidePairs][2];
+        if constexpr (GRAM) {                              // rows atom0.. of sum_i y_i y_i^T
 #pragma unroll
-        for (int u = 0; u < kWidePairs; ++u)
+            for (int u = 0; u < kWidePairs; ++u)
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) a[u][mt] = xd[u * 128 + mt * 32 + n];
+                for (int mt = 0; mt < 2; ++mt) {
+                    a[u][mt] = 0.f;
 #pragma unroll
-        for (int u = 0; u < kWidePairs; ++u)
-            if (k[u] >= 0) xd[u * 128 + k[u]] = 0.f;
+                    for (int w = 0; w < 4; ++w)
+                        a[u][mt] = wave == w ? yv[u][2 * w + mt] : a[u][mt];
+                }
+        } else {
+#pragma unroll
+            for (int u = 0; u < kWidePairs; ++u)
+                if (k[u] >= 0) xd[u * 128 + k[u]] = c[u];
+#pragma unroll
+            for (int u = 0; u < kWidePairs; ++u)
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) a[u][mt] = xd[u * 128 + mt * 32 + n];
+#pragma unroll
+            for (int u = 0; u < kWidePairs; ++u)
+                if (k[u] >= 0) xd[u * 128 + k[u]] = 0.f;
+        }
 #pragma unroll
         for (int u = 0; u < kWidePairs; ++u)
 #pragma unroll
@@ -340,12 +370,12 @@ hipError_t launch_ps(int K, const float* Y, int64_t m, const int32_t* supp, cons
     static bool raised = false;
     if (!raised) {
         hipError_t e =
-            hipFuncSetAttribute(reinterpret_cast<const void*>(&accum_piece_kernel<P, S0>),
+            hipFuncSetAttribute(reinterpret_cast<const void*>(&accum_piece_kernel<P, S0, false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL((accum_piece_kernel<P, S0>), dim3(max_pieces), dim3(64 * kTallWaves), lds1, st,
+    hipLaunchKernelGGL((accum_piece_kernel<P, S0, false>), dim3(max_pieces), dim3(64 * kTallWaves), lds1, st,
                        Y, K, piece, ws.offsets, ws.perm, supp, coef, ws.partial);
     const size_t lds2 = (K + 1 + 16) * sizeof(int);
     hipLaunchKernelGGL((accum_reduce_kernel<P>), dim3(K, (P * P + 255) / 256), dim3(256), lds2, st,
@@ -360,7 +390,7 @@ hipError_t launch_wide_s(int K, const float* Y, int64_t m, const int32_t* supp, 
     const int piece = accum_piece(m, K, P);
     const int max_pieces = accum_max_pieces(m, K, P);
     const size_t lds1 = (K + 1 + 16) * sizeof(int) + (size_t)4 * kWidePairs * 2 * 64 * sizeof(float);
-    hipLaunchKernelGGL((accum_wide_kernel<S0>), dim3(max_pieces), dim3(256), lds1, st, Y, K, piece,
+    hipLaunchKernelGGL((accum_wide_kernel<S0, false>), dim3(max_pieces), dim3(256), lds1, st, Y, K, piece,
                        ws.offsets, ws.perm, supp, coef, ws.partial);
     const size_t lds2 = (K + 1 + 16) * sizeof(int);
     hipLaunchKernelGGL((accum_reduce_kernel<P>), dim3(K, (P * P + 255) / 256), dim3(256), lds2, st,
@@ -395,7 +425,52 @@ hipError_t launch_p(int K, int s0, const float* Y, int64_t m, const int32_t* sup
     }
 }
 
+// G = sum over the n signals listed in ws.perm of y y^T (one block: ws.offsets = {0, n}).
+template <int P>
+hipError_t launch_gram_p(const float* Y, int64_t n, const Workspace& ws, float* G, hipStream_t st) {
+    constexpr int MT = P >= 32 ? P / 32 : 1;
+    const int piece = accum_tall_piece(n, 1);
+    const int max_pieces = (int)((n + piece - 1) / piece) + 1;
+    const size_t head = ((size_t)(1 + 1 + 16) + 3) & ~(size_t)3;
+    const size_t walk = (size_t)kTallWaves * 2 * kPairs * 64;
+    const size_t xch = (size_t)(kTallWaves / 2) * MT * MT * 16 * 64;
+    const size_t lds1 = (head + kTallMaxPiece + (walk > xch ? walk : xch)) * 4;
+    static bool raised = false;
+    if (!raised) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&accum_piece_kernel<P, 1, true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    hipLaunchKernelGGL((accum_piece_kernel<P, 1, true>), dim3(max_pieces), dim3(64 * kTallWaves), lds1, st,
+                       Y, 1, piece, ws.offsets, ws.perm, nullptr, nullptr, ws.partial);
+    hipLaunchKernelGGL((accum_reduce_kernel<P>), dim3(1, (P * P + 255) / 256), dim3(256),
+                       (1 + 1 + 16) * sizeof(int), st, 1, piece, ws.offsets, ws.partial, G);
+    return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t launch_gram(int p, const float* Y, int64_t n, const Workspace& ws, float* G,
+                       hipStream_t st) {
+    switch (p) {
+        case 16: return launch_gram_p<16>(Y, n, ws, G, st);
+        case 32: return launch_gram_p<32>(Y, n, ws, G, st);
+        case 64: return launch_gram_p<64>(Y, n, ws, G, st);
+        case 256: {
+            constexpr int P = 256;
+            const int piece = accum_piece(n, 1, P);
+            const int max_pieces = (int)((n + piece - 1) / piece) + 1;
+            const size_t lds1 = (1 + 1 + 16) * sizeof(int) + (size_t)4 * kWidePairs * 2 * 64 * sizeof(float);
+            hipLaunchKernelGGL((accum_wide_kernel<1, true>), dim3(max_pieces), dim3(256), lds1, st, Y, 1,
+                               piece, ws.offsets, ws.perm, nullptr, nullptr, ws.partial);
+            hipLaunchKernelGGL((accum_reduce_kernel<P>), dim3(1, (P * P + 255) / 256), dim3(256),
+                               (1 + 1 + 16) * sizeof(int), st, 1, piece, ws.offsets, ws.partial, G);
+            return hipGetLastError();
+        }
+        default: return hipErrorInvalidValue;
+    }
+}
 
 // M[j] = sum of the piece results of block j in ws.partial, in piece order.
 hipError_t launch_accum_reduce(int p, int K, int64_t m, const Workspace& ws, float* M,

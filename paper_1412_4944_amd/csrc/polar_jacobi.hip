@@ -25,7 +25,8 @@ template <int P, int TPP>
 __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __restrict__ M,
                                                              const int32_t* __restrict__ counts,
                                                              float* __restrict__ D,
-                                                             float* __restrict__ Vstate, int warm) {
+                                                             float* __restrict__ Vstate, int warm,
+                                                             float* __restrict__ eig_sv) {
     constexpr int LD = P + 4;
     constexpr int NT = (P / 2) * TPP;          // threads: TPP lanes per column pair
     constexpr int RPT = P / TPP;               // contiguous rows per lane in a rotation
@@ -232,6 +233,25 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
         for (int e = tid; e < P * P; e += NT) Vj[e] = V[(e / P) * LD + (e % P)];
     }
 
+    // Eigen mode (P_j symmetric positive semidefinite, e.g. a Gram matrix sum y y^T): the
+    // columns of V are its eigenvectors and the column norms of A its eigenvalues.  Output:
+    // atom k = eigenvector of the k-th largest eigenvalue (equal values: lower column first),
+    // eig_sv[k] = its square root, i.e. the k-th singular value of the underlying signal matrix.
+    if (eig_sv != nullptr) {
+        if (tid < P) {
+            int rank = 0;
+            for (int c = 0; c < P; ++c) rank += sig[c] > sig[tid] || (sig[c] == sig[tid] && c < tid);
+            isbad[tid] = rank;
+            // A_c = P_j V_c holds exactly (both received the same rotations), so the drift of
+            // the column norms over many rotations cancels in |A_c| / |V_c|
+            eig_sv[(int64_t)j * P + rank] = scale > 0.f ? sqrtf(sig[tid] * vec[tid] / scale) : 0.f;
+        }
+        __syncthreads();
+        float* Dj = D + (int64_t)j * P * P;
+        for (int e = tid; e < P * P; e += NT) Dj[isbad[e / P] * P + (e % P)] = V[(e / P) * LD + (e % P)];
+        return;                                // uniform
+    }
+
     if (shared_i[0] > 0) {                     // uniform
         for (int c = 0; c < P; ++c) {
             if (!isbad[c]) continue;           // uniform
@@ -306,24 +326,24 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
 
 template <int TPP>
 hipError_t launch_tpp(int p, int K, const float* M, const int32_t* counts, float* D, float* vstate,
-                      int warm, hipStream_t st) {
+                      int warm, float* eig_sv, hipStream_t st) {
     switch (p) {
-        case 16: hipLaunchKernelGGL((polar_kernel<16, TPP>), dim3(K), dim3(8 * TPP), 0, st, M, counts, D, vstate, warm); break;
-        case 32: hipLaunchKernelGGL((polar_kernel<32, TPP>), dim3(K), dim3(16 * TPP), 0, st, M, counts, D, vstate, warm); break;
-        case 64: hipLaunchKernelGGL((polar_kernel<64, TPP>), dim3(K), dim3(32 * TPP), 0, st, M, counts, D, vstate, warm); break;
+        case 16: hipLaunchKernelGGL((polar_kernel<16, TPP>), dim3(K), dim3(8 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv); break;
+        case 32: hipLaunchKernelGGL((polar_kernel<32, TPP>), dim3(K), dim3(16 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv); break;
+        case 64: hipLaunchKernelGGL((polar_kernel<64, TPP>), dim3(K), dim3(32 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
 hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
-                        float* vstate, int warm, float* jac_a, hipStream_t st) {
-    if (p == 256) return launch_polar_wide(K, M, counts, D, vstate, warm, jac_a, st);
+                        float* vstate, int warm, float* jac_a, float* eig_sv, hipStream_t st) {
+    if (p == 256) return launch_polar_wide(K, M, counts, D, vstate, warm, jac_a, eig_sv, st);
     int tpp = 16;
     if (const char* e = getenv("SBO_POLAR_TPP")) tpp = atoi(e);   // tuning override
-    if (tpp == 4) return launch_tpp<4>(p, K, M, counts, D, vstate, warm, st);
-    if (tpp == 8) return launch_tpp<8>(p, K, M, counts, D, vstate, warm, st);
-    return launch_tpp<16>(p, K, M, counts, D, vstate, warm, st);
+    if (tpp == 4) return launch_tpp<4>(p, K, M, counts, D, vstate, warm, eig_sv, st);
+    if (tpp == 8) return launch_tpp<8>(p, K, M, counts, D, vstate, warm, eig_sv, st);
+    return launch_tpp<16>(p, K, M, counts, D, vstate, warm, eig_sv, st);
 }
 
 }  // namespace sbo

@@ -290,9 +290,11 @@ __global__ __launch_bounds__(256) void wide_replay_kernel(const int32_t* __restr
         for (int c = lane; c < P; c += 64) V[c * P + row0 + rr] = rows[rr][c];
 }
 
-__global__ __launch_bounds__(1024) void wide_finish_kernel(const int32_t* __restrict__ counts,
+__global__ __launch_bounds__(1024) void wide_finish_kernel(const float* __restrict__ M,
+                                                           const int32_t* __restrict__ counts,
                                                            float* __restrict__ D, float* Vst,
-                                                           float* scratch, int K) {
+                                                           float* scratch, int K,
+                                                           float* __restrict__ eig_sv) {
     constexpr int NT = 1024;
     __shared__ float sig[P];
     __shared__ float coefs[P];
@@ -337,6 +339,32 @@ __global__ __launch_bounds__(1024) void wide_finish_kernel(const int32_t* __rest
     }
     __threadfence_block();
     __syncthreads();
+
+    // Eigen mode (see polar_kernel): atoms = eigenvectors (columns of V) by descending
+    // eigenvalue, eig_sv = square roots of the eigenvalues.  The scale the Jacobi kernel
+    // applied (1 / max|entry| of P_j) is recomputed here.
+    if (eig_sv != nullptr) {
+        const float* Mj = M + (int64_t)j * P * P;
+        float mx = 0.f;
+        for (int e = tid; e < P * P; e += NT) mx = fmaxf(mx, fabsf(Mj[e]));
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+        if ((tid & 63) == 0) coefs[tid >> 6] = mx;
+        __syncthreads();
+        mx = 0.f;
+        for (int w = 0; w < NT / 64; ++w) mx = fmaxf(mx, coefs[w]);
+        __syncthreads();
+        if (tid < P) {
+            int rank = 0;
+            for (int c = 0; c < P; ++c) rank += sig[c] > sig[tid] || (sig[c] == sig[tid] && c < tid);
+            isbad[tid] = rank;
+            eig_sv[(int64_t)j * P + rank] = sqrtf(sig[tid] * vec[tid] * mx);   // |A_c| / |V_c|, rescaled
+        }
+        __syncthreads();
+        float* Dj = D + (int64_t)j * P * P;
+        for (int e = tid; e < P * P; e += NT) Dj[isbad[e / P] * P + (e % P)] = V[e];
+        return;                                // uniform
+    }
 
     if (shared_i[0] > 0) {                     // uniform: complete the vanished columns
         for (int c = 0; c < P; ++c) {
@@ -413,7 +441,7 @@ size_t polar_wide_scratch_bytes(int K) {
 }
 
 hipError_t launch_polar_wide(int K, const float* M, const int32_t* counts, float* D, float* vstate,
-                             int warm, float* jac_a, hipStream_t st) {
+                             int warm, float* jac_a, float* eig_sv, hipStream_t st) {
     if (vstate == nullptr || jac_a == nullptr) return hipErrorInvalidValue;
     const size_t lds = (size_t)P * LDA * sizeof(float);
     static bool raised = false;
@@ -426,7 +454,8 @@ hipError_t launch_polar_wide(int K, const float* M, const int32_t* counts, float
     hipLaunchKernelGGL(wide_jacobi_kernel, dim3(K), dim3(1024), lds, st, M, counts, vstate, warm, jac_a, K);
     hipLaunchKernelGGL(wide_replay_kernel, dim3(K, P / (4 * kReplayRows)), dim3(256), 0, st, counts,
                        vstate, warm, jac_a, K);
-    hipLaunchKernelGGL(wide_finish_kernel, dim3(K), dim3(1024), 0, st, counts, D, vstate, jac_a, K);
+    hipLaunchKernelGGL(wide_finish_kernel, dim3(K), dim3(1024), 0, st, M, counts, D, vstate, jac_a, K,
+                       eig_sv);
     return hipGetLastError();
 }
 

@@ -36,6 +36,11 @@ size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char
     w.M = (float*)take((size_t)K * p * p * 4);
     w.vstate = (float*)take((size_t)K * p * p * 4);
     w.jac_a = (float*)take(p > 64 ? polar_wide_scratch_bytes(K) : 0);
+    const size_t sel_chunks = (size_t)((m_max + kSelChunk - 1) / kSelChunk);
+    w.sel_hist = (int32_t*)take((size_t)4 * 256 * 4);
+    w.sel_state = (int32_t*)take((size_t)4 * 2 * 4);
+    w.sel_cnt = (int32_t*)take(sel_chunks * 2 * 4);
+    w.sel_base = (int32_t*)take(sel_chunks * 2 * 4);
     w.sq_partial = (double*)take((size_t)kSqBlocks * 8);
     w.bytes = off;
     if (ws) *ws = w;
@@ -127,7 +132,7 @@ static int run_update_grouped(sbo_ctx* c, const float* Y, int64_t m, const int32
     }
     {
         StageTimer t(c, SBO_STAGE_SVD);
-        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, vstate, warm, c->ws.jac_a, c->stream));
+        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, vstate, warm, c->ws.jac_a, nullptr, c->stream));
     }
     return SBO_OK;
 }
@@ -228,7 +233,7 @@ int sbo_polar(sbo_ctx* c, const float* M, const int32_t* counts, float* D) {
     c->n_spans = 0;
     StageTimer t(c, SBO_STAGE_SVD);
     SBO_HIP(launch_polar(c->p, c->K, M, counts, D, c->p > 64 ? c->ws.vstate : nullptr, 0, c->ws.jac_a,
-                         c->stream));
+                         nullptr, c->stream));
     return SBO_OK;
 }
 
@@ -263,7 +268,7 @@ int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter, int
         if (!fused) {
             rc = run_code(c, Y, m, D, blk, supp, coef, err);
             if (rc) return rc;
-            if (sqerr_per_iter) SBO_HIP(launch_sqerr(err, m, c->ws, sqerr_per_iter + it, c->stream));
+            if (sqerr_per_iter) SBO_HIP(launch_sqerr(err, nullptr, m, c->ws, sqerr_per_iter + it, c->stream));
             rc = run_update_grouped(c, Y, m, supp, coef, D, c->ws.vstate, warm);  // grouping reused
             if (rc) return rc;
             continue;
@@ -279,7 +284,7 @@ int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter, int
             StageTimer t(c, SBO_STAGE_SELECT);  // includes the per-piece accumulation
             SBO_HIP(launch_select_accum(c->p, c->K, c->s0, Y, m, D, c->ws, supp, coef, err, c->stream));
         }
-        if (sqerr_per_iter) SBO_HIP(launch_sqerr(err, m, c->ws, sqerr_per_iter + it, c->stream));
+        if (sqerr_per_iter) SBO_HIP(launch_sqerr(err, nullptr, m, c->ws, sqerr_per_iter + it, c->stream));
         {
             StageTimer t(c, SBO_STAGE_ACCUM);   // only the sum over pieces remains
             SBO_HIP(launch_accum_reduce(c->p, c->K, m, c->ws, c->ws.M, c->stream));
@@ -287,7 +292,7 @@ int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter, int
         {
             StageTimer t(c, SBO_STAGE_SVD);
             SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws.vstate, warm,
-                                 c->ws.jac_a, c->stream));
+                                 c->ws.jac_a, nullptr, c->stream));
         }
     }
     return SBO_OK;
@@ -321,7 +326,72 @@ int sbo_train_rounds(sbo_ctx* c, const float* Y, int64_t m, const int32_t* blk, 
         }
         StageTimer t(c, SBO_STAGE_SVD);
         SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws.vstate, warm, c->ws.jac_a,
-                             c->stream));
+                             nullptr, c->stream));
+    }
+    return SBO_OK;
+}
+
+int sbo_sqerr(sbo_ctx* c, const float* err, int64_t m, double* out) {
+    int rc = check_call(c, m);
+    if (rc) return rc;
+    if (!err || !out) return SBO_EINVAL;
+    SBO_HIP(launch_sqerr(err, nullptr, m, c->ws, out, c->stream));
+    return SBO_OK;
+}
+
+int sbo_worst(sbo_ctx* c, const float* err, int64_t m, int64_t W, int32_t* ids) {
+    int rc = check_call(c, m);
+    if (rc) return rc;
+    if (!err || !ids || W < 1 || W > m) return SBO_EINVAL;
+    SBO_HIP(launch_worst(err, m, W, c->ws, ids, c->stream));
+    return SBO_OK;
+}
+
+// Gram matrix of the set -> its eigenvectors by descending eigenvalue (ws.perm etc. hold the set).
+static int run_init_base(sbo_ctx* c, const float* Y, int64_t n, float* Q, float* sv) {
+    SBO_HIP(launch_gram(c->p, Y, n, c->ws, c->ws.M, c->stream));
+    SBO_HIP(launch_polar(c->p, 1, c->ws.M, nullptr, Q, c->ws.vstate, 0, c->ws.jac_a,
+                         sv ? sv : c->ws.energy, c->stream));   // energy[m_max >= p] as a sink
+    return SBO_OK;
+}
+
+int sbo_init_base(sbo_ctx* c, const float* Y, int64_t m, const int32_t* ids, int64_t n, float* Q,
+                  float* sv) {
+    int rc = check_call(c, m);
+    if (rc) return rc;
+    if (!Y || !ids || !Q || n < 1 || n > m) return SBO_EINVAL;
+    if (c->m_max < c->p) return SBO_EINVAL;    // the workspace doubles as scratch of p floats
+    c->n_spans = 0;
+    SBO_HIP(launch_single_block(ids, n, m, c->ws, c->stream));
+    return run_init_base(c, Y, n, Q, sv);
+}
+
+int sbo_new_base(sbo_ctx* c, const float* Y, int64_t m, const int32_t* ids, int64_t n, int R,
+                 int have_q0, float* Q, int32_t* supp, float* coef, float* err,
+                 double* sqerr_per_round) {
+    int rc = check_call(c, m);
+    if (rc) return rc;
+    if (!Y || !ids || !Q || !supp || !coef || !err || n < 1 || n > m || R < 0) return SBO_EINVAL;
+    if (c->m_max < c->p) return SBO_EINVAL;
+    c->n_spans = 0;
+    SBO_HIP(launch_single_block(ids, n, m, c->ws, c->stream));
+    if (!have_q0) {
+        rc = run_init_base(c, Y, n, Q, nullptr);
+        if (rc) return rc;
+    }
+    for (int r = 0; r < R; ++r) {
+        const int warm = r % 8 != 0;
+        if (c->p <= 64) {
+            SBO_HIP(launch_select_accum(c->p, 1, c->s0, Y, n, Q, c->ws, supp, coef, err, c->stream));
+            SBO_HIP(launch_accum_reduce(c->p, 1, n, c->ws, c->ws.M, c->stream));
+        } else {
+            SBO_HIP(launch_select(c->p, 1, c->s0, Y, n, Q, c->ws, supp, coef, err, c->stream));
+            SBO_HIP(launch_accumulate(c->p, 1, c->s0, Y, n, supp, coef, c->ws, c->ws.M, c->stream));
+        }
+        if (sqerr_per_round)
+            SBO_HIP(launch_sqerr(err, c->ws.perm, n, c->ws, sqerr_per_round + r, c->stream));
+        SBO_HIP(launch_polar(c->p, 1, c->ws.M, c->ws.counts, Q, c->ws.vstate, warm, c->ws.jac_a,
+                             nullptr, c->stream));
     }
     return SBO_OK;
 }

@@ -82,11 +82,17 @@ struct Workspace {
     float* M;              // [K][p][p]
     float* vstate;         // [K][p][p] V of the previous decomposition (sbo_iterate only)
     float* jac_a;          // p > 64 only: scratch of the wide Jacobi (polar_wide_scratch_bytes)
+    // worst-W selection
+    int32_t* sel_hist;     // [4][256] digit histograms of the radix select
+    int32_t* sel_state;    // [4][2] (key prefix, entries still to take) after each pass
+    int32_t* sel_cnt;      // [ceil(m_max / kSelChunk)][2] entries above / equal to the threshold
+    int32_t* sel_base;     // same shape: exclusive sums of sel_cnt over the chunks
     // iterate
     double* sq_partial;    // [kSqBlocks]
     size_t bytes;
 };
 constexpr int kSqBlocks = 256;
+constexpr int kSelChunk = 2048;              // signals per workgroup in the worst-W compaction
 
 size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char* base);
 
@@ -137,16 +143,32 @@ hipError_t launch_select_accum(int p, int K, int s0, const float* Y, int64_t m, 
 hipError_t launch_accum_reduce(int p, int K, int64_t m, const Workspace& ws, float* M,
                                hipStream_t st);
 
+// eig_sv != nullptr switches to eigen mode: M[j] symmetric positive semidefinite, D[j] receives
+// its eigenvectors as atoms by descending eigenvalue and eig_sv[j][p] the square roots of the
+// eigenvalues.
 hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
-                        float* vstate, int warm, float* jac_a, hipStream_t st);
+                        float* vstate, int warm, float* jac_a, float* eig_sv, hipStream_t st);
 
 // p = 256 variant of launch_polar (polar_wide.hip) and the size of its scratch (working
 // copy of P_j, rotation log, sweep counts).
 size_t polar_wide_scratch_bytes(int K);
 hipError_t launch_polar_wide(int K, const float* M, const int32_t* counts, float* D, float* vstate,
-                             int warm, float* jac_a, hipStream_t st);
+                             int warm, float* jac_a, float* eig_sv, hipStream_t st);
 
-hipError_t launch_sqerr(const float* err, int64_t m, const Workspace& ws, double* out,
+// ids == nullptr: sum over all m signals; otherwise over the m listed ones.
+hipError_t launch_sqerr(const float* err, const int32_t* ids, int64_t m, const Workspace& ws,
+                        double* out, hipStream_t st);
+
+// A signal set as one block: ws.perm = ids clamped to [0, m), ws.counts = {n}, ws.offsets = {0, n}.
+hipError_t launch_single_block(const int32_t* ids, int64_t n, int64_t m, const Workspace& ws,
+                               hipStream_t st);
+
+// G = sum over the n signals listed in ws.perm of y y^T (ws.offsets = {0, n}).
+hipError_t launch_gram(int p, const float* Y, int64_t n, const Workspace& ws, float* G,
+                       hipStream_t st);
+
+// ids[0..W) = the W signals with the largest err (ties: lower index), ascending.
+hipError_t launch_worst(const float* err, int64_t m, int64_t W, const Workspace& ws, int32_t* ids,
                         hipStream_t st);
 
 }  // namespace sbo

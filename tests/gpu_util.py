@@ -95,6 +95,40 @@ class Sbo:
         self.torch.cuda.synchronize()
         return Dd.cpu().numpy(), supp.cpu().numpy(), coef.cpu().numpy(), err.cpu().numpy()
 
+    def sqerr(self, err):
+        out = self.torch.zeros((1,), dtype=self.torch.float64, device=self.dev)
+        sbo.sbo_sqerr(self.ctx, self.dev_f32(err), out)
+        self.torch.cuda.synchronize()
+        return float(out.item())
+
+    def worst(self, err, W):
+        ids = self.torch.full((W,), -7, dtype=self.torch.int32, device=self.dev)
+        sbo.sbo_worst(self.ctx, self.dev_f32(err), W, ids)
+        self.torch.cuda.synchronize()
+        return ids.cpu().numpy()
+
+    def init_base(self, Y, ids):
+        t = self.torch
+        Q = t.full((self.p, self.p), float("nan"), dtype=t.float32, device=self.dev)
+        sv = t.full((self.p,), float("nan"), dtype=t.float32, device=self.dev)
+        sbo.sbo_init_base(self.ctx, self.dev_f32(Y), self.dev_i32(ids), Q, sv)
+        t.cuda.synchronize()
+        return Q.cpu().numpy(), sv.cpu().numpy()
+
+    def new_base(self, Y, ids, R, Q0=None):
+        """Returns Q, the code arrays (rows outside the set keep their fill values) and the
+        per-round squared errors."""
+        t = self.torch
+        m = Y.shape[0]
+        Q = self.dev_f32(Q0) if Q0 is not None else t.full((self.p, self.p), float("nan"),
+                                                           dtype=t.float32, device=self.dev)
+        _b, supp, coef, err = self.outputs(m)
+        sq = t.zeros((max(R, 1),), dtype=t.float64, device=self.dev)
+        sbo.sbo_new_base(self.ctx, self.dev_f32(Y), self.dev_i32(ids), R, Q0 is not None, Q, supp, coef,
+                         err, sq)
+        t.cuda.synchronize()
+        return Q.cpu().numpy(), supp.cpu().numpy(), coef.cpu().numpy(), err.cpu().numpy(), sq.cpu().numpy()[:R]
+
     def iterate(self, Y, D, n_iter):
         t = self.torch
         Yd, Dd = self.dev_f32(Y), self.dev_f32(D)
