@@ -62,6 +62,8 @@ def main() -> int:
     ap.add_argument("--workload", default="headline")
     ap.add_argument("--cpu-sample", type=int, default=262144)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-next", action="store_true",
+                    help="skip the (untimed-region) measurement of worst-W / base initialisation / new base")
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run one plain 256 MiB device copy (a dispatch of known HBM traffic, used "
                          "to scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -115,6 +117,36 @@ def main() -> int:
     t1 = time.perf_counter()
     stage_sum = sbo.sbo_stage_ms(ctx)           # summed over the K iterations
     last_sq = float(sq[args.steps - 1].item())
+
+    # The rows beyond one iteration (outside the timed region): worst-W set, eq. (5)
+    # initialisation and a new orthobase trained with R = 6 rounds, on the same workload.
+    next_rows = None
+    if not args.no_next:
+        W, R = min(4096, m), 6
+        ids = torch.empty(W, dtype=torch.int32, device=dev)
+        Qn = torch.empty((p, p), dtype=torch.float32, device=dev)
+        sqr = torch.zeros(R, dtype=torch.float64, device=dev)
+        s2, c2, e2 = supp.clone(), coef.clone(), err.clone()
+
+        def best_ms(fn, reps=3):
+            best = float("inf")
+            for _ in range(reps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                fn()
+                b.record()
+                torch.cuda.synchronize()
+                best = min(best, a.elapsed_time(b))
+            return best
+
+        sbo.sbo_set_timing(ctx, False)
+        next_rows = {
+            "W": W, "R": R,
+            "worst_ms": best_ms(lambda: sbo.sbo_worst(ctx, err, W, ids)),
+            "init_base_ms": best_ms(lambda: sbo.sbo_init_base(ctx, Y, ids, Qn)),
+            "new_base_ms": best_ms(lambda: sbo.sbo_new_base(ctx, Y, ids, R, False, Qn, s2, c2, e2, sqr)),
+        }
+        del s2, c2, e2
     sbo.sbo_destroy(ctx)
 
     total_s = t1 - t0
@@ -158,6 +190,8 @@ def main() -> int:
                        "frac": upd_bytes / t_upd / 1e9 / PEAK_HBM_GBS},
         "rmse_first_last": [float(np.sqrt(first_sq / (p * m))), float(np.sqrt(last_sq / (p * m)))],
     }
+    if next_rows is not None:
+        out["next_rows"] = next_rows
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(pr, min(args.cpu_sample, m))
     print(json.dumps(out))

@@ -17,7 +17,8 @@ nuclear-norm maximality, Procrustes decrease, fixed point, monotone iteration an
 monotone frozen-assignment rounds; worst-W set against its defining inequalities;
 base initialisation against the eigen-decomposition of the Gram matrix, a rank-one
 case, a hand-worked diagonal case and a planted factorisation; new-base training
-against monotone error and the planted fixed point.
+against monotone error and the planted fixed point; the whole of Algorithm 2 against
+its stopping conditions, a monotone RMSE history and a step-by-step recomposition.
 No function here is "parity unpinned".
 """
 from __future__ import annotations
@@ -206,6 +207,33 @@ def o_new_base(Y, ids, s0, R, Q0=None, round_f32=True):
     D, _codes, sq = o_train_rounds(sub, np.zeros(ids.size, np.int32), Q0[None], s0, R,
                                    round_f32=round_f32)
     return D[0], sq
+
+
+def o_learn(Y, s0, init_sets, R, W, K_max, target_rmse=0.0, round_f32=True):
+    """Algorithm 2 as a whole.  init_sets: K0 index arrays, the randomly chosen signals each
+    initial orthobase is trained on (the random draw is the caller's).  Steps: train the K0
+    initial orthobases (eq. (5) start + R rounds each); represent every signal; then, while
+    fewer than K_max orthobases exist and the RMSE is above target_rmse: train a new
+    orthobase on the W worst represented signals and append it; represent every signal;
+    train every orthobase over its own signals for R rounds; evaluate the stopping rule.
+    The error used by the stopping rule and by the next worst-W set is that of the codes of
+    the last training round (taken before that round's update, which can only lower it).
+    Returns (D, blk, rmse_history): rmse_history[0] after the initial representation, then
+    one entry per iteration."""
+    Y = np.asarray(Y, dtype=np.float64)
+    m, p = Y.shape
+    cast = (lambda a: a.astype(np.float32).astype(np.float64)) if round_f32 else (lambda a: a)
+    D = np.stack([cast(o_new_base(Y, ids, s0, R, round_f32=round_f32)[0]) for ids in init_sets])
+    blk, _supp, _coef, err, _E = o_code(Y, D, s0)
+    hist = [rmse(err.sum(), p, m)]
+    while D.shape[0] < K_max and hist[-1] > target_rmse:
+        ids = o_worst(err.astype(np.float32) if round_f32 else err, W)
+        Qn = cast(o_new_base(Y, ids, s0, R, round_f32=round_f32)[0])
+        D = np.concatenate([D, Qn[None]], axis=0)
+        blk = o_code(Y, D, s0)[0]
+        D, (_supp, _coef, err), _sq = o_train_rounds(Y, blk, D, s0, R, round_f32=round_f32)
+        hist.append(rmse(err.sum(), p, m))
+    return D, blk, np.array(hist)
 
 
 def rmse(sqerr_total, p, m):

@@ -355,3 +355,31 @@ def test_new_base_error_monotone_and_planted_fixed_point():
     Q1, _M = orc.o_update(sub, blk, supp, coef, Q0[None])
     Qa, sqa = orc.o_new_base(pr.Y64, ids, 3, 1, round_f32=False)
     assert np.abs(Qa - Q1[0]).max() < 1e-12 and abs(sqa[0] - err.sum()) <= 1e-12 * err.sum()
+
+
+def test_learn_history_monotone_stops_and_matches_manual_steps():
+    pr = synth.generate(synth.custom("lrn", p=16, K=3, m=900, s0=3, snr_db=25.0), keep_fp64=True)
+    rng = np.random.default_rng(51)
+    sets = [np.sort(rng.choice(900, 120, replace=False)) for _ in range(2)]
+    D, blk, hist = orc.o_learn(pr.Y64, 3, sets, R=2, W=150, K_max=5, round_f32=False)
+    assert D.shape == (5, 16, 16) and hist.size == 4            # K0 = 2, three growth iterations
+    assert (np.diff(hist) <= 1e-12).all(), hist                 # the RMSE history never increases
+    for j in range(5):
+        assert np.abs(D[j] @ D[j].T - np.eye(16)).max() < 1e-12
+    assert blk.min() >= 0 and blk.max() < 5
+    # stopping rule: a target already met after the initial representation stops at once,
+    # a target met after the first iteration stops there
+    D0, _b, h0 = orc.o_learn(pr.Y64, 3, sets, R=2, W=150, K_max=5, target_rmse=hist[0] * 1.01, round_f32=False)
+    assert D0.shape[0] == 2 and h0.size == 1 and h0[0] == hist[0]
+    D1, _b, h1 = orc.o_learn(pr.Y64, 3, sets, R=2, W=150, K_max=5, target_rmse=(hist[1] + hist[2]) / 2,
+                             round_f32=False)
+    assert D1.shape[0] == 4 and np.allclose(h1, hist[:3], rtol=0, atol=1e-15)
+    # recomposition of the first iteration from the pinned pieces
+    Da = np.stack([orc.o_new_base(pr.Y64, ids, 3, 2, round_f32=False)[0] for ids in sets])
+    _blk, _s, _c, err, _E = orc.o_code(pr.Y64, Da, 3)
+    assert abs(orc.rmse(err.sum(), 16, 900) - hist[0]) < 1e-15
+    Qn = orc.o_new_base(pr.Y64, orc.o_worst(err, 150), 3, 2, round_f32=False)[0]
+    Db = np.concatenate([Da, Qn[None]])
+    blk1 = orc.o_code(pr.Y64, Db, 3)[0]
+    _D, (_s, _c, e1), _sq = orc.o_train_rounds(pr.Y64, blk1, Db, 3, 2, round_f32=False)
+    assert abs(orc.rmse(e1.sum(), 16, 900) - hist[1]) < 1e-15
