@@ -158,6 +158,31 @@ int sbo_new_base(sbo_ctx* c, const float* Y, int64_t m, const int32_t* ids, int6
                  int have_q0, float* Q, int32_t* supp, float* coef, float* err,
                  double* sqerr_per_round);
 
+/* Number of orthobases in use by the calls that follow: 1 <= K <= the K given to
+ * sbo_create (which sized the workspace).  A dictionary that grows (Algorithm 2, step 3)
+ * is handled by creating the context for the largest K and raising the count here. */
+int sbo_set_blocks(sbo_ctx* c, int K);
+
+/* Algorithm 2 as a whole.
+ *   Initialisation: K0 orthobases, base j trained by sbo_new_base (eq. (5) start + R rounds)
+ *   on the P0 signals init_ids[j][0..P0) (device int32 [K0][P0]; the random choice of those
+ *   signals is the caller's); then every signal is represented (sbo_code).
+ *   Iterations, while fewer than K_max orthobases exist and the RMSE is above target_rmse:
+ *   a new orthobase is trained on the W worst represented signals (sbo_worst, sbo_new_base)
+ *   and appended; every signal is represented; every orthobase is trained over its own
+ *   signals for R rounds (sbo_train_rounds); the stopping rule is evaluated on the host.
+ *   The error used by the stopping rule and by the next worst-W set is that of the codes of
+ *   the last training round.
+ * in : Y[m][p]; 1 <= K0 <= K_max <= K of sbo_create; 1 <= P0, W <= m; R >= 1
+ * out: D (device, room for K_max orthobases, the first *K_final are valid);
+ *      blk/supp/coef/err (device): the last representation and the codes of the last round;
+ *      K_final, n_hist (HOST ints); rmse_hist (HOST double[K_max - K0 + 1]): entry 0 after the
+ *      initial representation, then one per iteration, *n_hist entries.
+ * Synchronises the stream once per iteration (the stopping rule reads the error). */
+int sbo_learn(sbo_ctx* c, const float* Y, int64_t m, float* D, const int32_t* init_ids, int K0,
+              int64_t P0, int R, int64_t W, int K_max, double target_rmse, int32_t* blk,
+              int32_t* supp, float* coef, float* err, int* K_final, double* rmse_hist, int* n_hist);
+
 /* Per-stage timing with HIP events on the context's stream.  enable != 0 makes
  * every later call record events around each stage it runs. */
 int sbo_set_timing(sbo_ctx* c, int enable);

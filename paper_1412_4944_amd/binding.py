@@ -14,7 +14,7 @@ STAGES = ("energy", "group", "select", "accum", "svd")
 
 EXPORTS = ("sbo_create", "sbo_destroy", "sbo_workspace_bytes", "sbo_code", "sbo_group",
            "sbo_accumulate", "sbo_polar", "sbo_update", "sbo_train_rounds", "sbo_iterate", "sbo_sqerr",
-           "sbo_worst", "sbo_init_base", "sbo_new_base", "sbo_set_timing", "sbo_stage_ms", "sbo_strerror")
+           "sbo_worst", "sbo_init_base", "sbo_new_base", "sbo_set_blocks", "sbo_learn", "sbo_set_timing", "sbo_stage_ms", "sbo_strerror")
 
 _lib = None
 
@@ -50,6 +50,9 @@ def lib() -> ctypes.CDLL:
     L.sbo_worst.argtypes = [vp, vp, i64, i64, vp]
     L.sbo_init_base.argtypes = [vp, vp, i64, vp, i64, vp, vp]
     L.sbo_new_base.argtypes = [vp, vp, i64, vp, i64, i32, i32, vp, vp, vp, vp, vp]
+    L.sbo_set_blocks.argtypes = [vp, i32]
+    L.sbo_learn.argtypes = [vp, vp, i64, vp, vp, i32, i64, i32, i64, i32, ctypes.c_double, vp, vp, vp, vp,
+                            ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
     L.sbo_set_timing.argtypes = [vp, i32]
     L.sbo_stage_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     L.sbo_strerror.argtypes = [i32]
@@ -173,6 +176,24 @@ def sbo_new_base(ctx, Y, ids, R, have_q0, Q, supp, coef, err, sqerr_per_round=No
                               ids.shape[0], int(R), 1 if have_q0 else 0, _ptr(Q, torch.float32),
                               _ptr(supp, torch.int32), _ptr(coef, torch.float32),
                               _ptr(err, torch.float32), _ptr(sqerr_per_round, torch.float64, True)))
+
+
+def sbo_set_blocks(ctx, K: int) -> None:
+    _check(lib().sbo_set_blocks(ctx, int(K)))
+
+
+def sbo_learn(ctx, Y, D, init_ids, R, W, K_max, target_rmse, blk, supp, coef, err):
+    """Returns (K_final, rmse_history); D must have room for K_max orthobases."""
+    import torch
+    K0, P0 = init_ids.shape
+    kf, nh = ctypes.c_int(0), ctypes.c_int(0)
+    hist = (ctypes.c_double * (K_max - K0 + 1))()
+    _check(lib().sbo_learn(ctx, _ptr(Y, torch.float32), Y.shape[0], _ptr(D, torch.float32),
+                           _ptr(init_ids, torch.int32), int(K0), int(P0), int(R), int(W), int(K_max),
+                           float(target_rmse), _ptr(blk, torch.int32), _ptr(supp, torch.int32),
+                           _ptr(coef, torch.float32), _ptr(err, torch.float32), ctypes.byref(kf),
+                           hist, ctypes.byref(nh)))
+    return kf.value, [hist[i] for i in range(nh.value)]
 
 
 def sbo_set_timing(ctx, enable: bool) -> None:

@@ -2,6 +2,7 @@
 // All arithmetic is in the kernels; this file only enqueues them.
 #include "sbo_internal.h"
 
+#include <cmath>
 #include <new>
 #include <string>
 
@@ -41,6 +42,8 @@ size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char
     w.sel_state = (int32_t*)take((size_t)4 * 2 * 4);
     w.sel_cnt = (int32_t*)take(sel_chunks * 2 * 4);
     w.sel_base = (int32_t*)take(sel_chunks * 2 * 4);
+    w.sel_ids = (int32_t*)take((size_t)m_max * 4);
+    w.sq_out = (double*)take(8);
     w.sq_partial = (double*)take((size_t)kSqBlocks * 8);
     w.bytes = off;
     if (ws) *ws = w;
@@ -154,6 +157,7 @@ int sbo_create(sbo_ctx** out, int p, int K, int s0, int64_t m_max, void* hip_str
     if (!c) return SBO_ENOMEM;
     c->p = p;
     c->K = K;
+    c->K_cap = K;
     c->s0 = s0;
     c->m_max = m_max;
     c->stream = (hipStream_t)hip_stream;
@@ -298,13 +302,9 @@ int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter, int
     return SBO_OK;
 }
 
-int sbo_train_rounds(sbo_ctx* c, const float* Y, int64_t m, const int32_t* blk, float* D, int R,
-                     int32_t* supp, float* coef, float* err) {
-    int rc = check_call(c, m);
-    if (rc) return rc;
-    if (!Y || !blk || !D || !supp || !coef || !err || R < 1) return SBO_EINVAL;
-    c->n_spans = 0;
-    rc = run_group(c, blk, m);                 // the assignment, hence the grouping, is fixed
+static int run_train_rounds(sbo_ctx* c, const float* Y, int64_t m, const int32_t* blk, float* D, int R,
+                            int32_t* supp, float* coef, float* err) {
+    int rc = run_group(c, blk, m);             // the assignment, hence the grouping, is fixed
     if (rc) return rc;
     for (int r = 0; r < R; ++r) {
         const int warm = r % 8 != 0;           // later rounds start Jacobi from the last V
@@ -328,6 +328,21 @@ int sbo_train_rounds(sbo_ctx* c, const float* Y, int64_t m, const int32_t* blk, 
         SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws.vstate, warm, c->ws.jac_a,
                              nullptr, c->stream));
     }
+    return SBO_OK;
+}
+
+int sbo_train_rounds(sbo_ctx* c, const float* Y, int64_t m, const int32_t* blk, float* D, int R,
+                     int32_t* supp, float* coef, float* err) {
+    int rc = check_call(c, m);
+    if (rc) return rc;
+    if (!Y || !blk || !D || !supp || !coef || !err || R < 1) return SBO_EINVAL;
+    c->n_spans = 0;
+    return run_train_rounds(c, Y, m, blk, D, R, supp, coef, err);
+}
+
+int sbo_set_blocks(sbo_ctx* c, int K) {
+    if (!c || K < 1 || K > c->K_cap) return SBO_EINVAL;
+    c->K = K;
     return SBO_OK;
 }
 
@@ -366,17 +381,11 @@ int sbo_init_base(sbo_ctx* c, const float* Y, int64_t m, const int32_t* ids, int
     return run_init_base(c, Y, n, Q, sv);
 }
 
-int sbo_new_base(sbo_ctx* c, const float* Y, int64_t m, const int32_t* ids, int64_t n, int R,
-                 int have_q0, float* Q, int32_t* supp, float* coef, float* err,
-                 double* sqerr_per_round) {
-    int rc = check_call(c, m);
-    if (rc) return rc;
-    if (!Y || !ids || !Q || !supp || !coef || !err || n < 1 || n > m || R < 0) return SBO_EINVAL;
-    if (c->m_max < c->p) return SBO_EINVAL;
-    c->n_spans = 0;
-    SBO_HIP(launch_single_block(ids, n, m, c->ws, c->stream));
+// ws.perm etc. already hold the set (launch_single_block).
+static int run_new_base(sbo_ctx* c, const float* Y, int64_t n, int R, int have_q0, float* Q,
+                        int32_t* supp, float* coef, float* err, double* sqerr_per_round) {
     if (!have_q0) {
-        rc = run_init_base(c, Y, n, Q, nullptr);
+        int rc = run_init_base(c, Y, n, Q, nullptr);
         if (rc) return rc;
     }
     for (int r = 0; r < R; ++r) {
@@ -393,6 +402,86 @@ int sbo_new_base(sbo_ctx* c, const float* Y, int64_t m, const int32_t* ids, int6
         SBO_HIP(launch_polar(c->p, 1, c->ws.M, c->ws.counts, Q, c->ws.vstate, warm, c->ws.jac_a,
                              nullptr, c->stream));
     }
+    return SBO_OK;
+}
+
+int sbo_new_base(sbo_ctx* c, const float* Y, int64_t m, const int32_t* ids, int64_t n, int R,
+                 int have_q0, float* Q, int32_t* supp, float* coef, float* err,
+                 double* sqerr_per_round) {
+    int rc = check_call(c, m);
+    if (rc) return rc;
+    if (!Y || !ids || !Q || !supp || !coef || !err || n < 1 || n > m || R < 0) return SBO_EINVAL;
+    if (c->m_max < c->p) return SBO_EINVAL;
+    c->n_spans = 0;
+    SBO_HIP(launch_single_block(ids, n, m, c->ws, c->stream));
+    return run_new_base(c, Y, n, R, have_q0, Q, supp, coef, err, sqerr_per_round);
+}
+
+// RMSE of the codes in err (Section 4), read back to the host (synchronises the stream).
+static int host_rmse(sbo_ctx* c, const float* err, int64_t m, double* out) {
+    SBO_HIP(launch_sqerr(err, nullptr, m, c->ws, c->ws.sq_out, c->stream));
+    double sq = 0.0;
+    SBO_HIP(hipMemcpyAsync(&sq, c->ws.sq_out, sizeof(double), hipMemcpyDeviceToHost, c->stream));
+    SBO_HIP(hipStreamSynchronize(c->stream));
+    *out = sqrt(sq / ((double)c->p * (double)m));
+    return SBO_OK;
+}
+
+int sbo_learn(sbo_ctx* c, const float* Y, int64_t m, float* D, const int32_t* init_ids, int K0,
+              int64_t P0, int R, int64_t W, int K_max, double target_rmse, int32_t* blk,
+              int32_t* supp, float* coef, float* err, int* K_final, double* rmse_hist, int* n_hist) {
+    int rc = check_call(c, m);
+    if (rc) return rc;
+    if (!Y || !D || !init_ids || !blk || !supp || !coef || !err || !K_final || !rmse_hist || !n_hist)
+        return SBO_EINVAL;
+    if (K0 < 1 || K0 > K_max || K_max > c->K_cap || P0 < 1 || P0 > m || W < 1 || W > m || R < 1)
+        return SBO_EINVAL;
+    if (c->m_max < c->p) return SBO_EINVAL;
+    c->n_spans = 0;
+    const int K_before = c->K;
+    const size_t pp = (size_t)c->p * c->p;
+    auto fail = [&](int code) {
+        c->K = K_before;
+        return code;
+    };
+
+    // Initialisation: K0 orthobases, each trained on its own signal set; then represent.
+    for (int j = 0; j < K0; ++j) {
+        SBO_HIP(launch_single_block(init_ids + (size_t)j * P0, P0, m, c->ws, c->stream));
+        rc = run_new_base(c, Y, P0, R, 0, D + j * pp, supp, coef, err, nullptr);
+        if (rc) return fail(rc);
+    }
+    int K = K0;
+    c->K = K;
+    rc = run_code(c, Y, m, D, blk, supp, coef, err);
+    if (rc) return fail(rc);
+    int n = 0;
+    rc = host_rmse(c, err, m, &rmse_hist[n]);
+    if (rc) return fail(rc);
+    ++n;
+
+    // Iterations: grow by one orthobase trained on the worst-W set, represent, train every
+    // orthobase over its own signals, check the stopping rule.
+    while (K < K_max && rmse_hist[n - 1] > target_rmse) {
+        if (hipError_t e = launch_worst(err, m, W, c->ws, c->ws.sel_ids, c->stream); e != hipSuccess)
+            return fail(hip_fail(e));
+        if (hipError_t e = launch_single_block(c->ws.sel_ids, W, m, c->ws, c->stream); e != hipSuccess)
+            return fail(hip_fail(e));
+        rc = run_new_base(c, Y, W, R, 0, D + K * pp, supp, coef, err, nullptr);
+        if (rc) return fail(rc);
+        ++K;
+        c->K = K;
+        rc = run_code(c, Y, m, D, blk, supp, coef, err);
+        if (rc) return fail(rc);
+        rc = run_train_rounds(c, Y, m, blk, D, R, supp, coef, err);
+        if (rc) return fail(rc);
+        rc = host_rmse(c, err, m, &rmse_hist[n]);
+        if (rc) return fail(rc);
+        ++n;
+    }
+    *K_final = K;
+    *n_hist = n;
+    c->K = K_before;
     return SBO_OK;
 }
 

@@ -87,6 +87,8 @@ struct Workspace {
     int32_t* sel_state;    // [4][2] (key prefix, entries still to take) after each pass
     int32_t* sel_cnt;      // [ceil(m_max / kSelChunk)][2] entries above / equal to the threshold
     int32_t* sel_base;     // same shape: exclusive sums of sel_cnt over the chunks
+    int32_t* sel_ids;      // [m_max] worst-W set inside sbo_learn
+    double* sq_out;        // [1] squared-error total inside sbo_learn
     // iterate
     double* sq_partial;    // [kSqBlocks]
     size_t bytes;
@@ -104,7 +106,8 @@ struct sbo_span {
 };
 
 struct sbo_ctx {
-    int p, K, s0;
+    int p, K, s0;                    // K = blocks in use (<= K_cap, see sbo_set_blocks)
+    int K_cap;                       // blocks the workspace was sized for
     int64_t m_max;
     hipStream_t stream;
     char* ws_base;

@@ -187,3 +187,52 @@ def test_growth_step_reduces_error():
     # and the oracle agrees on the recoding with the grown dictionary
     from gpu_util import compare_code
     compare_code(pr.Y, D1, cfg.s0, orc.o_code(pr.Y, D1, cfg.s0), (blk1, supp1, coef1, err1))
+
+
+# ------------------------------------------------------------- Algorithm 2 as a whole
+@pytest.mark.parametrize("name,kw,K0,P0,R,W,K_max", [
+    ("tiny", dict(), 2, 200, 2, 128, 5),
+    ("patch8", dict(m=6000), 3, 600, 2, 512, 6),
+])
+def test_learn_against_oracle(name, kw, K0, P0, R, W, K_max):
+    """The whole of Algorithm 2 free-running on both sides from the same signal sets: same
+    number of orthobases, RMSE history never increasing and within 1 % of the oracle's
+    (near-tie choices differ), orthonormal result; the final representation is re-derived
+    by the oracle from the GPU's own dictionary; the stopping rule is honoured."""
+    import torch
+    import paper_1412_4944_amd as sbo
+    pr = _problem(name, **kw)
+    cfg = pr.cfg
+    m, p, s0 = pr.Y.shape[0], cfg.p, cfg.s0
+    rng = np.random.default_rng(46)
+    sets = np.stack([np.sort(rng.choice(m, P0, replace=False)) for _ in range(K0)]).astype(np.int32)
+    Do, blko, hist_o = orc.o_learn(pr.Y, s0, list(sets), R, W, K_max)
+    print(f"case {name}: oracle history {hist_o}", flush=True)
+    with Sbo(p, K_max, s0, m) as g:
+        t, dev = g.torch, g.dev
+        Yd = g.dev_f32(pr.Y)
+        D = t.zeros((K_max, p, p), dtype=t.float32, device=dev)
+        blk, supp, coef, err = g.outputs(m)
+        Kf, hist = sbo.sbo_learn(g.ctx, Yd, D, g.dev_i32(sets), R, W, K_max, 0.0, blk, supp, coef, err)
+        t.cuda.synchronize()
+        Dg, blkg, errg = D.cpu().numpy(), blk.cpu().numpy(), err.cpu().numpy()
+        hist = np.array(hist)
+        print(f"  gpu history {hist}", flush=True)
+        assert Kf == K_max == Do.shape[0] and hist.size == hist_o.size
+        assert (np.diff(hist) <= 1e-6 * hist[0]).all()
+        assert np.abs(hist - hist_o).max() <= 1e-2 * hist_o[0]
+        for j in range(Kf):
+            Q = Dg[j].astype(np.float64)
+            assert np.abs(Q @ Q.T - np.eye(p)).max() <= ORTHO_TOL
+        assert blkg.min() >= 0 and blkg.max() < Kf
+        assert abs(hist[-1] - orc.rmse(errg.astype(np.float64).sum(), p, m)) <= 1e-9 * hist[0]
+        # stopping rule: a target between two entries of the history stops right after the first below it
+        D2 = t.zeros_like(D)
+        target = 0.5 * (hist[1] + hist[2])
+        Kf2, hist2 = sbo.sbo_learn(g.ctx, Yd, D2, g.dev_i32(sets), R, W, K_max, float(target), blk, supp, coef, err)
+        t.cuda.synchronize()
+        assert Kf2 == K0 + 2 and len(hist2) == 3 and np.array_equal(np.array(hist2), hist[:3])
+        assert not t.isnan(D2[:Kf2]).any()
+        # the context is back to its own block count and still works
+        b2, *_r = g.code(pr.Y, Dg)
+    assert (b2 != orc.o_code(pr.Y, Dg, s0)[0]).mean() < 1e-3
