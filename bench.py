@@ -57,8 +57,9 @@ def cpu_baseline(pr, sample_m: int) -> dict:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=30,
+                    help="untimed iterations first (the clocks of an idle GPU take some tens of ms to settle)")
     ap.add_argument("--workload", default="headline")
     ap.add_argument("--cpu-sample", type=int, default=262144)
     ap.add_argument("--no-cpu", action="store_true")
@@ -102,21 +103,30 @@ def main() -> int:
         del src, dst
 
     ctx = sbo.sbo_create(p, K, s0, m)
-    sbo.sbo_set_timing(ctx, True)
+    # Timed region: HIP events around the roofline kernel only (an event pair per stage costs
+    # several microseconds on the stream, 4 % of a step here); the full per-stage breakdown comes
+    # from a second, untimed pass over the same number of iterations.
+    sbo.sbo_set_timing(ctx, 2)
     for _ in range(args.warmup):
         sbo.sbo_iterate(ctx, Y, D, 1, blk, supp, coef, err, sq)
     torch.cuda.synchronize()
     first_sq = float(sq[0].item())
 
     # K steps = one call that enqueues K x (code; update) on the stream with no host
-    # synchronisation in between; the library brackets every stage with HIP events.
+    # synchronisation in between.
+    D_start = D.clone()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     sbo.sbo_iterate(ctx, Y, D, args.steps, blk, supp, coef, err, sq)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    stage_sum = sbo.sbo_stage_ms(ctx)           # summed over the K iterations
+    energy_ms = sbo.sbo_stage_ms(ctx)["energy"] / args.steps
     last_sq = float(sq[args.steps - 1].item())
+
+    sbo.sbo_set_timing(ctx, 1)                  # untimed pass: same iterations, every stage bracketed by events
+    sbo.sbo_iterate(ctx, Y, D_start, args.steps, blk, supp, coef, err, sq)
+    torch.cuda.synchronize()
+    stage_sum = sbo.sbo_stage_ms(ctx)           # summed over the K iterations
 
     # The rows beyond one iteration (outside the timed region): worst-W set, eq. (5)
     # initialisation and a new orthobase trained with R = 6 rounds, on the same workload.
@@ -139,7 +149,7 @@ def main() -> int:
                 best = min(best, a.elapsed_time(b))
             return best
 
-        sbo.sbo_set_timing(ctx, False)
+        sbo.sbo_set_timing(ctx, 0)
         next_rows = {
             "W": W, "R": R,
             "worst_ms": best_ms(lambda: sbo.sbo_worst(ctx, err, W, ids)),
@@ -154,7 +164,7 @@ def main() -> int:
     stage_ms = {k: v / args.steps for k, v in stage_sum.items()}
 
     flops = 2.0 * K * p * p * m                 # projection onto all K orthobases
-    t_energy = stage_ms["energy"] * 1e-3
+    t_energy = energy_ms * 1e-3                 # from the timed region
     achieved = flops / t_energy / 1e12
     # Everything after the energy/argmax kernel that is bound by memory rather than by the
     # matrix pipe: grouping, support selection (fused with the per-piece accumulation for
@@ -183,6 +193,7 @@ def main() -> int:
                      "bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_F32_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_MFMA_F32_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name)},
+        "energy_ms_timed_region": energy_ms,
         "stage_ms": stage_ms,
         "update_hbm": {"stages": "group + select (fused with accumulate for p<=64) + accum",
                        "algorithmic_bytes": upd_bytes,

@@ -183,8 +183,10 @@ int sbo_learn(sbo_ctx* c, const float* Y, int64_t m, float* D, const int32_t* in
               int64_t P0, int R, int64_t W, int K_max, double target_rmse, int32_t* blk,
               int32_t* supp, float* coef, float* err, int* K_final, double* rmse_hist, int* n_hist);
 
-/* Per-stage timing with HIP events on the context's stream.  enable != 0 makes
- * every later call record events around each stage it runs. */
+/* Per-stage timing with HIP events on the context's stream.  enable = 1 makes every
+ * later call record events around each stage it runs; enable = 2 only around the energy
+ * kernel (an event pair costs a few microseconds on the stream, which shows in a step of
+ * under a millisecond); 0 switches timing off. */
 int sbo_set_timing(sbo_ctx* c, int enable);
 
 /* Synchronises the stream and writes, for the most recent timed call,

@@ -196,8 +196,9 @@ def sbo_learn(ctx, Y, D, init_ids, R, W, K_max, target_rmse, blk, supp, coef, er
     return kf.value, [hist[i] for i in range(nh.value)]
 
 
-def sbo_set_timing(ctx, enable: bool) -> None:
-    _check(lib().sbo_set_timing(ctx, 1 if enable else 0))
+def sbo_set_timing(ctx, enable) -> None:
+    """enable: False/0 off, True/1 every stage, 2 the energy kernel only."""
+    _check(lib().sbo_set_timing(ctx, int(enable)))
 
 
 def sbo_stage_ms(ctx) -> dict:

@@ -338,13 +338,66 @@ __global__ __launch_bounds__(256) void accum_wide_kernel(const float* __restrict
             }
 }
 
+// Besides the sums over pieces (blockIdx.x < K), the column blockIdx.x == K of the grid forms
+// the total squared error sum_i err[i] (sq_out != nullptr): every workgroup of the column sums
+// a contiguous share in a fixed order, and the one that finishes last adds the shares in
+// index order (it is identified by an integer counter, which it sets back to zero; nobody
+// waits for anybody).
 template <int P>
 __global__ __launch_bounds__(256) void accum_reduce_kernel(int K, int piece,
                                                            const int32_t* __restrict__ offsets,
                                                            const float* __restrict__ partial,
-                                                           float* __restrict__ M) {
+                                                           float* __restrict__ M,
+                                                           const float* __restrict__ err, int64_t m,
+                                                           double* sq_part, int* sq_counter,
+                                                           double* __restrict__ sq_out) {
     constexpr int PP = P * P;
     extern __shared__ int lds[];               // piece_start[K+1] | tmp[16]
+    if ((int)blockIdx.x == K) {                // uniform over the workgroup
+        if (sq_out == nullptr) return;
+        __shared__ double red[256];
+        __shared__ int is_last;
+        const int tid = threadIdx.x;
+        const int nb = gridDim.y, b = blockIdx.y;
+        const int64_t per = (m + nb - 1) / nb;
+        const int64_t beg = b * per, end = beg + per < m ? beg + per : m;
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;   // four loads in flight per thread
+        int64_t i = beg + tid;
+        for (; i + 768 < end; i += 1024) {
+            const float a = err[i], b2 = err[i + 256], c2 = err[i + 512], d2 = err[i + 768];
+            s0 += (double)a;
+            s1 += (double)b2;
+            s2 += (double)c2;
+            s3 += (double)d2;
+        }
+        for (; i < end; i += 256) s0 += (double)err[i];
+        red[tid] = (s0 + s1) + (s2 + s3);
+        __syncthreads();
+        for (int o = 128; o > 0; o >>= 1) {
+            if (tid < o) red[tid] += red[tid + o];
+            __syncthreads();
+        }
+        if (tid == 0) {
+            __hip_atomic_store(&sq_part[b], red[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __threadfence();
+            is_last = atomicAdd(sq_counter, 1) == nb - 1;
+        }
+        __syncthreads();
+        if (!is_last) return;
+        __threadfence();
+        red[tid] = tid < nb ? __hip_atomic_load(&sq_part[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                            : 0.0;
+        __syncthreads();
+        for (int o = 128; o > 0; o >>= 1) {
+            if (tid < o) red[tid] += red[tid + o];
+            __syncthreads();
+        }
+        if (tid == 0) {
+            *sq_out = red[0];
+            *sq_counter = 0;
+        }
+        return;
+    }
     int* piece_start = lds;
     int* tmp = lds + (K + 1);
     wg_exclusive_scan4([&](int j) { return (offsets[j + 1] - offsets[j] + piece - 1) / piece; }, K,
@@ -379,7 +432,7 @@ hipError_t launch_ps(int K, const float* Y, int64_t m, const int32_t* supp, cons
                        Y, K, piece, ws.offsets, ws.perm, supp, coef, ws.partial);
     const size_t lds2 = (K + 1 + 16) * sizeof(int);
     hipLaunchKernelGGL((accum_reduce_kernel<P>), dim3(K, (P * P + 255) / 256), dim3(256), lds2, st,
-                       K, piece, ws.offsets, ws.partial, M);
+                       K, piece, ws.offsets, ws.partial, M, nullptr, (int64_t)0, nullptr, nullptr, nullptr);
     return hipGetLastError();
 }
 
@@ -394,7 +447,7 @@ hipError_t launch_wide_s(int K, const float* Y, int64_t m, const int32_t* supp, 
                        ws.offsets, ws.perm, supp, coef, ws.partial);
     const size_t lds2 = (K + 1 + 16) * sizeof(int);
     hipLaunchKernelGGL((accum_reduce_kernel<P>), dim3(K, (P * P + 255) / 256), dim3(256), lds2, st,
-                       K, piece, ws.offsets, ws.partial, M);
+                       K, piece, ws.offsets, ws.partial, M, nullptr, (int64_t)0, nullptr, nullptr, nullptr);
     return hipGetLastError();
 }
 
@@ -445,7 +498,7 @@ hipError_t launch_gram_p(const float* Y, int64_t n, const Workspace& ws, float* 
     hipLaunchKernelGGL((accum_piece_kernel<P, 1, true>), dim3(max_pieces), dim3(64 * kTallWaves), lds1, st,
                        Y, 1, piece, ws.offsets, ws.perm, nullptr, nullptr, ws.partial);
     hipLaunchKernelGGL((accum_reduce_kernel<P>), dim3(1, (P * P + 255) / 256), dim3(256),
-                       (1 + 1 + 16) * sizeof(int), st, 1, piece, ws.offsets, ws.partial, G);
+                       (1 + 1 + 16) * sizeof(int), st, 1, piece, ws.offsets, ws.partial, G, nullptr, (int64_t)0, nullptr, nullptr, nullptr);
     return hipGetLastError();
 }
 
@@ -465,26 +518,33 @@ hipError_t launch_gram(int p, const float* Y, int64_t n, const Workspace& ws, fl
             hipLaunchKernelGGL((accum_wide_kernel<1, true>), dim3(max_pieces), dim3(256), lds1, st, Y, 1,
                                piece, ws.offsets, ws.perm, nullptr, nullptr, ws.partial);
             hipLaunchKernelGGL((accum_reduce_kernel<P>), dim3(1, (P * P + 255) / 256), dim3(256),
-                               (1 + 1 + 16) * sizeof(int), st, 1, piece, ws.offsets, ws.partial, G);
+                               (1 + 1 + 16) * sizeof(int), st, 1, piece, ws.offsets, ws.partial, G, nullptr, (int64_t)0, nullptr, nullptr, nullptr);
             return hipGetLastError();
         }
         default: return hipErrorInvalidValue;
     }
 }
 
-// M[j] = sum of the piece results of block j in ws.partial, in piece order.
+// M[j] = sum of the piece results of block j in ws.partial, in piece order; with sq_out also
+// *sq_out = sum of err[0..m) (same launch, extra workgroups).
 hipError_t launch_accum_reduce(int p, int K, int64_t m, const Workspace& ws, float* M,
-                               hipStream_t st) {
+                               const float* err, double* sq_out, hipStream_t st) {
     const int piece = accum_piece(m, K, p);
     const size_t lds = (K + 1 + 16) * sizeof(int);
-    const dim3 grid(K, (p * p + 255) / 256);
+    const int gy = (p * p + 255) / 256;
+    const bool sq = err != nullptr && sq_out != nullptr;
+    const dim3 grid(sq ? K + 1 : K, sq && gy < 128 ? 128 : gy);   // <= kSqBlocks shares of err
+    double* so = sq ? sq_out : nullptr;
+#define SBO_CASE(N)                                                                              \
+    case N:                                                                                      \
+        hipLaunchKernelGGL((accum_reduce_kernel<N>), grid, dim3(256), lds, st, K, piece, ws.offsets, \
+                           ws.partial, M, err, m, ws.sq_partial, ws.sq_counter, so);             \
+        break;
     switch (p) {
-        case 16: hipLaunchKernelGGL((accum_reduce_kernel<16>), grid, dim3(256), lds, st, K, piece, ws.offsets, ws.partial, M); break;
-        case 32: hipLaunchKernelGGL((accum_reduce_kernel<32>), grid, dim3(256), lds, st, K, piece, ws.offsets, ws.partial, M); break;
-        case 64: hipLaunchKernelGGL((accum_reduce_kernel<64>), grid, dim3(256), lds, st, K, piece, ws.offsets, ws.partial, M); break;
-        case 256: hipLaunchKernelGGL((accum_reduce_kernel<256>), grid, dim3(256), lds, st, K, piece, ws.offsets, ws.partial, M); break;
+        SBO_CASE(16) SBO_CASE(32) SBO_CASE(64) SBO_CASE(256)
         default: return hipErrorInvalidValue;
     }
+#undef SBO_CASE
     return hipGetLastError();
 }
 

@@ -136,7 +136,8 @@ template <int P, int S, int NT, bool EXACT>
 __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y, int m,
                                                      const f32x4* __restrict__ Dsw, int K, int s0,
                                                      int32_t* __restrict__ blk,
-                                                     float* __restrict__ energy) {
+                                                     float* __restrict__ energy,
+                                                     int32_t* __restrict__ chunk_count, int chunk) {
     constexpr int KS = P / 2;            // contraction steps (each lane half covers P/2 dims)
     constexpr int QN = P / 8;            // 16-byte groups of steps per 32-row tile
     constexpr int NB = P <= 64 ? 64 / P : 1;   // blocks per 64-row stage (p <= 64)
@@ -288,11 +289,30 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
             }
         }
     }
+
+    // First step of the grouping (Section 3.3), folded in here: chunk_count[c][j] += number of
+    // this workgroup's signals that chose block j, c = the chunk of consecutive signals the
+    // workgroup lies in (chunk is a multiple of the signals per workgroup; the array is zero
+    // on entry).  Integer atomics only: the sums do not depend on the order.
+    if (chunk_count != nullptr) {        // uniform
+        int* lh = reinterpret_cast<int*>(Qs_raw);          // the stage buffers are dead (>= 8 KiB)
+        for (int j = tid; j < K; j += 256) lh[j] = 0;
+        __syncthreads();
+        if (h == 0) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                if (sig0 + nt * 32 + n < m) atomicAdd(&lh[best[nt]], 1);
+        }
+        __syncthreads();
+        const int64_t c = ((int64_t)blockIdx.x * (4 * 32 * NT)) / chunk;
+        for (int j = tid; j < K; j += 256)
+            if (lh[j] != 0) atomicAdd(&chunk_count[c * K + j], lh[j]);
+    }
 }
 
 template <int P, int S, bool EXACT>
 hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, float* energy,
-                      const f32x4* Dsw, hipStream_t st) {
+                      const f32x4* Dsw, int32_t* chunk_count, hipStream_t st) {
     constexpr int NT = P <= 64 ? 2 : 1;
     constexpr int QN = P / 8;
     constexpr size_t lds = (size_t)2 * (2 * QN * 64) * sizeof(f32x4);
@@ -308,27 +328,29 @@ hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, fl
             raised = true;
         }
     }
+    const int chunk = group_geom(m).chunk;
+    if (chunk % per_wg != 0) return hipErrorInvalidValue;
     hipLaunchKernelGGL((energy_kernel<P, S, NT, EXACT>), grid, dim3(256), lds, st, Y, (int)m, Dsw, K,
-                       s0, blk, energy);
+                       s0, blk, energy, chunk_count, chunk);
     return hipGetLastError();
 }
 
 template <int P, int S>
 hipError_t launch_ps(const float* Y, int64_t m, int K, int s0, int32_t* blk, float* energy,
-                     const float* dsw, hipStream_t st) {
+                     const float* dsw, int32_t* chunk_count, hipStream_t st) {
     const f32x4* Dsw = reinterpret_cast<const f32x4*>(dsw);
-    if (s0 == S) return launch_pse<P, S, true>(Y, m, K, s0, blk, energy, Dsw, st);
-    return launch_pse<P, S, false>(Y, m, K, s0, blk, energy, Dsw, st);
+    if (s0 == S) return launch_pse<P, S, true>(Y, m, K, s0, blk, energy, Dsw, chunk_count, st);
+    return launch_pse<P, S, false>(Y, m, K, s0, blk, energy, Dsw, chunk_count, st);
 }
 
 template <int P>
 hipError_t launch_p(int s0, const float* Y, int64_t m, int K, int32_t* blk, float* energy,
-                    const float* dsw, hipStream_t st) {
-    if (s0 <= 1) return launch_ps<P, 1>(Y, m, K, s0, blk, energy, dsw, st);
-    if (s0 <= 2) return launch_ps<P, 2>(Y, m, K, s0, blk, energy, dsw, st);
-    if (s0 <= 4) return launch_ps<P, 4>(Y, m, K, s0, blk, energy, dsw, st);
-    if (s0 <= 8) return launch_ps<P, 8>(Y, m, K, s0, blk, energy, dsw, st);
-    return launch_ps<P, 16>(Y, m, K, s0, blk, energy, dsw, st);
+                    const float* dsw, int32_t* chunk_count, hipStream_t st) {
+    if (s0 <= 1) return launch_ps<P, 1>(Y, m, K, s0, blk, energy, dsw, chunk_count, st);
+    if (s0 <= 2) return launch_ps<P, 2>(Y, m, K, s0, blk, energy, dsw, chunk_count, st);
+    if (s0 <= 4) return launch_ps<P, 4>(Y, m, K, s0, blk, energy, dsw, chunk_count, st);
+    if (s0 <= 8) return launch_ps<P, 8>(Y, m, K, s0, blk, energy, dsw, chunk_count, st);
+    return launch_ps<P, 16>(Y, m, K, s0, blk, energy, dsw, chunk_count, st);
 }
 
 }  // namespace
@@ -347,12 +369,12 @@ hipError_t launch_dict_swizzle(int p, int K, const float* D, float* dsw, hipStre
 }
 
 hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const float* dsw,
-                         int32_t* blk, float* energy, hipStream_t st) {
+                         int32_t* blk, float* energy, int32_t* chunk_count, hipStream_t st) {
     switch (p) {
-        case 16: return launch_p<16>(s0, Y, m, K, blk, energy, dsw, st);
-        case 32: return launch_p<32>(s0, Y, m, K, blk, energy, dsw, st);
-        case 64: return launch_p<64>(s0, Y, m, K, blk, energy, dsw, st);
-        case 256: return launch_p<256>(s0, Y, m, K, blk, energy, dsw, st);
+        case 16: return launch_p<16>(s0, Y, m, K, blk, energy, dsw, chunk_count, st);
+        case 32: return launch_p<32>(s0, Y, m, K, blk, energy, dsw, chunk_count, st);
+        case 64: return launch_p<64>(s0, Y, m, K, blk, energy, dsw, chunk_count, st);
+        case 256: return launch_p<256>(s0, Y, m, K, blk, energy, dsw, chunk_count, st);
         default: return hipErrorInvalidValue;
     }
 }

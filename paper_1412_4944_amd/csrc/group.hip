@@ -38,7 +38,9 @@ __global__ __launch_bounds__(256) void group_hist_kernel(const int32_t* __restri
 }
 
 // 2. chunk_base[c][j] = number of signals of block j in chunks before c; counts[j] = total.
-__global__ __launch_bounds__(256) void group_scan_kernel(const int32_t* __restrict__ chunk_count,
+// The histogram entries are set back to zero once read: the coding kernel, which can
+// produce them itself, adds into the array.
+__global__ __launch_bounds__(256) void group_scan_kernel(int32_t* __restrict__ chunk_count,
                                                          int K, int n_chunks,
                                                          int32_t* __restrict__ chunk_base,
                                                          int32_t* __restrict__ counts) {
@@ -50,8 +52,10 @@ __global__ __launch_bounds__(256) void group_scan_kernel(const int32_t* __restri
         const int n = min(1024, n_chunks - c0);
         wg_exclusive_scan4([&](int idx) { return chunk_count[(int64_t)(c0 + idx) * K + j]; }, n,
                            out, tmp);
-        for (int idx = threadIdx.x; idx < n; idx += 256)
+        for (int idx = threadIdx.x; idx < n; idx += 256) {
             chunk_base[(int64_t)(c0 + idx) * K + j] = carry + out[idx];
+            chunk_count[(int64_t)(c0 + idx) * K + j] = 0;
+        }
         carry += out[n];
         __syncthreads();
     }
@@ -111,12 +115,16 @@ __global__ __launch_bounds__(256) void group_scatter_kernel(const int32_t* __res
 
 }  // namespace
 
-hipError_t launch_group(int K, const int32_t* blk, int64_t m, const Workspace& ws, hipStream_t st) {
+// have_hist: ws.chunk_count already holds the per-chunk histograms (written by the coding
+// kernel); otherwise they are computed from blk here.
+hipError_t launch_group(int K, const int32_t* blk, int64_t m, const Workspace& ws, bool have_hist,
+                        hipStream_t st) {
     if (K > kMaxK) return hipErrorInvalidValue;
     const GroupGeom g = group_geom(m);
     const unsigned wgs = (unsigned)((g.n_chunks + 3) / 4);
-    hipLaunchKernelGGL(group_hist_kernel, dim3(wgs), dim3(256), 4 * K * sizeof(int), st, blk,
-                       (int)m, K, g.chunk, g.n_chunks, ws.chunk_count);
+    if (!have_hist)
+        hipLaunchKernelGGL(group_hist_kernel, dim3(wgs), dim3(256), 4 * K * sizeof(int), st, blk,
+                           (int)m, K, g.chunk, g.n_chunks, ws.chunk_count);
     hipLaunchKernelGGL(group_scan_kernel, dim3(K), dim3(256), 0, st, ws.chunk_count, K,
                        g.n_chunks, ws.chunk_base, ws.counts);
     hipLaunchKernelGGL(group_scatter_kernel, dim3(wgs), dim3(256),

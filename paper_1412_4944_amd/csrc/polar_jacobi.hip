@@ -16,17 +16,17 @@ namespace {
 
 constexpr int kMaxSweeps = 30;
 // A pair is rotated while |a_i . a_j| > kTol |a_i| |a_j|.  Convergence is quadratic: a
-// sweep in which every pair already had a cosine below kDone leaves cosines of the order
-// of kDone^2 behind, so it is the last one and no sweep is spent on verifying.
+// sweep in which every pair already had a cosine below `done` (polar_done()) leaves cosines of
+// the order of done^2 behind, so it is the last one and no sweep is spent on verifying.
 constexpr float kTol = 1e-6f;
-constexpr float kDone = 1e-4f;
 
 template <int P, int TPP>
 __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __restrict__ M,
                                                              const int32_t* __restrict__ counts,
                                                              float* __restrict__ D,
                                                              float* __restrict__ Vstate, int warm,
-                                                             float* __restrict__ eig_sv) {
+                                                             float* __restrict__ eig_sv, float done,
+                                                             float* __restrict__ dsw) {
     constexpr int LD = P + 4;
     constexpr int NT = (P / 2) * TPP;          // threads: TPP lanes per column pair
     constexpr int RPT = P / TPP;               // contiguous rows per lane in a rotation
@@ -152,7 +152,7 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
 #pragma unroll
             for (int t = 0; t < RPT; ++t) asm volatile("" : "+v"(vx[t]), "+v"(vy[t]));
             const float g2ab = gamma * gamma, ab = alpha * beta;
-            if (g2ab > (kDone * kDone) * ab) rotated = 1;          // another sweep is needed
+            if (g2ab > (done * done) * ab) rotated = 1;          // another sweep is needed
             if (g2ab > (kTol * kTol) * ab && hh > 1e-36f) {
                 const float r = __builtin_amdgcn_rsqf(hh);
                 const float w = 0.5f + 0.5f * (fabsf(d) * r);
@@ -318,6 +318,15 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
         for (int a = 0; a < 4; ++a) {
             f32x4 row = {o[a][0], o[a][1], o[a][2], o[a][3]};
             *reinterpret_cast<f32x4*>(&Dj[(k0 + a) * P + q0]) = row;
+            // the same four values in the coding kernel's operand order (see dict_swizzle_kernel:
+            // stage of 64 dictionary rows, unit (mt*QN + q)*64 + hh*32 + nn)
+            if (dsw != nullptr) {
+                constexpr int QN = P / 8;
+                const int grow = j * P + k0 + a, d4 = q0 >> 2;
+                const int st = grow >> 6, mt = (grow >> 5) & 1, nn = grow & 31;
+                const int hh = d4 / QN, q = d4 % QN;
+                reinterpret_cast<f32x4*>(dsw)[(int64_t)st * (2 * QN * 64) + (mt * QN + q) * 64 + hh * 32 + nn] = row;
+            }
         }
     }
 }
@@ -326,24 +335,29 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
 
 template <int TPP>
 hipError_t launch_tpp(int p, int K, const float* M, const int32_t* counts, float* D, float* vstate,
-                      int warm, float* eig_sv, hipStream_t st) {
+                      int warm, float* eig_sv, float* dsw, hipStream_t st) {
+    const float done = polar_done();
     switch (p) {
-        case 16: hipLaunchKernelGGL((polar_kernel<16, TPP>), dim3(K), dim3(8 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv); break;
-        case 32: hipLaunchKernelGGL((polar_kernel<32, TPP>), dim3(K), dim3(16 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv); break;
-        case 64: hipLaunchKernelGGL((polar_kernel<64, TPP>), dim3(K), dim3(32 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv); break;
+        case 16: hipLaunchKernelGGL((polar_kernel<16, TPP>), dim3(K), dim3(8 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv, done, dsw); break;
+        case 32: hipLaunchKernelGGL((polar_kernel<32, TPP>), dim3(K), dim3(16 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv, done, dsw); break;
+        case 64: hipLaunchKernelGGL((polar_kernel<64, TPP>), dim3(K), dim3(32 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv, done, dsw); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
 hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
-                        float* vstate, int warm, float* jac_a, float* eig_sv, hipStream_t st) {
-    if (p == 256) return launch_polar_wide(K, M, counts, D, vstate, warm, jac_a, eig_sv, st);
+                        float* vstate, int warm, float* jac_a, float* eig_sv, float* dsw,
+                        hipStream_t st) {
+    if (p == 256) {
+        if (dsw != nullptr) return hipErrorInvalidValue;   // p = 256 rewrites the operand order itself
+        return launch_polar_wide(K, M, counts, D, vstate, warm, jac_a, eig_sv, st);
+    }
     int tpp = 16;
     if (const char* e = getenv("SBO_POLAR_TPP")) tpp = atoi(e);   // tuning override
-    if (tpp == 4) return launch_tpp<4>(p, K, M, counts, D, vstate, warm, eig_sv, st);
-    if (tpp == 8) return launch_tpp<8>(p, K, M, counts, D, vstate, warm, eig_sv, st);
-    return launch_tpp<16>(p, K, M, counts, D, vstate, warm, eig_sv, st);
+    if (tpp == 4) return launch_tpp<4>(p, K, M, counts, D, vstate, warm, eig_sv, dsw, st);
+    if (tpp == 8) return launch_tpp<8>(p, K, M, counts, D, vstate, warm, eig_sv, dsw, st);
+    return launch_tpp<16>(p, K, M, counts, D, vstate, warm, eig_sv, dsw, st);
 }
 
 }  // namespace sbo

@@ -28,7 +28,6 @@ constexpr int kPairs = P / 2;
 constexpr int kSteps = P - 1;
 constexpr int kMaxSweeps = 24;    // rounds logged per block: kMaxSweeps * kSteps
 constexpr float kTol = 1e-6f;     // rotate while |a_i . a_j| > kTol |a_i| |a_j|
-constexpr float kDone = 1e-4f;    // a sweep whose cosines were all below this is the last
 constexpr int LDA = 132;          // LDS leading dimension of the 128 on-chip rows
 constexpr int kRowsLds = 128;
 
@@ -65,7 +64,7 @@ __device__ __forceinline__ void pair_next(int pi, int& ca, int& cb) {
 __global__ __launch_bounds__(1024) void wide_jacobi_kernel(const float* __restrict__ M,
                                                            const int32_t* __restrict__ counts,
                                                            const float* __restrict__ Vst, int warm,
-                                                           float* scratch, int K) {
+                                                           float* scratch, int K, float done) {
     constexpr int NT = 1024;
     constexpr int TPP = 8;
     constexpr int RPT = P / TPP;               // 32 rows per lane: 16 on chip, 16 in global memory
@@ -168,7 +167,7 @@ __global__ __launch_bounds__(1024) void wide_jacobi_kernel(const float* __restri
             const float d = beta - alpha, g2 = 2.f * gamma;
             const float hh = d * d + g2 * g2;
             const float g2ab = gamma * gamma, ab = alpha * beta;
-            if (g2ab > (kDone * kDone) * ab) rotated = 1;
+            if (g2ab > (done * done) * ab) rotated = 1;
             float cs = 1.f, sn = 0.f;
             if (g2ab > (kTol * kTol) * ab && hh > 1e-36f) {
                 // cos(2 theta) = |d| / hypot(d, 2 gamma), |theta| <= pi/4
@@ -451,7 +450,8 @@ hipError_t launch_polar_wide(int K, const float* M, const int32_t* counts, float
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL(wide_jacobi_kernel, dim3(K), dim3(1024), lds, st, M, counts, vstate, warm, jac_a, K);
+    hipLaunchKernelGGL(wide_jacobi_kernel, dim3(K), dim3(1024), lds, st, M, counts, vstate, warm, jac_a, K,
+                       polar_done());
     hipLaunchKernelGGL(wide_replay_kernel, dim3(K, P / (4 * kReplayRows)), dim3(256), 0, st, counts,
                        vstate, warm, jac_a, K);
     hipLaunchKernelGGL(wide_finish_kernel, dim3(K), dim3(1024), 0, st, M, counts, D, vstate, jac_a, K,

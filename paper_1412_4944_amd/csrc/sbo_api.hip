@@ -44,6 +44,7 @@ size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char
     w.sel_base = (int32_t*)take(sel_chunks * 2 * 4);
     w.sel_ids = (int32_t*)take((size_t)m_max * 4);
     w.sq_out = (double*)take(8);
+    w.sq_counter = (int32_t*)take(4);
     w.sq_partial = (double*)take((size_t)kSqBlocks * 8);
     w.bytes = off;
     if (ws) *ws = w;
@@ -78,7 +79,7 @@ struct StageTimer {
     sbo_ctx* c;
     long idx;                                  // index into c->spans, -1 = not timing
     StageTimer(sbo_ctx* ctx, int stage) : c(ctx), idx(-1) {
-        if (!c->timing) return;
+        if (!c->timing || (c->timing == 2 && stage != SBO_STAGE_ENERGY)) return;
         if (c->n_spans == c->spans.size()) {
             sbo_span s;
             s.stage = stage;
@@ -104,9 +105,9 @@ static int check_call(const sbo_ctx* c, int64_t m) {
     return SBO_OK;
 }
 
-static int run_group(sbo_ctx* c, const int32_t* blk, int64_t m) {
+static int run_group(sbo_ctx* c, const int32_t* blk, int64_t m, bool have_hist = false) {
     StageTimer t(c, SBO_STAGE_GROUP);
-    SBO_HIP(launch_group(c->K, blk, m, c->ws, c->stream));
+    SBO_HIP(launch_group(c->K, blk, m, c->ws, have_hist, c->stream));
     return SBO_OK;
 }
 
@@ -115,9 +116,10 @@ static int run_code(sbo_ctx* c, const float* Y, int64_t m, const float* D, int32
     SBO_HIP(launch_dict_swizzle(c->p, c->K, D, c->ws.dsw, c->stream));   // tiny; outside the stages
     {
         StageTimer t(c, SBO_STAGE_ENERGY);
-        SBO_HIP(launch_energy(c->p, c->K, c->s0, Y, m, c->ws.dsw, blk, c->ws.energy, c->stream));
+        SBO_HIP(launch_energy(c->p, c->K, c->s0, Y, m, c->ws.dsw, blk, c->ws.energy,
+                              c->ws.chunk_count, c->stream));
     }
-    int rc = run_group(c, blk, m);
+    int rc = run_group(c, blk, m, true);       // the energy kernel left the chunk histograms
     if (rc) return rc;
     {
         StageTimer t(c, SBO_STAGE_SELECT);
@@ -135,7 +137,7 @@ static int run_update_grouped(sbo_ctx* c, const float* Y, int64_t m, const int32
     }
     {
         StageTimer t(c, SBO_STAGE_SVD);
-        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, vstate, warm, c->ws.jac_a, nullptr, c->stream));
+        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, vstate, warm, c->ws.jac_a, nullptr, nullptr, c->stream));
     }
     return SBO_OK;
 }
@@ -173,6 +175,15 @@ int sbo_create(sbo_ctx** out, int p, int K, int s0, int64_t m_max, void* hip_str
     }
     c->ws_base = (char*)base;
     workspace_layout(p, K, s0, m_max, &c->ws, c->ws_base);
+    // Two pieces of the workspace carry an invariant between calls: the chunk histograms and the
+    // finished-workgroup counter are zero whenever no call is in flight.
+    e = hipMemsetAsync(c->ws.chunk_count, 0, (size_t)max_chunks() * K * 4, c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(c->ws.sq_counter, 0, 4, c->stream);
+    if (e != hipSuccess) {
+        (void)hipFree(c->ws_base);
+        delete c;
+        return hip_fail(e);
+    }
     *out = c;
     return SBO_OK;
 }
@@ -237,7 +248,7 @@ int sbo_polar(sbo_ctx* c, const float* M, const int32_t* counts, float* D) {
     c->n_spans = 0;
     StageTimer t(c, SBO_STAGE_SVD);
     SBO_HIP(launch_polar(c->p, c->K, M, counts, D, c->p > 64 ? c->ws.vstate : nullptr, 0, c->ws.jac_a,
-                         nullptr, c->stream));
+                         nullptr, nullptr, c->stream));
     return SBO_OK;
 }
 
@@ -277,26 +288,29 @@ int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter, int
             if (rc) return rc;
             continue;
         }
-        SBO_HIP(launch_dict_swizzle(c->p, c->K, D, c->ws.dsw, c->stream));
+        // The dictionary in the coding kernel's operand order: rewritten from D at the start
+        // of the call, kept up to date by the SVD kernel afterwards.
+        if (it == 0) SBO_HIP(launch_dict_swizzle(c->p, c->K, D, c->ws.dsw, c->stream));
         {
-            StageTimer t(c, SBO_STAGE_ENERGY);
-            SBO_HIP(launch_energy(c->p, c->K, c->s0, Y, m, c->ws.dsw, blk, c->ws.energy, c->stream));
+            StageTimer t(c, SBO_STAGE_ENERGY);  // also leaves the chunk histograms of the grouping
+            SBO_HIP(launch_energy(c->p, c->K, c->s0, Y, m, c->ws.dsw, blk, c->ws.energy,
+                                  c->ws.chunk_count, c->stream));
         }
-        rc = run_group(c, blk, m);
+        rc = run_group(c, blk, m, true);
         if (rc) return rc;
         {
             StageTimer t(c, SBO_STAGE_SELECT);  // includes the per-piece accumulation
             SBO_HIP(launch_select_accum(c->p, c->K, c->s0, Y, m, D, c->ws, supp, coef, err, c->stream));
         }
-        if (sqerr_per_iter) SBO_HIP(launch_sqerr(err, nullptr, m, c->ws, sqerr_per_iter + it, c->stream));
         {
-            StageTimer t(c, SBO_STAGE_ACCUM);   // only the sum over pieces remains
-            SBO_HIP(launch_accum_reduce(c->p, c->K, m, c->ws, c->ws.M, c->stream));
+            StageTimer t(c, SBO_STAGE_ACCUM);   // the sum over pieces, and the squared-error total
+            SBO_HIP(launch_accum_reduce(c->p, c->K, m, c->ws, c->ws.M, err,
+                                        sqerr_per_iter ? sqerr_per_iter + it : nullptr, c->stream));
         }
         {
             StageTimer t(c, SBO_STAGE_SVD);
             SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws.vstate, warm,
-                                 c->ws.jac_a, nullptr, c->stream));
+                                 c->ws.jac_a, nullptr, c->ws.dsw, c->stream));
         }
     }
     return SBO_OK;
@@ -315,7 +329,7 @@ static int run_train_rounds(sbo_ctx* c, const float* Y, int64_t m, const int32_t
                                             c->stream));
             }
             StageTimer t(c, SBO_STAGE_ACCUM);
-            SBO_HIP(launch_accum_reduce(c->p, c->K, m, c->ws, c->ws.M, c->stream));
+            SBO_HIP(launch_accum_reduce(c->p, c->K, m, c->ws, c->ws.M, nullptr, nullptr, c->stream));
         } else {
             {
                 StageTimer t(c, SBO_STAGE_SELECT);
@@ -326,7 +340,7 @@ static int run_train_rounds(sbo_ctx* c, const float* Y, int64_t m, const int32_t
         }
         StageTimer t(c, SBO_STAGE_SVD);
         SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws.vstate, warm, c->ws.jac_a,
-                             nullptr, c->stream));
+                             nullptr, nullptr, c->stream));
     }
     return SBO_OK;
 }
@@ -366,7 +380,7 @@ int sbo_worst(sbo_ctx* c, const float* err, int64_t m, int64_t W, int32_t* ids) 
 static int run_init_base(sbo_ctx* c, const float* Y, int64_t n, float* Q, float* sv) {
     SBO_HIP(launch_gram(c->p, Y, n, c->ws, c->ws.M, c->stream));
     SBO_HIP(launch_polar(c->p, 1, c->ws.M, nullptr, Q, c->ws.vstate, 0, c->ws.jac_a,
-                         sv ? sv : c->ws.energy, c->stream));   // energy[m_max >= p] as a sink
+                         sv ? sv : c->ws.energy, nullptr, c->stream));   // energy[m_max >= p] as a sink
     return SBO_OK;
 }
 
@@ -392,7 +406,7 @@ static int run_new_base(sbo_ctx* c, const float* Y, int64_t n, int R, int have_q
         const int warm = r % 8 != 0;
         if (c->p <= 64) {
             SBO_HIP(launch_select_accum(c->p, 1, c->s0, Y, n, Q, c->ws, supp, coef, err, c->stream));
-            SBO_HIP(launch_accum_reduce(c->p, 1, n, c->ws, c->ws.M, c->stream));
+            SBO_HIP(launch_accum_reduce(c->p, 1, n, c->ws, c->ws.M, nullptr, nullptr, c->stream));
         } else {
             SBO_HIP(launch_select(c->p, 1, c->s0, Y, n, Q, c->ws, supp, coef, err, c->stream));
             SBO_HIP(launch_accumulate(c->p, 1, c->s0, Y, n, supp, coef, c->ws, c->ws.M, c->stream));
@@ -400,7 +414,7 @@ static int run_new_base(sbo_ctx* c, const float* Y, int64_t n, int R, int have_q
         if (sqerr_per_round)
             SBO_HIP(launch_sqerr(err, c->ws.perm, n, c->ws, sqerr_per_round + r, c->stream));
         SBO_HIP(launch_polar(c->p, 1, c->ws.M, c->ws.counts, Q, c->ws.vstate, warm, c->ws.jac_a,
-                             nullptr, c->stream));
+                             nullptr, nullptr, c->stream));
     }
     return SBO_OK;
 }
@@ -487,7 +501,7 @@ int sbo_learn(sbo_ctx* c, const float* Y, int64_t m, float* D, const int32_t* in
 
 int sbo_set_timing(sbo_ctx* c, int enable) {
     if (!c) return SBO_EINVAL;
-    c->timing = enable ? 1 : 0;
+    c->timing = enable == 2 ? 2 : (enable ? 1 : 0);
     c->n_spans = 0;
     return SBO_OK;
 }

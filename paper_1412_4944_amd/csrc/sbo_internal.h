@@ -17,12 +17,12 @@ constexpr int kWave = 64;
 // One wavefront owns one chunk of consecutive signals; a chunk is a multiple of
 // 64 signals, sized so that there are at most ~1024 chunks.
 struct GroupGeom {
-    int chunk;     // signals per chunk (multiple of 64)
+    int chunk;     // signals per chunk (multiple of 256)
     int n_chunks;  // ceil(m / chunk)
 };
 inline GroupGeom group_geom(int64_t m) {
     int64_t c = (m + 1023) / 1024;
-    c = ((c + 63) / 64) * 64;
+    c = ((c + 255) / 256) * 256;           // whole workgroups of the coding kernel (256 or 128 signals)
     if (c < 512) c = 512;
     GroupGeom g;
     g.chunk = (int)c;
@@ -66,6 +66,16 @@ inline int accum_max_pieces(int64_t m, int K, int p) {
     return (int)((m + piece - 1) / piece) + K;
 }
 
+// ---- Jacobi stopping threshold ---------------------------------------------------
+// A sweep in which every pair already had a cosine below this is the last one.
+inline float polar_done() {
+    if (const char* e = getenv("SBO_POLAR_DONE")) {       // tuning override
+        const float v = (float)atof(e);
+        if (v >= 1e-6f && v <= 1e-1f) return v;
+    }
+    return 1e-4f;
+}
+
 // ---- device workspace layout ---------------------------------------------------
 struct Workspace {
     // grouping
@@ -89,6 +99,7 @@ struct Workspace {
     int32_t* sel_base;     // same shape: exclusive sums of sel_cnt over the chunks
     int32_t* sel_ids;      // [m_max] worst-W set inside sbo_learn
     double* sq_out;        // [1] squared-error total inside sbo_learn
+    int32_t* sq_counter;   // [1] workgroups of the fused squared-error sum that have finished (0 between launches)
     // iterate
     double* sq_partial;    // [kSqBlocks]
     size_t bytes;
@@ -122,10 +133,13 @@ namespace sbo {
 
 // dsw = D rewritten by launch_dict_swizzle into the energy kernel's operand order.
 hipError_t launch_dict_swizzle(int p, int K, const float* D, float* dsw, hipStream_t st);
+// chunk_count != nullptr: also add the per-chunk histograms of the chosen blocks into it (the
+// first step of launch_group; the array must be zero on entry, launch_group leaves it so).
 hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const float* dsw,
-                         int32_t* blk, float* energy, hipStream_t st);
+                         int32_t* blk, float* energy, int32_t* chunk_count, hipStream_t st);
 
-hipError_t launch_group(int K, const int32_t* blk, int64_t m, const Workspace& ws, hipStream_t st);
+hipError_t launch_group(int K, const int32_t* blk, int64_t m, const Workspace& ws, bool have_hist,
+                        hipStream_t st);
 
 hipError_t launch_select(int p, int K, int s0, const float* Y, int64_t m, const float* D,
                          const Workspace& ws, int32_t* supp, float* coef, float* err,
@@ -143,14 +157,18 @@ hipError_t launch_accumulate(int p, int K, int s0, const float* Y, int64_t m, co
 hipError_t launch_select_accum(int p, int K, int s0, const float* Y, int64_t m, const float* D,
                                const Workspace& ws, int32_t* supp, float* coef, float* err,
                                hipStream_t st);
+// err, sq_out != nullptr: the same launch also forms *sq_out = sum of err[0..m).
 hipError_t launch_accum_reduce(int p, int K, int64_t m, const Workspace& ws, float* M,
-                               hipStream_t st);
+                               const float* err, double* sq_out, hipStream_t st);
 
 // eig_sv != nullptr switches to eigen mode: M[j] symmetric positive semidefinite, D[j] receives
 // its eigenvectors as atoms by descending eigenvalue and eig_sv[j][p] the square roots of the
 // eigenvalues.
+// dsw != nullptr (p <= 64): the rows of every updated block are also written into the coding
+// kernel's operand order (what launch_dict_swizzle would produce from the new D).
 hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
-                        float* vstate, int warm, float* jac_a, float* eig_sv, hipStream_t st);
+                        float* vstate, int warm, float* jac_a, float* eig_sv, float* dsw,
+                        hipStream_t st);
 
 // p = 256 variant of launch_polar (polar_wide.hip) and the size of its scratch (working
 // copy of P_j, rotation log, sweep counts).
