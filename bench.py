@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the roofline kernel, from the two rocprofv3 --pmc runs summarised in
 # profiles/headline_hbm_traffic_pmc.txt (FETCH_SIZE x 2.000 KiB + WRITE_SIZE x 1.000 KiB, factors
 # from a 256 MiB plain copy).  Only known for the workload those runs used.
-MEASURED_TRAFFIC_BYTES = {"headline": (70.29 + 2.00) * 1024 * 1024}
+MEASURED_TRAFFIC_BYTES = {"headline": (72.04 + 2.13) * 1024 * 1024}
 
 
 def cpu_baseline(pr, sample_m: int) -> dict:
