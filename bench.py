@@ -63,6 +63,8 @@ def main() -> int:
     ap.add_argument("--workload", default="headline")
     ap.add_argument("--cpu-sample", type=int, default=262144)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-probe", action="store_true",
+                    help="skip the fp32 MFMA loop / device copy probes (achievable peaks)")
     ap.add_argument("--no-next", action="store_true",
                     help="skip the (untimed-region) measurement of worst-W / base initialisation / new base")
     ap.add_argument("--copy-calib", action="store_true",
@@ -101,6 +103,14 @@ def main() -> int:
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    # Achievable peaks on this GPU (bare fp32 MFMA loop, plain device copy), measured first;
+    # they also bring the clocks up.
+    measured = None
+    if not args.no_probe:
+        measured = {"mfma_f32_tflops": sbo.sbo_probe_mfma(150),            # launches of ~0.6 ms, like the kernel's
+                    "mfma_f32_tflops_sustained": sbo.sbo_probe_mfma(4000),  # ~17 ms launches: power-limited
+                    "hbm_copy_GBps": sbo.sbo_probe_copy()}
 
     ctx = sbo.sbo_create(p, K, s0, m)
     # Timed region: HIP events around the roofline kernel only (an event pair per stage costs
@@ -201,6 +211,10 @@ def main() -> int:
                        "frac": upd_bytes / t_upd / 1e9 / PEAK_HBM_GBS},
         "rmse_first_last": [float(np.sqrt(first_sq / (p * m))), float(np.sqrt(last_sq / (p * m)))],
     }
+    if measured is not None:
+        out["measured_peaks"] = measured
+        out["roofline"]["frac_of_measured_peak"] = achieved / measured["mfma_f32_tflops"]
+        out["update_hbm"]["frac_of_measured_copy"] = out["update_hbm"]["achieved_GBps"] / measured["hbm_copy_GBps"]
     if next_rows is not None:
         out["next_rows"] = next_rows
     if not args.no_cpu:

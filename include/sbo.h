@@ -183,6 +183,16 @@ int sbo_learn(sbo_ctx* c, const float* Y, int64_t m, float* D, const int32_t* in
               int64_t P0, int R, int64_t W, int K_max, double target_rmse, int32_t* blk,
               int32_t* supp, float* coef, float* err, int* K_final, double* rmse_hist, int* n_hist);
 
+/* Measurement aids for a benchmark, not part of the path: the rate a bare fp32
+ * v_mfma_f32_32x32x2_f32 loop reaches on this GPU (TFLOP/s; 1024 workgroups of 4 wavefronts,
+ * each issuing 32 * iters MFMAs: iters = 150 is a launch of about 0.6 ms, iters = 4000 one of
+ * about 17 ms, long enough for the power limit to show) and the rate of a plain 256 MiB
+ * device copy (GB/s, bytes read + bytes written), as achievable peaks next to the published
+ * ones.  Each allocates and frees its own scratch and synchronises the stream.
+ * tflops, gbps: HOST pointers. */
+int sbo_probe_mfma(void* hip_stream, int iters, double* tflops);
+int sbo_probe_copy(void* hip_stream, double* gbps);
+
 /* Per-stage timing with HIP events on the context's stream.  enable = 1 makes every
  * later call record events around each stage it runs; enable = 2 only around the energy
  * kernel (an event pair costs a few microseconds on the stream, which shows in a step of

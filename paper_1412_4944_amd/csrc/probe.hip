@@ -1,0 +1,106 @@
+// Measurement aids for the benchmark, not part of the SBO path: what a bare fp32 MFMA loop
+// and a plain device copy reach on this GPU, so that a kernel's rate can be quoted against an
+// achievable peak as well as against the published one.
+#include "sbo_internal.h"
+#include "device_utils.h"
+
+namespace sbo {
+
+namespace {
+
+// 4 independent accumulator tiles per wavefront, nothing but v_mfma_f32_32x32x2_f32.
+__global__ __launch_bounds__(256) void probe_mfma_kernel(float* __restrict__ out, int iters) {
+    f32x16 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    const float a = threadIdx.x * 1e-3f, b = blockIdx.x * 1e-3f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[i], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[i][r];
+    out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+__global__ __launch_bounds__(256) void probe_copy_kernel(const f32x4* __restrict__ src,
+                                                         f32x4* __restrict__ dst, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+        dst[i] = src[i];
+}
+
+struct EventPair {
+    hipEvent_t a = nullptr, b = nullptr;
+    hipError_t init() {
+        hipError_t e = hipEventCreate(&a);
+        if (e != hipSuccess) return e;
+        return hipEventCreate(&b);
+    }
+    ~EventPair() {
+        if (a) (void)hipEventDestroy(a);
+        if (b) (void)hipEventDestroy(b);
+    }
+};
+
+}  // namespace
+
+hipError_t probe_mfma(hipStream_t st, int iters, double* tflops) {
+    constexpr int kWgs = 1024;
+    const int kIters = iters;
+    float* out = nullptr;
+    hipError_t e = hipMalloc(&out, (size_t)kWgs * 256 * sizeof(float));
+    if (e != hipSuccess) return e;
+    EventPair ev;
+    e = ev.init();
+    float best = 0.f;
+    for (int rep = 0; rep < 3 && e == hipSuccess; ++rep) {
+        hipLaunchKernelGGL(probe_mfma_kernel, dim3(kWgs), dim3(256), 0, st, out, rep == 0 ? 200 : kIters);
+        if (rep == 0) continue;                 // warm-up
+        (void)hipEventRecord(ev.a, st);
+        hipLaunchKernelGGL(probe_mfma_kernel, dim3(kWgs), dim3(256), 0, st, out, kIters);
+        (void)hipEventRecord(ev.b, st);
+        e = hipEventSynchronize(ev.b);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev.a, ev.b);
+        const float rate = (float)((double)kWgs * 4 * kIters * 8 * 4 * 4096.0 / (ms * 1e-3) / 1e12);
+        if (rate > best) best = rate;
+    }
+    (void)hipFree(out);
+    *tflops = best;
+    return e;
+}
+
+hipError_t probe_copy(hipStream_t st, double* gbps) {
+    const int64_t n = (int64_t)16 * 1024 * 1024;               // 16-byte units: 256 MiB each way
+    f32x4 *src = nullptr, *dst = nullptr;
+    hipError_t e = hipMalloc(&src, (size_t)n * sizeof(f32x4));
+    if (e == hipSuccess) e = hipMalloc(&dst, (size_t)n * sizeof(f32x4));
+    EventPair ev;
+    if (e == hipSuccess) e = ev.init();
+    if (e == hipSuccess) e = hipMemsetAsync(src, 0, (size_t)n * sizeof(f32x4), st);
+    float best = 0.f;
+    for (int rep = 0; rep < 4 && e == hipSuccess; ++rep) {
+        (void)hipEventRecord(ev.a, st);
+        hipLaunchKernelGGL(probe_copy_kernel, dim3(8192), dim3(256), 0, st, src, dst, n);
+        (void)hipEventRecord(ev.b, st);
+        e = hipEventSynchronize(ev.b);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev.a, ev.b);
+        const float rate = (float)(2.0 * (double)n * sizeof(f32x4) / (ms * 1e-3) / 1e9);
+        if (rep > 0 && rate > best) best = rate;
+    }
+    if (src) (void)hipFree(src);
+    if (dst) (void)hipFree(dst);
+    *gbps = best;
+    return e;
+}
+
+}  // namespace sbo

@@ -499,6 +499,18 @@ int sbo_learn(sbo_ctx* c, const float* Y, int64_t m, float* D, const int32_t* in
     return SBO_OK;
 }
 
+int sbo_probe_mfma(void* hip_stream, int iters, double* tflops) {
+    if (!tflops || iters < 1 || iters > 100000) return SBO_EINVAL;
+    SBO_HIP(probe_mfma((hipStream_t)hip_stream, iters, tflops));
+    return SBO_OK;
+}
+
+int sbo_probe_copy(void* hip_stream, double* gbps) {
+    if (!gbps) return SBO_EINVAL;
+    SBO_HIP(probe_copy((hipStream_t)hip_stream, gbps));
+    return SBO_OK;
+}
+
 int sbo_set_timing(sbo_ctx* c, int enable) {
     if (!c) return SBO_EINVAL;
     c->timing = enable == 2 ? 2 : (enable ? 1 : 0);

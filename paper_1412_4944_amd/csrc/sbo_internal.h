@@ -188,6 +188,10 @@ hipError_t launch_single_block(const int32_t* ids, int64_t n, int64_t m, const W
 hipError_t launch_gram(int p, const float* Y, int64_t n, const Workspace& ws, float* G,
                        hipStream_t st);
 
+// Achievable peaks for the benchmark (probe.hip): bare fp32 MFMA loop, plain device copy (read + write).
+hipError_t probe_mfma(hipStream_t st, int iters, double* tflops);
+hipError_t probe_copy(hipStream_t st, double* gbps);
+
 // ids[0..W) = the W signals with the largest err (ties: lower index), ascending.
 hipError_t launch_worst(const float* err, int64_t m, int64_t W, const Workspace& ws, int32_t* ids,
                         hipStream_t st);
