@@ -277,3 +277,28 @@ def test_errors_are_reported_not_faulted():
         counts, offsets, perm = g.group(b)
         assert counts.tolist() == [1, 1, 100, 1] and offsets[-1] == 103
         torch.cuda.synchronize()
+
+
+def test_largest_K_and_context_reuse():
+    """K = 1024 orthobases (the largest the boundary accepts), most of them empty after
+    coding; and one context (sized for m_max) used for calls with smaller and changing m."""
+    pr = synth.generate(synth.custom("bigK", p=16, K=1024, m=3000, s0=2, snr_db=20.0))
+    cfg = pr.cfg
+    with Sbo(16, 1024, 2, 4000) as g:                     # m_max > every m used below
+        for m in (3000, 777, 2500):
+            Y = pr.Y[:m]
+            o = orc.o_code(Y, pr.D_init, 2)
+            out = g.code(Y, pr.D_init)
+            compare_code(Y, pr.D_init, 2, o, out)
+            blk, supp, coef, _err = out
+            Dg, counts = g.update(Y, blk, supp, coef, pr.D_init)
+            assert np.array_equal(counts, np.bincount(blk, minlength=1024))
+            Dn, M = orc.o_update(Y, blk, supp, coef, pr.D_init)
+            compare_Q(Dg, Dn, M, counts > 0)
+            assert np.array_equal(Dg[counts == 0], pr.D_init[counts == 0]), "an empty block changed"
+        # iterate in the same context, then code again: the fused path must leave the
+        # workspace invariants intact for the call after it
+        Y = pr.Y[:1500]
+        Dg, blk, supp, coef, err, sq = g.iterate(Y, pr.D_init, 2)
+        assert sq[1] <= sq[0] * (1 + 1e-6)
+        compare_code(Y, Dg, 2, orc.o_code(Y, Dg, 2), g.code(Y, Dg))
