@@ -137,6 +137,18 @@ def main() -> int:
     sbo.sbo_iterate(ctx, Y, D_start, args.steps, blk, supp, coef, err, sq)
     torch.cuda.synchronize()
     stage_sum = sbo.sbo_stage_ms(ctx)           # summed over the K iterations
+    sweeps_warm = sbo.sbo_svd_sweeps(ctx, K)    # last iteration of the pass (warm-started Jacobi)
+
+    # a-2 and a-3 on their own (sbo_update: grouping of a given blk, accumulation from given
+    # codes, cold SVD), from the codes of the last pass; outside the timed region.
+    D_upd = D.clone()
+    sbo.sbo_update(ctx, Y, blk, supp, coef, D_upd)
+    D_upd.copy_(D)
+    sbo.sbo_update(ctx, Y, blk, supp, coef, D_upd)
+    torch.cuda.synchronize()
+    upd = sbo.sbo_stage_ms(ctx)
+    sweeps_cold = sbo.sbo_svd_sweeps(ctx, K)
+    del D_upd
 
     # The rows beyond one iteration (outside the timed region): worst-W set, eq. (5)
     # initialisation and a new orthobase trained with R = 6 rounds, on the same workload.
@@ -209,6 +221,14 @@ def main() -> int:
                        "algorithmic_bytes": upd_bytes,
                        "achieved_GBps": upd_bytes / t_upd / 1e9, "peak_GBps": PEAK_HBM_GBS,
                        "frac": upd_bytes / t_upd / 1e9 / PEAK_HBM_GBS},
+        "update_standalone": {"what": "sbo_update: a-2 grouping + a-3 accumulation (+ cold SVD) from given codes",
+                              "group_ms": upd["group"], "accum_ms": upd["accum"], "svd_cold_ms": upd["svd"],
+                              "algorithmic_bytes": m * (4 * p + 8 * s0 + 8) + 4 * K * p * p,
+                              "a2_a3_GBps": (m * (4 * p + 8 * s0 + 8) + 4 * K * p * p) /
+                                            ((upd["group"] + upd["accum"]) * 1e-3) / 1e9,
+                              "a3_GBps": (m * (4 * p + 8 * s0 + 8) + 4 * K * p * p) / (upd["accum"] * 1e-3) / 1e9},
+        "svd_sweeps": {"warm_mean": sum(sweeps_warm) / K, "warm_max": max(sweeps_warm),
+                       "cold_mean": sum(sweeps_cold) / K, "cold_max": max(sweeps_cold)},
         "rmse_first_last": [float(np.sqrt(first_sq / (p * m))), float(np.sqrt(last_sq / (p * m)))],
     }
     if measured is not None:

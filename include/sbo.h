@@ -183,6 +183,10 @@ int sbo_learn(sbo_ctx* c, const float* Y, int64_t m, float* D, const int32_t* in
               int64_t P0, int R, int64_t W, int K_max, double target_rmse, int32_t* blk,
               int32_t* supp, float* coef, float* err, int* K_final, double* rmse_hist, int* n_hist);
 
+/* Jacobi sweeps the most recent SVD stage of this context needed, per orthobase (0 for an
+ * orthobase that kept its basis).  sweeps: HOST int32[K].  Synchronises the stream. */
+int sbo_svd_sweeps(sbo_ctx* c, int32_t* sweeps);
+
 /* Measurement aids for a benchmark, not part of the path: the rate a bare fp32
  * v_mfma_f32_32x32x2_f32 loop reaches on this GPU (TFLOP/s; 1024 workgroups of 4 wavefronts,
  * each issuing 32 * iters MFMAs: iters = 150 is a launch of about 0.6 ms, iters = 4000 one of

@@ -14,7 +14,7 @@ STAGES = ("energy", "group", "select", "accum", "svd")
 
 EXPORTS = ("sbo_create", "sbo_destroy", "sbo_workspace_bytes", "sbo_code", "sbo_group",
            "sbo_accumulate", "sbo_polar", "sbo_update", "sbo_train_rounds", "sbo_iterate", "sbo_sqerr",
-           "sbo_worst", "sbo_init_base", "sbo_new_base", "sbo_set_blocks", "sbo_learn", "sbo_probe_mfma", "sbo_probe_copy", "sbo_set_timing", "sbo_stage_ms", "sbo_strerror")
+           "sbo_worst", "sbo_init_base", "sbo_new_base", "sbo_set_blocks", "sbo_learn", "sbo_svd_sweeps", "sbo_probe_mfma", "sbo_probe_copy", "sbo_set_timing", "sbo_stage_ms", "sbo_strerror")
 
 _lib = None
 
@@ -53,6 +53,7 @@ def lib() -> ctypes.CDLL:
     L.sbo_set_blocks.argtypes = [vp, i32]
     L.sbo_learn.argtypes = [vp, vp, i64, vp, vp, i32, i64, i32, i64, i32, ctypes.c_double, vp, vp, vp, vp,
                             ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
+    L.sbo_svd_sweeps.argtypes = [vp, ctypes.POINTER(ctypes.c_int32)]
     L.sbo_probe_mfma.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double)]
     L.sbo_probe_copy.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
     L.sbo_set_timing.argtypes = [vp, i32]
@@ -196,6 +197,13 @@ def sbo_learn(ctx, Y, D, init_ids, R, W, K_max, target_rmse, blk, supp, coef, er
                            _ptr(coef, torch.float32), _ptr(err, torch.float32), ctypes.byref(kf),
                            hist, ctypes.byref(nh)))
     return kf.value, [hist[i] for i in range(nh.value)]
+
+
+def sbo_svd_sweeps(ctx, K: int) -> list:
+    """Jacobi sweeps per orthobase in the most recent SVD stage (K = blocks in use)."""
+    buf = (ctypes.c_int32 * K)()
+    _check(lib().sbo_svd_sweeps(ctx, buf))
+    return list(buf)
 
 
 def _stream(stream):

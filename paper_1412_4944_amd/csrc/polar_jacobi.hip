@@ -26,7 +26,8 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
                                                              float* __restrict__ D,
                                                              float* __restrict__ Vstate, int warm,
                                                              float* __restrict__ eig_sv, float done,
-                                                             float* __restrict__ dsw) {
+                                                             float* __restrict__ dsw,
+                                                             int32_t* __restrict__ sweeps_out) {
     constexpr int LD = P + 4;
     constexpr int NT = (P / 2) * TPP;          // threads: TPP lanes per column pair
     constexpr int RPT = P / TPP;               // contiguous rows per lane in a rotation
@@ -47,6 +48,7 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
         if (Vstate != nullptr && !warm)                 // a cold pass defines every block's V
             for (int e = tid; e < P * P; e += NT)
                 Vstate[(int64_t)j * P * P + e] = (e / P == e % P) ? 1.f : 0.f;
+        if (sweeps_out != nullptr && tid == 0) sweeps_out[j] = 0;
         return;
     }
 
@@ -98,6 +100,7 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
     // meets columns ca, cb, which advance by one (mod P-1) every round.
     const int pi = tid / TPP, sub = tid % TPP;
     const int r0 = sub * RPT;
+    int sweeps_done = 0;
     for (int sweep = 0; sweep < kMaxSweeps; ++sweep) {
         int rotated = 0;
         int ca = pi == 0 ? P - 1 : pi;
@@ -193,8 +196,10 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
             }
             __syncthreads();
         }
+        sweeps_done = sweep + 1;
         if (!__syncthreads_or(rotated)) break;
     }
+    if (sweeps_out != nullptr && tid == 0) sweeps_out[j] = sweeps_done;
 
     // Singular values = column norms; U = A diag(1/sigma).
     // The accumulated rotations leave V orthogonal but let its column norms drift by a few
@@ -335,12 +340,12 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
 
 template <int TPP>
 hipError_t launch_tpp(int p, int K, const float* M, const int32_t* counts, float* D, float* vstate,
-                      int warm, float* eig_sv, float* dsw, hipStream_t st) {
+                      int warm, float* eig_sv, float* dsw, int32_t* sweeps, hipStream_t st) {
     const float done = polar_done();
     switch (p) {
-        case 16: hipLaunchKernelGGL((polar_kernel<16, TPP>), dim3(K), dim3(8 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv, done, dsw); break;
-        case 32: hipLaunchKernelGGL((polar_kernel<32, TPP>), dim3(K), dim3(16 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv, done, dsw); break;
-        case 64: hipLaunchKernelGGL((polar_kernel<64, TPP>), dim3(K), dim3(32 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv, done, dsw); break;
+        case 16: hipLaunchKernelGGL((polar_kernel<16, TPP>), dim3(K), dim3(8 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv, done, dsw, sweeps); break;
+        case 32: hipLaunchKernelGGL((polar_kernel<32, TPP>), dim3(K), dim3(16 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv, done, dsw, sweeps); break;
+        case 64: hipLaunchKernelGGL((polar_kernel<64, TPP>), dim3(K), dim3(32 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv, done, dsw, sweeps); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -348,16 +353,16 @@ hipError_t launch_tpp(int p, int K, const float* M, const int32_t* counts, float
 
 hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
                         float* vstate, int warm, float* jac_a, float* eig_sv, float* dsw,
-                        hipStream_t st) {
+                        int32_t* sweeps, hipStream_t st) {
     if (p == 256) {
         if (dsw != nullptr) return hipErrorInvalidValue;   // p = 256 rewrites the operand order itself
-        return launch_polar_wide(K, M, counts, D, vstate, warm, jac_a, eig_sv, st);
+        return launch_polar_wide(K, M, counts, D, vstate, warm, jac_a, eig_sv, sweeps, st);
     }
     int tpp = 16;
     if (const char* e = getenv("SBO_POLAR_TPP")) tpp = atoi(e);   // tuning override
-    if (tpp == 4) return launch_tpp<4>(p, K, M, counts, D, vstate, warm, eig_sv, dsw, st);
-    if (tpp == 8) return launch_tpp<8>(p, K, M, counts, D, vstate, warm, eig_sv, dsw, st);
-    return launch_tpp<16>(p, K, M, counts, D, vstate, warm, eig_sv, dsw, st);
+    if (tpp == 4) return launch_tpp<4>(p, K, M, counts, D, vstate, warm, eig_sv, dsw, sweeps, st);
+    if (tpp == 8) return launch_tpp<8>(p, K, M, counts, D, vstate, warm, eig_sv, dsw, sweeps, st);
+    return launch_tpp<16>(p, K, M, counts, D, vstate, warm, eig_sv, dsw, sweeps, st);
 }
 
 }  // namespace sbo

@@ -64,7 +64,8 @@ __device__ __forceinline__ void pair_next(int pi, int& ca, int& cb) {
 __global__ __launch_bounds__(1024) void wide_jacobi_kernel(const float* __restrict__ M,
                                                            const int32_t* __restrict__ counts,
                                                            const float* __restrict__ Vst, int warm,
-                                                           float* scratch, int K, float done) {
+                                                           float* scratch, int K, float done,
+                                                           int32_t* __restrict__ sweeps_out) {
     constexpr int NT = 1024;
     constexpr int TPP = 8;
     constexpr int RPT = P / TPP;               // 32 rows per lane: 16 on chip, 16 in global memory
@@ -77,7 +78,10 @@ __global__ __launch_bounds__(1024) void wide_jacobi_kernel(const float* __restri
     const int j = blockIdx.x;
     const int tid = threadIdx.x;
     if (counts != nullptr && counts[j] == 0) { // uniform: block keeps its basis
-        if (tid == 0) ws.nsweeps[j] = 0;
+        if (tid == 0) {
+            ws.nsweeps[j] = 0;
+            if (sweeps_out != nullptr) sweeps_out[j] = 0;
+        }
         return;
     }
     float* A = ws.A + (int64_t)j * P * P;      // column c = A[c*P .. c*P+P); rows >= 128 used here
@@ -210,7 +214,10 @@ __global__ __launch_bounds__(1024) void wide_jacobi_kernel(const float* __restri
         sweeps_done = sweep + 1;
         if (!__syncthreads_or(rotated)) break;
     }
-    if (tid == 0) ws.nsweeps[j] = sweeps_done;
+    if (tid == 0) {
+        ws.nsweeps[j] = sweeps_done;
+        if (sweeps_out != nullptr) sweeps_out[j] = sweeps_done;
+    }
 
     // the on-chip rows go back next to the others for the finishing kernel
     for (int o = tid; o < P * kRowsLds / 4; o += NT) {
@@ -440,7 +447,7 @@ size_t polar_wide_scratch_bytes(int K) {
 }
 
 hipError_t launch_polar_wide(int K, const float* M, const int32_t* counts, float* D, float* vstate,
-                             int warm, float* jac_a, float* eig_sv, hipStream_t st) {
+                             int warm, float* jac_a, float* eig_sv, int32_t* sweeps, hipStream_t st) {
     if (vstate == nullptr || jac_a == nullptr) return hipErrorInvalidValue;
     const size_t lds = (size_t)P * LDA * sizeof(float);
     static bool raised = false;
@@ -451,7 +458,7 @@ hipError_t launch_polar_wide(int K, const float* M, const int32_t* counts, float
         raised = true;
     }
     hipLaunchKernelGGL(wide_jacobi_kernel, dim3(K), dim3(1024), lds, st, M, counts, vstate, warm, jac_a, K,
-                       polar_done());
+                       polar_done(), sweeps);
     hipLaunchKernelGGL(wide_replay_kernel, dim3(K, P / (4 * kReplayRows)), dim3(256), 0, st, counts,
                        vstate, warm, jac_a, K);
     hipLaunchKernelGGL(wide_finish_kernel, dim3(K), dim3(1024), 0, st, M, counts, D, vstate, jac_a, K,

@@ -45,6 +45,7 @@ size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char
     w.sel_ids = (int32_t*)take((size_t)m_max * 4);
     w.sq_out = (double*)take(8);
     w.sq_counter = (int32_t*)take(4);
+    w.sweeps = (int32_t*)take((size_t)K * 4);
     w.sq_partial = (double*)take((size_t)kSqBlocks * 8);
     w.bytes = off;
     if (ws) *ws = w;
@@ -137,7 +138,7 @@ static int run_update_grouped(sbo_ctx* c, const float* Y, int64_t m, const int32
     }
     {
         StageTimer t(c, SBO_STAGE_SVD);
-        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, vstate, warm, c->ws.jac_a, nullptr, nullptr, c->stream));
+        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, vstate, warm, c->ws.jac_a, nullptr, nullptr, c->ws.sweeps, c->stream));
     }
     return SBO_OK;
 }
@@ -248,7 +249,7 @@ int sbo_polar(sbo_ctx* c, const float* M, const int32_t* counts, float* D) {
     c->n_spans = 0;
     StageTimer t(c, SBO_STAGE_SVD);
     SBO_HIP(launch_polar(c->p, c->K, M, counts, D, c->p > 64 ? c->ws.vstate : nullptr, 0, c->ws.jac_a,
-                         nullptr, nullptr, c->stream));
+                         nullptr, nullptr, c->ws.sweeps, c->stream));
     return SBO_OK;
 }
 
@@ -310,7 +311,7 @@ int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter, int
         {
             StageTimer t(c, SBO_STAGE_SVD);
             SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws.vstate, warm,
-                                 c->ws.jac_a, nullptr, c->ws.dsw, c->stream));
+                                 c->ws.jac_a, nullptr, c->ws.dsw, c->ws.sweeps, c->stream));
         }
     }
     return SBO_OK;
@@ -340,7 +341,7 @@ static int run_train_rounds(sbo_ctx* c, const float* Y, int64_t m, const int32_t
         }
         StageTimer t(c, SBO_STAGE_SVD);
         SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws.vstate, warm, c->ws.jac_a,
-                             nullptr, nullptr, c->stream));
+                             nullptr, nullptr, c->ws.sweeps, c->stream));
     }
     return SBO_OK;
 }
@@ -380,7 +381,7 @@ int sbo_worst(sbo_ctx* c, const float* err, int64_t m, int64_t W, int32_t* ids) 
 static int run_init_base(sbo_ctx* c, const float* Y, int64_t n, float* Q, float* sv) {
     SBO_HIP(launch_gram(c->p, Y, n, c->ws, c->ws.M, c->stream));
     SBO_HIP(launch_polar(c->p, 1, c->ws.M, nullptr, Q, c->ws.vstate, 0, c->ws.jac_a,
-                         sv ? sv : c->ws.energy, nullptr, c->stream));   // energy[m_max >= p] as a sink
+                         sv ? sv : c->ws.energy, nullptr, c->ws.sweeps, c->stream));   // energy[m_max >= p] as a sink
     return SBO_OK;
 }
 
@@ -414,7 +415,7 @@ static int run_new_base(sbo_ctx* c, const float* Y, int64_t n, int R, int have_q
         if (sqerr_per_round)
             SBO_HIP(launch_sqerr(err, c->ws.perm, n, c->ws, sqerr_per_round + r, c->stream));
         SBO_HIP(launch_polar(c->p, 1, c->ws.M, c->ws.counts, Q, c->ws.vstate, warm, c->ws.jac_a,
-                             nullptr, nullptr, c->stream));
+                             nullptr, nullptr, c->ws.sweeps, c->stream));
     }
     return SBO_OK;
 }
@@ -496,6 +497,13 @@ int sbo_learn(sbo_ctx* c, const float* Y, int64_t m, float* D, const int32_t* in
     *K_final = K;
     *n_hist = n;
     c->K = K_before;
+    return SBO_OK;
+}
+
+int sbo_svd_sweeps(sbo_ctx* c, int32_t* sweeps) {
+    if (!c || !sweeps) return SBO_EINVAL;
+    SBO_HIP(hipMemcpyAsync(sweeps, c->ws.sweeps, (size_t)c->K * 4, hipMemcpyDeviceToHost, c->stream));
+    SBO_HIP(hipStreamSynchronize(c->stream));
     return SBO_OK;
 }
 

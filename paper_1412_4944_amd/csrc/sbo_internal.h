@@ -99,6 +99,7 @@ struct Workspace {
     int32_t* sel_base;     // same shape: exclusive sums of sel_cnt over the chunks
     int32_t* sel_ids;      // [m_max] worst-W set inside sbo_learn
     double* sq_out;        // [1] squared-error total inside sbo_learn
+    int32_t* sweeps;       // [K] Jacobi sweeps of the most recent SVD stage
     int32_t* sq_counter;   // [1] workgroups of the fused squared-error sum that have finished (0 between launches)
     // iterate
     double* sq_partial;    // [kSqBlocks]
@@ -168,13 +169,13 @@ hipError_t launch_accum_reduce(int p, int K, int64_t m, const Workspace& ws, flo
 // kernel's operand order (what launch_dict_swizzle would produce from the new D).
 hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
                         float* vstate, int warm, float* jac_a, float* eig_sv, float* dsw,
-                        hipStream_t st);
+                        int32_t* sweeps, hipStream_t st);   // sweeps: [K] Jacobi sweeps used, may be nullptr
 
 // p = 256 variant of launch_polar (polar_wide.hip) and the size of its scratch (working
 // copy of P_j, rotation log, sweep counts).
 size_t polar_wide_scratch_bytes(int K);
 hipError_t launch_polar_wide(int K, const float* M, const int32_t* counts, float* D, float* vstate,
-                             int warm, float* jac_a, float* eig_sv, hipStream_t st);
+                             int warm, float* jac_a, float* eig_sv, int32_t* sweeps, hipStream_t st);
 
 // ids == nullptr: sum over all m signals; otherwise over the m listed ones.
 hipError_t launch_sqerr(const float* err, const int32_t* ids, int64_t m, const Workspace& ws,
