@@ -150,6 +150,17 @@ def main() -> int:
     sweeps_cold = sbo.sbo_svd_sweeps(ctx, K)
     del D_upd
 
+    # Representation only (sbo_code with a fixed dictionary: the paper's t_rep operation).
+    sbo.sbo_set_timing(ctx, 0)
+    code_ms = float("inf")
+    for _ in range(3):
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        sbo.sbo_code(ctx, Y, D, blk, supp, coef, err)
+        ev1.record()
+        torch.cuda.synchronize()
+        code_ms = min(code_ms, ev0.elapsed_time(ev1))
+
     # The rows beyond one iteration (outside the timed region): worst-W set, eq. (5)
     # initialisation and a new orthobase trained with R = 6 rounds, on the same workload.
     next_rows = None
@@ -227,6 +238,7 @@ def main() -> int:
                               "a2_a3_GBps": (m * (4 * p + 8 * s0 + 8) + 4 * K * p * p) /
                                             ((upd["group"] + upd["accum"]) * 1e-3) / 1e9,
                               "a3_GBps": (m * (4 * p + 8 * s0 + 8) + 4 * K * p * p) / (upd["accum"] * 1e-3) / 1e9},
+        "code_only_ms": code_ms,
         "svd_sweeps": {"warm_mean": sum(sweeps_warm) / K, "warm_max": max(sweeps_warm),
                        "cold_mean": sum(sweeps_cold) / K, "cold_max": max(sweeps_cold)},
         "rmse_first_last": [float(np.sqrt(first_sq / (p * m))), float(np.sqrt(last_sq / (p * m)))],
