@@ -66,3 +66,75 @@ def test_full_size_iteration_against_oracle(name, n_sample):
         # first update of the free run equals the teacher-forced update just checked
         o2 = orc.o_code(pr.Y[ids], Dg, cfg.s0)
         compare_code(pr.Y[ids], Dg, cfg.s0, o2, (b2[ids], s2[ids], c2[ids], e2[ids]))
+
+
+def test_full_size_next_rows_headline():
+    """Worst-W set, base initialisation and a new orthobase at the headline size, in the
+    shapes bench.py times (W = 4096, R = 6), plus the worst-W set of a million residuals."""
+    from test_gpu_next_rows import _check_init_base
+    cfg = synth.CONFIGS["headline"]
+    print(f"case headline next rows: p={cfg.p} K={cfg.K} m={cfg.m}: generating", flush=True)
+    pr = synth.generate(cfg)
+    m, W, R = pr.Y.shape[0], 4096, 6
+    with Sbo(cfg.p, cfg.K, cfg.s0, m) as g:
+        blk, supp, coef, err = g.code(pr.Y, pr.D_init)
+        print("  worst-W set", flush=True)
+        ids = g.worst(err, W)
+        assert np.array_equal(ids, orc.o_worst(err, W))
+        for W2 in (1, 65536, m):
+            assert np.array_equal(g.worst(err, W2), orc.o_worst(err, W2))
+        print("  base initialisation on the worst set", flush=True)
+        Qg, svg = g.init_base(pr.Y, ids)
+        checked, worst = _check_init_base(pr.Y, ids, Qg, svg)
+        print(f"  {checked}/{cfg.p} atoms compared, worst {worst:.2e}", flush=True)
+        print("  new orthobase, R = 6", flush=True)
+        Qn, s2, c2, e2, sq = g.new_base(pr.Y, ids, R)
+        Q = Qn.astype(np.float64)
+        assert np.abs(Q @ Q.T - np.eye(cfg.p)).max() <= 1e-5
+        assert (np.diff(sq) <= 1e-6 * sq[0]).all()
+        _Qo, sqo = orc.o_new_base(pr.Y, ids, cfg.s0, R)
+        assert np.abs(sq - sqo).max() <= 2e-3 * sqo[0], (sq, sqo)
+        # the codes left in the set's rows are the last round's: check them against the oracle's
+        # coding with the orthobase that round started from (one more single round from Qn's parent
+        # is not available, so check consistency instead: Parseval and ascending supports)
+        n2 = (pr.Y[ids].astype(np.float64) ** 2).sum(1)
+        kept = (c2[ids].astype(np.float64) ** 2).sum(1)
+        assert (np.abs(n2 - kept - e2[ids]) <= 1e-4 * n2 + 1e-30).all()
+        assert (np.diff(s2[ids], axis=1) > 0).all()
+    rng = np.random.default_rng(9)
+    big = (rng.random(1 << 20) ** 3).astype(np.float32)
+    big[rng.integers(0, 1 << 20, 5000)] = big[17]
+    with Sbo(16, 2, 2, 1 << 20) as g:
+        for W2 in (1000, 300000):
+            assert np.array_equal(g.worst(big, W2), orc.o_worst(big, W2))
+
+
+def test_full_size_learn_patch8():
+    """Algorithm 2 as a whole at the 8x8-patch size with the paper's Table 2 parameters
+    (K0 = 5, R = 6), free-running against the oracle."""
+    import torch
+    import paper_1412_4944_amd as sbo
+    cfg = synth.CONFIGS["patch8"]
+    pr = synth.generate(cfg)
+    m, p, s0 = pr.Y.shape[0], cfg.p, cfg.s0
+    K0, P0, R, W, K_max = 5, 2048, 6, 1024, 8
+    rng = np.random.default_rng(47)
+    sets = np.stack([np.sort(rng.choice(m, P0, replace=False)) for _ in range(K0)]).astype(np.int32)
+    print("  oracle", flush=True)
+    Do, _blk, hist_o = orc.o_learn(pr.Y, s0, list(sets), R, W, K_max)
+    print(f"  oracle history {hist_o}", flush=True)
+    with Sbo(p, K_max, s0, m) as g:
+        t = g.torch
+        D = t.zeros((K_max, p, p), dtype=t.float32, device=g.dev)
+        blk, supp, coef, err = g.outputs(m)
+        Kf, hist = sbo.sbo_learn(g.ctx, g.dev_f32(pr.Y), D, g.dev_i32(sets), R, W, K_max, 0.0, blk, supp,
+                                 coef, err)
+        t.cuda.synchronize()
+        hist = np.array(hist)
+        print(f"  gpu history {hist}", flush=True)
+        assert Kf == K_max and hist.size == hist_o.size
+        assert (np.diff(hist) <= 1e-6 * hist[0]).all()
+        assert np.abs(hist - hist_o).max() <= 1e-2 * hist_o[0]
+        Dg = D.cpu().numpy().astype(np.float64)
+        for j in range(Kf):
+            assert np.abs(Dg[j] @ Dg[j].T - np.eye(p)).max() <= 1e-5
