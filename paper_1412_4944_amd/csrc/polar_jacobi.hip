@@ -103,14 +103,16 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
     int sweeps_done = 0;
     for (int sweep = 0; sweep < kMaxSweeps; ++sweep) {
         int rotated = 0;
-        int ca = pi == 0 ? P - 1 : pi;
-        int cb = pi == 0 ? 0 : P - 1 - pi;
+        // columns as LDS offsets (column * LD), advanced by additions only
+        constexpr int WRAP = (P - 1) * LD;
+        int oa = (pi == 0 ? P - 1 : pi) * LD;
+        int ob = (pi == 0 ? 0 : P - 1 - pi) * LD;
         for (int step = 0; step < P - 1; ++step) {
-            const int ci = min(ca, cb), cj = max(ca, cb);
-            float* ai = A + ci * LD + r0;
-            float* aj = A + cj * LD + r0;
-            float* vi = V + ci * LD + r0;
-            float* vj = V + cj * LD + r0;
+            const int oi = min(oa, ob), oj = max(oa, ob);
+            float* ai = A + oi + r0;
+            float* aj = A + oj + r0;
+            float* vi = V + oi + r0;
+            float* vj = V + oj + r0;
             float x[RPT], y[RPT], vx[RPT], vy[RPT];
             if constexpr (RPT % 4 == 0) {
 #pragma unroll
@@ -188,11 +190,10 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
                     }
                 }
             }
-            if (pi == 0) {
-                cb = cb + 1;                   // 0, 1, ..., P-2
-            } else {
-                ca = ca + 1 == P - 1 ? 0 : ca + 1;
-                cb = cb + 1 == P - 1 ? 0 : cb + 1;
+            {
+                const int na = oa + LD, nb = ob + LD;
+                oa = pi == 0 ? oa : (na == WRAP ? 0 : na);        // player P-1 stays
+                ob = (pi == 0 || nb != WRAP) ? nb : 0;            // pi == 0: 0, 1, ..., P-2
             }
             __syncthreads();
         }
