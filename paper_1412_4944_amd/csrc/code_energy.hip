@@ -137,7 +137,8 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
                                                      const f32x4* __restrict__ Dsw, int K, int s0,
                                                      int32_t* __restrict__ blk,
                                                      float* __restrict__ energy,
-                                                     int32_t* __restrict__ chunk_count, int chunk) {
+                                                     int32_t* __restrict__ chunk_count, int chunk,
+                                                     int units_per_y) {
     constexpr int KS = P / 2;            // contraction steps (each lane half covers P/2 dims)
     constexpr int QN = P / 8;            // 16-byte groups of steps per 32-row tile
     constexpr int NB = P <= 64 ? 64 / P : 1;   // blocks per 64-row stage (p <= 64)
@@ -177,7 +178,18 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
         }
     }
 
+    // Small m: the blocks are split over blockIdx.y (units_per_y > 0: that many stages, for
+    // p > 64 that many blocks, per workgroup row), so that the chip is filled; every row then
+    // writes its own best (energy, block) per signal at offset blockIdx.y * m and
+    // energy_merge_kernel picks the winner.
     const int n_stage = (K * P + 63) / 64;
+    int s_beg = 0, s_end = n_stage;
+    if (units_per_y > 0) {
+        s_beg = min(n_stage, (int)blockIdx.y * units_per_y * SPB);
+        s_end = min(n_stage, s_beg + units_per_y * SPB);
+        blk += (int64_t)blockIdx.y * m;
+        energy += (int64_t)blockIdx.y * m;
+    }
 
     f32x4 pre[FPT];
     auto fetch = [&](int s) {
@@ -189,8 +201,10 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
         for (int r = 0; r < FPT; ++r) Qs[buf][tid + 256 * r] = pre[r];
     };
 
-    fetch(0);
-    stash(0);
+    if (s_beg < s_end) {                 // uniform
+        fetch(s_beg);
+        stash(0);
+    }
     __syncthreads();
 
     int best[NT];
@@ -204,9 +218,9 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
         for (int i = 0; i < S; ++i) run[nt][i] = 0.f;
     }
 
-    for (int s = 0; s < n_stage; ++s) {
-        const int cur = s & 1;
-        if (s + 1 < n_stage) fetch(s + 1);
+    for (int s = s_beg; s < s_end; ++s) {
+        const int cur = (s - s_beg) & 1;
+        if (s + 1 < s_end) fetch(s + 1);
 
         f32x16 acc[NT][2];
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
@@ -227,7 +241,7 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
                             0, 0, 0);
         }
 
-        if (s + 1 < n_stage) stash(cur ^ 1);
+        if (s + 1 < s_end) stash(cur ^ 1);
 
         if constexpr (P <= 64) {
 #pragma unroll
@@ -310,9 +324,48 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
     }
 }
 
+// Winner over the rows of a split launch: part_E / part_j hold, per row y, the best energy
+// and block of the row's share of the blocks (rows in ascending block order, so the strict
+// comparison keeps the lowest block among equal energies).  Also the grouping histogram
+// (see energy_kernel).
+__global__ __launch_bounds__(256) void energy_merge_kernel(const float* __restrict__ part_E,
+                                                           const int32_t* __restrict__ part_j,
+                                                           int rows, int m, int K,
+                                                           int32_t* __restrict__ blk,
+                                                           float* __restrict__ energy,
+                                                           int32_t* __restrict__ chunk_count,
+                                                           int chunk) {
+    extern __shared__ int lh[];          // [K]
+    const int tid = threadIdx.x;
+    const int i = blockIdx.x * 256 + tid;
+    int best = 0;
+    float bestE = -1.f;
+    if (i < m) {
+        for (int y = 0; y < rows; ++y) {
+            const float e = part_E[(int64_t)y * m + i];
+            if (e > bestE) {
+                bestE = e;
+                best = part_j[(int64_t)y * m + i];
+            }
+        }
+        blk[i] = best;
+        energy[i] = bestE;
+    }
+    if (chunk_count != nullptr) {        // uniform
+        for (int j = tid; j < K; j += 256) lh[j] = 0;
+        __syncthreads();
+        if (i < m) atomicAdd(&lh[best], 1);
+        __syncthreads();
+        const int64_t c = ((int64_t)blockIdx.x * 256) / chunk;
+        for (int j = tid; j < K; j += 256)
+            if (lh[j] != 0) atomicAdd(&chunk_count[c * K + j], lh[j]);
+    }
+}
+
 template <int P, int S, bool EXACT>
 hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, float* energy,
-                      const f32x4* Dsw, int32_t* chunk_count, hipStream_t st) {
+                      const f32x4* Dsw, int32_t* chunk_count, float* part_E, int32_t* part_j,
+                      hipStream_t st) {
     constexpr int NT = P <= 64 ? 2 : 1;
     constexpr int QN = P / 8;
     constexpr size_t lds = (size_t)2 * (2 * QN * 64) * sizeof(f32x4);
@@ -330,27 +383,47 @@ hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, fl
     }
     const int chunk = group_geom(m).chunk;
     if (chunk % per_wg != 0) return hipErrorInvalidValue;
+    // Fewer workgroups than CUs: split the blocks over a second grid dimension.
+    const int units = P <= 64 ? (K * P + 63) / 64 : K;     // stages (p <= 64) or blocks
+    const int rows_wanted = (int)grid.x >= kEnergySplitBelow ? 1
+                                                             : (2 * kNumCU + (int)grid.x - 1) / (int)grid.x;
+    int rows = rows_wanted < units ? rows_wanted : units;
+    if (rows > kEnergySplitRows) rows = kEnergySplitRows;
+    if (rows > 1 && part_E != nullptr && part_j != nullptr && m <= kEnergySplitSignals) {
+        const int units_per_y = (units + rows - 1) / rows;
+        rows = (units + units_per_y - 1) / units_per_y;
+        grid.y = rows;
+        hipLaunchKernelGGL((energy_kernel<P, S, NT, EXACT>), grid, dim3(256), lds, st, Y, (int)m, Dsw,
+                           K, s0, part_j, part_E, nullptr, chunk, units_per_y);
+        hipLaunchKernelGGL(energy_merge_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256),
+                           (size_t)K * sizeof(int), st, part_E, part_j, rows, (int)m, K, blk, energy,
+                           chunk_count, chunk);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL((energy_kernel<P, S, NT, EXACT>), grid, dim3(256), lds, st, Y, (int)m, Dsw, K,
-                       s0, blk, energy, chunk_count, chunk);
+                       s0, blk, energy, chunk_count, chunk, 0);
     return hipGetLastError();
 }
 
 template <int P, int S>
 hipError_t launch_ps(const float* Y, int64_t m, int K, int s0, int32_t* blk, float* energy,
-                     const float* dsw, int32_t* chunk_count, hipStream_t st) {
+                     const float* dsw, int32_t* chunk_count, float* part_E, int32_t* part_j,
+                     hipStream_t st) {
     const f32x4* Dsw = reinterpret_cast<const f32x4*>(dsw);
-    if (s0 == S) return launch_pse<P, S, true>(Y, m, K, s0, blk, energy, Dsw, chunk_count, st);
-    return launch_pse<P, S, false>(Y, m, K, s0, blk, energy, Dsw, chunk_count, st);
+    if (s0 == S)
+        return launch_pse<P, S, true>(Y, m, K, s0, blk, energy, Dsw, chunk_count, part_E, part_j, st);
+    return launch_pse<P, S, false>(Y, m, K, s0, blk, energy, Dsw, chunk_count, part_E, part_j, st);
 }
 
 template <int P>
 hipError_t launch_p(int s0, const float* Y, int64_t m, int K, int32_t* blk, float* energy,
-                    const float* dsw, int32_t* chunk_count, hipStream_t st) {
-    if (s0 <= 1) return launch_ps<P, 1>(Y, m, K, s0, blk, energy, dsw, chunk_count, st);
-    if (s0 <= 2) return launch_ps<P, 2>(Y, m, K, s0, blk, energy, dsw, chunk_count, st);
-    if (s0 <= 4) return launch_ps<P, 4>(Y, m, K, s0, blk, energy, dsw, chunk_count, st);
-    if (s0 <= 8) return launch_ps<P, 8>(Y, m, K, s0, blk, energy, dsw, chunk_count, st);
-    return launch_ps<P, 16>(Y, m, K, s0, blk, energy, dsw, chunk_count, st);
+                    const float* dsw, int32_t* chunk_count, float* part_E, int32_t* part_j,
+                    hipStream_t st) {
+    if (s0 <= 1) return launch_ps<P, 1>(Y, m, K, s0, blk, energy, dsw, chunk_count, part_E, part_j, st);
+    if (s0 <= 2) return launch_ps<P, 2>(Y, m, K, s0, blk, energy, dsw, chunk_count, part_E, part_j, st);
+    if (s0 <= 4) return launch_ps<P, 4>(Y, m, K, s0, blk, energy, dsw, chunk_count, part_E, part_j, st);
+    if (s0 <= 8) return launch_ps<P, 8>(Y, m, K, s0, blk, energy, dsw, chunk_count, part_E, part_j, st);
+    return launch_ps<P, 16>(Y, m, K, s0, blk, energy, dsw, chunk_count, part_E, part_j, st);
 }
 
 }  // namespace
@@ -369,12 +442,13 @@ hipError_t launch_dict_swizzle(int p, int K, const float* D, float* dsw, hipStre
 }
 
 hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const float* dsw,
-                         int32_t* blk, float* energy, int32_t* chunk_count, hipStream_t st) {
+                         int32_t* blk, float* energy, int32_t* chunk_count, float* part_E,
+                         int32_t* part_j, hipStream_t st) {
     switch (p) {
-        case 16: return launch_p<16>(s0, Y, m, K, blk, energy, dsw, chunk_count, st);
-        case 32: return launch_p<32>(s0, Y, m, K, blk, energy, dsw, chunk_count, st);
-        case 64: return launch_p<64>(s0, Y, m, K, blk, energy, dsw, chunk_count, st);
-        case 256: return launch_p<256>(s0, Y, m, K, blk, energy, dsw, chunk_count, st);
+        case 16: return launch_p<16>(s0, Y, m, K, blk, energy, dsw, chunk_count, part_E, part_j, st);
+        case 32: return launch_p<32>(s0, Y, m, K, blk, energy, dsw, chunk_count, part_E, part_j, st);
+        case 64: return launch_p<64>(s0, Y, m, K, blk, energy, dsw, chunk_count, part_E, part_j, st);
+        case 256: return launch_p<256>(s0, Y, m, K, blk, energy, dsw, chunk_count, part_E, part_j, st);
         default: return hipErrorInvalidValue;
     }
 }

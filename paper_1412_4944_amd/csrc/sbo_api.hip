@@ -33,6 +33,9 @@ size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char
     w.perm = (int32_t*)take((size_t)m_max * 4);
     w.energy = (float*)take((size_t)m_max * 4);
     w.dsw = (float*)take((size_t)((K * p + 63) / 64) * 64 * p * 4);
+    const size_t split_m = (size_t)(m_max < kEnergySplitSignals ? m_max : kEnergySplitSignals);
+    w.part_E = (float*)take((size_t)kEnergySplitRows * split_m * 4);
+    w.part_j = (int32_t*)take((size_t)kEnergySplitRows * split_m * 4);
     w.partial = (float*)take((size_t)max_pieces_bound(m_max, K, p) * p * p * 4);
     w.M = (float*)take((size_t)K * p * p * 4);
     w.vstate = (float*)take((size_t)K * p * p * 4);
@@ -118,7 +121,7 @@ static int run_code(sbo_ctx* c, const float* Y, int64_t m, const float* D, int32
     {
         StageTimer t(c, SBO_STAGE_ENERGY);
         SBO_HIP(launch_energy(c->p, c->K, c->s0, Y, m, c->ws.dsw, blk, c->ws.energy,
-                              c->ws.chunk_count, c->stream));
+                              c->ws.chunk_count, c->ws.part_E, c->ws.part_j, c->stream));
     }
     int rc = run_group(c, blk, m, true);       // the energy kernel left the chunk histograms
     if (rc) return rc;
@@ -295,7 +298,7 @@ int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter, int
         {
             StageTimer t(c, SBO_STAGE_ENERGY);  // also leaves the chunk histograms of the grouping
             SBO_HIP(launch_energy(c->p, c->K, c->s0, Y, m, c->ws.dsw, blk, c->ws.energy,
-                                  c->ws.chunk_count, c->stream));
+                                  c->ws.chunk_count, c->ws.part_E, c->ws.part_j, c->stream));
         }
         rc = run_group(c, blk, m, true);
         if (rc) return rc;

@@ -87,6 +87,8 @@ struct Workspace {
     // coding
     float* energy;         // [m_max] kept energy in the winning block
     float* dsw;            // [ceil(K*p/64)*64][p] dictionary in MFMA operand order
+    float* part_E;         // [kEnergySplitRows][min(m_max, kEnergySplitSignals)] split coding: best energy per row
+    int32_t* part_j;       // same shape: its block
     // accumulation
     float* partial;        // [max_pieces][p][p]
     float* M;              // [K][p][p]
@@ -106,6 +108,9 @@ struct Workspace {
     size_t bytes;
 };
 constexpr int kSqBlocks = 256;
+constexpr int kEnergySplitBelow = 192;       // coding launches with fewer workgroups split the blocks
+constexpr int kEnergySplitRows = 16;         // at most this many workgroup rows
+constexpr int kEnergySplitSignals = 49152;   // and only up to this many signals (scratch size)
 constexpr int kSelChunk = 2048;              // signals per workgroup in the worst-W compaction
 
 size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char* base);
@@ -136,8 +141,11 @@ namespace sbo {
 hipError_t launch_dict_swizzle(int p, int K, const float* D, float* dsw, hipStream_t st);
 // chunk_count != nullptr: also add the per-chunk histograms of the chosen blocks into it (the
 // first step of launch_group; the array must be zero on entry, launch_group leaves it so).
+// part_E / part_j ([kEnergySplitRows][min(m_max, kEnergySplitSignals)], may be nullptr): scratch
+// for small m, where the blocks are split over several workgroup rows to fill the chip.
 hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const float* dsw,
-                         int32_t* blk, float* energy, int32_t* chunk_count, hipStream_t st);
+                         int32_t* blk, float* energy, int32_t* chunk_count, float* part_E,
+                         int32_t* part_j, hipStream_t st);
 
 hipError_t launch_group(int K, const int32_t* blk, int64_t m, const Workspace& ws, bool have_hist,
                         hipStream_t st);
