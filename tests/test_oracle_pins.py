@@ -383,3 +383,18 @@ def test_learn_history_monotone_stops_and_matches_manual_steps():
     blk1 = orc.o_code(pr.Y64, Db, 3)[0]
     _D, (_s, _c, e1), _sq = orc.o_train_rounds(pr.Y64, blk1, Db, 3, 2, round_f32=False)
     assert abs(orc.rmse(e1.sum(), 16, 900) - hist[1]) < 1e-15
+
+
+def test_hand_worked_2d_worst_set_and_base_initialisation():
+    g = json.load(open(os.path.join(HERE, "golden", "hand_2d.json")))
+    h = json.load(open(os.path.join(HERE, "golden", "hand_2d_next.json")))
+    Y = np.array(g["Y"], float)
+    D = np.array(g["Q"], float)
+    err = orc.o_code(Y, D, 1)[3]
+    assert np.allclose(err, h["err"], atol=1e-14)
+    for W, ids in h["worst"].items():
+        assert orc.o_worst(err, int(W)).tolist() == ids
+    Q0, sv = orc.o_init_base(Y, h["init_set"])
+    assert np.allclose(sv, h["singular_values"], rtol=1e-14)
+    assert np.allclose(np.abs(Q0), h["Q0_abs_atoms"], atol=1e-14)
+    assert abs(Q0[0, 0] / Q0[0, 1] - h["Q0_atom0_over_atom0_ratio"]) < 1e-12     # same sign inside the atom
