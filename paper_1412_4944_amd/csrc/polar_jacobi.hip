@@ -27,7 +27,8 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
                                                              float* __restrict__ Vstate, int warm,
                                                              float* __restrict__ eig_sv, float done,
                                                              float* __restrict__ dsw,
-                                                             int32_t* __restrict__ sweeps_out) {
+                                                             int32_t* __restrict__ sweeps_out,
+                                                             const int32_t* __restrict__ only) {
     constexpr int LD = P + 4;
     constexpr int NT = (P / 2) * TPP;          // threads: TPP lanes per column pair
     constexpr int RPT = P / TPP;               // contiguous rows per lane in a rotation
@@ -44,6 +45,7 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
 
     const int j = blockIdx.x;
     const int tid = threadIdx.x;
+    if (only != nullptr && only[j] == 0) return;        // uniform: another kernel has done this block
     if (counts != nullptr && counts[j] == 0) {          // uniform: block keeps its basis
         if (Vstate != nullptr && !warm)                 // a cold pass defines every block's V
             for (int e = tid; e < P * P; e += NT)
@@ -341,29 +343,44 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
 
 template <int TPP>
 hipError_t launch_tpp(int p, int K, const float* M, const int32_t* counts, float* D, float* vstate,
-                      int warm, float* eig_sv, float* dsw, int32_t* sweeps, hipStream_t st) {
+                      int warm, float* eig_sv, float* dsw, int32_t* sweeps, const int32_t* only,
+                      hipStream_t st) {
     const float done = polar_done();
     switch (p) {
-        case 16: hipLaunchKernelGGL((polar_kernel<16, TPP>), dim3(K), dim3(8 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv, done, dsw, sweeps); break;
-        case 32: hipLaunchKernelGGL((polar_kernel<32, TPP>), dim3(K), dim3(16 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv, done, dsw, sweeps); break;
-        case 64: hipLaunchKernelGGL((polar_kernel<64, TPP>), dim3(K), dim3(32 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv, done, dsw, sweeps); break;
+        case 16: hipLaunchKernelGGL((polar_kernel<16, TPP>), dim3(K), dim3(8 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv, done, dsw, sweeps, only); break;
+        case 32: hipLaunchKernelGGL((polar_kernel<32, TPP>), dim3(K), dim3(16 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv, done, dsw, sweeps, only); break;
+        case 64: hipLaunchKernelGGL((polar_kernel<64, TPP>), dim3(K), dim3(32 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv, done, dsw, sweeps, only); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
-hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
-                        float* vstate, int warm, float* jac_a, float* eig_sv, float* dsw,
-                        int32_t* sweeps, hipStream_t st) {
-    if (p == 256) {
-        if (dsw != nullptr) return hipErrorInvalidValue;   // p = 256 rewrites the operand order itself
-        return launch_polar_wide(K, M, counts, D, vstate, warm, jac_a, eig_sv, sweeps, st);
-    }
+static hipError_t launch_jacobi(int p, int K, const float* M, const int32_t* counts, float* D,
+                                float* vstate, int warm, float* eig_sv, float* dsw, int32_t* sweeps,
+                                const int32_t* only, hipStream_t st) {
     int tpp = 16;
     if (const char* e = getenv("SBO_POLAR_TPP")) tpp = atoi(e);   // tuning override
-    if (tpp == 4) return launch_tpp<4>(p, K, M, counts, D, vstate, warm, eig_sv, dsw, sweeps, st);
-    if (tpp == 8) return launch_tpp<8>(p, K, M, counts, D, vstate, warm, eig_sv, dsw, sweeps, st);
-    return launch_tpp<16>(p, K, M, counts, D, vstate, warm, eig_sv, dsw, sweeps, st);
+    if (tpp == 4) return launch_tpp<4>(p, K, M, counts, D, vstate, warm, eig_sv, dsw, sweeps, only, st);
+    if (tpp == 8) return launch_tpp<8>(p, K, M, counts, D, vstate, warm, eig_sv, dsw, sweeps, only, st);
+    return launch_tpp<16>(p, K, M, counts, D, vstate, warm, eig_sv, dsw, sweeps, only, st);
+}
+
+hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
+                        const Workspace& ws, int warm, float* eig_sv, bool write_dsw,
+                        hipStream_t st) {
+    if (p == 256) {
+        if (write_dsw) return hipErrorInvalidValue;   // p = 256 rewrites the operand order itself
+        return launch_polar_wide(K, M, counts, D, ws.vstate, warm, ws.jac_a, eig_sv, ws.sweeps, st);
+    }
+    float* dsw = write_dsw ? ws.dsw : nullptr;
+    bool ns = eig_sv == nullptr;
+    if (const char* e = getenv("SBO_POLAR_NS")) ns = ns && atoi(e) != 0;   // 0: Jacobi only
+    if (!ns) return launch_jacobi(p, K, M, counts, D, ws.vstate, warm, eig_sv, dsw, ws.sweeps, nullptr, st);
+    // Newton-Schulz for every block; the Jacobi SVD (cold: no V of a previous call is kept for
+    // these blocks) only for the ones it flags.
+    hipError_t e = launch_polar_ns(p, K, M, counts, D, dsw, ws.ns_fallback, ws.sweeps, st);
+    if (e != hipSuccess) return e;
+    return launch_jacobi(p, K, M, counts, D, ws.vstate, 0, nullptr, dsw, ws.sweeps, ws.ns_fallback, st);
 }
 
 }  // namespace sbo

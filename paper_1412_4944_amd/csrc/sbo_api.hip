@@ -49,6 +49,7 @@ size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char
     w.sq_out = (double*)take(8);
     w.sq_counter = (int32_t*)take(4);
     w.sweeps = (int32_t*)take((size_t)K * 4);
+    w.ns_fallback = (int32_t*)take((size_t)K * 4);
     w.sq_partial = (double*)take((size_t)kSqBlocks * 8);
     w.bytes = off;
     if (ws) *ws = w;
@@ -141,7 +142,7 @@ static int run_update_grouped(sbo_ctx* c, const float* Y, int64_t m, const int32
     }
     {
         StageTimer t(c, SBO_STAGE_SVD);
-        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, vstate, warm, c->ws.jac_a, nullptr, nullptr, c->ws.sweeps, c->stream));
+        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws, warm, nullptr, false, c->stream));
     }
     return SBO_OK;
 }
@@ -251,8 +252,7 @@ int sbo_polar(sbo_ctx* c, const float* M, const int32_t* counts, float* D) {
     if (!c || !M || !D) return SBO_EINVAL;
     c->n_spans = 0;
     StageTimer t(c, SBO_STAGE_SVD);
-    SBO_HIP(launch_polar(c->p, c->K, M, counts, D, c->p > 64 ? c->ws.vstate : nullptr, 0, c->ws.jac_a,
-                         nullptr, nullptr, c->ws.sweeps, c->stream));
+    SBO_HIP(launch_polar(c->p, c->K, M, counts, D, c->ws, 0, nullptr, false, c->stream));
     return SBO_OK;
 }
 
@@ -313,8 +313,8 @@ int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter, int
         }
         {
             StageTimer t(c, SBO_STAGE_SVD);
-            SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws.vstate, warm,
-                                 c->ws.jac_a, nullptr, c->ws.dsw, c->ws.sweeps, c->stream));
+            SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws, warm, nullptr, true,
+                                 c->stream));
         }
     }
     return SBO_OK;
@@ -343,8 +343,7 @@ static int run_train_rounds(sbo_ctx* c, const float* Y, int64_t m, const int32_t
             SBO_HIP(launch_accumulate(c->p, c->K, c->s0, Y, m, supp, coef, c->ws, c->ws.M, c->stream));
         }
         StageTimer t(c, SBO_STAGE_SVD);
-        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws.vstate, warm, c->ws.jac_a,
-                             nullptr, nullptr, c->ws.sweeps, c->stream));
+        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws, warm, nullptr, false, c->stream));
     }
     return SBO_OK;
 }
@@ -383,8 +382,8 @@ int sbo_worst(sbo_ctx* c, const float* err, int64_t m, int64_t W, int32_t* ids) 
 // Gram matrix of the set -> its eigenvectors by descending eigenvalue (ws.perm etc. hold the set).
 static int run_init_base(sbo_ctx* c, const float* Y, int64_t n, float* Q, float* sv) {
     SBO_HIP(launch_gram(c->p, Y, n, c->ws, c->ws.M, c->stream));
-    SBO_HIP(launch_polar(c->p, 1, c->ws.M, nullptr, Q, c->ws.vstate, 0, c->ws.jac_a,
-                         sv ? sv : c->ws.energy, nullptr, c->ws.sweeps, c->stream));   // energy[m_max >= p] as a sink
+    SBO_HIP(launch_polar(c->p, 1, c->ws.M, nullptr, Q, c->ws, 0, sv ? sv : c->ws.energy, false,
+                         c->stream));              // energy[m_max >= p] as a sink
     return SBO_OK;
 }
 
@@ -417,8 +416,7 @@ static int run_new_base(sbo_ctx* c, const float* Y, int64_t n, int R, int have_q
         }
         if (sqerr_per_round)
             SBO_HIP(launch_sqerr(err, c->ws.perm, n, c->ws, sqerr_per_round + r, c->stream));
-        SBO_HIP(launch_polar(c->p, 1, c->ws.M, c->ws.counts, Q, c->ws.vstate, warm, c->ws.jac_a,
-                             nullptr, nullptr, c->ws.sweeps, c->stream));
+        SBO_HIP(launch_polar(c->p, 1, c->ws.M, c->ws.counts, Q, c->ws, warm, nullptr, false, c->stream));
     }
     return SBO_OK;
 }

@@ -101,7 +101,8 @@ struct Workspace {
     int32_t* sel_base;     // same shape: exclusive sums of sel_cnt over the chunks
     int32_t* sel_ids;      // [m_max] worst-W set inside sbo_learn
     double* sq_out;        // [1] squared-error total inside sbo_learn
-    int32_t* sweeps;       // [K] Jacobi sweeps of the most recent SVD stage
+    int32_t* sweeps;       // [K] most recent SVD stage: Jacobi sweeps, or minus the Newton-Schulz steps
+    int32_t* ns_fallback;  // [K] 1 = Newton-Schulz left the block to the Jacobi kernel
     int32_t* sq_counter;   // [1] workgroups of the fused squared-error sum that have finished (0 between launches)
     // iterate
     double* sq_partial;    // [kSqBlocks]
@@ -157,10 +158,6 @@ hipError_t launch_select(int p, int K, int s0, const float* Y, int64_t m, const 
 hipError_t launch_accumulate(int p, int K, int s0, const float* Y, int64_t m, const int32_t* supp,
                              const float* coef, const Workspace& ws, float* M, hipStream_t st);
 
-// vstate: [K][p][p] right singular vectors kept between calls (nullptr = none); warm != 0
-// starts the decomposition from them.
-// jac_a: scratch of polar_wide_scratch_bytes(K) bytes, used when p > 64 (vstate then doubles
-// as the V working copy and must not be nullptr).
 // Fused select + per-piece accumulation (p <= 64); the piece results land in ws.partial
 // and launch_accum_reduce sums them into M.
 hipError_t launch_select_accum(int p, int K, int s0, const float* Y, int64_t m, const float* D,
@@ -170,14 +167,22 @@ hipError_t launch_select_accum(int p, int K, int s0, const float* Y, int64_t m, 
 hipError_t launch_accum_reduce(int p, int K, int64_t m, const Workspace& ws, float* M,
                                const float* err, double* sq_out, hipStream_t st);
 
-// eig_sv != nullptr switches to eigen mode: M[j] symmetric positive semidefinite, D[j] receives
-// its eigenvectors as atoms by descending eigenvalue and eig_sv[j][p] the square roots of the
-// eigenvalues.
-// dsw != nullptr (p <= 64): the rows of every updated block are also written into the coding
+// The SVD update Q_j = U V^T of every block with counts[j] > 0 (counts == nullptr: all).
+// p <= 64: Newton-Schulz on the matrix cores (polar_ns.hip) first, then the Jacobi SVD for the
+// blocks that left flagged (rank-deficient ones); p = 256: Jacobi (polar_wide.hip).
+// Uses ws.vstate (V kept between calls: warm != 0 starts Jacobi from it), ws.jac_a, ws.sweeps
+// (per block: Jacobi sweeps, or minus the Newton-Schulz steps), ws.ns_fallback.
+// eig_sv != nullptr switches to eigen mode (always Jacobi): M[j] symmetric positive
+// semidefinite, D[j] receives its eigenvectors as atoms by descending eigenvalue and
+// eig_sv[j][p] the square roots of the eigenvalues.
+// write_dsw (p <= 64): the rows of every updated block are also written into ws.dsw, the coding
 // kernel's operand order (what launch_dict_swizzle would produce from the new D).
 hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
-                        float* vstate, int warm, float* jac_a, float* eig_sv, float* dsw,
-                        int32_t* sweeps, hipStream_t st);   // sweeps: [K] Jacobi sweeps used, may be nullptr
+                        const Workspace& ws, int warm, float* eig_sv, bool write_dsw,
+                        hipStream_t st);
+
+hipError_t launch_polar_ns(int p, int K, const float* M, const int32_t* counts, float* D, float* dsw,
+                           int32_t* fallback, int32_t* iters, hipStream_t st);
 
 // p = 256 variant of launch_polar (polar_wide.hip) and the size of its scratch (working
 // copy of P_j, rotation log, sweep counts).
