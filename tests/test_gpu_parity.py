@@ -6,6 +6,7 @@ import pytest
 import sbo_synth as synth
 from oracle import sbo_oracle as orc
 from gpu_util import Sbo, compare_code, compare_Q
+import paper_1412_4944_amd as sbo
 
 pytestmark = pytest.mark.gpu
 
@@ -302,3 +303,42 @@ def test_largest_K_and_context_reuse():
         Dg, blk, supp, coef, err, sq = g.iterate(Y, pr.D_init, 2)
         assert sq[1] <= sq[0] * (1 + 1e-6)
         compare_code(Y, Dg, 2, orc.o_code(Y, Dg, 2), g.code(Y, Dg))
+
+
+@pytest.mark.parametrize("p", [16, 32, 64])
+def test_polar_condition_sweep_and_both_paths(p):
+    """The SVD update over a range of condition numbers, once with the default path
+    (Newton-Schulz, Jacobi for the blocks it flags) and once with the Jacobi SVD alone: each
+    against the oracle, and the two against each other."""
+    import os
+    rng = np.random.default_rng(23 + p)
+    conds = [1.0, 3.0, 30.0, 300.0, 900.0, 3e3, 3e4, 1e6, np.inf]
+    K = len(conds)
+    M = np.empty((K, p, p))
+    for j, c in enumerate(conds):
+        u = synth.random_onb(rng, p)
+        v = synth.random_onb(rng, p)
+        s = np.geomspace(1.0, 1.0 / c, p) if np.isfinite(c) else np.r_[np.geomspace(1.0, 0.1, p - 3), 0, 0, 0]
+        M[j] = (u * s) @ v.T * (10.0 ** rng.uniform(-3, 3))          # any overall scale
+    M32 = M.astype(np.float32)
+    D_old = synth.random_dictionary(rng, K, p).astype(np.float32)
+    Dn = np.stack([orc.o_polar(M32[j].astype(np.float64)) for j in range(K)])
+    out = {}
+    with Sbo(p, K, min(4, p), 64) as g:
+        for mode in ("default", "jacobi"):
+            if mode == "jacobi":
+                os.environ["SBO_POLAR_NS"] = "0"
+            try:
+                out[mode] = g.polar(M32, D_old, None)
+                sweeps = sbo.sbo_svd_sweeps(g.ctx, K)
+            finally:
+                os.environ.pop("SBO_POLAR_NS", None)
+            w = compare_Q(out[mode], Dn, M32.astype(np.float64), np.ones(K, bool))
+            print(f"  p={p} {mode}: worst |Q - Q_oracle| {w:.2e}, per block {sweeps}", flush=True)
+            if mode == "default":
+                assert all(x < 0 for x in sweeps[:4]), "well-conditioned blocks should not need the fallback"
+                assert sweeps[-1] > 0, "the rank-deficient block must go to the Jacobi SVD"
+            else:
+                assert all(x > 0 for x in sweeps)
+    good = [j for j, c in enumerate(conds) if c <= 900.0]
+    assert np.abs(out["default"][good] - out["jacobi"][good]).max() <= 1e-4
