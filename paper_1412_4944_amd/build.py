@@ -17,7 +17,7 @@ LIB_DIR = os.path.join(HERE, "lib")
 LIB = os.path.join(LIB_DIR, "libsbo.so")
 
 SOURCES = ["sbo_api.hip", "code_energy.hip", "code_select.hip", "select_accum.hip", "group.hip", "accumulate.hip",
-           "polar_jacobi.hip", "polar_ns.hip", "polar_wide.hip", "reduce.hip", "worst.hip", "probe.hip"]
+           "polar_jacobi.hip", "polar_ns.hip", "polar_wide.hip", "polar_wide_ns.hip", "reduce.hip", "worst.hip", "probe.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

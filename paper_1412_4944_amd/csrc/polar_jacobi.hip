@@ -368,13 +368,17 @@ static hipError_t launch_jacobi(int p, int K, const float* M, const int32_t* cou
 hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
                         const Workspace& ws, int warm, float* eig_sv, bool write_dsw,
                         hipStream_t st) {
-    if (p == 256) {
-        if (write_dsw) return hipErrorInvalidValue;   // p = 256 rewrites the operand order itself
-        return launch_polar_wide(K, M, counts, D, ws.vstate, warm, ws.jac_a, eig_sv, ws.sweeps, st);
-    }
-    float* dsw = write_dsw ? ws.dsw : nullptr;
     bool ns = eig_sv == nullptr;
     if (const char* e = getenv("SBO_POLAR_NS")) ns = ns && atoi(e) != 0;   // 0: Jacobi only
+    if (p == 256) {
+        if (write_dsw) return hipErrorInvalidValue;   // p = 256 rewrites the operand order itself
+        if (!ns)
+            return launch_polar_wide(K, M, counts, D, ws.vstate, warm, ws.jac_a, eig_sv, ws.sweeps, nullptr, st);
+        hipError_t e = launch_polar_wide_ns(K, M, counts, D, ws.jac_a, ws.ns_fallback, ws.sweeps, st);
+        if (e != hipSuccess) return e;
+        return launch_polar_wide(K, M, counts, D, ws.vstate, 0, ws.jac_a, nullptr, ws.sweeps, ws.ns_fallback, st);
+    }
+    float* dsw = write_dsw ? ws.dsw : nullptr;
     if (!ns) return launch_jacobi(p, K, M, counts, D, ws.vstate, warm, eig_sv, dsw, ws.sweeps, nullptr, st);
     // Newton-Schulz for every block; the Jacobi SVD (cold: no V of a previous call is kept for
     // these blocks) only for the ones it flags.

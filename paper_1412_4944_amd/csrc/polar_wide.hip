@@ -65,7 +65,8 @@ __global__ __launch_bounds__(1024) void wide_jacobi_kernel(const float* __restri
                                                            const int32_t* __restrict__ counts,
                                                            const float* __restrict__ Vst, int warm,
                                                            float* scratch, int K, float done,
-                                                           int32_t* __restrict__ sweeps_out) {
+                                                           int32_t* __restrict__ sweeps_out,
+                                                           const int32_t* __restrict__ only) {
     constexpr int NT = 1024;
     constexpr int TPP = 8;
     constexpr int RPT = P / TPP;               // 32 rows per lane: 16 on chip, 16 in global memory
@@ -77,6 +78,7 @@ __global__ __launch_bounds__(1024) void wide_jacobi_kernel(const float* __restri
     const WideScratch ws = carve(scratch, K);
     const int j = blockIdx.x;
     const int tid = threadIdx.x;
+    if (only != nullptr && only[j] == 0) return;   // uniform: another kernel has done this block
     if (counts != nullptr && counts[j] == 0) { // uniform: block keeps its basis
         if (tid == 0) {
             ws.nsweeps[j] = 0;
@@ -231,10 +233,12 @@ constexpr int kReplayRows = 4;
 
 __global__ __launch_bounds__(256) void wide_replay_kernel(const int32_t* __restrict__ counts,
                                                           float* Vst, int warm,
-                                                          const float* scratch, int K) {
+                                                          const float* scratch, int K,
+                                                          const int32_t* __restrict__ only) {
     __shared__ float rows_all[4][kReplayRows][P];
     const WideScratch ws = carve(const_cast<float*>(scratch), K);
     const int j = blockIdx.x;
+    if (only != nullptr && only[j] == 0) return;   // uniform
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int row0 = (blockIdx.y * 4 + wave) * kReplayRows;
     float* V = Vst + (int64_t)j * P * P;       // column-major: V[c*P + r]
@@ -300,7 +304,8 @@ __global__ __launch_bounds__(1024) void wide_finish_kernel(const float* __restri
                                                            const int32_t* __restrict__ counts,
                                                            float* __restrict__ D, float* Vst,
                                                            float* scratch, int K,
-                                                           float* __restrict__ eig_sv) {
+                                                           float* __restrict__ eig_sv,
+                                                           const int32_t* __restrict__ only) {
     constexpr int NT = 1024;
     __shared__ float sig[P];
     __shared__ float coefs[P];
@@ -311,6 +316,7 @@ __global__ __launch_bounds__(1024) void wide_finish_kernel(const float* __restri
     const WideScratch ws = carve(scratch, K);
     const int j = blockIdx.x;
     const int tid = threadIdx.x;
+    if (only != nullptr && only[j] == 0) return;       // uniform
     if (counts != nullptr && counts[j] == 0) return;   // uniform: block keeps its basis
     float* A = ws.A + (int64_t)j * P * P;
     float* V = Vst + (int64_t)j * P * P;
@@ -447,7 +453,8 @@ size_t polar_wide_scratch_bytes(int K) {
 }
 
 hipError_t launch_polar_wide(int K, const float* M, const int32_t* counts, float* D, float* vstate,
-                             int warm, float* jac_a, float* eig_sv, int32_t* sweeps, hipStream_t st) {
+                             int warm, float* jac_a, float* eig_sv, int32_t* sweeps,
+                             const int32_t* only, hipStream_t st) {
     if (vstate == nullptr || jac_a == nullptr) return hipErrorInvalidValue;
     const size_t lds = (size_t)P * LDA * sizeof(float);
     static bool raised = false;
@@ -458,11 +465,11 @@ hipError_t launch_polar_wide(int K, const float* M, const int32_t* counts, float
         raised = true;
     }
     hipLaunchKernelGGL(wide_jacobi_kernel, dim3(K), dim3(1024), lds, st, M, counts, vstate, warm, jac_a, K,
-                       polar_done(), sweeps);
+                       polar_done(), sweeps, only);
     hipLaunchKernelGGL(wide_replay_kernel, dim3(K, P / (4 * kReplayRows)), dim3(256), 0, st, counts,
-                       vstate, warm, jac_a, K);
+                       vstate, warm, jac_a, K, only);
     hipLaunchKernelGGL(wide_finish_kernel, dim3(K), dim3(1024), 0, st, M, counts, D, vstate, jac_a, K,
-                       eig_sv);
+                       eig_sv, only);
     return hipGetLastError();
 }
 

@@ -39,7 +39,8 @@ size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char
     w.partial = (float*)take((size_t)max_pieces_bound(m_max, K, p) * p * p * 4);
     w.M = (float*)take((size_t)K * p * p * 4);
     w.vstate = (float*)take((size_t)K * p * p * 4);
-    w.jac_a = (float*)take(p > 64 ? polar_wide_scratch_bytes(K) : 0);
+    const size_t wide_a = polar_wide_scratch_bytes(K), wide_b = polar_wide_ns_scratch_bytes(K);
+    w.jac_a = (float*)take(p > 64 ? (wide_a > wide_b ? wide_a : wide_b) : 0);
     const size_t sel_chunks = (size_t)((m_max + kSelChunk - 1) / kSelChunk);
     w.sel_hist = (int32_t*)take((size_t)4 * 256 * 4);
     w.sel_state = (int32_t*)take((size_t)4 * 2 * 4);

@@ -169,7 +169,8 @@ hipError_t launch_accum_reduce(int p, int K, int64_t m, const Workspace& ws, flo
 
 // The SVD update Q_j = U V^T of every block with counts[j] > 0 (counts == nullptr: all).
 // p <= 64: Newton-Schulz on the matrix cores (polar_ns.hip) first, then the Jacobi SVD for the
-// blocks that left flagged (rank-deficient ones); p = 256: Jacobi (polar_wide.hip).
+// blocks it leaves flagged (rank-deficient ones); p = 256: the same two steps spread over the whole
+// chip (polar_wide_ns.hip, polar_wide.hip).
 // Uses ws.vstate (V kept between calls: warm != 0 starts Jacobi from it), ws.jac_a, ws.sweeps
 // (per block: Jacobi sweeps, or minus the Newton-Schulz steps), ws.ns_fallback.
 // eig_sv != nullptr switches to eigen mode (always Jacobi): M[j] symmetric positive
@@ -187,8 +188,14 @@ hipError_t launch_polar_ns(int p, int K, const float* M, const int32_t* counts, 
 // p = 256 variant of launch_polar (polar_wide.hip) and the size of its scratch (working
 // copy of P_j, rotation log, sweep counts).
 size_t polar_wide_scratch_bytes(int K);
+// only != nullptr: blocks with only[j] == 0 are skipped.
 hipError_t launch_polar_wide(int K, const float* M, const int32_t* counts, float* D, float* vstate,
-                             int warm, float* jac_a, float* eig_sv, int32_t* sweeps, hipStream_t st);
+                             int warm, float* jac_a, float* eig_sv, int32_t* sweeps,
+                             const int32_t* only, hipStream_t st);
+// p = 256 Newton-Schulz over the whole chip (polar_wide_ns.hip); scratch as for the Jacobi variant.
+size_t polar_wide_ns_scratch_bytes(int K);
+hipError_t launch_polar_wide_ns(int K, const float* M, const int32_t* counts, float* D, float* scratch,
+                                int32_t* fallback, int32_t* iters, hipStream_t st);
 
 // ids == nullptr: sum over all m signals; otherwise over the m listed ones.
 hipError_t launch_sqerr(const float* err, const int32_t* ids, int64_t m, const Workspace& ws,

@@ -305,7 +305,7 @@ def test_largest_K_and_context_reuse():
         compare_code(Y, Dg, 2, orc.o_code(Y, Dg, 2), g.code(Y, Dg))
 
 
-@pytest.mark.parametrize("p", [16, 32, 64])
+@pytest.mark.parametrize("p", [16, 32, 64, 256])
 def test_polar_condition_sweep_and_both_paths(p):
     """The SVD update over a range of condition numbers, once with the default path
     (Newton-Schulz, Jacobi for the blocks it flags) and once with the Jacobi SVD alone: each
@@ -324,7 +324,7 @@ def test_polar_condition_sweep_and_both_paths(p):
     D_old = synth.random_dictionary(rng, K, p).astype(np.float32)
     Dn = np.stack([orc.o_polar(M32[j].astype(np.float64)) for j in range(K)])
     out = {}
-    with Sbo(p, K, min(4, p), 64) as g:
+    with Sbo(p, K, min(4, p), 256) as g:
         for mode in ("default", "jacobi"):
             if mode == "jacobi":
                 os.environ["SBO_POLAR_NS"] = "0"
