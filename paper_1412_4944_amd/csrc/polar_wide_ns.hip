@@ -77,11 +77,18 @@ __global__ __launch_bounds__(256) void wide_ns_gram_kernel(const float* __restri
     f32x16 acc;
 #pragma unroll
     for (int q = 0; q < 16; ++q) acc[q] = 0.f;
-#pragma unroll 8
-    for (int s = 0; s < P / 2; ++s) {
-        const float a = X[(2 * s + h) * P + ta * 32 + n];
-        const float b = X[(2 * s + h) * P + tb * 32 + n];
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+    // 32 steps (64 loads) in flight per wavefront: with one wavefront per SIMD the loads are
+    // what the kernel waits on
+#pragma unroll 1
+    for (int s0 = 0; s0 < P / 2; s0 += 32) {
+        float a[32], b[32];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) {
+            a[u] = X[(2 * (s0 + u) + h) * P + ta * 32 + n];
+            b[u] = X[(2 * (s0 + u) + h) * P + tb * 32 + n];
+        }
+#pragma unroll
+        for (int u = 0; u < 32; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[u], acc, 0, 0, 0);
     }
     float* Gj = ns.G + (int64_t)j * P * P;
     float dev = 0.f;
@@ -152,13 +159,21 @@ __global__ __launch_bounds__(256) void wide_ns_update_kernel(const float* __rest
 #pragma unroll
     for (int q = 0; q < 16; ++q) acc[q] = 0.f;
     const f32x4* xrow = reinterpret_cast<const f32x4*>(Xin + (tr * 32 + n) * P);
-#pragma unroll 4
-    for (int q = 0; q < P / 4; ++q) {
-        const f32x4 v = xrow[q];
-        const float b0 = Gj[(4 * q + h) * P + tb * 32 + n];
-        const float b1 = Gj[(4 * q + 2 + h) * P + tb * 32 + n];
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(h ? v.y : v.x, b0, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(h ? v.w : v.z, b1, acc, 0, 0, 0);
+#pragma unroll 1
+    for (int q0 = 0; q0 < P / 4; q0 += 16) {
+        f32x4 v[16];
+        float b0[16], b1[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            v[u] = xrow[q0 + u];
+            b0[u] = Gj[(4 * (q0 + u) + h) * P + tb * 32 + n];
+            b1[u] = Gj[(4 * (q0 + u) + 2 + h) * P + tb * 32 + n];
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(h ? v[u].y : v[u].x, b0[u], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(h ? v[u].w : v[u].z, b1[u], acc, 0, 0, 0);
+        }
     }
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
