@@ -28,9 +28,12 @@ __global__ __launch_bounds__(P == 64 ? 256 : 64) void polar_ns_kernel(
     constexpr int T = P == 64 ? 2 : 1;         // 32-wide tiles per side
     constexpr int NTH = T * T * 64;
     constexpr int PAD = T * 32;                // padded dimension (p = 16 sits in one tile)
-    constexpr int LD = PAD + 1;
-    __shared__ float X[PAD * LD];
-    __shared__ float G[PAD * LD];
+    constexpr int LD = PAD + 4;                // rows stay 16-byte aligned
+    // X, its transpose Xt and G = X^T X (symmetric), all row-major: every MFMA operand is then
+    // four consecutive floats of one row (one 16-byte LDS read feeds two MFMA steps).
+    __shared__ __attribute__((aligned(16))) float X[PAD * LD];
+    __shared__ __attribute__((aligned(16))) float Xt[PAD * LD];
+    __shared__ __attribute__((aligned(16))) float G[PAD * LD];
     __shared__ float red[8];
 
     const int j = blockIdx.x;
@@ -47,30 +50,42 @@ __global__ __launch_bounds__(P == 64 ? 256 : 64) void polar_ns_kernel(
     }
 
     const float* Mj = M + (int64_t)j * P * P;
-    for (int e = tid; e < PAD * LD; e += NTH) {
-        const int r = e / LD, c = e % LD;
-        X[e] = (r < P && c < P) ? Mj[r * P + c] : 0.f;
+    for (int e = tid; e < PAD * PAD; e += NTH) {
+        const int r = e / PAD, c = e % PAD;
+        const float v = (r < P && c < P) ? Mj[r * P + c] : 0.f;
+        X[r * LD + c] = v;
+        Xt[c * LD + r] = v;
     }
     __syncthreads();
 
-    // acc = (X^T X) tile (ta, tb): rows a = ta*32 + .., columns b = tb*32 + n; contraction over
-    // the rows r = 2s + h of X.  Register q of lane (h, n) is row (q/4)*8 + h*4 + q%4 of the tile.
-    auto gram_tile = [&]() {
+    // sum over k of A[ra][k] * B[rb][k] for the rows ra = ta*32 + n of A and rb = tb*32 + n of B
+    // (both row-major in LDS): the tile (ta, tb) of A B^T.  Register q of lane (h, n) is row
+    // (q/4)*8 + h*4 + q%4, column n of the tile.
+    auto abt_tile = [&](const float* A, const float* B) {
         f32x16 acc;
 #pragma unroll
         for (int q = 0; q < 16; ++q) acc[q] = 0.f;
-#pragma unroll 8
-        for (int s = 0; s < P / 2; ++s) {
-            const float a = X[(2 * s + h) * LD + ta * 32 + n];
-            const float b = X[(2 * s + h) * LD + tb * 32 + n];
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+        const f32x4* ar = reinterpret_cast<const f32x4*>(A + (ta * 32 + n) * LD);
+        const f32x4* br = reinterpret_cast<const f32x4*>(B + (tb * 32 + n) * LD);
+#pragma unroll
+        for (int q = 0; q < P / 4; ++q) {
+            const f32x4 a = ar[q], b = br[q];
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(h ? a.y : a.x, h ? b.y : b.x, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(h ? a.w : a.z, h ? b.w : b.z, acc, 0, 0, 0);
         }
         return acc;
     };
-    auto store_tile = [&](float* dst, const f32x16& acc, float scale) {
+    // G tile (ta, tb) -> LDS; returns the lane's max |G - I| (after scaling)
+    auto store_gram = [&](const f32x16& acc, float scale) {
+        float dev = 0.f;
 #pragma unroll
-        for (int q = 0; q < 16; ++q)
-            dst[(ta * 32 + (q >> 2) * 8 + h * 4 + (q & 3)) * LD + tb * 32 + n] = acc[q] * scale;
+        for (int q = 0; q < 16; ++q) {
+            const int row = ta * 32 + (q >> 2) * 8 + h * 4 + (q & 3), col = tb * 32 + n;
+            const float g = acc[q] * scale;
+            G[row * LD + col] = g;
+            if (row < P && col < P) dev = fmaxf(dev, fabsf(g - (row == col ? 1.f : 0.f)));
+        }
+        return dev;
     };
     // maximum over the workgroup of a per-thread value (ends with a barrier)
     auto wg_max = [&](float v) {
@@ -85,50 +100,73 @@ __global__ __launch_bounds__(P == 64 ? 256 : 64) void polar_ns_kernel(
         return r;
     };
 
-    // Scale so that every singular value is at most one: sigma_max^2 <= max row sum of |X^T X|.
-    store_tile(G, gram_tile(), 1.f);
+    // Scale so that the largest singular value is about one.  sigma_max^2 is the largest
+    // eigenvalue of G = X^T X: a few power-iteration steps from the vector of absolute row sums
+    // give a Rayleigh quotient just below it (a bound such as the largest row sum is safe but
+    // often two to three times too large, which costs iterations).  The iteration converges for
+    // any sigma_max < sqrt(3), so an estimate within that factor is good enough; should it ever
+    // be worse, the deviation test below sends the block to the fallback.
+    // (X^T X = Xt Xt^T: both operands are rows of Xt.)
+    __shared__ float vec[PAD], wec[PAD];
+    f32x16 g0 = abt_tile(Xt, Xt);
+    store_gram(g0, 1.f);
     __syncthreads();
-    float rs = 0.f;
-    if (tid < P)
+    if (tid < P) {
+        float rs = 0.f;
         for (int b = 0; b < P; ++b) rs += fabsf(G[tid * LD + b]);
-    const float s2 = wg_max(rs);
-    bool ok = s2 > 0.f && s2 < 3e38f;          // zero, infinite or NaN input: not for this kernel
+        vec[tid] = rs;
+    }
+    __syncthreads();
+    float s2 = 0.f;
+    for (int round = 0; round < 4; ++round) {
+        if (tid < P) {
+            float w = 0.f;
+            for (int b = 0; b < P; ++b) w += G[tid * LD + b] * vec[b];
+            wec[tid] = w;
+        }
+        __syncthreads();
+        float vv = 0.f, vw = 0.f, wmax = 0.f;  // every thread, same order: same values
+        for (int a = 0; a < P; ++a) {
+            vv += vec[a] * vec[a];
+            vw += vec[a] * wec[a];
+            wmax = fmaxf(wmax, fabsf(wec[a]));
+        }
+        s2 = 1.08f * vw / vv;                  // NaN for a zero matrix: caught below
+        __syncthreads();
+        if (tid < P) vec[tid] = wec[tid] / wmax;
+        __syncthreads();
+    }
+    const bool ok = s2 > 0.f && s2 < 3e38f;    // zero, infinite or NaN input: not for this kernel
     const float inv = ok ? __builtin_amdgcn_rsqf(s2) : 0.f;
     for (int e = tid; e < PAD * LD; e += NTH) {
         X[e] *= inv;
-        G[e] *= inv * inv;
+        Xt[e] *= inv;
     }
-    __syncthreads();
-
+    float dev = store_gram(g0, inv * inv);     // same tile, scaled (nobody reads G in between)
     int it = 0;
     bool converged = false;
     while (ok) {
         // d = max |X^T X - I|; below 2e-4 the step that follows is the last (quadratic
-        // convergence leaves about d^2 behind)
-        float dev = 0.f;
-        for (int e = tid; e < P * P; e += NTH) {
-            const int a = e / P, b = e % P;
-            dev = fmaxf(dev, fabsf(G[a * LD + b] - (a == b ? 1.f : 0.f)));
-        }
+        // convergence leaves about d^2 behind).  The barriers inside also publish G, X, Xt.
         const float d = wg_max(dev);
         const bool last = d < 2e-4f;
         if (!(d < 4.f)) break;                 // NaN or diverging: leave it to the fallback
 
-        // X <- 1.5 X - 0.5 X G: tile (ta, tb) of X G, rows r = ta*32 + n, contraction over a
-        f32x16 acc;
-#pragma unroll
-        for (int q = 0; q < 16; ++q) acc[q] = 0.f;
-#pragma unroll 8
-        for (int s = 0; s < P / 2; ++s) {
-            const float a = X[(ta * 32 + n) * LD + 2 * s + h];
-            const float b = G[(2 * s + h) * LD + tb * 32 + n];
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
-        }
+        // X <- 1.5 X - 0.5 X G; (X G)[r][b] = sum_a X[r][a] G[b][a] (G symmetric)
+        const f32x16 acc = abt_tile(X, G);
         __syncthreads();                       // every wavefront has read the old X
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            float* x = &X[(ta * 32 + (q >> 2) * 8 + h * 4 + (q & 3)) * LD + tb * 32 + n];
-            *x = 1.5f * *x - 0.5f * acc[q];
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const int row0 = ta * 32 + q4 * 8 + h * 4, col = tb * 32 + n;
+            f32x4* xt4 = reinterpret_cast<f32x4*>(&Xt[col * LD + row0]);
+            const f32x4 old = *xt4;
+            const f32x4 nw = {1.5f * old.x - 0.5f * acc[4 * q4], 1.5f * old.y - 0.5f * acc[4 * q4 + 1],
+                              1.5f * old.z - 0.5f * acc[4 * q4 + 2], 1.5f * old.w - 0.5f * acc[4 * q4 + 3]};
+            *xt4 = nw;
+            X[(row0 + 0) * LD + col] = nw.x;
+            X[(row0 + 1) * LD + col] = nw.y;
+            X[(row0 + 2) * LD + col] = nw.z;
+            X[(row0 + 3) * LD + col] = nw.w;
         }
         __syncthreads();
         ++it;
@@ -137,8 +175,7 @@ __global__ __launch_bounds__(P == 64 ? 256 : 64) void polar_ns_kernel(
             break;
         }
         if (it >= max_iters) break;
-        store_tile(G, gram_tile(), 1.f);
-        __syncthreads();
+        dev = store_gram(abt_tile(Xt, Xt), 1.f);
     }
 
     if (!converged) {                          // uniform

@@ -106,10 +106,12 @@ __global__ __launch_bounds__(256) void wide_ns_gram_kernel(const float* __restri
     }
 }
 
-// s2[j] = max row sum of |G| (G symmetric: summed down the columns, coalesced) >= sigma_max^2.
+// s2[j] ~ sigma_max^2 of the input = largest eigenvalue of G: Rayleigh quotient after a few
+// power-iteration steps from the vector of absolute row sums, times 1.08 (see polar_ns.hip;
+// G is symmetric, so rows are read as columns, coalesced).
 __global__ __launch_bounds__(256) void wide_ns_scale_kernel(const int32_t* __restrict__ counts,
                                                             float* scratch, int K) {
-    __shared__ float red[4];
+    __shared__ float vec[P], wec[P];
     const NsScratch ns = ns_carve(scratch, K);
     const int j = blockIdx.x;
     if (counts != nullptr && counts[j] == 0) return;
@@ -117,12 +119,26 @@ __global__ __launch_bounds__(256) void wide_ns_scale_kernel(const int32_t* __res
     const float* Gj = ns.G + (int64_t)j * P * P;
     float rs = 0.f;
     for (int b = 0; b < P; ++b) rs += fabsf(Gj[b * P + tid]);
-    if (!(rs == rs)) rs = __uint_as_float(0x7f800000u);
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) rs = fmaxf(rs, __shfl_xor(rs, o, 64));
-    if ((tid & 63) == 0) red[tid >> 6] = rs;
+    vec[tid] = rs;
     __syncthreads();
-    if (tid == 0) ns.s2[j] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float s2 = 0.f;
+    for (int round = 0; round < 4; ++round) {
+        float w = 0.f;
+        for (int b = 0; b < P; ++b) w += Gj[b * P + tid] * vec[b];
+        wec[tid] = w;
+        __syncthreads();
+        float vv = 0.f, vw = 0.f, wmax = 0.f;  // every thread, same order: same values
+        for (int a = 0; a < P; ++a) {
+            vv += vec[a] * vec[a];
+            vw += vec[a] * wec[a];
+            wmax = fmaxf(wmax, fabsf(wec[a]));
+        }
+        s2 = 1.08f * vw / vv;                  // NaN for a zero matrix: the update kernel checks
+        __syncthreads();
+        vec[tid] = wec[tid] / wmax;
+        __syncthreads();
+    }
+    if (tid == 0) ns.s2[j] = s2;
 }
 
 // Step `it`: X_out = c1 X_in - c2 X_in G (c1 = 3/2, c2 = 1/2; step 0 folds the scaling in).
