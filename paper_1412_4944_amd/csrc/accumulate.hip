@@ -228,6 +228,7 @@ __global__ __launch_bounds__(64 * kTallWaves) void accum_piece_kernel(
 // wavefront densifies only its own 64 atoms of x_i; the wave results are disjoint slabs of
 // the piece's partial matrix, so no cross-wave reduction is needed.
 constexpr int kWidePairs = 4;
+constexpr int kWideMaxPiece = 4096;            // accum_piece() never returns more
 
 template <int S0, bool GRAM>
 __global__ __launch_bounds__(256) void accum_wide_kernel(const float* __restrict__ Y, int K,
@@ -239,13 +240,15 @@ __global__ __launch_bounds__(256) void accum_wide_kernel(const float* __restrict
                                                          float* __restrict__ partial) {
     constexpr int P = 256;
     constexpr int NTL = 8;                     // 32-wide tiles along the dimensions
-    extern __shared__ int lds[];               // piece_start[K+1] | tmp[16] | xd[4][kWidePairs][2][64]
+    // piece_start[K+1] | tmp[16] | xd[4][kWidePairs][2][64] | ids[kWideMaxPiece]
+    extern __shared__ int lds[];
     int* piece_start = lds;
     int* tmp = lds + (K + 1);
     float* xd_all = reinterpret_cast<float*>(tmp + 16);
+    int* ids = reinterpret_cast<int*>(xd_all + 4 * kWidePairs * 2 * 64);
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int h = lane >> 5, n = lane & 31;
 
     for (int e = tid; e < 4 * kWidePairs * 2 * 64; e += 256) xd_all[e] = 0.f;
@@ -256,7 +259,9 @@ __global__ __launch_bounds__(256) void accum_wide_kernel(const float* __restrict
 
     const int j = upper_slot(piece_start, K, id);
     const int pos0 = offsets[j] + (id - piece_start[j]) * piece;
-    const int cnt = min(piece, offsets[j + 1] - pos0);
+    const int cnt = min(piece, offsets[j + 1] - pos0);   // <= kWideMaxPiece (launcher)
+    for (int q = tid; q < cnt; q += 256) ids[q] = perm[pos0 + q];
+    __syncthreads();
 
     f32x16 acc[2][NTL];
 #pragma unroll
@@ -269,52 +274,61 @@ __global__ __launch_bounds__(256) void accum_wide_kernel(const float* __restrict
     const int atom0 = 64 * wave;               // this wavefront's atoms: atom0 .. atom0+63
     float* xd = xd_all + (wave * kWidePairs * 2 + h) * 64;
     const int n_pairs = (cnt + 1) >> 1;
-    for (int g = 0; g < n_pairs; g += kWidePairs) {
-        int64_t i[kWidePairs];
-#pragma unroll
-        for (int u = 0; u < kWidePairs; ++u) {
-            const int q = 2 * (g + u) + h;
-            i[u] = q < cnt ? perm[pos0 + q] : -1;
-        }
+
+    // Operands of a step (kWidePairs signal pairs; lane half h takes the h-th signal of a pair).
+    // Two sets alternate, so that the loads of the next step are in flight while the current
+    // one feeds the matrix cores.  Loads are unconditional: positions past the end of the
+    // piece are clamped to its last signal and get no (atom, coefficient) pair when consumed.
+    struct Operands {
         float yv[kWidePairs][NTL], c[kWidePairs];
         int k[kWidePairs];
+    };
+    const int t_lane = n < S0 ? n : S0 - 1;
+    auto fetch = [&](Operands& o, int g) {
 #pragma unroll
         for (int u = 0; u < kWidePairs; ++u) {
-            const bool on = i[u] >= 0;
+            const int64_t i = ids[min(2 * (g + u) + h, cnt - 1)];
 #pragma unroll
-            for (int nt = 0; nt < NTL; ++nt) yv[u][nt] = on ? Y[i[u] * P + nt * 32 + n] : 0.f;
-            k[u] = -1;
-            c[u] = 0.f;
+            for (int nt = 0; nt < NTL; ++nt) o.yv[u][nt] = Y[i * P + nt * 32 + n];
             if constexpr (!GRAM) {
-                if (on && n < S0) {
-                    k[u] = supp[i[u] * S0 + n] - atom0;
-                    c[u] = coef[i[u] * S0 + n];
-                }
-                if ((unsigned)k[u] >= 64u) k[u] = -1;      // another wavefront's atom, or invalid
+                o.k[u] = supp[i * S0 + t_lane];
+                o.c[u] = coef[i * S0 + t_lane];
             }
         }
+    };
+    auto consume = [&](const Operands& o, int g) {
         float a[kWidePairs][2];
         if constexpr (GRAM) {                              // rows atom0.. of sum_i y_i y_i^T
 #pragma unroll
-            for (int u = 0; u < kWidePairs; ++u)
+            for (int u = 0; u < kWidePairs; ++u) {
+                const bool on = 2 * (g + u) + h < cnt;
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt) {
                     a[u][mt] = 0.f;
 #pragma unroll
                     for (int w = 0; w < 4; ++w)
-                        a[u][mt] = wave == w ? yv[u][2 * w + mt] : a[u][mt];
+                        a[u][mt] = (on && wave == w) ? o.yv[u][2 * w + mt] : a[u][mt];
                 }
+            }
         } else {
+            int k[kWidePairs];
+#pragma unroll
+            for (int u = 0; u < kWidePairs; ++u) {
+                const int kk = o.k[u] - atom0;
+                const bool valid = 2 * (g + u) + h < cnt && n < S0 &&
+                                   (unsigned)kk < 64u;     // another wavefront's atom, or invalid
+                k[u] = valid ? u * 128 + kk : -1;
+            }
 #pragma unroll
             for (int u = 0; u < kWidePairs; ++u)
-                if (k[u] >= 0) xd[u * 128 + k[u]] = c[u];
+                if (k[u] >= 0) xd[k[u]] = o.c[u];
 #pragma unroll
             for (int u = 0; u < kWidePairs; ++u)
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt) a[u][mt] = xd[u * 128 + mt * 32 + n];
 #pragma unroll
             for (int u = 0; u < kWidePairs; ++u)
-                if (k[u] >= 0) xd[u * 128 + k[u]] = 0.f;
+                if (k[u] >= 0) xd[k[u]] = 0.f;
         }
 #pragma unroll
         for (int u = 0; u < kWidePairs; ++u)
@@ -322,8 +336,17 @@ __global__ __launch_bounds__(256) void accum_wide_kernel(const float* __restrict
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                 for (int nt = 0; nt < NTL; ++nt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][mt], yv[u][nt],
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][mt], o.yv[u][nt],
                                                                        acc[mt][nt], 0, 0, 0);
+    };
+
+    Operands opA, opB;
+    fetch(opA, 0);
+    for (int g = 0; g < n_pairs; g += 2 * kWidePairs) {
+        fetch(opB, g + kWidePairs);
+        consume(opA, g);
+        fetch(opA, g + 2 * kWidePairs);
+        consume(opB, g + kWidePairs);          // past the end: contributes nothing
     }
 
     float* out = partial + (int64_t)id * P * P;
@@ -442,7 +465,7 @@ hipError_t launch_wide_s(int K, const float* Y, int64_t m, const int32_t* supp, 
     constexpr int P = 256;
     const int piece = accum_piece(m, K, P);
     const int max_pieces = accum_max_pieces(m, K, P);
-    const size_t lds1 = (K + 1 + 16) * sizeof(int) + (size_t)4 * kWidePairs * 2 * 64 * sizeof(float);
+    const size_t lds1 = (K + 1 + 16 + kWideMaxPiece) * sizeof(int) + (size_t)4 * kWidePairs * 2 * 64 * sizeof(float);
     hipLaunchKernelGGL((accum_wide_kernel<S0, false>), dim3(max_pieces), dim3(256), lds1, st, Y, K, piece,
                        ws.offsets, ws.perm, supp, coef, ws.partial);
     const size_t lds2 = (K + 1 + 16) * sizeof(int);
@@ -514,7 +537,7 @@ hipError_t launch_gram(int p, const float* Y, int64_t n, const Workspace& ws, fl
             constexpr int P = 256;
             const int piece = accum_piece(n, 1, P);
             const int max_pieces = (int)((n + piece - 1) / piece) + 1;
-            const size_t lds1 = (1 + 1 + 16) * sizeof(int) + (size_t)4 * kWidePairs * 2 * 64 * sizeof(float);
+            const size_t lds1 = (1 + 1 + 16 + kWideMaxPiece) * sizeof(int) + (size_t)4 * kWidePairs * 2 * 64 * sizeof(float);
             hipLaunchKernelGGL((accum_wide_kernel<1, true>), dim3(max_pieces), dim3(256), lds1, st, Y, 1,
                                piece, ws.offsets, ws.perm, nullptr, nullptr, ws.partial);
             hipLaunchKernelGGL((accum_reduce_kernel<P>), dim3(1, (P * P + 255) / 256), dim3(256),
