@@ -156,22 +156,33 @@ __global__ __launch_bounds__(256) void select_wide_kernel(const float* __restric
     for (int t = 0; t < S; ++t) run[t] = 0.f;
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
                          0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll 1
-    for (int mt = 0; mt < MT; ++mt) {
+    // A operand = rows of Q_j straight from L2, QCH 16-byte groups per chunk; the next chunk is
+    // requested before the MFMAs of the current one (a wavefront has its SIMD to itself here,
+    // so nothing else would cover the load latency).
+    auto load_chunk = [&](f32x4 (&a)[QCH], int mt, int q0) {
         const f32x4* arow =
             reinterpret_cast<const f32x4*>(D + ((int64_t)j * P + mt * 32 + n) * P + h * KS);
+#pragma unroll
+        for (int q = 0; q < QCH; ++q) a[q] = arow[q0 + q];
+    };
+    constexpr int NCH = QN / QCH;              // chunks per tile row of atoms (even)
+    static_assert(NCH % 2 == 0, "chunk parity");
+    f32x4 abuf[2][QCH];
+    load_chunk(abuf[0], 0, 0);
+#pragma unroll 1
+    for (int mt = 0; mt < MT; ++mt) {
         f32x16 acc = zero;
 #pragma unroll
-        for (int q0 = 0; q0 < QN; q0 += QCH) {
-            f32x4 a[QCH];
-#pragma unroll
-            for (int q = 0; q < QCH; ++q) a[q] = arow[q0 + q];
+        for (int cc = 0; cc < NCH; ++cc) {
+            // the last prefetch of all re-reads a valid row and is not used
+            const int nmt = cc + 1 < NCH ? mt : min(mt + 1, MT - 1);
+            load_chunk(abuf[(cc + 1) & 1], nmt, ((cc + 1) % NCH) * QCH);
 #pragma unroll
             for (int q = 0; q < QCH; ++q)
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk)
-                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q][kk], yb[4 * (q0 + q) + kk], acc, 0,
-                                                               0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(abuf[cc & 1][q][kk],
+                                                               yb[4 * (cc * QCH + q) + kk], acc, 0, 0, 0);
         }
         float x[16], top[S];
 #pragma unroll
