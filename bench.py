@@ -239,8 +239,10 @@ def main() -> int:
                                             ((upd["group"] + upd["accum"]) * 1e-3) / 1e9,
                               "a3_GBps": (m * (4 * p + 8 * s0 + 8) + 4 * K * p * p) / (upd["accum"] * 1e-3) / 1e9},
         "code_only_ms": code_ms,
-        "svd_sweeps": {"warm_mean": sum(sweeps_warm) / K, "warm_max": max(sweeps_warm),
-                       "cold_mean": sum(sweeps_cold) / K, "cold_max": max(sweeps_cold)},
+        "svd_work": {"note": "per block: Jacobi sweeps (> 0) or minus the Newton-Schulz steps (< 0)",
+                     "iterate_last_mean": sum(sweeps_warm) / K, "iterate_last_min": min(sweeps_warm),
+                     "iterate_last_max": max(sweeps_warm), "update_mean": sum(sweeps_cold) / K,
+                     "update_min": min(sweeps_cold), "update_max": max(sweeps_cold)},
         "rmse_first_last": [float(np.sqrt(first_sq / (p * m))), float(np.sqrt(last_sq / (p * m)))],
     }
     if measured is not None:

@@ -52,7 +52,7 @@ enum {
     SBO_STAGE_GROUP  = 1,  /* counting-sort bucketing of signals by block */
     SBO_STAGE_SELECT = 2,  /* support/coefficients/error in the winning block */
     SBO_STAGE_ACCUM  = 3,  /* P_j = Y_j X_j^T */
-    SBO_STAGE_SVD    = 4,  /* Jacobi SVD of each P_j and Q_j = U V^T */
+    SBO_STAGE_SVD    = 4,  /* Q_j = U V^T of each P_j (Algorithm 1, steps 6-7) */
     SBO_N_STAGES     = 5
 };
 
@@ -92,11 +92,13 @@ int sbo_group(sbo_ctx* c, const int32_t* blk, int64_t m,
 int sbo_accumulate(sbo_ctx* c, const float* Y, int64_t m, const int32_t* blk,
                    const int32_t* supp, const float* coef, float* M);
 
-/* Orthogonal factor of each M_j (Algorithm 1, steps 6-7): M_j = U S V^T by
- * one-sided Jacobi, Q_j = U V^T written to D[j] (atom-major, same convention as
- * M).  A block with counts[j] == 0 is left untouched (counts may be NULL = all
- * blocks updated).  Rank-deficient M_j: the null directions are completed to an
- * orthonormal basis (any completion is a valid U V^T).
+/* Orthogonal factor of each M_j (Algorithm 1, steps 6-7): with M_j = U S V^T,
+ * Q_j = U V^T written to D[j] (atom-major, same convention as M).  U V^T is the
+ * orthogonal polar factor of M_j; it is computed by the Newton-Schulz iteration on the
+ * matrix cores where that converges (condition numbers up to about 3000) and by a
+ * one-sided Jacobi SVD otherwise.  A block with counts[j] == 0 is left untouched
+ * (counts may be NULL = all blocks updated).  Rank-deficient M_j: the null directions
+ * are completed to an orthonormal basis (any completion is a valid U V^T).
  * in : M[K][p][p], counts[K] or NULL in/out: D[K][p][p] */
 int sbo_polar(sbo_ctx* c, const float* M, const int32_t* counts, float* D);
 
@@ -183,8 +185,9 @@ int sbo_learn(sbo_ctx* c, const float* Y, int64_t m, float* D, const int32_t* in
               int64_t P0, int R, int64_t W, int K_max, double target_rmse, int32_t* blk,
               int32_t* supp, float* coef, float* err, int* K_final, double* rmse_hist, int* n_hist);
 
-/* Jacobi sweeps the most recent SVD stage of this context needed, per orthobase (0 for an
- * orthobase that kept its basis).  sweeps: HOST int32[K].  Synchronises the stream. */
+/* Work of the most recent SVD stage of this context, per orthobase: a positive value is
+ * the number of Jacobi sweeps, a negative one minus the number of Newton-Schulz steps, 0 an
+ * orthobase that kept its basis.  sweeps: HOST int32[K].  Synchronises the stream. */
 int sbo_svd_sweeps(sbo_ctx* c, int32_t* sweeps);
 
 /* Measurement aids for a benchmark, not part of the path: the rate a bare fp32

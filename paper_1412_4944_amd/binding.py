@@ -200,7 +200,8 @@ def sbo_learn(ctx, Y, D, init_ids, R, W, K_max, target_rmse, blk, supp, coef, er
 
 
 def sbo_svd_sweeps(ctx, K: int) -> list:
-    """Jacobi sweeps per orthobase in the most recent SVD stage (K = blocks in use)."""
+    """Per orthobase, for the most recent SVD stage (K = blocks in use): Jacobi sweeps (> 0) or
+    minus the Newton-Schulz steps (< 0); 0 = kept its basis."""
     buf = (ctypes.c_int32 * K)()
     _check(lib().sbo_svd_sweeps(ctx, buf))
     return list(buf)
