@@ -3,7 +3,8 @@
 // chip: a 256 x 256 matrix does not fit the LDS of a CU, but every product of the iteration
 // splits into 64 independent 32 x 32 output tiles per block, so each step is two launches
 // (G = X^T X, then the update) over all tiles of all blocks, with X ping-ponging between two
-// global buffers (L2-resident: 256 KiB per block).
+// global buffers (L2-resident: 256 KiB per block); a workgroup computes a 64 x 64 part of the
+// result from two operand panels that it first copies into LDS.
 //
 // No launch depends on the host: the deviation d_k = max |X^T X - I| of every step is kept
 // per block (integer atomic maximum on the bit pattern of a non-negative float, so the
@@ -54,10 +55,50 @@ __device__ __forceinline__ int block_state(const NsScratch& ns, int j, int it) {
     return 0;
 }
 
+constexpr int kPanelLd = 64 + 4;               // leading dimension of a 256 x 64 panel in LDS
+constexpr int kRowLd = P + 4;                  // leading dimension of a 64 x 256 panel in LDS
+
+// Copies of operand panels into LDS: every thread issues all its 16-byte loads before the
+// first store, so a workgroup has its whole 64 KiB panel in flight at once (with one wavefront
+// per SIMD, loads issued a few at a time next to the MFMAs were what these kernels waited on).
+// cols: src[r][c0 .. c0+63], r < 256  ->  dst[r][0..63]
+__device__ __forceinline__ void load_col_panel(const float* __restrict__ src, int c0, float* dst,
+                                               int tid) {
+    f32x4 v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const int e = tid + 256 * u;           // 4096 units of 16 bytes: row e / 16, unit e % 16
+        v[u] = *reinterpret_cast<const f32x4*>(src + (e >> 4) * P + c0 + 4 * (e & 15));
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const int e = tid + 256 * u;
+        *reinterpret_cast<f32x4*>(dst + (e >> 4) * kPanelLd + 4 * (e & 15)) = v[u];
+    }
+}
+// rows: src[r0 .. r0+63][c], c < 256  ->  dst[0..63][c]
+__device__ __forceinline__ void load_row_panel(const float* __restrict__ src, int r0, float* dst,
+                                               int tid) {
+    f32x4 v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const int e = tid + 256 * u;           // row e / 64, unit e % 64
+        v[u] = *reinterpret_cast<const f32x4*>(src + (r0 + (e >> 6)) * P + 4 * (e & 63));
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const int e = tid + 256 * u;
+        *reinterpret_cast<f32x4*>(dst + (e >> 6) * kRowLd + 4 * (e & 63)) = v[u];
+    }
+}
+
 // G = X^T X for the X before step `it`; for it >= 1 also the deviation of the step.
+// A workgroup owns a 64 x 64 part of G (a wavefront one 32 x 32 tile of it) and stages the two
+// 256 x 64 column panels of X it needs in LDS.
 __global__ __launch_bounds__(256) void wide_ns_gram_kernel(const float* __restrict__ M,
                                                            const int32_t* __restrict__ counts,
                                                            float* scratch, int K, int it) {
+    extern __shared__ float panels[];          // [2][256][kPanelLd]
     const NsScratch ns = ns_carve(scratch, K);
     const int j = blockIdx.y;
     if (counts != nullptr && counts[j] == 0) return;       // uniform
@@ -69,27 +110,25 @@ __global__ __launch_bounds__(256) void wide_ns_gram_kernel(const float* __restri
     }
     const int lane = tid & 63, wave = tid >> 6;
     const int h = lane >> 5, n = lane & 31;
-    // a workgroup owns a 64 x 64 part of G, a wavefront one 32 x 32 tile of it
-    const int ta = 2 * (blockIdx.x / (kTiles / 2)) + (wave >> 1);
-    const int tb = 2 * (blockIdx.x % (kTiles / 2)) + (wave & 1);
+    const int sa = blockIdx.x / (kTiles / 2), sb = blockIdx.x % (kTiles / 2);
+    const int ta = 2 * sa + (wave >> 1), tb = 2 * sb + (wave & 1);
     const float* X = (it == 0 ? M : ((it & 1) ? ns.Xb : ns.Xa)) + (int64_t)j * P * P;
+
+    float* pa = panels;
+    float* pb = sa == sb ? panels : panels + P * kPanelLd;
+    load_col_panel(X, 64 * sa, pa, tid);
+    if (sa != sb) load_col_panel(X, 64 * sb, pb, tid);     // uniform
+    __syncthreads();
 
     f32x16 acc;
 #pragma unroll
     for (int q = 0; q < 16; ++q) acc[q] = 0.f;
-    // 32 steps (64 loads) in flight per wavefront: with one wavefront per SIMD the loads are
-    // what the kernel waits on
-#pragma unroll 1
-    for (int s0 = 0; s0 < P / 2; s0 += 32) {
-        float a[32], b[32];
-#pragma unroll
-        for (int u = 0; u < 32; ++u) {
-            a[u] = X[(2 * (s0 + u) + h) * P + ta * 32 + n];
-            b[u] = X[(2 * (s0 + u) + h) * P + tb * 32 + n];
-        }
-#pragma unroll
-        for (int u = 0; u < 32; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[u], acc, 0, 0, 0);
-    }
+    const float* ca = pa + (wave >> 1) * 32 + n;
+    const float* cb = pb + (wave & 1) * 32 + n;
+#pragma unroll 16
+    for (int s = 0; s < P / 2; ++s)
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ca[(2 * s + h) * kPanelLd], cb[(2 * s + h) * kPanelLd],
+                                                   acc, 0, 0, 0);
     float* Gj = ns.G + (int64_t)j * P * P;
     float dev = 0.f;
 #pragma unroll
@@ -142,9 +181,12 @@ __global__ __launch_bounds__(256) void wide_ns_scale_kernel(const int32_t* __res
 }
 
 // Step `it`: X_out = c1 X_in - c2 X_in G (c1 = 3/2, c2 = 1/2; step 0 folds the scaling in).
+// A workgroup owns a 64 x 64 part of X_out and stages the 64 x 256 row panel of X_in and the
+// 256 x 64 column panel of G in LDS.
 __global__ __launch_bounds__(256) void wide_ns_update_kernel(const float* __restrict__ M,
                                                              const int32_t* __restrict__ counts,
                                                              float* scratch, int K, int it) {
+    extern __shared__ float panels[];          // xrows[64][kRowLd] | gcols[256][kPanelLd]
     const NsScratch ns = ns_carve(scratch, K);
     const int j = blockIdx.y;
     if (counts != nullptr && counts[j] == 0) return;       // uniform
@@ -163,38 +205,34 @@ __global__ __launch_bounds__(256) void wide_ns_update_kernel(const float* __rest
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int h = lane >> 5, n = lane & 31;
-    const int tr = 2 * (blockIdx.x / (kTiles / 2)) + (wave >> 1);
-    const int tb = 2 * (blockIdx.x % (kTiles / 2)) + (wave & 1);
+    const int sr = blockIdx.x / (kTiles / 2), sb = blockIdx.x % (kTiles / 2);
     const float* Xin = (it == 0 ? M : ((it & 1) ? ns.Xb : ns.Xa)) + (int64_t)j * P * P;
     float* Xout = ((it & 1) ? ns.Xa : ns.Xb) + (int64_t)j * P * P;
     const float* Gj = ns.G + (int64_t)j * P * P;
 
-    // tile (tr, tb) of X G: rows r = tr*32 + n of X (16 bytes of a row feed two steps),
-    // contraction over a, columns tb*32 + n of G
+    float* xrows = panels;
+    float* gcols = panels + 64 * kRowLd;
+    load_row_panel(Xin, 64 * sr, xrows, tid);
+    load_col_panel(Gj, 64 * sb, gcols, tid);
+    __syncthreads();
+
+    // tile of X G: rows (wave>>1)*32 + n of the row panel (16 bytes of a row feed two steps),
+    // contraction over a, columns (wave&1)*32 + n of the column panel
     f32x16 acc;
 #pragma unroll
     for (int q = 0; q < 16; ++q) acc[q] = 0.f;
-    const f32x4* xrow = reinterpret_cast<const f32x4*>(Xin + (tr * 32 + n) * P);
-#pragma unroll 1
-    for (int q0 = 0; q0 < P / 4; q0 += 16) {
-        f32x4 v[16];
-        float b0[16], b1[16];
-#pragma unroll
-        for (int u = 0; u < 16; ++u) {
-            v[u] = xrow[q0 + u];
-            b0[u] = Gj[(4 * (q0 + u) + h) * P + tb * 32 + n];
-            b1[u] = Gj[(4 * (q0 + u) + 2 + h) * P + tb * 32 + n];
-        }
-#pragma unroll
-        for (int u = 0; u < 16; ++u) {
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(h ? v[u].y : v[u].x, b0[u], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(h ? v[u].w : v[u].z, b1[u], acc, 0, 0, 0);
-        }
+    const f32x4* xrow = reinterpret_cast<const f32x4*>(xrows + ((wave >> 1) * 32 + n) * kRowLd);
+    const float* gc = gcols + (wave & 1) * 32 + n;
+#pragma unroll 8
+    for (int q = 0; q < P / 4; ++q) {
+        const f32x4 v = xrow[q];
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(h ? v.y : v.x, gc[(4 * q + h) * kPanelLd], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(h ? v.w : v.z, gc[(4 * q + 2 + h) * kPanelLd], acc, 0, 0, 0);
     }
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
-        const int row = tr * 32 + (q >> 2) * 8 + h * 4 + (q & 3), col = tb * 32 + n;
-        Xout[row * P + col] = c1 * Xin[row * P + col] - c2 * acc[q];
+        const int lr = (wave >> 1) * 32 + (q >> 2) * 8 + h * 4 + (q & 3), lc = (wave & 1) * 32 + n;
+        Xout[(64 * sr + lr) * P + 64 * sb + lc] = c1 * xrows[lr * kRowLd + 64 * sb + lc] - c2 * acc[q];
     }
 }
 
@@ -247,11 +285,23 @@ size_t polar_wide_ns_scratch_bytes(int K) {
 hipError_t launch_polar_wide_ns(int K, const float* M, const int32_t* counts, float* D, float* scratch,
                                 int32_t* fallback, int32_t* iters, hipStream_t st) {
     constexpr int kSteps = 20;                 // < kHist
+    const size_t lds_gram = (size_t)2 * P * kPanelLd * sizeof(float);
+    const size_t lds_upd = ((size_t)64 * kRowLd + (size_t)P * kPanelLd) * sizeof(float);
+    static bool raised = false;
+    if (!raised) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wide_ns_gram_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_gram);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wide_ns_update_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_upd);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
     const dim3 grid((kTiles / 2) * (kTiles / 2), K);
     for (int it = 0; it < kSteps; ++it) {
-        hipLaunchKernelGGL(wide_ns_gram_kernel, grid, dim3(256), 0, st, M, counts, scratch, K, it);
+        hipLaunchKernelGGL(wide_ns_gram_kernel, grid, dim3(256), lds_gram, st, M, counts, scratch, K, it);
         if (it == 0) hipLaunchKernelGGL(wide_ns_scale_kernel, dim3(K), dim3(256), 0, st, counts, scratch, K);
-        hipLaunchKernelGGL(wide_ns_update_kernel, grid, dim3(256), 0, st, M, counts, scratch, K, it);
+        hipLaunchKernelGGL(wide_ns_update_kernel, grid, dim3(256), lds_upd, st, M, counts, scratch, K, it);
     }
     hipLaunchKernelGGL(wide_ns_finish_kernel, dim3(K), dim3(256), 0, st, counts, D, scratch, K, kSteps,
                        fallback, iters);
