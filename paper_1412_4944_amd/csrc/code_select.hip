@@ -220,6 +220,7 @@ __global__ __launch_bounds__(256) void select_wide_kernel(const float* __restric
     // lane h of a pair owns atoms [h*P/2, (h+1)*P/2) of its signal
     const float* mine = ct + h * (P / 2);
     int gt_own = 0, eq_own = 0;
+#pragma unroll 16
     for (int k = 0; k < P / 2; ++k) {
         const float a = fabsf(mine[k]);
         gt_own += a > tau;
@@ -232,6 +233,7 @@ __global__ __launch_bounds__(256) void select_wide_kernel(const float* __restric
     int pos = h ? gt_lo + eq_lo_taken : 0;
     int eq_taken = h ? eq_lo_taken : 0;
     float dropped = 0.f;
+#pragma unroll 16
     for (int k = 0; k < P / 2; ++k) {
         const float v = mine[k];
         const float a = fabsf(v);
