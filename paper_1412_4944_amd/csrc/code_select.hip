@@ -101,7 +101,7 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ Y
 // walking one half of the atoms in index order (which resolves magnitude ties directly).
 template <int P, int S>
 __global__ __launch_bounds__(256) void select_wide_kernel(const float* __restrict__ Y,
-                                                          const float* __restrict__ D, int K, int s0,
+                                                          const f32x4* __restrict__ Dsw, int K, int s0,
                                                           const int32_t* __restrict__ offsets,
                                                           const int32_t* __restrict__ perm,
                                                           int32_t* __restrict__ supp,
@@ -159,11 +159,15 @@ __global__ __launch_bounds__(256) void select_wide_kernel(const float* __restric
     // A operand = rows of Q_j straight from L2, QCH 16-byte groups per chunk; the next chunk is
     // requested before the MFMAs of the current one (a wavefront has its SIMD to itself here,
     // so nothing else would cover the load latency).
+    // Dsw is Q in the coding kernel's operand order (dict_swizzle_kernel): stage of 64 rows,
+    // unit (mt2*QN + q)*64 + lane = dims h*P/2 + 4q.. of row stage*64 + mt2*32 + n, so a
+    // wavefront's load is 1 KiB contiguous and the four wavefronts of a workgroup (tiles of the
+    // same block, in step) ask for the same lines.
     auto load_chunk = [&](f32x4 (&a)[QCH], int mt, int q0) {
-        const f32x4* arow =
-            reinterpret_cast<const f32x4*>(D + ((int64_t)j * P + mt * 32 + n) * P + h * KS);
+        const f32x4* src = Dsw + ((int64_t)j * (P / 64) + (mt >> 1)) * (2 * QN * 64) +
+                           ((mt & 1) * QN + q0) * 64 + lane;
 #pragma unroll
-        for (int q = 0; q < QCH; ++q) a[q] = arow[q0 + q];
+        for (int q = 0; q < QCH; ++q) a[q] = src[q * 64];
     };
     constexpr int NCH = QN / QCH;              // chunks per tile row of atoms (even)
     static_assert(NCH % 2 == 0, "chunk parity");
@@ -270,8 +274,9 @@ hipError_t launch_wide_ps(const float* Y, int64_t m, const float* D, int K, int 
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL((select_wide_kernel<P, S>), grid, dim3(256), lds, st, Y, D, K, s0,
-                       ws.offsets, ws.perm, supp, coef, err);
+    (void)D;                                   // the kernel reads ws.dsw, the same Q in operand order
+    hipLaunchKernelGGL((select_wide_kernel<P, S>), grid, dim3(256), lds, st, Y,
+                       reinterpret_cast<const f32x4*>(ws.dsw), K, s0, ws.offsets, ws.perm, supp, coef, err);
     return hipGetLastError();
 }
 
@@ -311,8 +316,12 @@ hipError_t launch_p(int s0, const float* Y, int64_t m, const float* D, int K, co
 }  // namespace
 
 hipError_t launch_select(int p, int K, int s0, const float* Y, int64_t m, const float* D,
-                         const Workspace& ws, int32_t* supp, float* coef, float* err,
+                         const Workspace& ws, int32_t* supp, float* coef, float* err, bool dsw_valid,
                          hipStream_t st) {
+    if (p == 256 && !dsw_valid) {              // the p = 256 kernel reads Q in operand order
+        hipError_t e = launch_dict_swizzle(p, K, D, ws.dsw, st);
+        if (e != hipSuccess) return e;
+    }
     switch (p) {
         case 16: return launch_p<16>(s0, Y, m, D, K, ws, supp, coef, err, st);
         case 32: return launch_p<32>(s0, Y, m, D, K, ws, supp, coef, err, st);

@@ -129,7 +129,7 @@ static int run_code(sbo_ctx* c, const float* Y, int64_t m, const float* D, int32
     if (rc) return rc;
     {
         StageTimer t(c, SBO_STAGE_SELECT);
-        SBO_HIP(launch_select(c->p, c->K, c->s0, Y, m, D, c->ws, supp, coef, err, c->stream));
+        SBO_HIP(launch_select(c->p, c->K, c->s0, Y, m, D, c->ws, supp, coef, err, true, c->stream));
     }
     return SBO_OK;
 }
@@ -338,7 +338,8 @@ static int run_train_rounds(sbo_ctx* c, const float* Y, int64_t m, const int32_t
         } else {
             {
                 StageTimer t(c, SBO_STAGE_SELECT);
-                SBO_HIP(launch_select(c->p, c->K, c->s0, Y, m, D, c->ws, supp, coef, err, c->stream));
+                SBO_HIP(launch_select(c->p, c->K, c->s0, Y, m, D, c->ws, supp, coef, err, false,
+                                      c->stream));
             }
             StageTimer t(c, SBO_STAGE_ACCUM);
             SBO_HIP(launch_accumulate(c->p, c->K, c->s0, Y, m, supp, coef, c->ws, c->ws.M, c->stream));
@@ -412,7 +413,7 @@ static int run_new_base(sbo_ctx* c, const float* Y, int64_t n, int R, int have_q
             SBO_HIP(launch_select_accum(c->p, 1, c->s0, Y, n, Q, c->ws, supp, coef, err, c->stream));
             SBO_HIP(launch_accum_reduce(c->p, 1, n, c->ws, c->ws.M, nullptr, nullptr, c->stream));
         } else {
-            SBO_HIP(launch_select(c->p, 1, c->s0, Y, n, Q, c->ws, supp, coef, err, c->stream));
+            SBO_HIP(launch_select(c->p, 1, c->s0, Y, n, Q, c->ws, supp, coef, err, false, c->stream));
             SBO_HIP(launch_accumulate(c->p, 1, c->s0, Y, n, supp, coef, c->ws, c->ws.M, c->stream));
         }
         if (sqerr_per_round)

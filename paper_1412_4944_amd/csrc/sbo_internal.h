@@ -151,8 +151,10 @@ hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const 
 hipError_t launch_group(int K, const int32_t* blk, int64_t m, const Workspace& ws, bool have_hist,
                         hipStream_t st);
 
+// dsw_valid: ws.dsw already holds this D in operand order (launch_dict_swizzle); p = 256 reads
+// it and rewrites it first otherwise.
 hipError_t launch_select(int p, int K, int s0, const float* Y, int64_t m, const float* D,
-                         const Workspace& ws, int32_t* supp, float* coef, float* err,
+                         const Workspace& ws, int32_t* supp, float* coef, float* err, bool dsw_valid,
                          hipStream_t st);
 
 hipError_t launch_accumulate(int p, int K, int s0, const float* Y, int64_t m, const int32_t* supp,
