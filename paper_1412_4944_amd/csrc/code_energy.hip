@@ -33,34 +33,41 @@ __device__ __forceinline__ SwapPair swap32(float x, float z) {
     return {__builtin_bit_cast(float, u0), __builtin_bit_cast(float, u1)};
 }
 
-// Sum of squares of the S largest magnitudes of the union of two sorted (descending)
-// S-lists, one per lane of a lane pair; valid and bitwise equal in both lanes.  The S
-// largest of the union are max(a_i(lo), a_{S-1-i}(hi)); the high lane reverses its list
-// so that both operands of one maximum sit in the same register, and one swap serves
-// two maxima.
-template <int S>
+// Sum of squares of the N largest magnitudes of the union of two sorted (descending)
+// lists, one per lane of a lane pair, of which the first N <= S entries are used (the N
+// largest of the union lie among the N largest of either list); valid and bitwise equal in
+// both lanes.  The N largest of the union are max(a_i(lo), a_{N-1-i}(hi)); the high lane
+// reverses its list so that both operands of one maximum sit in the same register, and one
+// swap serves two maxima.
+template <int S, int N>
 __device__ __forceinline__ float pair_fold_energy(const float (&a)[S], bool hi) {
-    if constexpr (S == 1) {
+    static_assert(N >= 1 && N <= S, "fold width");
+    if constexpr (N == 1) {
         SwapPair t = swap32(a[0], a[0]);
         const float m = fmaxf(t.first, t.second);
         return m * m;
     } else {
-        // r_i = hi ? a_{S-1-i} : a_i as one bit-select per element (written with integer
+        // r_i = hi ? a_{N-1-i} : a_i as one bit-select per element (written with integer
         // masks so that it is not rewritten into a lane-dependent index into a[])
         const unsigned msk = hi ? 0xffffffffu : 0u;
-        float r[S];
+        float r[N];
 #pragma unroll
-        for (int i = 0; i < S; ++i) {
+        for (int i = 0; i < N; ++i) {
             const unsigned fwd = __builtin_bit_cast(unsigned, a[i]);
-            const unsigned rev = __builtin_bit_cast(unsigned, a[S - 1 - i]);
+            const unsigned rev = __builtin_bit_cast(unsigned, a[N - 1 - i]);
             r[i] = __builtin_bit_cast(float, (rev & msk) | (fwd & ~msk));
         }
         float sum = 0.f;
 #pragma unroll
-        for (int i = 0; i < S; i += 2) {
+        for (int i = 0; i + 1 < N; i += 2) {
             SwapPair t = swap32(r[i], r[i + 1]);
             const float m = fmaxf(t.first, t.second);   // low lanes: maximum i, high: i+1
             sum = fmaf(m, m, sum);
+        }
+        if constexpr (N % 2 == 1) {            // the middle maximum: the same in both lanes, counted once
+            SwapPair t = swap32(r[N - 1], r[N - 1]);
+            const float m = fmaxf(t.first, t.second);
+            sum = fmaf(hi ? 0.f : m, m, sum);
         }
         SwapPair t = swap32(sum, sum);
         return t.first + t.second;
@@ -68,11 +75,12 @@ __device__ __forceinline__ float pair_fold_energy(const float (&a)[S], bool hi) 
 }
 
 // Energy (sum of squares) of the s0 largest magnitudes in the union of two sorted
-// (descending) S-lists of magnitudes, one per lane of a lane pair.  EXACT means s0 == S.
-template <int S, bool EXACT>
+// (descending) S-lists of magnitudes, one per lane of a lane pair.  SX = s0 when it is known
+// at compile time (S/2 < SX <= S), 0 otherwise.
+template <int S, int SX>
 __device__ __forceinline__ float pair_list_energy(const float (&a)[S], int s0, bool hi) {
-    if constexpr (EXACT) {
-        return pair_fold_energy<S>(a, hi);
+    if constexpr (SX > 0) {
+        return pair_fold_energy<S, SX>(a, hi);
     } else {
         float b[S], c[S];
 #pragma unroll
@@ -89,13 +97,13 @@ __device__ __forceinline__ float pair_list_energy(const float (&a)[S], int s0, b
 
 // The same for the NV magnitudes x held by this lane and the NV held by its partner
 // (one block's coefficients of one signal).  S = power of two >= s0, S <= 2 * NV.
-template <int NV, int S, bool EXACT>
+template <int NV, int S, int SX>
 __device__ __forceinline__ float pair_top_energy(const float (&x)[NV], int s0, bool hi) {
     constexpr int L = S < NV ? S : NV;
     float a[L];
     top_sorted<NV, L>(x, a);
     if constexpr (L == S) {
-        return pair_list_energy<S, EXACT>(a, s0, hi);
+        return pair_list_energy<S, SX>(a, s0, hi);
     } else {
         static_assert(2 * L == S, "sort width exceeds the coefficients of a lane pair");
         float c[S];
@@ -132,7 +140,7 @@ __global__ __launch_bounds__(256) void dict_swizzle_kernel(const float* __restri
     }
 }
 
-template <int P, int S, int NT, bool EXACT>
+template <int P, int S, int NT, int SX>
 __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y, int m,
                                                      const f32x4* __restrict__ Dsw, int K, int s0,
                                                      int32_t* __restrict__ blk,
@@ -254,7 +262,7 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
                         const int f = b * NV + v;      // flattened (tile, register)
                         x[v] = fabsf(acc[nt][f >> 4][f & 15]);
                     }
-                    const float e = pair_top_energy<NV, S, EXACT>(x, s0, h != 0);
+                    const float e = pair_top_energy<NV, S, SX>(x, s0, h != 0);
                     const int j = s * NB + b;
                     if (j < K && e > bestE[nt]) {
                         bestE[nt] = e;
@@ -281,7 +289,7 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
                     bitonic_merge_desc<S>(run[nt]);
                 }
                 if (part == SPB - 1) {
-                    const float e = pair_list_energy<S, EXACT>(run[nt], s0, h != 0);
+                    const float e = pair_list_energy<S, SX>(run[nt], s0, h != 0);
                     const int j = s / SPB;
                     if (j < K && e > bestE[nt]) {
                         bestE[nt] = e;
@@ -362,7 +370,7 @@ __global__ __launch_bounds__(256) void energy_merge_kernel(const float* __restri
     }
 }
 
-template <int P, int S, bool EXACT>
+template <int P, int S, int SX>
 hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, float* energy,
                       const f32x4* Dsw, int32_t* chunk_count, float* part_E, int32_t* part_j,
                       hipStream_t st) {
@@ -375,7 +383,7 @@ hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, fl
         static bool raised = false;
         if (!raised) {
             hipError_t e = hipFuncSetAttribute(
-                reinterpret_cast<const void*>(&energy_kernel<P, S, NT, EXACT>),
+                reinterpret_cast<const void*>(&energy_kernel<P, S, NT, SX>),
                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
             raised = true;
@@ -393,26 +401,43 @@ hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, fl
         const int units_per_y = (units + rows - 1) / rows;
         rows = (units + units_per_y - 1) / units_per_y;
         grid.y = rows;
-        hipLaunchKernelGGL((energy_kernel<P, S, NT, EXACT>), grid, dim3(256), lds, st, Y, (int)m, Dsw,
+        hipLaunchKernelGGL((energy_kernel<P, S, NT, SX>), grid, dim3(256), lds, st, Y, (int)m, Dsw,
                            K, s0, part_j, part_E, nullptr, chunk, units_per_y);
         hipLaunchKernelGGL(energy_merge_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256),
                            (size_t)K * sizeof(int), st, part_E, part_j, rows, (int)m, K, blk, energy,
                            chunk_count, chunk);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL((energy_kernel<P, S, NT, EXACT>), grid, dim3(256), lds, st, Y, (int)m, Dsw, K,
+    hipLaunchKernelGGL((energy_kernel<P, S, NT, SX>), grid, dim3(256), lds, st, Y, (int)m, Dsw, K,
                        s0, blk, energy, chunk_count, chunk, 0);
     return hipGetLastError();
 }
 
+// s0 in (S/2, S] is made a compile-time constant of the kernel (the lane-pair fold then
+// needs no sort), except where a lane holds fewer than S coefficients of a block (p = 16,
+// s0 > 8), which takes the run-time path.
 template <int P, int S>
 hipError_t launch_ps(const float* Y, int64_t m, int K, int s0, int32_t* blk, float* energy,
                      const float* dsw, int32_t* chunk_count, float* part_E, int32_t* part_j,
                      hipStream_t st) {
     const f32x4* Dsw = reinterpret_cast<const f32x4*>(dsw);
-    if (s0 == S)
-        return launch_pse<P, S, true>(Y, m, K, s0, blk, energy, Dsw, chunk_count, part_E, part_j, st);
-    return launch_pse<P, S, false>(Y, m, K, s0, blk, energy, Dsw, chunk_count, part_E, part_j, st);
+    constexpr int NV = P <= 64 ? P / 2 : 32;
+    if constexpr (S > NV) {
+        return launch_pse<P, S, 0>(Y, m, K, s0, blk, energy, Dsw, chunk_count, part_E, part_j, st);
+    } else {
+        switch (S - s0) {
+#define SBO_CASE(DELTA)                                                                          \
+    case DELTA:                                                                                  \
+        if constexpr (S - DELTA > S / 2 || S == 1)                                               \
+            return launch_pse<P, S, S - DELTA>(Y, m, K, s0, blk, energy, Dsw, chunk_count, part_E, \
+                                               part_j, st);                                      \
+        break;
+            SBO_CASE(0) SBO_CASE(1) SBO_CASE(2) SBO_CASE(3) SBO_CASE(4) SBO_CASE(5) SBO_CASE(6) SBO_CASE(7)
+#undef SBO_CASE
+            default: break;
+        }
+        return hipErrorInvalidValue;
+    }
 }
 
 template <int P>
