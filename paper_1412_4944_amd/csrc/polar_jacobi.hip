@@ -1,10 +1,14 @@
-// Batched SVD update Q_j = U V^T (Algorithm 1, steps 6-7), one workgroup per block.
+// Batched SVD update Q_j = U V^T (Algorithm 1, steps 6-7) by a Jacobi SVD, one workgroup per
+// block, and the dispatch between this kernel and the Newton-Schulz kernels (launch_polar):
+// the SVD runs for the blocks the Newton-Schulz iteration leaves flagged (rank-deficient or
+// very ill-conditioned P_j), in eigen mode (symmetric input, eigenvectors wanted), and for
+// every block when Newton-Schulz is switched off.
 //
 // One-sided (Hestenes) Jacobi: plane rotations applied from the right to the columns
 // of A = P_j and to V (starting at I) until all columns of A are mutually orthogonal;
 // then A = U diag(sigma) and P_j = U diag(sigma) V^T, so Q_j = sum_c (A_c / sigma_c) V_c^T.
 // A and V live in LDS for the whole decomposition.  p/2 disjoint column pairs (round-
-// robin tournament) are rotated concurrently, eight lanes per pair, with one barrier
+// robin tournament) are rotated concurrently, TPP (default 16) lanes per pair, with one barrier
 // per tournament round.  Columns whose norm vanishes (rank-deficient P_j) are replaced
 // by an orthonormal completion, which is a valid choice of U there.
 #include "sbo_internal.h"
