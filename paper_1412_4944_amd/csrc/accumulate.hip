@@ -361,7 +361,7 @@ __global__ __launch_bounds__(256) void accum_wide_kernel(const float* __restrict
             }
 }
 
-// Besides the sums over pieces (blockIdx.x < K), the column blockIdx.x == K of the grid forms
+// Besides the sums over pieces (blockIdx.x < K), nb workgroups in the grid columns from K on form
 // the total squared error sum_i err[i] (sq_out != nullptr): every workgroup of the column sums
 // a contiguous share in a fixed order, and the one that finishes last adds the shares in
 // index order (it is identified by an integer counter, which it sets back to zero; nobody
@@ -373,15 +373,16 @@ __global__ __launch_bounds__(256) void accum_reduce_kernel(int K, int piece,
                                                            float* __restrict__ M,
                                                            const float* __restrict__ err, int64_t m,
                                                            double* sq_part, int* sq_counter,
-                                                           double* __restrict__ sq_out) {
+                                                           double* __restrict__ sq_out, int nb) {
     constexpr int PP = P * P;
     extern __shared__ int lds[];               // piece_start[K+1] | tmp[16]
-    if ((int)blockIdx.x == K) {                // uniform over the workgroup
-        if (sq_out == nullptr) return;
+    if ((int)blockIdx.x >= K) {                // uniform over the workgroup
+        // the nb workgroups of the squared-error sum occupy the grid columns from K on
+        const int b = ((int)blockIdx.x - K) * (int)gridDim.y + (int)blockIdx.y;
+        if (sq_out == nullptr || b >= nb) return;
         __shared__ double red[256];
         __shared__ int is_last;
         const int tid = threadIdx.x;
-        const int nb = gridDim.y, b = blockIdx.y;
         const int64_t per = (m + nb - 1) / nb;
         const int64_t beg = b * per, end = beg + per < m ? beg + per : m;
         double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;   // four loads in flight per thread
@@ -455,7 +456,7 @@ hipError_t launch_ps(int K, const float* Y, int64_t m, const int32_t* supp, cons
                        Y, K, piece, ws.offsets, ws.perm, supp, coef, ws.partial);
     const size_t lds2 = (K + 1 + 16) * sizeof(int);
     hipLaunchKernelGGL((accum_reduce_kernel<P>), dim3(K, (P * P + 255) / 256), dim3(256), lds2, st,
-                       K, piece, ws.offsets, ws.partial, M, nullptr, (int64_t)0, nullptr, nullptr, nullptr);
+                       K, piece, ws.offsets, ws.partial, M, nullptr, (int64_t)0, nullptr, nullptr, nullptr, 0);
     return hipGetLastError();
 }
 
@@ -470,7 +471,7 @@ hipError_t launch_wide_s(int K, const float* Y, int64_t m, const int32_t* supp, 
                        ws.offsets, ws.perm, supp, coef, ws.partial);
     const size_t lds2 = (K + 1 + 16) * sizeof(int);
     hipLaunchKernelGGL((accum_reduce_kernel<P>), dim3(K, (P * P + 255) / 256), dim3(256), lds2, st,
-                       K, piece, ws.offsets, ws.partial, M, nullptr, (int64_t)0, nullptr, nullptr, nullptr);
+                       K, piece, ws.offsets, ws.partial, M, nullptr, (int64_t)0, nullptr, nullptr, nullptr, 0);
     return hipGetLastError();
 }
 
@@ -521,7 +522,7 @@ hipError_t launch_gram_p(const float* Y, int64_t n, const Workspace& ws, float* 
     hipLaunchKernelGGL((accum_piece_kernel<P, 1, true>), dim3(max_pieces), dim3(64 * kTallWaves), lds1, st,
                        Y, 1, piece, ws.offsets, ws.perm, nullptr, nullptr, ws.partial);
     hipLaunchKernelGGL((accum_reduce_kernel<P>), dim3(1, (P * P + 255) / 256), dim3(256),
-                       (1 + 1 + 16) * sizeof(int), st, 1, piece, ws.offsets, ws.partial, G, nullptr, (int64_t)0, nullptr, nullptr, nullptr);
+                       (1 + 1 + 16) * sizeof(int), st, 1, piece, ws.offsets, ws.partial, G, nullptr, (int64_t)0, nullptr, nullptr, nullptr, 0);
     return hipGetLastError();
 }
 
@@ -541,7 +542,7 @@ hipError_t launch_gram(int p, const float* Y, int64_t n, const Workspace& ws, fl
             hipLaunchKernelGGL((accum_wide_kernel<1, true>), dim3(max_pieces), dim3(256), lds1, st, Y, 1,
                                piece, ws.offsets, ws.perm, nullptr, nullptr, ws.partial);
             hipLaunchKernelGGL((accum_reduce_kernel<P>), dim3(1, (P * P + 255) / 256), dim3(256),
-                               (1 + 1 + 16) * sizeof(int), st, 1, piece, ws.offsets, ws.partial, G, nullptr, (int64_t)0, nullptr, nullptr, nullptr);
+                               (1 + 1 + 16) * sizeof(int), st, 1, piece, ws.offsets, ws.partial, G, nullptr, (int64_t)0, nullptr, nullptr, nullptr, 0);
             return hipGetLastError();
         }
         default: return hipErrorInvalidValue;
@@ -556,12 +557,13 @@ hipError_t launch_accum_reduce(int p, int K, int64_t m, const Workspace& ws, flo
     const size_t lds = (K + 1 + 16) * sizeof(int);
     const int gy = (p * p + 255) / 256;
     const bool sq = err != nullptr && sq_out != nullptr;
-    const dim3 grid(sq ? K + 1 : K, sq && gy < 128 ? 128 : gy);   // <= kSqBlocks shares of err
+    const int nb = sq ? 128 : 0;               // <= kSqBlocks shares of err
+    const dim3 grid(K + (nb + gy - 1) / gy, gy);
     double* so = sq ? sq_out : nullptr;
 #define SBO_CASE(N)                                                                              \
     case N:                                                                                      \
         hipLaunchKernelGGL((accum_reduce_kernel<N>), grid, dim3(256), lds, st, K, piece, ws.offsets, \
-                           ws.partial, M, err, m, ws.sq_partial, ws.sq_counter, so);             \
+                           ws.partial, M, err, m, ws.sq_partial, ws.sq_counter, so, nb);         \
         break;
     switch (p) {
         SBO_CASE(16) SBO_CASE(32) SBO_CASE(64) SBO_CASE(256)
