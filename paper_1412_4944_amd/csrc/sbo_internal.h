@@ -23,7 +23,7 @@ struct GroupGeom {
 inline GroupGeom group_geom(int64_t m) {
     int64_t c = (m + 1023) / 1024;
     c = ((c + 255) / 256) * 256;           // whole workgroups of the coding kernel (256 or 128 signals)
-    if (c < 512) c = 512;
+    if (c < 256) c = 256;
     GroupGeom g;
     g.chunk = (int)c;
     g.n_chunks = (int)((m + c - 1) / c);
