@@ -169,23 +169,25 @@ __global__ __launch_bounds__(256) void select_wide_kernel(const float* __restric
 #pragma unroll
         for (int q = 0; q < QCH; ++q) a[q] = src[q * 64];
     };
-    constexpr int NCH = QN / QCH;              // chunks per tile row of atoms (even)
-    static_assert(NCH % 2 == 0, "chunk parity");
-    f32x4 abuf[2][QCH];
+    constexpr int NCH = QN / QCH;              // chunks per tile row of atoms
+    static_assert(NCH == 4, "the operand ring below has four slots, one per chunk of a row");
+    // chunk t (t = mt * NCH + cc) lives in slot cc; it is requested two chunks ahead
+    f32x4 abuf[NCH][QCH];
     load_chunk(abuf[0], 0, 0);
+    load_chunk(abuf[1], 0, QCH);
 #pragma unroll 1
     for (int mt = 0; mt < MT; ++mt) {
         f32x16 acc = zero;
 #pragma unroll
         for (int cc = 0; cc < NCH; ++cc) {
-            // the last prefetch of all re-reads a valid row and is not used
-            const int nmt = cc + 1 < NCH ? mt : min(mt + 1, MT - 1);
-            load_chunk(abuf[(cc + 1) & 1], nmt, ((cc + 1) % NCH) * QCH);
+            // the last two requests of all re-read a valid row and are not used
+            const int nmt = cc + 2 < NCH ? mt : min(mt + 1, MT - 1);
+            load_chunk(abuf[(cc + 2) % NCH], nmt, ((cc + 2) % NCH) * QCH);
 #pragma unroll
             for (int q = 0; q < QCH; ++q)
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk)
-                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(abuf[cc & 1][q][kk],
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(abuf[cc][q][kk],
                                                                yb[4 * (cc * QCH + q) + kk], acc, 0, 0, 0);
         }
         float x[16], top[S];

@@ -40,11 +40,12 @@ inline int accum_piece(int64_t m, int K, int p) {
         if (v >= (p <= 64 ? 64 : 256) && v <= 4096 && v % 64 == 0) return v;
     }
     // p <= 64: two workgroups fit a CU, and all pieces should be resident in one round
-    // (pieces <= 2 * CUs where K allows); at p = 256 a piece result is 256 KiB, so fewer,
-    // larger pieces
+    // (pieces <= 2 * CUs where K allows)
     const int slots = 2 * kNumCU;
     const int target = K < slots / 2 ? slots - K : slots / 2;
-    int64_t c = p <= 64 ? (m + target - 1) / target : m / 300;
+    // p = 256: one workgroup per CU (512 registers per lane), so all pieces fit one round
+    const int target_wide = K < kNumCU / 2 ? kNumCU - K : kNumCU / 2;
+    int64_t c = p <= 64 ? (m + target - 1) / target : (m + target_wide - 1) / target_wide;
     c = ((c + 63) / 64) * 64;
     if (c < (p <= 64 ? 64 : 256)) c = p <= 64 ? 64 : 256;
     if (c > 4096) c = 4096;
