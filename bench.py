@@ -65,6 +65,8 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-probe", action="store_true",
                     help="skip the fp32 MFMA loop / device copy probes (achievable peaks)")
+    ap.add_argument("--no-learn", action="store_true",
+                    help="skip the timing of Algorithm 2 as a whole in the shape of the paper's Table 2")
     ap.add_argument("--no-next", action="store_true",
                     help="skip the (untimed-region) measurement of worst-W / base initialisation / new base")
     ap.add_argument("--copy-calib", action="store_true",
@@ -192,6 +194,41 @@ def main() -> int:
         del s2, c2, e2
     sbo.sbo_destroy(ctx)
 
+    # Algorithm 2 as a whole in the shape of the paper's Table 2 (m = 32768, p = 64, s0 = 8,
+    # K0 = 5, R = 6, dictionary grown to K = 8 / 16 / 32) on synthetic data of that shape; the
+    # paper prints neither W nor P0: W = 1024, P0 = 2048 here.  Context only (other data, other
+    # hardware): never the headline value.
+    learn = None
+    if not args.no_learn and p == 64:
+        import dataclasses
+        lcfg = dataclasses.replace(cfg, m=32768, s0=8)
+        lpr = synth.generate(lcfg)
+        lm, K0, P0, R, W = 32768, 5, 2048, 6, 1024
+        rng = np.random.default_rng(14124944)
+        sets = torch.from_numpy(np.stack([np.sort(rng.choice(lm, P0, replace=False))
+                                          for _ in range(K0)]).astype(np.int32)).to(dev)
+        Yl = torch.from_numpy(lpr.Y).to(dev)
+        lb = torch.empty(lm, dtype=torch.int32, device=dev)
+        ls = torch.empty((lm, 8), dtype=torch.int32, device=dev)
+        lc = torch.empty((lm, 8), dtype=torch.float32, device=dev)
+        le = torch.empty(lm, dtype=torch.float32, device=dev)
+        learn = {"m": lm, "p": 64, "s0": 8, "K0": K0, "P0": P0, "R": R, "W": W, "K": [], "seconds": [],
+                 "rmse": []}
+        for Kmax in (8, 16, 32):
+            lctx = sbo.sbo_create(64, Kmax, 8, lm)
+            Dl = torch.zeros((Kmax, 64, 64), dtype=torch.float32, device=dev)
+            best = float("inf")
+            for _ in range(2):
+                torch.cuda.synchronize()
+                ta = time.perf_counter()
+                Kf, hist = sbo.sbo_learn(lctx, Yl, Dl, sets, R, W, Kmax, 0.0, lb, ls, lc, le)
+                torch.cuda.synchronize()
+                best = min(best, time.perf_counter() - ta)
+            sbo.sbo_destroy(lctx)
+            learn["K"].append(Kf)
+            learn["seconds"].append(best)
+            learn["rmse"].append(hist[-1])
+
     total_s = t1 - t0
     ms_per_step = 1e3 * total_s / args.steps
     stage_ms = {k: v / args.steps for k, v in stage_sum.items()}
@@ -251,6 +288,8 @@ def main() -> int:
         out["update_hbm"]["frac_of_measured_copy"] = out["update_hbm"]["achieved_GBps"] / measured["hbm_copy_GBps"]
     if next_rows is not None:
         out["next_rows"] = next_rows
+    if learn is not None:
+        out["learn_table2_shape"] = learn
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(pr, min(args.cpu_sample, m))
     print(json.dumps(out))
