@@ -502,13 +502,14 @@ hipError_t launch_p(int K, int s0, const float* Y, int64_t m, const int32_t* sup
     }
 }
 
-// G = sum over the n signals listed in ws.perm of y y^T (one block: ws.offsets = {0, n}).
+// G[j] = sum over the signals of block j (ws.perm / ws.offsets, n signals in all) of y y^T.
 template <int P>
-hipError_t launch_gram_p(const float* Y, int64_t n, const Workspace& ws, float* G, hipStream_t st) {
+hipError_t launch_gram_p(int K, const float* Y, int64_t n, const Workspace& ws, float* G,
+                         hipStream_t st) {
     constexpr int MT = P >= 32 ? P / 32 : 1;
-    const int piece = accum_tall_piece(n, 1);
-    const int max_pieces = (int)((n + piece - 1) / piece) + 1;
-    const size_t head = ((size_t)(1 + 1 + 16) + 3) & ~(size_t)3;
+    const int piece = accum_tall_piece(n, K);
+    const int max_pieces = (int)((n + piece - 1) / piece) + K;
+    const size_t head = ((size_t)(K + 1 + 16) + 3) & ~(size_t)3;
     const size_t walk = (size_t)kTallWaves * 2 * kPairs * 64;
     const size_t xch = (size_t)(kTallWaves / 2) * MT * MT * 16 * 64;
     const size_t lds1 = (head + kTallMaxPiece + (walk > xch ? walk : xch)) * 4;
@@ -520,29 +521,31 @@ hipError_t launch_gram_p(const float* Y, int64_t n, const Workspace& ws, float* 
         raised = true;
     }
     hipLaunchKernelGGL((accum_piece_kernel<P, 1, true>), dim3(max_pieces), dim3(64 * kTallWaves), lds1, st,
-                       Y, 1, piece, ws.offsets, ws.perm, nullptr, nullptr, ws.partial);
-    hipLaunchKernelGGL((accum_reduce_kernel<P>), dim3(1, (P * P + 255) / 256), dim3(256),
-                       (1 + 1 + 16) * sizeof(int), st, 1, piece, ws.offsets, ws.partial, G, nullptr, (int64_t)0, nullptr, nullptr, nullptr, 0);
+                       Y, K, piece, ws.offsets, ws.perm, nullptr, nullptr, ws.partial);
+    hipLaunchKernelGGL((accum_reduce_kernel<P>), dim3(K, (P * P + 255) / 256), dim3(256),
+                       (K + 1 + 16) * sizeof(int), st, K, piece, ws.offsets, ws.partial, G, nullptr,
+                       (int64_t)0, nullptr, nullptr, nullptr, 0);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_gram(int p, const float* Y, int64_t n, const Workspace& ws, float* G,
+hipError_t launch_gram(int p, int K, const float* Y, int64_t n, const Workspace& ws, float* G,
                        hipStream_t st) {
     switch (p) {
-        case 16: return launch_gram_p<16>(Y, n, ws, G, st);
-        case 32: return launch_gram_p<32>(Y, n, ws, G, st);
-        case 64: return launch_gram_p<64>(Y, n, ws, G, st);
+        case 16: return launch_gram_p<16>(K, Y, n, ws, G, st);
+        case 32: return launch_gram_p<32>(K, Y, n, ws, G, st);
+        case 64: return launch_gram_p<64>(K, Y, n, ws, G, st);
         case 256: {
             constexpr int P = 256;
-            const int piece = accum_piece(n, 1, P);
-            const int max_pieces = (int)((n + piece - 1) / piece) + 1;
-            const size_t lds1 = (1 + 1 + 16 + kWideMaxPiece) * sizeof(int) + (size_t)4 * kWidePairs * 2 * 64 * sizeof(float);
-            hipLaunchKernelGGL((accum_wide_kernel<1, true>), dim3(max_pieces), dim3(256), lds1, st, Y, 1,
+            const int piece = accum_piece(n, K, P);
+            const int max_pieces = (int)((n + piece - 1) / piece) + K;
+            const size_t lds1 = (K + 1 + 16 + kWideMaxPiece) * sizeof(int) + (size_t)4 * kWidePairs * 2 * 64 * sizeof(float);
+            hipLaunchKernelGGL((accum_wide_kernel<1, true>), dim3(max_pieces), dim3(256), lds1, st, Y, K,
                                piece, ws.offsets, ws.perm, nullptr, nullptr, ws.partial);
-            hipLaunchKernelGGL((accum_reduce_kernel<P>), dim3(1, (P * P + 255) / 256), dim3(256),
-                               (1 + 1 + 16) * sizeof(int), st, 1, piece, ws.offsets, ws.partial, G, nullptr, (int64_t)0, nullptr, nullptr, nullptr, 0);
+            hipLaunchKernelGGL((accum_reduce_kernel<P>), dim3(K, (P * P + 255) / 256), dim3(256),
+                               (K + 1 + 16) * sizeof(int), st, K, piece, ws.offsets, ws.partial, G, nullptr,
+                               (int64_t)0, nullptr, nullptr, nullptr, 0);
             return hipGetLastError();
         }
         default: return hipErrorInvalidValue;

@@ -60,6 +60,32 @@ hipError_t launch_single_block(const int32_t* ids, int64_t n, int64_t m, const W
     return hipGetLastError();
 }
 
+namespace {
+
+__global__ __launch_bounds__(256) void equal_blocks_kernel(const int32_t* __restrict__ ids, int32_t n_blocks,
+                                                           int32_t per_block, int32_t m,
+                                                           int32_t* __restrict__ perm,
+                                                           int32_t* __restrict__ counts,
+                                                           int32_t* __restrict__ offsets) {
+    const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (q < (int64_t)n_blocks * per_block) perm[q] = min(max(ids[q], 0), m - 1);
+    if (q < n_blocks) counts[q] = per_block;
+    if (q <= n_blocks) offsets[q] = (int32_t)(q * per_block);
+}
+
+}  // namespace
+
+// n_blocks signal sets of per_block signals each (ids[n_blocks][per_block]) as the grouping of
+// n_blocks blocks: perm = the ids (clamped), counts[j] = per_block, offsets[j] = j * per_block.
+hipError_t launch_equal_blocks(const int32_t* ids, int n_blocks, int64_t per_block, int64_t m,
+                               const Workspace& ws, hipStream_t st) {
+    const int64_t n = (int64_t)n_blocks * per_block;
+    hipLaunchKernelGGL(equal_blocks_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, ids,
+                       n_blocks, (int32_t)per_block, (int32_t)m, ws.perm, ws.counts, ws.offsets);
+    return hipGetLastError();
+}
+
+
 // Sum of err over all m signals (ids == nullptr) or over the m listed signals.
 hipError_t launch_sqerr(const float* err, const int32_t* ids, int64_t m, const Workspace& ws,
                         double* out, hipStream_t st) {

@@ -383,7 +383,7 @@ int sbo_worst(sbo_ctx* c, const float* err, int64_t m, int64_t W, int32_t* ids) 
 
 // Gram matrix of the set -> its eigenvectors by descending eigenvalue (ws.perm etc. hold the set).
 static int run_init_base(sbo_ctx* c, const float* Y, int64_t n, float* Q, float* sv) {
-    SBO_HIP(launch_gram(c->p, Y, n, c->ws, c->ws.M, c->stream));
+    SBO_HIP(launch_gram(c->p, 1, Y, n, c->ws, c->ws.M, c->stream));
     SBO_HIP(launch_polar(c->p, 1, c->ws.M, nullptr, Q, c->ws, 0, sv ? sv : c->ws.energy, false,
                          c->stream));              // energy[m_max >= p] as a sink
     return SBO_OK;
@@ -464,10 +464,27 @@ int sbo_learn(sbo_ctx* c, const float* Y, int64_t m, float* D, const int32_t* in
     };
 
     // Initialisation: K0 orthobases, each trained on its own signal set; then represent.
-    for (int j = 0; j < K0; ++j) {
-        SBO_HIP(launch_single_block(init_ids + (size_t)j * P0, P0, m, c->ws, c->stream));
-        rc = run_new_base(c, Y, P0, R, 0, D + j * pp, supp, coef, err, nullptr);
-        if (rc) return fail(rc);
+    // p <= 64: all K0 at once, the sets as K0 blocks of one grouping (eq. (5) for every block,
+    // then R rounds of the fused select + accumulate and the SVD update over K0 blocks; a
+    // signal that sits in two sets only has its scratch rows of supp / coef / err written
+    // twice, which nothing reads).  Otherwise, and when the sets do not fit the workspace, one
+    // after the other.
+    const int64_t n_init = (int64_t)K0 * P0;
+    if (c->p <= 64 && n_init <= c->m_max && (int64_t)K0 * c->p <= c->m_max) {
+        SBO_HIP(launch_equal_blocks(init_ids, K0, P0, m, c->ws, c->stream));
+        SBO_HIP(launch_gram(c->p, K0, Y, n_init, c->ws, c->ws.M, c->stream));
+        SBO_HIP(launch_polar(c->p, K0, c->ws.M, nullptr, D, c->ws, 0, c->ws.energy, false, c->stream));
+        for (int r = 0; r < R; ++r) {
+            SBO_HIP(launch_select_accum(c->p, K0, c->s0, Y, n_init, D, c->ws, supp, coef, err, c->stream));
+            SBO_HIP(launch_accum_reduce(c->p, K0, n_init, c->ws, c->ws.M, nullptr, nullptr, c->stream));
+            SBO_HIP(launch_polar(c->p, K0, c->ws.M, c->ws.counts, D, c->ws, 0, nullptr, false, c->stream));
+        }
+    } else {
+        for (int j = 0; j < K0; ++j) {
+            SBO_HIP(launch_single_block(init_ids + (size_t)j * P0, P0, m, c->ws, c->stream));
+            rc = run_new_base(c, Y, P0, R, 0, D + j * pp, supp, coef, err, nullptr);
+            if (rc) return fail(rc);
+        }
     }
     int K = K0;
     c->K = K;

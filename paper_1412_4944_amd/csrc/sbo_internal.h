@@ -208,8 +208,14 @@ hipError_t launch_sqerr(const float* err, const int32_t* ids, int64_t m, const W
 hipError_t launch_single_block(const int32_t* ids, int64_t n, int64_t m, const Workspace& ws,
                                hipStream_t st);
 
-// G = sum over the n signals listed in ws.perm of y y^T (ws.offsets = {0, n}).
-hipError_t launch_gram(int p, const float* Y, int64_t n, const Workspace& ws, float* G,
+// n_blocks signal sets of per_block signals each (ids[n_blocks][per_block]) as K = n_blocks blocks:
+// ws.perm = the ids clamped to [0, m), ws.counts[j] = per_block, ws.offsets[j] = j * per_block.
+hipError_t launch_equal_blocks(const int32_t* ids, int n_blocks, int64_t per_block, int64_t m,
+                               const Workspace& ws, hipStream_t st);
+
+// G[j] = sum over the signals of block j (ws.perm / ws.offsets for K blocks, n signals in all)
+// of y y^T.
+hipError_t launch_gram(int p, int K, const float* Y, int64_t n, const Workspace& ws, float* G,
                        hipStream_t st);
 
 // Achievable peaks for the benchmark (probe.hip): bare fp32 MFMA loop, plain device copy (read + write).
