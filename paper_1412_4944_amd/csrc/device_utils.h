@@ -136,9 +136,47 @@ __host__ __device__ __forceinline__ void sort8_desc(float (&v)[8]) {
     cmpx_desc(v[1], v[2]); cmpx_desc(v[3], v[4]); cmpx_desc(v[5], v[6]);
 }
 
+// Median of three (one instruction on the device).
+__host__ __device__ __forceinline__ float med3(float a, float b, float c) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_fmed3f(a, b, c);
+#else
+    return fmaxf(fminf(a, b), fminf(fmaxf(a, b), c));
+#endif
+}
+
+// Insertion sort as a network of three-input operations (descending): inserting d into the
+// sorted v[0..n) gives max(v0, d), med3(v[i-1], d, v[i]) for 0 < i < n, min(v[n-1], d): n + 1
+// independent instructions.  3 + 4 + ... + N operations in all (33 for 8 keys, against 38 for
+// the 19-comparator network; 133 against 160 for 16 keys).
+template <int N>
+__host__ __device__ __forceinline__ void insertion_sort_desc(float (&v)[N]) {
+    if constexpr (N == 2) {
+        cmpx_desc(v[0], v[1]);
+    } else if constexpr (N >= 3) {
+        {
+            const float a = v[0], b = v[1], c = v[2];
+            v[0] = fmaxf(fmaxf(a, b), c);
+            v[1] = med3(a, b, c);
+            v[2] = fminf(fminf(a, b), c);
+        }
+#pragma unroll
+        for (int n = 3; n < N; ++n) {
+            const float d = v[n];
+            float r[N];
+            r[0] = fmaxf(v[0], d);
+#pragma unroll
+            for (int i = 1; i < n; ++i) r[i] = med3(v[i - 1], d, v[i]);
+            r[n] = fminf(v[n - 1], d);
+#pragma unroll
+            for (int i = 0; i <= n; ++i) v[i] = r[i];
+        }
+    }
+}
+
 template <int N>
 __host__ __device__ __forceinline__ void sort_desc(float (&v)[N]) {
-    if constexpr (N == 8) sort8_desc(v);
+    if constexpr (N <= 16) insertion_sort_desc<N>(v);
     else bitonic_sort_desc<N>(v);
 }
 
