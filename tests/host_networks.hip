@@ -33,6 +33,27 @@ template <int N> static void test_sort() {
     }
 }
 
+// the three-input insertion networks: exhaustive 0-1 inputs (a network of min / max / median
+// operations that sorts every 0-1 input sorts every input) and random floats
+template <int N> static void test_insertion() {
+    for (unsigned long long b = 0; b < (1ull << N); ++b) {
+        float v[N];
+        int ones = 0;
+        for (int i = 0; i < N; ++i) { v[i] = (b >> i) & 1; ones += (b >> i) & 1; }
+        insertion_sort_desc<N>(v);
+        for (int i = 0; i < N; ++i) CHECK(v[i] == (i < ones ? 1.f : 0.f));
+    }
+    std::mt19937 g(300 + N);
+    std::normal_distribution<float> d;
+    for (int rep = 0; rep < 2000; ++rep) {
+        float v[N], w[N];
+        for (int i = 0; i < N; ++i) v[i] = w[i] = (rep & 3) == 0 ? float(int(d(g) * 2)) : d(g);   // with ties
+        insertion_sort_desc<N>(v);
+        std::sort(w, w + N, [](float a, float b) { return a > b; });
+        for (int i = 0; i < N; ++i) CHECK(v[i] == w[i]);
+    }
+}
+
 static void test_sort8() {
     for (unsigned b = 0; b < 256; ++b) {
         float v[8];
@@ -104,6 +125,7 @@ static void test_slot() {
 
 int main() {
     test_sort8();
+    test_insertion<2>(); test_insertion<3>(); test_insertion<4>(); test_insertion<8>(); test_insertion<16>();
     test_sort<1>(); test_sort<2>(); test_sort<4>(); test_sort<8>(); test_sort<16>(); test_sort<32>();
     test_merge<1>(); test_merge<2>(); test_merge<4>(); test_merge<8>(); test_merge<16>();
     test_top<8, 1>(); test_top<8, 2>(); test_top<8, 4>(); test_top<8, 8>();
