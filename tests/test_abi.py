@@ -59,3 +59,15 @@ def test_compare_exchange_networks_on_host(tmp_path):
     assert r.returncode == 0, r.stderr[-2000:]
     r = subprocess.run([exe], capture_output=True, text=True)
     assert r.returncode == 0 and r.stdout.strip() == "ok", r.stdout[-2000:]
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    """No CPU fallback: with the shared library absent the binding raises instead of
+    computing anything some other way."""
+    import paper_1412_4944_amd.binding as b
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "LIB_PATH", str(tmp_path / "libsbo.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        b.lib()
+    with pytest.raises(RuntimeError):
+        b.sbo_workspace_bytes(64, 4, 8, 1024)
