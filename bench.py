@@ -213,7 +213,7 @@ def main() -> int:
         lc = torch.empty((lm, 8), dtype=torch.float32, device=dev)
         le = torch.empty(lm, dtype=torch.float32, device=dev)
         learn = {"m": lm, "p": 64, "s0": 8, "K0": K0, "P0": P0, "R": R, "W": W, "K": [], "seconds": [],
-                 "rmse": []}
+                 "rmse": [], "t_rep_ms": []}
         for Kmax in (8, 16, 32):
             lctx = sbo.sbo_create(64, Kmax, 8, lm)
             Dl = torch.zeros((Kmax, 64, 64), dtype=torch.float32, device=dev)
@@ -224,6 +224,15 @@ def main() -> int:
                 Kf, hist = sbo.sbo_learn(lctx, Yl, Dl, sets, R, W, Kmax, 0.0, lb, ls, lc, le)
                 torch.cuda.synchronize()
                 best = min(best, time.perf_counter() - ta)
+            rep = float("inf")                  # one representation pass with the learnt dictionary
+            for _ in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                sbo.sbo_code(lctx, Yl, Dl, lb, ls, lc, le)
+                e1.record()
+                torch.cuda.synchronize()
+                rep = min(rep, e0.elapsed_time(e1))
+            learn["t_rep_ms"].append(rep)
             sbo.sbo_destroy(lctx)
             learn["K"].append(Kf)
             learn["seconds"].append(best)
