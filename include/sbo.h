@@ -20,8 +20,9 @@
  *   - err  [m]        float : ||y_i - Q_blk x_i||^2 (squared residual).
  *   - All per-signal outputs are in the ORIGINAL signal order.
  *   - Work is enqueued on the HIP stream given to sbo_create; calls return
- *     without synchronising the host (exception: sbo_stage_ms).  Calls on one
- *     context must not overlap.
+ *     without synchronising the host (exceptions, each stated at its declaration:
+ *     sbo_stage_ms, sbo_svd_sweeps, sbo_learn, the two probes).  Calls on one context
+ *     must not overlap.
  *   - Return value: 0 on success, a negative SBO_E* code otherwise.  On error no
  *     output is defined; no exception crosses this boundary.
  *   - Supported shapes: p in {16, 32, 64, 256}, 1 <= s0 <= min(p, 16), 1 <= K <= 1024,
