@@ -24,10 +24,55 @@ if ROOT not in sys.path:
 PEAK_MFMA_F32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the roofline kernel, from the two rocprofv3 --pmc runs summarised in
-# profiles/headline_hbm_traffic_pmc.txt (FETCH_SIZE x 2.000 KiB + WRITE_SIZE x 1.000 KiB, factors
-# from a 256 MiB plain copy).  Only known for the workload those runs used.
-MEASURED_TRAFFIC_BYTES = {"headline": (72.04 + 2.13) * 1024 * 1024}
+ROOFLINE_KERNEL = "energy_kernel"
+
+
+def measured_traffic_bytes(workload: str):
+    """HBM bytes per launch of the roofline kernel from the tracked rocprofv3 --pmc summary
+    profiles/<workload>_hbm_traffic_pmc.txt (its line `roofline_kernel_hbm_bytes_per_launch:
+    <bytes> kernel=<name>`); None when there is no summary for this workload or it is for
+    another kernel."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic_pmc.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("roofline_kernel_hbm_bytes_per_launch:"):
+                    parts = line.split()
+                    if f"kernel={ROOFLINE_KERNEL}" in parts:
+                        return float(parts[1])
+    except OSError:
+        pass
+    return None
+
+
+class Probes:
+    """bench-only helper library (achievable peaks); not part of libsbo."""
+
+    def __init__(self):
+        import ctypes
+        path = os.path.join(ROOT, "paper_1412_4944_amd", "lib", "libsbo_benchprobe.so")
+        self.L = ctypes.CDLL(path)
+        self.L.bench_probe_mfma.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
+        self.L.bench_probe_copy.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_double)]
+        self.ct = ctypes
+
+    def _stream(self):
+        import torch
+        return self.ct.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    def mfma(self, iters):
+        v = self.ct.c_double(0.0)
+        rc = self.L.bench_probe_mfma(self._stream(), int(iters), self.ct.byref(v))
+        if rc != 0:
+            raise RuntimeError(f"bench_probe_mfma: HIP error {rc}")
+        return v.value
+
+    def copy(self):
+        v = self.ct.c_double(0.0)
+        rc = self.L.bench_probe_copy(self._stream(), self.ct.byref(v))
+        if rc != 0:
+            raise RuntimeError(f"bench_probe_copy: HIP error {rc}")
+        return v.value
 
 
 def cpu_baseline(pr, sample_m: int) -> dict:
@@ -110,9 +155,10 @@ def main() -> int:
     # they also bring the clocks up.
     measured = None
     if not args.no_probe:
-        measured = {"mfma_f32_tflops": sbo.sbo_probe_mfma(150),            # launches of ~0.6 ms, like the kernel's
-                    "mfma_f32_tflops_sustained": sbo.sbo_probe_mfma(4000),  # ~17 ms launches: power-limited
-                    "hbm_copy_GBps": sbo.sbo_probe_copy()}
+        pb = Probes()
+        measured = {"mfma_f32_tflops": pb.mfma(150),            # launches of ~0.6 ms, like the kernel's
+                    "mfma_f32_tflops_sustained": pb.mfma(4000),  # ~17 ms launches: power-limited
+                    "hbm_copy_GBps": pb.copy()}
 
     ctx = sbo.sbo_create(p, K, s0, m)
     # Timed region: HIP events around the roofline kernel only (an event pair per stage costs
@@ -271,7 +317,7 @@ def main() -> int:
         "roofline": {"kernel": "energy_kernel (fused Q^T y MFMA + top-s0 energy + block argmax)",
                      "bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_F32_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_MFMA_F32_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name)},
+                     "traffic": measured_traffic_bytes(cfg.name)},
         "energy_ms_timed_region": energy_ms,
         "stage_ms": stage_ms,
         "update_hbm": {"stages": "group + select (fused with accumulate for p<=64) + accum",

@@ -21,8 +21,7 @@
  *   - All per-signal outputs are in the ORIGINAL signal order.
  *   - Work is enqueued on the HIP stream given to sbo_create; calls return
  *     without synchronising the host (exceptions, each stated at its declaration:
- *     sbo_stage_ms, sbo_svd_sweeps, sbo_learn, the two probes).  Calls on one context
- *     must not overlap.
+ *     sbo_stage_ms, sbo_svd_sweeps, sbo_learn).  Calls on one context must not overlap.
  *   - Return value: 0 on success, a negative SBO_E* code otherwise.  On error no
  *     output is defined; no exception crosses this boundary.
  *   - Supported shapes: p in {16, 32, 64, 256}, 1 <= s0 <= min(p, 16), 1 <= K <= 1024,
@@ -97,7 +96,7 @@ int sbo_accumulate(sbo_ctx* c, const float* Y, int64_t m, const int32_t* blk,
  * Q_j = U V^T written to D[j] (atom-major, same convention as M).  U V^T is the
  * orthogonal polar factor of M_j; it is computed by the Newton-Schulz iteration on the
  * matrix cores where that converges (condition numbers up to about 3000) and by a
- * one-sided Jacobi SVD otherwise.  A block with counts[j] == 0 is left untouched
+ * one-sided Jacobi SVD otherwise (or always: sbo_set_option).  A block with counts[j] == 0 is left untouched
  * (counts may be NULL = all blocks updated).  Rank-deficient M_j: the null directions
  * are completed to an orthonormal basis (any completion is a valid U V^T).
  * in : M[K][p][p], counts[K] or NULL in/out: D[K][p][p] */
@@ -191,15 +190,20 @@ int sbo_learn(sbo_ctx* c, const float* Y, int64_t m, float* D, const int32_t* in
  * orthobase that kept its basis.  sweeps: HOST int32[K].  Synchronises the stream. */
 int sbo_svd_sweeps(sbo_ctx* c, int32_t* sweeps);
 
-/* Measurement aids for a benchmark, not part of the path: the rate a bare fp32
- * v_mfma_f32_32x32x2_f32 loop reaches on this GPU (TFLOP/s; 1024 workgroups of 4 wavefronts,
- * each issuing 32 * iters MFMAs: iters = 150 is a launch of about 0.6 ms, iters = 4000 one of
- * about 17 ms, long enough for the power limit to show) and the rate of a plain 256 MiB
- * device copy (GB/s, bytes read + bytes written), as achievable peaks next to the published
- * ones.  Each allocates and frees its own scratch and synchronises the stream.
- * tflops, gbps: HOST pointers. */
-int sbo_probe_mfma(void* hip_stream, int iters, double* tflops);
-int sbo_probe_copy(void* hip_stream, double* gbps);
+/* Options of a context (sbo_set_option). */
+enum {
+    SBO_OPT_SVD_METHOD = 0   /* how Q_j = U V^T is computed: SBO_SVD_AUTO or SBO_SVD_JACOBI */
+};
+enum {
+    SBO_SVD_AUTO   = 0,  /* default: Newton-Schulz polar factor on the matrix cores, the one-sided
+                            Jacobi SVD for the orthobases it flags (rank-deficient P_j) */
+    SBO_SVD_JACOBI = 1   /* the one-sided Jacobi SVD (one workgroup per orthobase) for every orthobase */
+};
+
+/* Set an option for every later call on this context (Algorithm 1 steps 6-7 leave the SVD
+ * routine open; both choices give the same Q_j up to rounding).  Unknown option or value:
+ * SBO_EINVAL, nothing changed. */
+int sbo_set_option(sbo_ctx* c, int option, int value);
 
 /* Per-stage timing with HIP events on the context's stream.  enable = 1 makes every
  * later call record events around each stage it runs; enable = 2 only around the energy

@@ -14,7 +14,7 @@ STAGES = ("energy", "group", "select", "accum", "svd")
 
 EXPORTS = ("sbo_create", "sbo_destroy", "sbo_workspace_bytes", "sbo_code", "sbo_group",
            "sbo_accumulate", "sbo_polar", "sbo_update", "sbo_train_rounds", "sbo_iterate", "sbo_sqerr",
-           "sbo_worst", "sbo_init_base", "sbo_new_base", "sbo_set_blocks", "sbo_learn", "sbo_svd_sweeps", "sbo_probe_mfma", "sbo_probe_copy", "sbo_set_timing", "sbo_stage_ms", "sbo_strerror")
+           "sbo_worst", "sbo_init_base", "sbo_new_base", "sbo_set_blocks", "sbo_learn", "sbo_svd_sweeps", "sbo_set_option", "sbo_set_timing", "sbo_stage_ms", "sbo_strerror")
 
 _lib = None
 
@@ -54,8 +54,7 @@ def lib() -> ctypes.CDLL:
     L.sbo_learn.argtypes = [vp, vp, i64, vp, vp, i32, i64, i32, i64, i32, ctypes.c_double, vp, vp, vp, vp,
                             ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
     L.sbo_svd_sweeps.argtypes = [vp, ctypes.POINTER(ctypes.c_int32)]
-    L.sbo_probe_mfma.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double)]
-    L.sbo_probe_copy.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
+    L.sbo_set_option.argtypes = [vp, i32, i32]
     L.sbo_set_timing.argtypes = [vp, i32]
     L.sbo_stage_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     L.sbo_strerror.argtypes = [i32]
@@ -207,25 +206,12 @@ def sbo_svd_sweeps(ctx, K: int) -> list:
     return list(buf)
 
 
-def _stream(stream):
-    if stream is None:
-        import torch
-        stream = torch.cuda.current_stream().cuda_stream
-    return ctypes.c_void_p(stream)
+SBO_OPT_SVD_METHOD = 0
+SBO_SVD_AUTO, SBO_SVD_JACOBI = 0, 1
 
 
-def sbo_probe_mfma(iters: int = 150, stream: int | None = None) -> float:
-    """TFLOP/s of a bare fp32 MFMA loop on this GPU (iters = 150: a launch of about 0.6 ms)."""
-    v = ctypes.c_double(0.0)
-    _check(lib().sbo_probe_mfma(_stream(stream), int(iters), ctypes.byref(v)))
-    return v.value
-
-
-def sbo_probe_copy(stream: int | None = None) -> float:
-    """GB/s (read + write) of a plain 256 MiB device copy on this GPU."""
-    v = ctypes.c_double(0.0)
-    _check(lib().sbo_probe_copy(_stream(stream), ctypes.byref(v)))
-    return v.value
+def sbo_set_option(ctx, option: int, value: int) -> None:
+    _check(lib().sbo_set_option(ctx, int(option), int(value)))
 
 
 def sbo_set_timing(ctx, enable) -> None:

@@ -444,14 +444,10 @@ hipError_t launch_ps(int K, const float* Y, int64_t m, const int32_t* supp, cons
     const size_t walk = (size_t)kTallWaves * 2 * kPairs * 64;
     const size_t xch = (size_t)(kTallWaves / 2) * MT * MT * 16 * 64;
     const size_t lds1 = (head + kTallMaxPiece + (walk > xch ? walk : xch)) * 4;
-    static bool raised = false;
-    if (!raised) {
-        hipError_t e =
-            hipFuncSetAttribute(reinterpret_cast<const void*>(&accum_piece_kernel<P, S0, false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
-        if (e != hipSuccess) return e;
-        raised = true;
-    }
+    if (hipError_t e = ws.raised->ensure(reinterpret_cast<const void*>(&accum_piece_kernel<P, S0, false>),
+                                         144 * 1024);
+        e != hipSuccess)
+        return e;
     hipLaunchKernelGGL((accum_piece_kernel<P, S0, false>), dim3(max_pieces), dim3(64 * kTallWaves), lds1, st,
                        Y, K, piece, ws.offsets, ws.perm, supp, coef, ws.partial);
     const size_t lds2 = (K + 1 + 16) * sizeof(int);
@@ -513,13 +509,10 @@ hipError_t launch_gram_p(int K, const float* Y, int64_t n, const Workspace& ws, 
     const size_t walk = (size_t)kTallWaves * 2 * kPairs * 64;
     const size_t xch = (size_t)(kTallWaves / 2) * MT * MT * 16 * 64;
     const size_t lds1 = (head + kTallMaxPiece + (walk > xch ? walk : xch)) * 4;
-    static bool raised = false;
-    if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&accum_piece_kernel<P, 1, true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
-        if (e != hipSuccess) return e;
-        raised = true;
-    }
+    if (hipError_t e = ws.raised->ensure(reinterpret_cast<const void*>(&accum_piece_kernel<P, 1, true>),
+                                         144 * 1024);
+        e != hipSuccess)
+        return e;
     hipLaunchKernelGGL((accum_piece_kernel<P, 1, true>), dim3(max_pieces), dim3(64 * kTallWaves), lds1, st,
                        Y, K, piece, ws.offsets, ws.perm, nullptr, nullptr, ws.partial);
     hipLaunchKernelGGL((accum_reduce_kernel<P>), dim3(K, (P * P + 255) / 256), dim3(256),

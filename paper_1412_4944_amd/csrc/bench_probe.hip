@@ -1,12 +1,23 @@
-// Measurement aids for the benchmark, not part of the SBO path: what a bare fp32 MFMA loop
-// and a plain device copy reach on this GPU, so that a kernel's rate can be quoted against an
-// achievable peak as well as against the published one.
-#include "sbo_internal.h"
-#include "device_utils.h"
-
-namespace sbo {
+// Measurement aids for the benchmark, NOT part of libsbo (built into a shared library of its
+// own, which only bench.py loads): what a bare fp32 MFMA loop and a plain device copy reach on
+// this GPU, so that a kernel's rate can be quoted against an achievable peak as well as against
+// the published one.
+//
+//   int bench_probe_mfma(void* hip_stream, int iters, double* tflops)
+//       rate of a bare v_mfma_f32_32x32x2_f32 loop (TFLOP/s; 1024 workgroups of 4 wavefronts,
+//       each issuing 32 * iters MFMAs: iters = 150 is a launch of about 0.6 ms, iters = 4000
+//       one of about 17 ms, long enough for the power limit to show)
+//   int bench_probe_copy(void* hip_stream, double* gbps)
+//       rate of a plain 256 MiB device copy (GB/s, bytes read + bytes written)
+// Both allocate and free their own scratch and synchronise the stream; tflops / gbps are host
+// pointers; the return value is a hipError_t (0 = success).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
 namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 // 4 independent accumulator tiles per wavefront, nothing but v_mfma_f32_32x32x2_f32.
 __global__ __launch_bounds__(256) void probe_mfma_kernel(float* __restrict__ out, int iters) {
@@ -49,8 +60,6 @@ struct EventPair {
         if (b) (void)hipEventDestroy(b);
     }
 };
-
-}  // namespace
 
 hipError_t probe_mfma(hipStream_t st, int iters, double* tflops) {
     constexpr int kWgs = 1024;
@@ -103,4 +112,14 @@ hipError_t probe_copy(hipStream_t st, double* gbps) {
     return e;
 }
 
-}  // namespace sbo
+}  // namespace
+
+extern "C" int bench_probe_mfma(void* hip_stream, int iters, double* tflops) {
+    if (!tflops || iters < 1 || iters > 100000) return (int)hipErrorInvalidValue;
+    return (int)probe_mfma((hipStream_t)hip_stream, iters, tflops);
+}
+
+extern "C" int bench_probe_copy(void* hip_stream, double* gbps) {
+    if (!gbps) return (int)hipErrorInvalidValue;
+    return (int)probe_copy((hipStream_t)hip_stream, gbps);
+}

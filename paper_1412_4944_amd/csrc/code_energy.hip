@@ -373,21 +373,17 @@ __global__ __launch_bounds__(256) void energy_merge_kernel(const float* __restri
 template <int P, int S, int SX>
 hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, float* energy,
                       const f32x4* Dsw, int32_t* chunk_count, float* part_E, int32_t* part_j,
-                      hipStream_t st) {
+                      LdsRaised* raised, hipStream_t st) {
     constexpr int NT = P <= 64 ? 2 : 1;
     constexpr int QN = P / 8;
     constexpr size_t lds = (size_t)2 * (2 * QN * 64) * sizeof(f32x4);
     const int per_wg = 4 * 32 * NT;
     dim3 grid((unsigned)((m + per_wg - 1) / per_wg));
     if (lds > 64 * 1024) {
-        static bool raised = false;
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute(
-                reinterpret_cast<const void*>(&energy_kernel<P, S, NT, SX>),
-                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            raised = true;
-        }
+        if (raised == nullptr) return hipErrorInvalidValue;
+        if (hipError_t e = raised->ensure(reinterpret_cast<const void*>(&energy_kernel<P, S, NT, SX>), lds);
+            e != hipSuccess)
+            return e;
     }
     const int chunk = group_geom(m).chunk;
     if (chunk % per_wg != 0) return hipErrorInvalidValue;
@@ -419,18 +415,18 @@ hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, fl
 template <int P, int S>
 hipError_t launch_ps(const float* Y, int64_t m, int K, int s0, int32_t* blk, float* energy,
                      const float* dsw, int32_t* chunk_count, float* part_E, int32_t* part_j,
-                     hipStream_t st) {
+                     LdsRaised* raised, hipStream_t st) {
     const f32x4* Dsw = reinterpret_cast<const f32x4*>(dsw);
     constexpr int NV = P <= 64 ? P / 2 : 32;
     if constexpr (S > NV) {
-        return launch_pse<P, S, 0>(Y, m, K, s0, blk, energy, Dsw, chunk_count, part_E, part_j, st);
+        return launch_pse<P, S, 0>(Y, m, K, s0, blk, energy, Dsw, chunk_count, part_E, part_j, raised, st);
     } else {
         switch (S - s0) {
 #define SBO_CASE(DELTA)                                                                          \
     case DELTA:                                                                                  \
         if constexpr (S - DELTA > S / 2 || S == 1)                                               \
             return launch_pse<P, S, S - DELTA>(Y, m, K, s0, blk, energy, Dsw, chunk_count, part_E, \
-                                               part_j, st);                                      \
+                                               part_j, raised, st);                              \
         break;
             SBO_CASE(0) SBO_CASE(1) SBO_CASE(2) SBO_CASE(3) SBO_CASE(4) SBO_CASE(5) SBO_CASE(6) SBO_CASE(7)
 #undef SBO_CASE
@@ -443,12 +439,12 @@ hipError_t launch_ps(const float* Y, int64_t m, int K, int s0, int32_t* blk, flo
 template <int P>
 hipError_t launch_p(int s0, const float* Y, int64_t m, int K, int32_t* blk, float* energy,
                     const float* dsw, int32_t* chunk_count, float* part_E, int32_t* part_j,
-                    hipStream_t st) {
-    if (s0 <= 1) return launch_ps<P, 1>(Y, m, K, s0, blk, energy, dsw, chunk_count, part_E, part_j, st);
-    if (s0 <= 2) return launch_ps<P, 2>(Y, m, K, s0, blk, energy, dsw, chunk_count, part_E, part_j, st);
-    if (s0 <= 4) return launch_ps<P, 4>(Y, m, K, s0, blk, energy, dsw, chunk_count, part_E, part_j, st);
-    if (s0 <= 8) return launch_ps<P, 8>(Y, m, K, s0, blk, energy, dsw, chunk_count, part_E, part_j, st);
-    return launch_ps<P, 16>(Y, m, K, s0, blk, energy, dsw, chunk_count, part_E, part_j, st);
+                    LdsRaised* raised, hipStream_t st) {
+    if (s0 <= 1) return launch_ps<P, 1>(Y, m, K, s0, blk, energy, dsw, chunk_count, part_E, part_j, raised, st);
+    if (s0 <= 2) return launch_ps<P, 2>(Y, m, K, s0, blk, energy, dsw, chunk_count, part_E, part_j, raised, st);
+    if (s0 <= 4) return launch_ps<P, 4>(Y, m, K, s0, blk, energy, dsw, chunk_count, part_E, part_j, raised, st);
+    if (s0 <= 8) return launch_ps<P, 8>(Y, m, K, s0, blk, energy, dsw, chunk_count, part_E, part_j, raised, st);
+    return launch_ps<P, 16>(Y, m, K, s0, blk, energy, dsw, chunk_count, part_E, part_j, raised, st);
 }
 
 }  // namespace
@@ -468,12 +464,12 @@ hipError_t launch_dict_swizzle(int p, int K, const float* D, float* dsw, hipStre
 
 hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const float* dsw,
                          int32_t* blk, float* energy, int32_t* chunk_count, float* part_E,
-                         int32_t* part_j, hipStream_t st) {
+                         int32_t* part_j, LdsRaised* raised, hipStream_t st) {
     switch (p) {
-        case 16: return launch_p<16>(s0, Y, m, K, blk, energy, dsw, chunk_count, part_E, part_j, st);
-        case 32: return launch_p<32>(s0, Y, m, K, blk, energy, dsw, chunk_count, part_E, part_j, st);
-        case 64: return launch_p<64>(s0, Y, m, K, blk, energy, dsw, chunk_count, part_E, part_j, st);
-        case 256: return launch_p<256>(s0, Y, m, K, blk, energy, dsw, chunk_count, part_E, part_j, st);
+        case 16: return launch_p<16>(s0, Y, m, K, blk, energy, dsw, chunk_count, part_E, part_j, raised, st);
+        case 32: return launch_p<32>(s0, Y, m, K, blk, energy, dsw, chunk_count, part_E, part_j, raised, st);
+        case 64: return launch_p<64>(s0, Y, m, K, blk, energy, dsw, chunk_count, part_E, part_j, raised, st);
+        case 256: return launch_p<256>(s0, Y, m, K, blk, energy, dsw, chunk_count, part_E, part_j, raised, st);
         default: return hipErrorInvalidValue;
     }
 }

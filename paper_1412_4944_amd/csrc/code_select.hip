@@ -269,13 +269,9 @@ hipError_t launch_wide_ps(const float* Y, int64_t m, const float* D, int K, int 
     const int64_t max_tiles = (m + 31) / 32 + K;
     dim3 grid((unsigned)((max_tiles + 3) / 4));
     const size_t lds = (K + 1 + 16) * sizeof(int) + 4 * 32 * (P + 1) * sizeof(float);
-    static bool raised = false;
-    if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_wide_kernel<P, S>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        raised = true;
-    }
+    if (hipError_t e = ws.raised->ensure(reinterpret_cast<const void*>(&select_wide_kernel<P, S>), lds);
+        e != hipSuccess)
+        return e;
     (void)D;                                   // the kernel reads ws.dsw, the same Q in operand order
     hipLaunchKernelGGL((select_wide_kernel<P, S>), grid, dim3(256), lds, st, Y,
                        reinterpret_cast<const f32x4*>(ws.dsw), K, s0, ws.offsets, ws.perm, supp, coef, err);

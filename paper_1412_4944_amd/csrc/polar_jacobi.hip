@@ -20,7 +20,7 @@ namespace {
 
 constexpr int kMaxSweeps = 30;
 // A pair is rotated while |a_i . a_j| > kTol |a_i| |a_j|.  Convergence is quadratic: a
-// sweep in which every pair already had a cosine below `done` (polar_done()) leaves cosines of
+// sweep in which every pair already had a cosine below `done` (kPolarDone) leaves cosines of
 // the order of done^2 behind, so it is the last one and no sweep is spent on verifying.
 constexpr float kTol = 1e-6f;
 
@@ -28,7 +28,6 @@ template <int P, int TPP>
 __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __restrict__ M,
                                                              const int32_t* __restrict__ counts,
                                                              float* __restrict__ D,
-                                                             float* __restrict__ Vstate, int warm,
                                                              float* __restrict__ eig_sv, float done,
                                                              float* __restrict__ dsw,
                                                              int32_t* __restrict__ sweeps_out,
@@ -40,7 +39,6 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
     static_assert(RPT >= 1 && P % TPP == 0, "rows per lane");
     __shared__ __attribute__((aligned(16))) float A[P * LD];
     __shared__ __attribute__((aligned(16))) float V[P * LD];
-    __shared__ __attribute__((aligned(16))) float B[P * LD];   // warm start only
     __shared__ float sig[P];
     __shared__ float coefs[P];
     __shared__ float vec[P];
@@ -51,9 +49,6 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
     const int tid = threadIdx.x;
     if (only != nullptr && only[j] == 0) return;        // uniform: another kernel has done this block
     if (counts != nullptr && counts[j] == 0) {          // uniform: block keeps its basis
-        if (Vstate != nullptr && !warm)                 // a cold pass defines every block's V
-            for (int e = tid; e < P * P; e += NT)
-                Vstate[(int64_t)j * P * P + e] = (e / P == e % P) ? 1.f : 0.f;
         if (sweeps_out != nullptr && tid == 0) sweeps_out[j] = 0;
         return;
     }
@@ -77,30 +72,6 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
         V[c * LD + r] = (c == r) ? 1.f : 0.f;
     }
     __syncthreads();
-
-    // Warm start: begin from the V of this block's previous decomposition.  Any orthogonal
-    // start is valid (P_j V is decomposed instead of P_j and the products are accumulated
-    // into the same V); one close to the answer saves sweeps.
-    if (Vstate != nullptr && warm) {
-        const float* Vj = Vstate + (int64_t)j * P * P;
-        for (int e = tid; e < P * P; e += NT) {
-            const int c = e / P, r = e % P;
-            B[c * LD + r] = A[c * LD + r];
-            V[c * LD + r] = Vj[e];
-        }
-        __syncthreads();
-        for (int o = tid; o < P * P / 4; o += NT) {
-            const int c = o / (P / 4), r4 = (o % (P / 4)) * 4;
-            f32x4 s4 = {0.f, 0.f, 0.f, 0.f};
-            for (int k = 0; k < P; ++k) {
-                const f32x4 b4 = *reinterpret_cast<const f32x4*>(&B[k * LD + r4]);
-                const float v = V[c * LD + k];
-                s4 += b4 * v;
-            }
-            *reinterpret_cast<f32x4*>(&A[c * LD + r4]) = s4;
-        }
-        __syncthreads();
-    }
 
     // Round-robin tournament on P players: player P-1 stays, the others rotate; group pi
     // meets columns ca, cb, which advance by one (mod P-1) every round.
@@ -240,11 +211,6 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
     }
     __syncthreads();
 
-    if (Vstate != nullptr) {
-        float* Vj = Vstate + (int64_t)j * P * P;
-        for (int e = tid; e < P * P; e += NT) Vj[e] = V[(e / P) * LD + (e % P)];
-    }
-
     // Eigen mode (P_j symmetric positive semidefinite, e.g. a Gram matrix sum y y^T): the
     // columns of V are its eigenvectors and the column norms of A its eigenvalues.  Output:
     // atom k = eigenvector of the k-th largest eigenvalue (equal values: lower column first),
@@ -345,50 +311,42 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
 
 }  // namespace
 
-template <int TPP>
-hipError_t launch_tpp(int p, int K, const float* M, const int32_t* counts, float* D, float* vstate,
-                      int warm, float* eig_sv, float* dsw, int32_t* sweeps, const int32_t* only,
-                      hipStream_t st) {
-    const float done = polar_done();
+// TPP = 16 lanes per column pair (4 and 8 were measured slower at every p).
+static hipError_t launch_jacobi(int p, int K, const float* M, const int32_t* counts, float* D,
+                                float* eig_sv, float* dsw, int32_t* sweeps, const int32_t* only,
+                                hipStream_t st) {
+    constexpr int TPP = 16;
+    const float done = kPolarDone;
     switch (p) {
-        case 16: hipLaunchKernelGGL((polar_kernel<16, TPP>), dim3(K), dim3(8 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv, done, dsw, sweeps, only); break;
-        case 32: hipLaunchKernelGGL((polar_kernel<32, TPP>), dim3(K), dim3(16 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv, done, dsw, sweeps, only); break;
-        case 64: hipLaunchKernelGGL((polar_kernel<64, TPP>), dim3(K), dim3(32 * TPP), 0, st, M, counts, D, vstate, warm, eig_sv, done, dsw, sweeps, only); break;
+        case 16: hipLaunchKernelGGL((polar_kernel<16, TPP>), dim3(K), dim3(8 * TPP), 0, st, M, counts, D, eig_sv, done, dsw, sweeps, only); break;
+        case 32: hipLaunchKernelGGL((polar_kernel<32, TPP>), dim3(K), dim3(16 * TPP), 0, st, M, counts, D, eig_sv, done, dsw, sweeps, only); break;
+        case 64: hipLaunchKernelGGL((polar_kernel<64, TPP>), dim3(K), dim3(32 * TPP), 0, st, M, counts, D, eig_sv, done, dsw, sweeps, only); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
-static hipError_t launch_jacobi(int p, int K, const float* M, const int32_t* counts, float* D,
-                                float* vstate, int warm, float* eig_sv, float* dsw, int32_t* sweeps,
-                                const int32_t* only, hipStream_t st) {
-    int tpp = 16;
-    if (const char* e = getenv("SBO_POLAR_TPP")) tpp = atoi(e);   // tuning override
-    if (tpp == 4) return launch_tpp<4>(p, K, M, counts, D, vstate, warm, eig_sv, dsw, sweeps, only, st);
-    if (tpp == 8) return launch_tpp<8>(p, K, M, counts, D, vstate, warm, eig_sv, dsw, sweeps, only, st);
-    return launch_tpp<16>(p, K, M, counts, D, vstate, warm, eig_sv, dsw, sweeps, only, st);
-}
-
 hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
-                        const Workspace& ws, int warm, float* eig_sv, bool write_dsw,
+                        const Workspace& ws, int jacobi_only, float* eig_sv, bool write_dsw,
                         hipStream_t st) {
-    bool ns = eig_sv == nullptr;
-    if (const char* e = getenv("SBO_POLAR_NS")) ns = ns && atoi(e) != 0;   // 0: Jacobi only
+    const bool ns = eig_sv == nullptr && !jacobi_only;
     if (p == 256) {
         if (write_dsw) return hipErrorInvalidValue;   // p = 256 rewrites the operand order itself
         if (!ns)
-            return launch_polar_wide(K, M, counts, D, ws.vstate, warm, ws.jac_a, eig_sv, ws.sweeps, nullptr, st);
-        hipError_t e = launch_polar_wide_ns(K, M, counts, D, ws.jac_a, ws.ns_fallback, ws.sweeps, st);
+            return launch_polar_wide(K, M, counts, D, ws.vwork, ws.jac_a, eig_sv, ws.sweeps, nullptr,
+                                     ws.raised, st);
+        hipError_t e = launch_polar_wide_ns(K, M, counts, D, ws.jac_a, ws.ns_fallback, ws.sweeps,
+                                            ws.raised, st);
         if (e != hipSuccess) return e;
-        return launch_polar_wide(K, M, counts, D, ws.vstate, 0, ws.jac_a, nullptr, ws.sweeps, ws.ns_fallback, st);
+        return launch_polar_wide(K, M, counts, D, ws.vwork, ws.jac_a, nullptr, ws.sweeps,
+                                 ws.ns_fallback, ws.raised, st);
     }
     float* dsw = write_dsw ? ws.dsw : nullptr;
-    if (!ns) return launch_jacobi(p, K, M, counts, D, ws.vstate, warm, eig_sv, dsw, ws.sweeps, nullptr, st);
-    // Newton-Schulz for every block; the Jacobi SVD (cold: no V of a previous call is kept for
-    // these blocks) only for the ones it flags.
+    if (!ns) return launch_jacobi(p, K, M, counts, D, eig_sv, dsw, ws.sweeps, nullptr, st);
+    // Newton-Schulz for every block; the Jacobi SVD only for the ones it flags.
     hipError_t e = launch_polar_ns(p, K, M, counts, D, dsw, ws.ns_fallback, ws.sweeps, st);
     if (e != hipSuccess) return e;
-    return launch_jacobi(p, K, M, counts, D, ws.vstate, 0, nullptr, dsw, ws.sweeps, ws.ns_fallback, st);
+    return launch_jacobi(p, K, M, counts, D, nullptr, dsw, ws.sweeps, ws.ns_fallback, st);
 }
 
 }  // namespace sbo

@@ -101,11 +101,14 @@ __global__ __launch_bounds__(P == 64 ? 256 : 64) void polar_ns_kernel(
     };
 
     // Scale so that the largest singular value is about one.  sigma_max^2 is the largest
-    // eigenvalue of G = X^T X: a few power-iteration steps from the vector of absolute row sums
-    // give a Rayleigh quotient just below it (a bound such as the largest row sum is safe but
-    // often two to three times too large, which costs iterations).  The iteration converges for
-    // any sigma_max < sqrt(3), so an estimate within that factor is good enough; should it ever
-    // be worse, the deviation test below sends the block to the fallback.
+    // eigenvalue of G = X^T X.  The iteration sends every singular value in (0, sqrt(3)) to +1,
+    // one in (sqrt(3), sqrt(5)) to -1 (an orthogonal matrix that is NOT U V^T, and which the
+    // deviation test cannot tell apart), so the scale must be a guaranteed bound: the largest
+    // absolute row sum of G is at least its largest eigenvalue, and dividing G by that sum / 2.9
+    // keeps every scaled sigma^2 at or below 2.9.  That bound alone is often two to three times
+    // too large, which costs iterations; a Rayleigh quotient after a few power-iteration steps
+    // from the vector of absolute row sums is a lower estimate that is usually tight, so the
+    // scale is the larger of (1.08 x that quotient) and (row-sum bound / 2.9).
     // (X^T X = Xt Xt^T: both operands are rows of Xt.)
     __shared__ float vec[PAD], wec[PAD];
     f32x16 g0 = abt_tile(Xt, Xt);
@@ -117,6 +120,8 @@ __global__ __launch_bounds__(P == 64 ? 256 : 64) void polar_ns_kernel(
         vec[tid] = rs;
     }
     __syncthreads();
+    float rsmax = 0.f;                         // every thread, same order: same value
+    for (int a = 0; a < P; ++a) rsmax = fmaxf(rsmax, vec[a]);
     float s2 = 0.f;
     for (int round = 0; round < 4; ++round) {
         if (tid < P) {
@@ -136,7 +141,9 @@ __global__ __launch_bounds__(P == 64 ? 256 : 64) void polar_ns_kernel(
         if (tid < P) vec[tid] = wec[tid] / wmax;
         __syncthreads();
     }
-    const bool ok = s2 > 0.f && s2 < 3e38f;    // zero, infinite or NaN input: not for this kernel
+    const bool rq_ok = s2 > 0.f && s2 < 3e38f; // zero, infinite or NaN input: not for this kernel
+    s2 = fmaxf(s2, rsmax * (1.f / 2.9f));
+    const bool ok = rq_ok && s2 < 3e38f;
     const float inv = ok ? __builtin_amdgcn_rsqf(s2) : 0.f;
     for (int e = tid; e < PAD * LD; e += NTH) {
         X[e] *= inv;

@@ -63,7 +63,6 @@ __device__ __forceinline__ void pair_next(int pi, int& ca, int& cb) {
 
 __global__ __launch_bounds__(1024) void wide_jacobi_kernel(const float* __restrict__ M,
                                                            const int32_t* __restrict__ counts,
-                                                           const float* __restrict__ Vst, int warm,
                                                            float* scratch, int K, float done,
                                                            int32_t* __restrict__ sweeps_out,
                                                            const int32_t* __restrict__ only) {
@@ -101,20 +100,10 @@ __global__ __launch_bounds__(1024) void wide_jacobi_kernel(const float* __restri
     for (int w = 0; w < NT / 64; ++w) mx = fmaxf(mx, red[w]);
     const float scale = mx > 0.f ? 1.f / mx : 0.f;
 
-    // A = scale * P_j (cold) or scale * P_j * V_prev (warm)
-    const float* Vj = Vst + (int64_t)j * P * P;
+    // A = scale * P_j
     for (int o = tid; o < P * P / 4; o += NT) {
         const int c = o / (P / 4), r4 = (o % (P / 4)) * 4;
-        f32x4 s4;
-        if (!warm) {
-            s4 = *reinterpret_cast<const f32x4*>(&Mj[c * P + r4]);
-        } else {
-            s4 = f32x4{0.f, 0.f, 0.f, 0.f};
-            for (int k = 0; k < P; ++k) {
-                const f32x4 b4 = *reinterpret_cast<const f32x4*>(&Mj[k * P + r4]);
-                s4 += b4 * Vj[c * P + k];
-            }
-        }
+        f32x4 s4 = *reinterpret_cast<const f32x4*>(&Mj[c * P + r4]);
         s4 *= scale;
         if (r4 < kRowsLds) *reinterpret_cast<f32x4*>(&AL[c * LDA + r4]) = s4;
         else *reinterpret_cast<f32x4*>(&A[c * P + r4]) = s4;
@@ -228,11 +217,11 @@ __global__ __launch_bounds__(1024) void wide_jacobi_kernel(const float* __restri
     }
 }
 
-// V <- V_start * (logged rotations), four rows per wavefront.
+// V <- I * (logged rotations), four rows per wavefront.
 constexpr int kReplayRows = 4;
 
 __global__ __launch_bounds__(256) void wide_replay_kernel(const int32_t* __restrict__ counts,
-                                                          float* Vst, int warm,
+                                                          float* Vst,
                                                           const float* scratch, int K,
                                                           const int32_t* __restrict__ only) {
     __shared__ float rows_all[4][kReplayRows][P];
@@ -244,16 +233,14 @@ __global__ __launch_bounds__(256) void wide_replay_kernel(const int32_t* __restr
     float* V = Vst + (int64_t)j * P * P;       // column-major: V[c*P + r]
     float(*rows)[P] = rows_all[wave];
 
-    const bool empty = counts != nullptr && counts[j] == 0;
-    if (empty && warm) return;                 // nothing to do: V keeps its value
+    if (counts != nullptr && counts[j] == 0) return;   // uniform: block keeps its basis, V unused
 #pragma unroll
     for (int rr = 0; rr < kReplayRows; ++rr)
-        for (int c = lane; c < P; c += 64)
-            rows[rr][c] = (warm && !empty) ? V[c * P + row0 + rr] : (c == row0 + rr ? 1.f : 0.f);
+        for (int c = lane; c < P; c += 64) rows[rr][c] = c == row0 + rr ? 1.f : 0.f;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
 
-    const int ns = empty ? 0 : ws.nsweeps[j];
+    const int ns = ws.nsweeps[j];
     const float* log = ws.log + (int64_t)j * kLogFloatsPerBlock;
     const int p0 = lane, p1 = lane + 64;       // this lane's pairs (neighbouring lanes touch
                                                // neighbouring columns: no bank conflicts)
@@ -452,23 +439,18 @@ size_t polar_wide_scratch_bytes(int K) {
     return ((size_t)K * P * P + (size_t)K * kLogFloatsPerBlock) * sizeof(float) + (size_t)K * sizeof(int);
 }
 
-hipError_t launch_polar_wide(int K, const float* M, const int32_t* counts, float* D, float* vstate,
-                             int warm, float* jac_a, float* eig_sv, int32_t* sweeps,
-                             const int32_t* only, hipStream_t st) {
-    if (vstate == nullptr || jac_a == nullptr) return hipErrorInvalidValue;
+hipError_t launch_polar_wide(int K, const float* M, const int32_t* counts, float* D, float* vwork,
+                             float* jac_a, float* eig_sv, int32_t* sweeps, const int32_t* only,
+                             LdsRaised* raised, hipStream_t st) {
+    if (vwork == nullptr || jac_a == nullptr || raised == nullptr) return hipErrorInvalidValue;
     const size_t lds = (size_t)P * LDA * sizeof(float);
-    static bool raised = false;
-    if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wide_jacobi_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        raised = true;
-    }
-    hipLaunchKernelGGL(wide_jacobi_kernel, dim3(K), dim3(1024), lds, st, M, counts, vstate, warm, jac_a, K,
-                       polar_done(), sweeps, only);
+    hipError_t e = raised->ensure(reinterpret_cast<const void*>(&wide_jacobi_kernel), lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(wide_jacobi_kernel, dim3(K), dim3(1024), lds, st, M, counts, jac_a, K, kPolarDone,
+                       sweeps, only);
     hipLaunchKernelGGL(wide_replay_kernel, dim3(K, P / (4 * kReplayRows)), dim3(256), 0, st, counts,
-                       vstate, warm, jac_a, K, only);
-    hipLaunchKernelGGL(wide_finish_kernel, dim3(K), dim3(1024), 0, st, M, counts, D, vstate, jac_a, K,
+                       vwork, jac_a, K, only);
+    hipLaunchKernelGGL(wide_finish_kernel, dim3(K), dim3(1024), 0, st, M, counts, D, vwork, jac_a, K,
                        eig_sv, only);
     return hipGetLastError();
 }

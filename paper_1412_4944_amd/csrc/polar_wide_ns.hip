@@ -145,9 +145,11 @@ __global__ __launch_bounds__(256) void wide_ns_gram_kernel(const float* __restri
     }
 }
 
-// s2[j] ~ sigma_max^2 of the input = largest eigenvalue of G: Rayleigh quotient after a few
-// power-iteration steps from the vector of absolute row sums, times 1.08 (see polar_ns.hip;
-// G is symmetric, so rows are read as columns, coalesced).
+// s2[j] = the scale of the input: the larger of 1.08 x a Rayleigh quotient after a few
+// power-iteration steps from the vector of absolute row sums (a usually tight lower estimate of
+// the largest eigenvalue of G = sigma_max^2) and the largest absolute row sum / 2.9 (a guaranteed
+// upper bound / 2.9, which keeps every scaled sigma^2 below 3: see polar_ns.hip; G is symmetric,
+// so rows are read as columns, coalesced).
 __global__ __launch_bounds__(256) void wide_ns_scale_kernel(const int32_t* __restrict__ counts,
                                                             float* scratch, int K) {
     __shared__ float vec[P], wec[P];
@@ -160,6 +162,8 @@ __global__ __launch_bounds__(256) void wide_ns_scale_kernel(const int32_t* __res
     for (int b = 0; b < P; ++b) rs += fabsf(Gj[b * P + tid]);
     vec[tid] = rs;
     __syncthreads();
+    float rsmax = 0.f;                         // every thread, same order: same value
+    for (int a = 0; a < P; ++a) rsmax = fmaxf(rsmax, vec[a]);
     float s2 = 0.f;
     for (int round = 0; round < 4; ++round) {
         float w = 0.f;
@@ -177,6 +181,9 @@ __global__ __launch_bounds__(256) void wide_ns_scale_kernel(const int32_t* __res
         vec[tid] = wec[tid] / wmax;
         __syncthreads();
     }
+    // a zero, infinite or NaN quotient stays that way (the update kernel then leaves the block
+    // to the fallback); otherwise the guaranteed bound applies
+    if (s2 > 0.f && s2 < 3e38f) s2 = fmaxf(s2, rsmax * (1.f / 2.9f));
     if (tid == 0) ns.s2[j] = s2;
 }
 
@@ -283,20 +290,14 @@ size_t polar_wide_ns_scratch_bytes(int K) {
 
 // Newton-Schulz for all K blocks; fallback[j] = 1 for every block left to the Jacobi SVD.
 hipError_t launch_polar_wide_ns(int K, const float* M, const int32_t* counts, float* D, float* scratch,
-                                int32_t* fallback, int32_t* iters, hipStream_t st) {
+                                int32_t* fallback, int32_t* iters, LdsRaised* raised, hipStream_t st) {
     constexpr int kSteps = 20;                 // < kHist
     const size_t lds_gram = (size_t)2 * P * kPanelLd * sizeof(float);
     const size_t lds_upd = ((size_t)64 * kRowLd + (size_t)P * kPanelLd) * sizeof(float);
-    static bool raised = false;
-    if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wide_ns_gram_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_gram);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wide_ns_update_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_upd);
-        if (e != hipSuccess) return e;
-        raised = true;
-    }
+    if (raised == nullptr) return hipErrorInvalidValue;
+    hipError_t e = raised->ensure(reinterpret_cast<const void*>(&wide_ns_gram_kernel), lds_gram);
+    if (e == hipSuccess) e = raised->ensure(reinterpret_cast<const void*>(&wide_ns_update_kernel), lds_upd);
+    if (e != hipSuccess) return e;
     const dim3 grid((kTiles / 2) * (kTiles / 2), K);
     for (int it = 0; it < kSteps; ++it) {
         hipLaunchKernelGGL(wide_ns_gram_kernel, grid, dim3(256), lds_gram, st, M, counts, scratch, K, it);

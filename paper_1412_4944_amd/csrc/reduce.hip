@@ -80,7 +80,8 @@ __global__ __launch_bounds__(256) void equal_blocks_kernel(const int32_t* __rest
 hipError_t launch_equal_blocks(const int32_t* ids, int n_blocks, int64_t per_block, int64_t m,
                                const Workspace& ws, hipStream_t st) {
     const int64_t n = (int64_t)n_blocks * per_block;
-    hipLaunchKernelGGL(equal_blocks_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, ids,
+    const int64_t threads = n > n_blocks + 1 ? n : n_blocks + 1;   // offsets has n_blocks + 1 entries
+    hipLaunchKernelGGL(equal_blocks_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, ids,
                        n_blocks, (int32_t)per_block, (int32_t)m, ws.perm, ws.counts, ws.offsets);
     return hipGetLastError();
 }

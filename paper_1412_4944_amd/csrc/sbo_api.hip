@@ -38,7 +38,7 @@ size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char
     w.part_j = (int32_t*)take((size_t)kEnergySplitRows * split_m * 4);
     w.partial = (float*)take((size_t)max_pieces_bound(m_max, K, p) * p * p * 4);
     w.M = (float*)take((size_t)K * p * p * 4);
-    w.vstate = (float*)take((size_t)K * p * p * 4);
+    w.vwork = (float*)take(p > 64 ? (size_t)K * p * p * 4 : 0);
     const size_t wide_a = polar_wide_scratch_bytes(K), wide_b = polar_wide_ns_scratch_bytes(K);
     w.jac_a = (float*)take(p > 64 ? (wide_a > wide_b ? wide_a : wide_b) : 0);
     const size_t sel_chunks = (size_t)((m_max + kSelChunk - 1) / kSelChunk);
@@ -53,6 +53,7 @@ size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char
     w.ns_fallback = (int32_t*)take((size_t)K * 4);
     w.sq_partial = (double*)take((size_t)kSqBlocks * 8);
     w.bytes = off;
+    w.raised = nullptr;
     if (ws) *ws = w;
     return off;
 }
@@ -123,7 +124,7 @@ static int run_code(sbo_ctx* c, const float* Y, int64_t m, const float* D, int32
     {
         StageTimer t(c, SBO_STAGE_ENERGY);
         SBO_HIP(launch_energy(c->p, c->K, c->s0, Y, m, c->ws.dsw, blk, c->ws.energy,
-                              c->ws.chunk_count, c->ws.part_E, c->ws.part_j, c->stream));
+                              c->ws.chunk_count, c->ws.part_E, c->ws.part_j, &c->raised, c->stream));
     }
     int rc = run_group(c, blk, m, true);       // the energy kernel left the chunk histograms
     if (rc) return rc;
@@ -136,14 +137,15 @@ static int run_code(sbo_ctx* c, const float* Y, int64_t m, const float* D, int32
 
 // Accumulate + SVD for signals already grouped in the workspace.
 static int run_update_grouped(sbo_ctx* c, const float* Y, int64_t m, const int32_t* supp,
-                              const float* coef, float* D, float* vstate, int warm) {
+                              const float* coef, float* D) {
     {
         StageTimer t(c, SBO_STAGE_ACCUM);
         SBO_HIP(launch_accumulate(c->p, c->K, c->s0, Y, m, supp, coef, c->ws, c->ws.M, c->stream));
     }
     {
         StageTimer t(c, SBO_STAGE_SVD);
-        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws, warm, nullptr, false, c->stream));
+        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws, c->svd_method, nullptr, false,
+                             c->stream));
     }
     return SBO_OK;
 }
@@ -169,6 +171,7 @@ int sbo_create(sbo_ctx** out, int p, int K, int s0, int64_t m_max, void* hip_str
     c->s0 = s0;
     c->m_max = m_max;
     c->stream = (hipStream_t)hip_stream;
+    c->svd_method = SBO_SVD_AUTO;
     c->timing = 0;
     c->n_spans = 0;
     const size_t bytes = workspace_layout(p, K, s0, m_max, nullptr, nullptr);
@@ -181,6 +184,7 @@ int sbo_create(sbo_ctx** out, int p, int K, int s0, int64_t m_max, void* hip_str
     }
     c->ws_base = (char*)base;
     workspace_layout(p, K, s0, m_max, &c->ws, c->ws_base);
+    c->ws.raised = &c->raised;
     // Two pieces of the workspace carry an invariant between calls: the chunk histograms and the
     // finished-workgroup counter are zero whenever no call is in flight.
     e = hipMemsetAsync(c->ws.chunk_count, 0, (size_t)max_chunks() * K * 4, c->stream);
@@ -253,7 +257,7 @@ int sbo_polar(sbo_ctx* c, const float* M, const int32_t* counts, float* D) {
     if (!c || !M || !D) return SBO_EINVAL;
     c->n_spans = 0;
     StageTimer t(c, SBO_STAGE_SVD);
-    SBO_HIP(launch_polar(c->p, c->K, M, counts, D, c->ws, 0, nullptr, false, c->stream));
+    SBO_HIP(launch_polar(c->p, c->K, M, counts, D, c->ws, c->svd_method, nullptr, false, c->stream));
     return SBO_OK;
 }
 
@@ -265,7 +269,7 @@ int sbo_update(sbo_ctx* c, const float* Y, int64_t m, const int32_t* blk, const 
     c->n_spans = 0;
     rc = run_group(c, blk, m);
     if (rc) return rc;
-    rc = run_update_grouped(c, Y, m, supp, coef, D, c->p > 64 ? c->ws.vstate : nullptr, 0);
+    rc = run_update_grouped(c, Y, m, supp, coef, D);
     if (rc) return rc;
     if (counts)
         SBO_HIP(hipMemcpyAsync(counts, c->ws.counts, (size_t)c->K * 4, hipMemcpyDeviceToDevice,
@@ -281,15 +285,11 @@ int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter, int
     c->n_spans = 0;
     const bool fused = c->p <= 64;             // select and accumulate share one pass over Y
     for (int it = 0; it < n_iter; ++it) {
-        // Within one call the Jacobi SVD of every block starts from the previous
-        // iteration's V (restarted from the identity every 8th iteration to bound the
-        // accumulated rounding in V).
-        const int warm = it % 8 != 0;
         if (!fused) {
             rc = run_code(c, Y, m, D, blk, supp, coef, err);
             if (rc) return rc;
             if (sqerr_per_iter) SBO_HIP(launch_sqerr(err, nullptr, m, c->ws, sqerr_per_iter + it, c->stream));
-            rc = run_update_grouped(c, Y, m, supp, coef, D, c->ws.vstate, warm);  // grouping reused
+            rc = run_update_grouped(c, Y, m, supp, coef, D);   // grouping reused
             if (rc) return rc;
             continue;
         }
@@ -299,7 +299,7 @@ int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter, int
         {
             StageTimer t(c, SBO_STAGE_ENERGY);  // also leaves the chunk histograms of the grouping
             SBO_HIP(launch_energy(c->p, c->K, c->s0, Y, m, c->ws.dsw, blk, c->ws.energy,
-                                  c->ws.chunk_count, c->ws.part_E, c->ws.part_j, c->stream));
+                                  c->ws.chunk_count, c->ws.part_E, c->ws.part_j, &c->raised, c->stream));
         }
         rc = run_group(c, blk, m, true);
         if (rc) return rc;
@@ -314,7 +314,7 @@ int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter, int
         }
         {
             StageTimer t(c, SBO_STAGE_SVD);
-            SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws, warm, nullptr, true,
+            SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws, c->svd_method, nullptr, true,
                                  c->stream));
         }
     }
@@ -326,7 +326,6 @@ static int run_train_rounds(sbo_ctx* c, const float* Y, int64_t m, const int32_t
     int rc = run_group(c, blk, m);             // the assignment, hence the grouping, is fixed
     if (rc) return rc;
     for (int r = 0; r < R; ++r) {
-        const int warm = r % 8 != 0;           // later rounds start Jacobi from the last V
         if (c->p <= 64) {
             {
                 StageTimer t(c, SBO_STAGE_SELECT);
@@ -345,7 +344,8 @@ static int run_train_rounds(sbo_ctx* c, const float* Y, int64_t m, const int32_t
             SBO_HIP(launch_accumulate(c->p, c->K, c->s0, Y, m, supp, coef, c->ws, c->ws.M, c->stream));
         }
         StageTimer t(c, SBO_STAGE_SVD);
-        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws, warm, nullptr, false, c->stream));
+        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws, c->svd_method, nullptr, false,
+                             c->stream));
     }
     return SBO_OK;
 }
@@ -408,7 +408,6 @@ static int run_new_base(sbo_ctx* c, const float* Y, int64_t n, int R, int have_q
         if (rc) return rc;
     }
     for (int r = 0; r < R; ++r) {
-        const int warm = r % 8 != 0;
         if (c->p <= 64) {
             SBO_HIP(launch_select_accum(c->p, 1, c->s0, Y, n, Q, c->ws, supp, coef, err, c->stream));
             SBO_HIP(launch_accum_reduce(c->p, 1, n, c->ws, c->ws.M, nullptr, nullptr, c->stream));
@@ -418,7 +417,8 @@ static int run_new_base(sbo_ctx* c, const float* Y, int64_t n, int R, int have_q
         }
         if (sqerr_per_round)
             SBO_HIP(launch_sqerr(err, c->ws.perm, n, c->ws, sqerr_per_round + r, c->stream));
-        SBO_HIP(launch_polar(c->p, 1, c->ws.M, c->ws.counts, Q, c->ws, warm, nullptr, false, c->stream));
+        SBO_HIP(launch_polar(c->p, 1, c->ws.M, c->ws.counts, Q, c->ws, c->svd_method, nullptr, false,
+                             c->stream));
     }
     return SBO_OK;
 }
@@ -477,7 +477,8 @@ int sbo_learn(sbo_ctx* c, const float* Y, int64_t m, float* D, const int32_t* in
         for (int r = 0; r < R; ++r) {
             SBO_HIP(launch_select_accum(c->p, K0, c->s0, Y, n_init, D, c->ws, supp, coef, err, c->stream));
             SBO_HIP(launch_accum_reduce(c->p, K0, n_init, c->ws, c->ws.M, nullptr, nullptr, c->stream));
-            SBO_HIP(launch_polar(c->p, K0, c->ws.M, c->ws.counts, D, c->ws, 0, nullptr, false, c->stream));
+            SBO_HIP(launch_polar(c->p, K0, c->ws.M, c->ws.counts, D, c->ws, c->svd_method, nullptr, false,
+                                 c->stream));
         }
     } else {
         for (int j = 0; j < K0; ++j) {
@@ -527,16 +528,15 @@ int sbo_svd_sweeps(sbo_ctx* c, int32_t* sweeps) {
     return SBO_OK;
 }
 
-int sbo_probe_mfma(void* hip_stream, int iters, double* tflops) {
-    if (!tflops || iters < 1 || iters > 100000) return SBO_EINVAL;
-    SBO_HIP(probe_mfma((hipStream_t)hip_stream, iters, tflops));
-    return SBO_OK;
-}
-
-int sbo_probe_copy(void* hip_stream, double* gbps) {
-    if (!gbps) return SBO_EINVAL;
-    SBO_HIP(probe_copy((hipStream_t)hip_stream, gbps));
-    return SBO_OK;
+int sbo_set_option(sbo_ctx* c, int option, int value) {
+    if (!c) return SBO_EINVAL;
+    switch (option) {
+        case SBO_OPT_SVD_METHOD:
+            if (value != SBO_SVD_AUTO && value != SBO_SVD_JACOBI) return SBO_EINVAL;
+            c->svd_method = value;
+            return SBO_OK;
+        default: return SBO_EINVAL;
+    }
 }
 
 int sbo_set_timing(sbo_ctx* c, int enable) {

@@ -35,10 +35,6 @@ inline GroupGeom group_geom(int64_t m) {
 // workgroup reduces one piece into a partial p x p matrix.
 constexpr int kNumCU = 256;
 inline int accum_piece(int64_t m, int K, int p) {
-    if (const char* e = getenv("SBO_ACCUM_PIECE")) {      // tuning override, multiple of 64
-        int v = atoi(e);
-        if (v >= (p <= 64 ? 64 : 256) && v <= 4096 && v % 64 == 0) return v;
-    }
     // p <= 64: two workgroups fit a CU, and all pieces should be resident in one round
     // (pieces <= 2 * CUs where K allows)
     const int slots = 2 * kNumCU;
@@ -69,13 +65,21 @@ inline int accum_max_pieces(int64_t m, int K, int p) {
 
 // ---- Jacobi stopping threshold ---------------------------------------------------
 // A sweep in which every pair already had a cosine below this is the last one.
-inline float polar_done() {
-    if (const char* e = getenv("SBO_POLAR_DONE")) {       // tuning override
-        const float v = (float)atof(e);
-        if (v >= 1e-6f && v <= 1e-1f) return v;
+constexpr float kPolarDone = 1e-4f;
+
+// ---- kernels that need more dynamic LDS than the default limit ---------------------
+// Their limit is raised once per context (a context belongs to one device and its calls do
+// not overlap), before the first launch; the context remembers which kernels have been done.
+struct LdsRaised {
+    std::vector<const void*> fns;
+    hipError_t ensure(const void* fn, size_t bytes) {
+        for (const void* f : fns)
+            if (f == fn) return hipSuccess;
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e == hipSuccess) fns.push_back(fn);
+        return e;
     }
-    return 1e-4f;
-}
+};
 
 // ---- device workspace layout ---------------------------------------------------
 struct Workspace {
@@ -93,7 +97,7 @@ struct Workspace {
     // accumulation
     float* partial;        // [max_pieces][p][p]
     float* M;              // [K][p][p]
-    float* vstate;         // [K][p][p] V of the previous decomposition (sbo_iterate only)
+    float* vwork;          // p > 64 only: [K][p][p] the V of the wide Jacobi SVD
     float* jac_a;          // p > 64 only: scratch of the wide Jacobi (polar_wide_scratch_bytes)
     // worst-W selection
     int32_t* sel_hist;     // [4][256] digit histograms of the radix select
@@ -108,6 +112,8 @@ struct Workspace {
     // iterate
     double* sq_partial;    // [kSqBlocks]
     size_t bytes;
+    // host side: launch state of the owning context (not device memory)
+    LdsRaised* raised;
 };
 constexpr int kSqBlocks = 256;
 constexpr int kEnergySplitBelow = 192;       // coding launches with fewer workgroups split the blocks
@@ -131,6 +137,8 @@ struct sbo_ctx {
     hipStream_t stream;
     char* ws_base;
     sbo::Workspace ws;
+    int svd_method;                  // SBO_SVD_AUTO or SBO_SVD_JACOBI (sbo_set_option)
+    sbo::LdsRaised raised;
     int timing;
     std::vector<sbo_span> spans;     // event pool; the first n_spans are in use
     size_t n_spans;
@@ -147,7 +155,7 @@ hipError_t launch_dict_swizzle(int p, int K, const float* D, float* dsw, hipStre
 // for small m, where the blocks are split over several workgroup rows to fill the chip.
 hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const float* dsw,
                          int32_t* blk, float* energy, int32_t* chunk_count, float* part_E,
-                         int32_t* part_j, hipStream_t st);
+                         int32_t* part_j, LdsRaised* raised, hipStream_t st);
 
 hipError_t launch_group(int K, const int32_t* blk, int64_t m, const Workspace& ws, bool have_hist,
                         hipStream_t st);
@@ -174,15 +182,16 @@ hipError_t launch_accum_reduce(int p, int K, int64_t m, const Workspace& ws, flo
 // p <= 64: Newton-Schulz on the matrix cores (polar_ns.hip) first, then the Jacobi SVD for the
 // blocks it leaves flagged (rank-deficient ones); p = 256: the same two steps spread over the whole
 // chip (polar_wide_ns.hip, polar_wide.hip).
-// Uses ws.vstate (V kept between calls: warm != 0 starts Jacobi from it), ws.jac_a, ws.sweeps
-// (per block: Jacobi sweeps, or minus the Newton-Schulz steps), ws.ns_fallback.
+// jacobi_only != 0: the Jacobi SVD for every block (SBO_SVD_JACOBI).
+// Uses ws.vwork and ws.jac_a (p = 256), ws.sweeps (per block: Jacobi sweeps, or minus the
+// Newton-Schulz steps), ws.ns_fallback.
 // eig_sv != nullptr switches to eigen mode (always Jacobi): M[j] symmetric positive
 // semidefinite, D[j] receives its eigenvectors as atoms by descending eigenvalue and
 // eig_sv[j][p] the square roots of the eigenvalues.
 // write_dsw (p <= 64): the rows of every updated block are also written into ws.dsw, the coding
 // kernel's operand order (what launch_dict_swizzle would produce from the new D).
 hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
-                        const Workspace& ws, int warm, float* eig_sv, bool write_dsw,
+                        const Workspace& ws, int jacobi_only, float* eig_sv, bool write_dsw,
                         hipStream_t st);
 
 hipError_t launch_polar_ns(int p, int K, const float* M, const int32_t* counts, float* D, float* dsw,
@@ -192,13 +201,13 @@ hipError_t launch_polar_ns(int p, int K, const float* M, const int32_t* counts, 
 // copy of P_j, rotation log, sweep counts).
 size_t polar_wide_scratch_bytes(int K);
 // only != nullptr: blocks with only[j] == 0 are skipped.
-hipError_t launch_polar_wide(int K, const float* M, const int32_t* counts, float* D, float* vstate,
-                             int warm, float* jac_a, float* eig_sv, int32_t* sweeps,
-                             const int32_t* only, hipStream_t st);
+hipError_t launch_polar_wide(int K, const float* M, const int32_t* counts, float* D, float* vwork,
+                             float* jac_a, float* eig_sv, int32_t* sweeps, const int32_t* only,
+                             LdsRaised* raised, hipStream_t st);
 // p = 256 Newton-Schulz over the whole chip (polar_wide_ns.hip); scratch as for the Jacobi variant.
 size_t polar_wide_ns_scratch_bytes(int K);
 hipError_t launch_polar_wide_ns(int K, const float* M, const int32_t* counts, float* D, float* scratch,
-                                int32_t* fallback, int32_t* iters, hipStream_t st);
+                                int32_t* fallback, int32_t* iters, LdsRaised* raised, hipStream_t st);
 
 // ids == nullptr: sum over all m signals; otherwise over the m listed ones.
 hipError_t launch_sqerr(const float* err, const int32_t* ids, int64_t m, const Workspace& ws,
@@ -217,10 +226,6 @@ hipError_t launch_equal_blocks(const int32_t* ids, int n_blocks, int64_t per_blo
 // of y y^T.
 hipError_t launch_gram(int p, int K, const float* Y, int64_t n, const Workspace& ws, float* G,
                        hipStream_t st);
-
-// Achievable peaks for the benchmark (probe.hip): bare fp32 MFMA loop, plain device copy (read + write).
-hipError_t probe_mfma(hipStream_t st, int iters, double* tflops);
-hipError_t probe_copy(hipStream_t st, double* gbps);
 
 // ids[0..W) = the W signals with the largest err (ties: lower index), ascending.
 hipError_t launch_worst(const float* err, int64_t m, int64_t W, const Workspace& ws, int32_t* ids,

@@ -207,13 +207,10 @@ hipError_t launch_ps(const float* Y, int64_t m, const float* D, int K, int s0, c
     const size_t lds = (size_t)head * sizeof(int) + (size_t)MT * (P / 8) * 64 * sizeof(f32x4) +
                        (size_t)4 * 32 * (P + 4) * sizeof(float) +
                        (size_t)4 * kSelectStageWords * sizeof(int);
-    static bool raised = false;
-    if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_accum_kernel<P, S>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-        if (e != hipSuccess) return e;
-        raised = true;
-    }
+    if (hipError_t e = ws.raised->ensure(reinterpret_cast<const void*>(&select_accum_kernel<P, S>),
+                                         96 * 1024);
+        e != hipSuccess)
+        return e;
     hipLaunchKernelGGL((select_accum_kernel<P, S>), dim3(max_pieces), dim3(256), lds, st, Y, D, K, s0,
                        piece, ws.offsets, ws.perm, supp, coef, err, ws.partial);
     return hipGetLastError();

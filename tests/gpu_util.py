@@ -17,12 +17,18 @@ ORTHO_TOL = 1e-5     # max |Q^T Q - I| of every block written by the GPU
 class Sbo:
     """One libsbo context plus device copies; everything returned is numpy."""
 
-    def __init__(self, p, K, s0, m_max):
+    def __init__(self, p, K, s0, m_max, jacobi_only=False):
         import torch
         self.torch = torch
         self.dev = torch.device("cuda:0")
         self.p, self.K, self.s0 = p, K, s0
         self.ctx = sbo.sbo_create(p, K, s0, m_max)
+        if jacobi_only:
+            self.svd_jacobi(True)
+
+    def svd_jacobi(self, on):
+        """Jacobi SVD for every orthobase (on) or the default Newton-Schulz + Jacobi fallback."""
+        sbo.sbo_set_option(self.ctx, sbo.SBO_OPT_SVD_METHOD, sbo.SBO_SVD_JACOBI if on else sbo.SBO_SVD_AUTO)
 
     def close(self):
         if self.ctx is not None:
@@ -197,6 +203,28 @@ def compare_code(Y, D, s0, oracle_out, gpu_out, max_exempt_frac=0.01):
     frac = ex.size / m
     assert frac <= max_exempt_frac, f"exempt fraction {frac}"
     return frac
+
+
+def compare_assigned_code(Y, D, blk, s0, oracle_out, gpu_out, max_exempt_frac=0.01):
+    """Codes computed with the block assignment GIVEN (frozen-assignment rounds, a new orthobase
+    on a set): per block, the same gated comparison as compare_code with that block as the only
+    candidate (support bit-exact unless the s0-th / (s0+1)-th magnitudes nearly tie, and then a
+    valid code whose error is within the gap).  oracle_out / gpu_out = (supp, coef, err) over
+    the rows of Y.  Returns the exempt fraction over all signals."""
+    so, co, eo = oracle_out
+    sg, cg, eg = gpu_out
+    blk = np.asarray(blk)
+    m = Y.shape[0]
+    exempt = 0.0
+    for j in np.unique(blk):
+        ids = np.nonzero(blk == j)[0]
+        z = np.zeros(ids.size, np.int32)
+        frac = compare_code(Y[ids], np.asarray(D)[j:j + 1], s0, (z, so[ids], co[ids], eo[ids], None),
+                            (z, sg[ids], cg[ids], eg[ids]), max_exempt_frac=1.0)
+        exempt += frac * ids.size
+    exempt /= m
+    assert exempt <= max_exempt_frac, f"exempt fraction {exempt}"
+    return exempt
 
 
 def compare_Q(D_gpu, D_oracle, M_oracle, updated):

@@ -6,7 +6,7 @@ import pytest
 
 import sbo_synth as synth
 from oracle import sbo_oracle as orc
-from gpu_util import Sbo, compare_Q, ORTHO_TOL
+from gpu_util import Sbo, compare_assigned_code, compare_Q, ORTHO_TOL
 
 pytestmark = pytest.mark.gpu
 
@@ -115,7 +115,6 @@ def test_new_base_rounds_teacher_forced(name, kw, n, R):
     rng = np.random.default_rng(44)
     ids = np.sort(rng.choice(m, n, replace=False)).astype(np.int32)
     sub = pr.Y[ids]
-    n2 = (sub.astype(np.float64) ** 2).sum(1)
     zeros = np.zeros(n, np.int32)
     print(f"case {name}: p={cfg.p} m={m} n={n} R={R}", flush=True)
     Q = orc.o_init_base(pr.Y, ids)[0]
@@ -127,15 +126,12 @@ def test_new_base_rounds_teacher_forced(name, kw, n, R):
             outside = np.setdiff1d(np.arange(m), ids)
             assert (sg[outside] == -7).all() and np.isnan(eg[outside]).all(), "rows outside the set written"
             sg, cg, eg = sg[ids], cg[ids], eg[ids]
-            bad = (sg != so).any(axis=1)
-            assert bad.mean() <= 0.002, f"round {r}: {bad.sum()} supports differ"
-            ok = ~bad
-            assert (np.abs(cg[ok] - co[ok]) <= 1e-4 * np.sqrt(n2[ok, None]) + 1e-30).all()
-            assert (np.abs(eg[ok] - eo[ok]) <= 1e-4 * n2[ok] + 1e-30).all()
+            # supports bit-exact except below the near-tie gap, exempt codes valid in fp64
+            frac = compare_assigned_code(sub, Q32[None], zeros, cfg.s0, (so, co, eo), (sg, cg, eg))
             assert abs(sq[0] - eg.astype(np.float64).sum()) <= 1e-9 * sq[0] + 1e-30
             Dn, M = orc.o_update(sub, zeros, sg, cg, Q32[None])
             w = compare_Q(Qg[None], Dn, M, np.array([True]))
-            print(f"  round {r}: {bad.sum()} near-tie supports, worst dQ {w:.2e}", flush=True)
+            print(f"  round {r}: exempt fraction {frac:.5f}, worst dQ {w:.2e}", flush=True)
             Q = orc.o_train_rounds(sub, zeros, Q32[None], cfg.s0, 1)[0][0]
 
 
@@ -234,5 +230,6 @@ def test_learn_against_oracle(name, kw, K0, P0, R, W, K_max):
         assert Kf2 == K0 + 2 and len(hist2) == 3 and np.array_equal(np.array(hist2), hist[:3])
         assert not t.isnan(D2[:Kf2]).any()
         # the context is back to its own block count and still works
-        b2, *_r = g.code(pr.Y, Dg)
-    assert (b2 != orc.o_code(pr.Y, Dg, s0)[0]).mean() < 1e-3
+        from gpu_util import compare_code
+        frac = compare_code(pr.Y, Dg, s0, orc.o_code(pr.Y, Dg, s0), g.code(pr.Y, Dg))
+        print(f"  coding with the learnt dictionary: exempt fraction {frac:.5f}", flush=True)
