@@ -43,6 +43,7 @@ extern "C" {
 #define SBO_EINVAL  (-1)  /* bad or unsupported shape, NULL pointer, m > m_max */
 #define SBO_ENOMEM  (-2)  /* workspace allocation failed */
 #define SBO_EHIP    (-3)  /* a HIP call failed; text via sbo_strerror */
+#define SBO_ELIMIT  (-4)  /* a size beyond a stated fixed limit; text via sbo_strerror */
 
 typedef struct sbo_ctx sbo_ctx;   /* opaque: shapes, stream, device workspace */
 
@@ -83,6 +84,22 @@ int sbo_code(sbo_ctx* c, const float* Y, int64_t m, const float* D,
  * Any output pointer may be NULL (that output is then not copied out). */
 int sbo_group(sbo_ctx* c, const int32_t* blk, int64_t m,
               int32_t* counts, int32_t* offsets, int32_t* perm);
+
+/* sbo_group for callers that cannot allocate device memory or hold a context: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same result as
+ * sbo_group (same kernels); takes no context and calls no allocating routine: its scratch
+ * (per-chunk histograms and bases, 1 MiB) is a static device array that every GPU the
+ * library runs on holds until the process ends.
+ * Limits: 1 <= K <= SBO_GROUP_STATIC_MAX_K, 1 <= m <= SBO_GROUP_STATIC_MAX_M; beyond them
+ * SBO_ELIMIT is returned and nothing is enqueued.  counts, offsets and perm are all required.
+ * Work is enqueued on hip_stream (NULL = the default stream) of the current device.  All
+ * calls on one GPU share the one scratch array: calls that overlap on a GPU (different
+ * streams, different threads) race; serialise them.  Nothing in the scratch needs clearing
+ * between calls (every entry read is written first by the same call). */
+#define SBO_GROUP_STATIC_MAX_K 128
+#define SBO_GROUP_STATIC_MAX_M 1048576
+int sbo_group_static(const int32_t* blk, int64_t m, int K, int32_t* counts, int32_t* offsets,
+                     int32_t* perm, void* hip_stream);
 
 /* Block accumulation P_j = Y_j X_j^T for every block (Algorithm 1, step 5),
  * atom-major: M[j][k][:] = sum over the block's signals of x_i[k] * y_i.

@@ -9,10 +9,11 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "lib", "libsbo.so")
 
-SBO_OK, SBO_EINVAL, SBO_ENOMEM, SBO_EHIP = 0, -1, -2, -3
+SBO_OK, SBO_EINVAL, SBO_ENOMEM, SBO_EHIP, SBO_ELIMIT = 0, -1, -2, -3, -4
+SBO_GROUP_STATIC_MAX_K, SBO_GROUP_STATIC_MAX_M = 128, 1 << 20
 STAGES = ("energy", "group", "select", "accum", "svd")
 
-EXPORTS = ("sbo_create", "sbo_destroy", "sbo_workspace_bytes", "sbo_code", "sbo_group",
+EXPORTS = ("sbo_create", "sbo_destroy", "sbo_workspace_bytes", "sbo_code", "sbo_group", "sbo_group_static",
            "sbo_accumulate", "sbo_polar", "sbo_update", "sbo_train_rounds", "sbo_iterate", "sbo_sqerr",
            "sbo_worst", "sbo_init_base", "sbo_new_base", "sbo_set_blocks", "sbo_learn", "sbo_svd_sweeps", "sbo_set_option", "sbo_set_timing", "sbo_stage_ms", "sbo_strerror")
 
@@ -41,6 +42,7 @@ def lib() -> ctypes.CDLL:
     L.sbo_workspace_bytes.restype = ctypes.c_size_t
     L.sbo_code.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp]
     L.sbo_group.argtypes = [vp, vp, i64, vp, vp, vp]
+    L.sbo_group_static.argtypes = [vp, i64, i32, vp, vp, vp, vp]
     L.sbo_accumulate.argtypes = [vp, vp, i64, vp, vp, vp, vp]
     L.sbo_polar.argtypes = [vp, vp, vp, vp]
     L.sbo_update.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp]
@@ -119,6 +121,16 @@ def sbo_group(ctx, blk, counts=None, offsets=None, perm=None) -> None:
     _check(lib().sbo_group(ctx, _ptr(blk, torch.int32), blk.shape[0],
                            _ptr(counts, torch.int32, True), _ptr(offsets, torch.int32, True),
                            _ptr(perm, torch.int32, True)))
+
+
+def sbo_group_static(blk, K: int, counts, offsets, perm, stream: int | None = None) -> None:
+    """sbo_group without a context and without any allocation (static device scratch)."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    _check(lib().sbo_group_static(_ptr(blk, torch.int32), blk.shape[0], int(K), _ptr(counts, torch.int32),
+                                  _ptr(offsets, torch.int32), _ptr(perm, torch.int32),
+                                  ctypes.c_void_p(stream)))
 
 
 def sbo_accumulate(ctx, Y, blk, supp, coef, M) -> None:

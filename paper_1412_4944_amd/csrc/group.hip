@@ -8,11 +8,42 @@
 #include "sbo_internal.h"
 #include "device_utils.h"
 
+#include <mutex>
+
 namespace sbo {
 
 namespace {
 
 constexpr int kMaxK = 1024;
+
+// Scratch of launch_group_static (the grouping for callers that must not allocate): the
+// per-chunk histograms and per-chunk bases, [2][kStaticChunks][kGroupStaticMaxK] ints = 1 MiB
+// on every GPU the library runs on, held until the process ends.
+constexpr int kStaticChunks = 1024;            // group_geom() never makes more for m <= 2^20
+static __device__ __align__(256) int32_t scratch[2 * kStaticChunks * kGroupStaticMaxK];
+
+// Device address of `scratch` on each GPU (every GPU holds its own copy of the array); looked
+// up once per device.  In host code the array's name is only a handle for this lookup.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+int32_t* g_scratch_ptr[kMaxDevices] = {};
+
+hipError_t static_scratch(int32_t** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        int32_t* ptr = nullptr;
+        e = hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (ptr == nullptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
 
 // 1. chunk_count[c][j] = number of signals of chunk c that chose block j.
 __global__ __launch_bounds__(256) void group_hist_kernel(const int32_t* __restrict__ blk, int m,
@@ -130,6 +161,30 @@ hipError_t launch_group(int K, const int32_t* blk, int64_t m, const Workspace& w
     hipLaunchKernelGGL(group_scatter_kernel, dim3(wgs), dim3(256),
                        (K + 1 + 16 + 4 * K) * sizeof(int), st, blk, (int)m, K, g.chunk, g.n_chunks,
                        ws.chunk_base, ws.counts, ws.offsets, ws.perm);
+    return hipGetLastError();
+}
+
+// The same three kernels with the chunk arrays in the static device array above instead of
+// a context's workspace: no allocation anywhere.  m <= kGroupStaticMaxM, K <= kGroupStaticMaxK
+// (checked by the caller).  Nothing in the scratch has to start at zero: the histogram kernel
+// writes every entry the later kernels read.
+hipError_t launch_group_static(int K, const int32_t* blk, int64_t m, int32_t* counts, int32_t* offsets,
+                               int32_t* perm, hipStream_t st) {
+    if (K < 1 || K > kGroupStaticMaxK || m < 1 || m > kGroupStaticMaxM) return hipErrorInvalidValue;
+    int32_t* base = nullptr;
+    hipError_t e = static_scratch(&base);
+    if (e != hipSuccess) return e;
+    const GroupGeom g = group_geom(m);
+    if (g.n_chunks > kStaticChunks) return hipErrorInvalidValue;
+    int32_t* chunk_count = base;
+    int32_t* chunk_base = base + (size_t)kStaticChunks * kGroupStaticMaxK;
+    const unsigned wgs = (unsigned)((g.n_chunks + 3) / 4);
+    hipLaunchKernelGGL(group_hist_kernel, dim3(wgs), dim3(256), 4 * K * sizeof(int), st, blk, (int)m, K,
+                       g.chunk, g.n_chunks, chunk_count);
+    hipLaunchKernelGGL(group_scan_kernel, dim3(K), dim3(256), 0, st, chunk_count, K, g.n_chunks,
+                       chunk_base, counts);
+    hipLaunchKernelGGL(group_scatter_kernel, dim3(wgs), dim3(256), (K + 1 + 16 + 4 * K) * sizeof(int), st,
+                       blk, (int)m, K, g.chunk, g.n_chunks, chunk_base, counts, offsets, perm);
     return hipGetLastError();
 }
 

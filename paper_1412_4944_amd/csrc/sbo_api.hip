@@ -240,6 +240,19 @@ int sbo_group(sbo_ctx* c, const int32_t* blk, int64_t m, int32_t* counts, int32_
     return SBO_OK;
 }
 
+int sbo_group_static(const int32_t* blk, int64_t m, int K, int32_t* counts, int32_t* offsets,
+                     int32_t* perm, void* hip_stream) {
+    if (!blk || !counts || !offsets || !perm) return SBO_EINVAL;
+    if (K < 1 || K > SBO_GROUP_STATIC_MAX_K || m < 1 || m > SBO_GROUP_STATIC_MAX_M) {
+        g_hip_text = "sbo_group_static: K or m beyond the static scratch (K <= 128, m <= 1048576)";
+        return SBO_ELIMIT;
+    }
+    static_assert(SBO_GROUP_STATIC_MAX_K == kGroupStaticMaxK && SBO_GROUP_STATIC_MAX_M == kGroupStaticMaxM,
+                  "header and kernel limits differ");
+    SBO_HIP(launch_group_static(K, blk, m, counts, offsets, perm, (hipStream_t)hip_stream));
+    return SBO_OK;
+}
+
 int sbo_accumulate(sbo_ctx* c, const float* Y, int64_t m, const int32_t* blk, const int32_t* supp,
                    const float* coef, float* M) {
     int rc = check_call(c, m);
@@ -563,6 +576,7 @@ const char* sbo_strerror(int code) {
         case SBO_OK: return "success";
         case SBO_EINVAL: return "invalid argument or unsupported shape";
         case SBO_ENOMEM: return "out of device memory";
+        case SBO_ELIMIT: return g_hip_text.c_str();
         case SBO_EHIP: return g_hip_text.c_str();
         default: return "unknown error code";
     }

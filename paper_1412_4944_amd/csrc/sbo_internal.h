@@ -159,6 +159,11 @@ hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const 
 
 hipError_t launch_group(int K, const int32_t* blk, int64_t m, const Workspace& ws, bool have_hist,
                         hipStream_t st);
+// The grouping with its scratch in a static device array (no workspace, no allocation).
+constexpr int kGroupStaticMaxK = 128;
+constexpr int64_t kGroupStaticMaxM = (int64_t)1 << 20;
+hipError_t launch_group_static(int K, const int32_t* blk, int64_t m, int32_t* counts, int32_t* offsets,
+                               int32_t* perm, hipStream_t st);
 
 // dsw_valid: ws.dsw already holds this D in operand order (launch_dict_swizzle); p = 256 reads
 // it and rewrites it first otherwise.
