@@ -106,6 +106,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=30,
                     help="untimed iterations first (the clocks of an idle GPU take some tens of ms to settle)")
     ap.add_argument("--workload", default="headline")
+    ap.add_argument("--arith", default="bf16x3", choices=["f32", "bf16x3"],
+                    help="how the projection onto all K orthobases is multiplied out (SBO_OPT_CODING_ARITH)")
     ap.add_argument("--cpu-sample", type=int, default=262144)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-probe", action="store_true",
@@ -161,6 +163,8 @@ def main() -> int:
                     "hbm_copy_GBps": pb.copy()}
 
     ctx = sbo.sbo_create(p, K, s0, m)
+    sbo.sbo_set_option(ctx, sbo.SBO_OPT_CODING_ARITH,
+                       sbo.SBO_ARITH_BF16X3 if args.arith == "bf16x3" else sbo.SBO_ARITH_F32)
     # Timed region: HIP events around the roofline kernel only (an event pair per stage costs
     # several microseconds on the stream, 4 % of a step here); the full per-stage breakdown comes
     # from a second, untimed pass over the same number of iterations.

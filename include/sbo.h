@@ -209,12 +209,23 @@ int sbo_svd_sweeps(sbo_ctx* c, int32_t* sweeps);
 
 /* Options of a context (sbo_set_option). */
 enum {
-    SBO_OPT_SVD_METHOD = 0   /* how Q_j = U V^T is computed: SBO_SVD_AUTO or SBO_SVD_JACOBI */
+    SBO_OPT_SVD_METHOD   = 0,  /* how Q_j = U V^T is computed: SBO_SVD_AUTO or SBO_SVD_JACOBI */
+    SBO_OPT_CODING_ARITH = 1   /* how the projection Q_j^T y onto all K orthobases is multiplied out:
+                                  SBO_ARITH_F32 or SBO_ARITH_BF16X3 */
 };
 enum {
     SBO_SVD_AUTO   = 0,  /* default: Newton-Schulz polar factor on the matrix cores, the one-sided
                             Jacobi SVD for the orthobases it flags (rank-deficient P_j) */
     SBO_SVD_JACOBI = 1   /* the one-sided Jacobi SVD (one workgroup per orthobase) for every orthobase */
+};
+
+enum {
+    SBO_ARITH_F32    = 0,  /* the fp32 matrix instruction (v_mfma_f32_32x32x2_f32) */
+    SBO_ARITH_BF16X3 = 1   /* default.  p <= 64: every fp32 operand entry written as the exact sum of
+                              three bf16 numbers; the six partial products that matter at fp32 accuracy
+                              run on the bf16 matrix cores with fp32 accumulation (same fp32 inputs and
+                              outputs, rounding at the fp32 level: the dropped partial products are below
+                              2^-24 of |a||b|).  p = 256 uses the fp32 instruction either way. */
 };
 
 /* Set an option for every later call on this context (Algorithm 1 steps 6-7 leave the SVD

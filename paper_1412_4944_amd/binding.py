@@ -218,8 +218,9 @@ def sbo_svd_sweeps(ctx, K: int) -> list:
     return list(buf)
 
 
-SBO_OPT_SVD_METHOD = 0
+SBO_OPT_SVD_METHOD, SBO_OPT_CODING_ARITH = 0, 1
 SBO_SVD_AUTO, SBO_SVD_JACOBI = 0, 1
+SBO_ARITH_F32, SBO_ARITH_BF16X3 = 0, 1
 
 
 def sbo_set_option(ctx, option: int, value: int) -> None:

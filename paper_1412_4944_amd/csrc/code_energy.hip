@@ -16,6 +16,8 @@
 #include "sbo_internal.h"
 #include "device_utils.h"
 
+#include <type_traits>
+
 namespace sbo {
 
 namespace {
@@ -137,6 +139,34 @@ __global__ __launch_bounds__(256) void dict_swizzle_kernel(const float* __restri
         const int d4 = hh * QN + q;
         Dsw[(int64_t)s * STAGE_F4 + f] =
             grow < rows ? D4[(int64_t)grow * (P / 4) + d4] : f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+}
+
+// The same dictionary in the split operand order (see device_utils.h): every entry as three
+// bf16 parts, 8 consecutive dims of a row per 16-byte unit and part.
+template <int P>
+__global__ __launch_bounds__(256) void dict_swizzle_split_kernel(const float* __restrict__ D, int K,
+                                                                 u32x4* __restrict__ Dsb) {
+    constexpr int KS16 = P / 16;
+    constexpr int STAGE_U = 2 * KS16 * 3 * 64;
+    const f32x4* D4 = reinterpret_cast<const f32x4*>(D);
+    const int rows = K * P;
+    const int s = blockIdx.x;
+    for (int g = threadIdx.x; g < 2 * KS16 * 64; g += 256) {       // (mt, ks, lane)
+        const int lane = g & 63, mk = g >> 6;
+        const int nn = lane & 31, hh = lane >> 5, ks = mk % KS16, mt = mk / KS16;
+        const int grow = s * 64 + mt * 32 + nn;
+        f32x4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = v0;
+        if (grow < rows) {
+            v0 = D4[(int64_t)grow * (P / 4) + ks * 4 + hh * 2];
+            v1 = D4[(int64_t)grow * (P / 4) + ks * 4 + hh * 2 + 1];
+        }
+        const Bf16x3Pair a = split_bf16x3(v0.x, v0.y), b = split_bf16x3(v0.z, v0.w);
+        const Bf16x3Pair c = split_bf16x3(v1.x, v1.y), d = split_bf16x3(v1.z, v1.w);
+        u32x4* out = Dsb + (int64_t)s * STAGE_U + (mk * 3) * 64 + lane;
+        out[0] = u32x4{a.hi, b.hi, c.hi, d.hi};
+        out[64] = u32x4{a.mid, b.mid, c.mid, d.mid};
+        out[128] = u32x4{a.lo, b.lo, c.lo, d.lo};
     }
 }
 
@@ -332,6 +362,195 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
     }
 }
 
+// The same kernel with the projection on the bf16 matrix cores (p <= 64): every fp32 operand
+// entry is the exact sum of three bf16 parts (device_utils.h), and the six partial products
+// that matter at fp32 accuracy are accumulated in fp32 by v_mfma_f32_32x32x16_bf16.  Per
+// 32 x 32 x 16 step that is six matrix instructions of 8 passes each where the fp32 instruction
+// needs 8 x 16 passes for the same 16 dims, and, unlike the fp32 matrix instruction, they run
+// beside the vector ALU.  To use that, a workgroup is two teams of four wavefronts, one
+// wavefront of each team per SIMD, half a stage apart: while team 0 multiplies stage s, team 1
+// runs the selection networks on its stage s - 1 results, then the roles swap; both read the
+// same LDS stage, and the one barrier per stage keeps them in this order.  The signals' three
+// parts stay in registers for the whole kernel (B operand, 8 bf16 per lane and step); the
+// dictionary arrives pre-split (Dsb) and is staged through LDS as in the fp32 kernel (24 KiB
+// per 64-row stage at p = 64).
+constexpr int kSplitWaves = 8;
+
+template <int P, int S, int NT, int SX>
+__global__ __launch_bounds__(64 * kSplitWaves) void energy_split_kernel(
+    const float* __restrict__ Y, int m, const u32x4* __restrict__ Dsb, int K, int s0,
+    int32_t* __restrict__ blk, float* __restrict__ energy, int32_t* __restrict__ chunk_count, int chunk,
+    int units_per_y) {
+    constexpr int NTH = 64 * kSplitWaves;
+    constexpr int KS16 = P / 16;         // contraction steps of 16 dims (a lane half covers 8 of them)
+    constexpr int NB = 64 / P;           // blocks per 64-row stage
+    constexpr int NV = P / 2;            // coefficients per lane per block
+    constexpr int STAGE_U = 2 * KS16 * 3 * 64;
+    constexpr int FPT = (STAGE_U + NTH - 1) / NTH;   // 16-byte units each thread moves per stage
+    constexpr bool kWhole = STAGE_U % NTH == 0;
+    static_assert(P == 16 || P == 32 || P == 64, "the split kernel covers p <= 64");
+
+    extern __shared__ u32x4 Qb_raw[];    // [2][STAGE_U]
+    u32x4(*Qs)[STAGE_U] = reinterpret_cast<u32x4(*)[STAGE_U]>(Qb_raw);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int team = wave >> 2;          // wavefronts w and w + 4 share a SIMD
+    const int h = lane >> 5, n = lane & 31;
+    const int64_t sig0 = ((int64_t)blockIdx.x * kSplitWaves + wave) * (32 * NT);
+
+    // B operand: the three bf16 parts of this lane's dims (ks*16 + h*8 .. +7) of NT signals.
+    u32x4 yq[NT][KS16][3];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int64_t i = sig0 + nt * 32 + n;
+#pragma unroll
+        for (int ks = 0; ks < KS16; ++ks) {
+            f32x4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = v0;
+            if (i < m) {
+                const f32x4* src = reinterpret_cast<const f32x4*>(Y + i * P + ks * 16 + h * 8);
+                v0 = src[0];
+                v1 = src[1];
+            }
+            const Bf16x3Pair a = split_bf16x3(v0.x, v0.y), b = split_bf16x3(v0.z, v0.w);
+            const Bf16x3Pair c = split_bf16x3(v1.x, v1.y), d = split_bf16x3(v1.z, v1.w);
+            yq[nt][ks][0] = u32x4{a.hi, b.hi, c.hi, d.hi};
+            yq[nt][ks][1] = u32x4{a.mid, b.mid, c.mid, d.mid};
+            yq[nt][ks][2] = u32x4{a.lo, b.lo, c.lo, d.lo};
+        }
+    }
+
+    // Small m: the stages are split over blockIdx.y exactly as in energy_kernel.
+    const int n_stage = (K * P + 63) / 64;
+    int s_beg = 0, s_end = n_stage;
+    if (units_per_y > 0) {
+        s_beg = min(n_stage, (int)blockIdx.y * units_per_y);
+        s_end = min(n_stage, s_beg + units_per_y);
+        blk += (int64_t)blockIdx.y * m;
+        energy += (int64_t)blockIdx.y * m;
+    }
+
+    u32x4 pre[FPT];
+    auto fetch = [&](int s) {
+#pragma unroll
+        for (int r = 0; r < FPT; ++r)
+            if (kWhole || tid + NTH * r < STAGE_U) pre[r] = Dsb[(int64_t)s * STAGE_U + tid + NTH * r];
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int r = 0; r < FPT; ++r)
+            if (kWhole || tid + NTH * r < STAGE_U) Qs[buf][tid + NTH * r] = pre[r];
+    };
+
+    int best[NT];
+    float bestE[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        best[nt] = 0;
+        bestE[nt] = -1.f;
+    }
+
+    // the six partial products, smallest first: (A part, B part)
+    constexpr int TA[6] = {2, 0, 1, 1, 0, 0};
+    constexpr int TB[6] = {0, 2, 1, 0, 1, 0};
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
+                         0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x16 acc[NT][2];
+
+    // Projection of the wavefront's signals onto the 64 rows staged in buffer buf:
+    // NT x 2 x KS16 x 6 matrix instructions into acc.
+    auto project = [&](int buf) {
+#pragma unroll
+        for (int ks = 0; ks < KS16; ++ks) {
+            u32x4 a[2][3];
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int pl = 0; pl < 3; ++pl) a[mt][pl] = Qs[buf][((mt * KS16 + ks) * 3 + pl) * 64 + lane];
+#pragma unroll
+            for (int t = 0; t < 6; ++t)
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, a[mt][TA[t]]),
+                            __builtin_bit_cast(bf16x8, yq[nt][ks][TB[t]]),
+                            (ks == 0 && t == 0) ? zero : acc[nt][mt], 0, 0, 0);
+        }
+    };
+    // Kept energy of the wavefront's signals in the blocks of stage s (from acc) against the
+    // running best.
+    auto select = [&](int s) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                float x[NV];
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+                    const int f = b * NV + v;      // flattened (tile, register)
+                    x[v] = fabsf(acc[nt][f >> 4][f & 15]);
+                }
+                const float e = pair_top_energy<NV, S, SX>(x, s0, h != 0);
+                const int j = s * NB + b;
+                if (j < K && e > bestE[nt]) {
+                    bestE[nt] = e;
+                    best[nt] = j;
+                }
+            }
+        }
+    };
+
+    if (s_beg < s_end) {                 // uniform
+        fetch(s_beg);
+        stash(0);
+    }
+    __syncthreads();
+    for (int s = s_beg; s < s_end; ++s) {
+        const int cur = (s - s_beg) & 1;
+        if (s + 1 < s_end) fetch(s + 1);
+        if (team == 0) {                 // uniform over the wavefront
+            project(cur);
+            select(s);
+        } else {
+            if (s > s_beg) select(s - 1);
+            project(cur);
+        }
+        if (s + 1 < s_end) stash(cur ^ 1);
+        __syncthreads();
+    }
+    if (team == 1 && s_beg < s_end) select(s_end - 1);
+
+    if (h == 0) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int64_t i = sig0 + nt * 32 + n;
+            if (i < m) {
+                blk[i] = best[nt];
+                energy[i] = bestE[nt];
+            }
+        }
+    }
+
+    // the grouping's chunk histograms (see energy_kernel)
+    if (chunk_count != nullptr) {        // uniform
+        int* lh = reinterpret_cast<int*>(Qb_raw);          // the stage buffers are dead (>= 12 KiB): the
+                                                           // loop's last barrier follows the last read
+        for (int j = tid; j < K; j += NTH) lh[j] = 0;
+        __syncthreads();
+        if (h == 0) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                if (sig0 + nt * 32 + n < m) atomicAdd(&lh[best[nt]], 1);
+        }
+        __syncthreads();
+        const int64_t c = ((int64_t)blockIdx.x * (kSplitWaves * 32 * NT)) / chunk;
+        for (int j = tid; j < K; j += NTH)
+            if (lh[j] != 0) atomicAdd(&chunk_count[c * K + j], lh[j]);
+    }
+}
+
 // Winner over the rows of a split launch: part_E / part_j hold, per row y, the best energy
 // and block of the row's share of the blocks (rows in ascending block order, so the strict
 // comparison keeps the lowest block among equal energies).  Also the grouping histogram
@@ -370,16 +589,19 @@ __global__ __launch_bounds__(256) void energy_merge_kernel(const float* __restri
     }
 }
 
+// Dsb != nullptr (p <= 64): the projection on the bf16 matrix cores from the split dictionary.
 template <int P, int S, int SX>
 hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, float* energy,
-                      const f32x4* Dsw, int32_t* chunk_count, float* part_E, int32_t* part_j,
-                      LdsRaised* raised, hipStream_t st) {
+                      const f32x4* Dsw, const u32x4* Dsb, int32_t* chunk_count, float* part_E,
+                      int32_t* part_j, LdsRaised* raised, hipStream_t st) {
     constexpr int NT = P <= 64 ? 2 : 1;
     constexpr int QN = P / 8;
     constexpr size_t lds = (size_t)2 * (2 * QN * 64) * sizeof(f32x4);
-    const int per_wg = 4 * 32 * NT;
+    constexpr size_t lds_split = (size_t)2 * (2 * (P / 16) * 3 * 64) * sizeof(u32x4);
+    const bool split = Dsb != nullptr && P <= 64;
+    const int per_wg = (split ? kSplitWaves : 4) * 32 * NT;
     dim3 grid((unsigned)((m + per_wg - 1) / per_wg));
-    if (lds > 64 * 1024) {
+    if (!split && lds > 64 * 1024) {
         if (raised == nullptr) return hipErrorInvalidValue;
         if (hipError_t e = raised->ensure(reinterpret_cast<const void*>(&energy_kernel<P, S, NT, SX>), lds);
             e != hipSuccess)
@@ -393,19 +615,28 @@ hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, fl
                                                              : (2 * kNumCU + (int)grid.x - 1) / (int)grid.x;
     int rows = rows_wanted < units ? rows_wanted : units;
     if (rows > kEnergySplitRows) rows = kEnergySplitRows;
-    if (rows > 1 && part_E != nullptr && part_j != nullptr && m <= kEnergySplitSignals) {
-        const int units_per_y = (units + rows - 1) / rows;
+    const bool by_rows = rows > 1 && part_E != nullptr && part_j != nullptr && m <= kEnergySplitSignals;
+    int units_per_y = 0;
+    if (by_rows) {
+        units_per_y = (units + rows - 1) / rows;
         rows = (units + units_per_y - 1) / units_per_y;
         grid.y = rows;
-        hipLaunchKernelGGL((energy_kernel<P, S, NT, SX>), grid, dim3(256), lds, st, Y, (int)m, Dsw,
-                           K, s0, part_j, part_E, nullptr, chunk, units_per_y);
+    }
+    int32_t* out_j = by_rows ? part_j : blk;
+    float* out_E = by_rows ? part_E : energy;
+    int32_t* hist = by_rows ? nullptr : chunk_count;
+    if (split) {
+        if constexpr (P <= 64)
+            hipLaunchKernelGGL((energy_split_kernel<P, S, NT, SX>), grid, dim3(64 * kSplitWaves), lds_split, st, Y, (int)m,
+                               Dsb, K, s0, out_j, out_E, hist, chunk, units_per_y);
+    } else {
+        hipLaunchKernelGGL((energy_kernel<P, S, NT, SX>), grid, dim3(256), lds, st, Y, (int)m, Dsw, K, s0,
+                           out_j, out_E, hist, chunk, units_per_y);
+    }
+    if (by_rows)
         hipLaunchKernelGGL(energy_merge_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256),
                            (size_t)K * sizeof(int), st, part_E, part_j, rows, (int)m, K, blk, energy,
                            chunk_count, chunk);
-        return hipGetLastError();
-    }
-    hipLaunchKernelGGL((energy_kernel<P, S, NT, SX>), grid, dim3(256), lds, st, Y, (int)m, Dsw, K,
-                       s0, blk, energy, chunk_count, chunk, 0);
     return hipGetLastError();
 }
 
@@ -414,19 +645,20 @@ hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, fl
 // s0 > 8), which takes the run-time path.
 template <int P, int S>
 hipError_t launch_ps(const float* Y, int64_t m, int K, int s0, int32_t* blk, float* energy,
-                     const float* dsw, int32_t* chunk_count, float* part_E, int32_t* part_j,
-                     LdsRaised* raised, hipStream_t st) {
+                     const float* dsw, const unsigned* dsb, int32_t* chunk_count, float* part_E,
+                     int32_t* part_j, LdsRaised* raised, hipStream_t st) {
     const f32x4* Dsw = reinterpret_cast<const f32x4*>(dsw);
+    const u32x4* Dsb = reinterpret_cast<const u32x4*>(dsb);
     constexpr int NV = P <= 64 ? P / 2 : 32;
     if constexpr (S > NV) {
-        return launch_pse<P, S, 0>(Y, m, K, s0, blk, energy, Dsw, chunk_count, part_E, part_j, raised, st);
+        return launch_pse<P, S, 0>(Y, m, K, s0, blk, energy, Dsw, Dsb, chunk_count, part_E, part_j, raised, st);
     } else {
         switch (S - s0) {
 #define SBO_CASE(DELTA)                                                                          \
     case DELTA:                                                                                  \
         if constexpr (S - DELTA > S / 2 || S == 1)                                               \
-            return launch_pse<P, S, S - DELTA>(Y, m, K, s0, blk, energy, Dsw, chunk_count, part_E, \
-                                               part_j, raised, st);                              \
+            return launch_pse<P, S, S - DELTA>(Y, m, K, s0, blk, energy, Dsw, Dsb, chunk_count,  \
+                                               part_E, part_j, raised, st);                      \
         break;
             SBO_CASE(0) SBO_CASE(1) SBO_CASE(2) SBO_CASE(3) SBO_CASE(4) SBO_CASE(5) SBO_CASE(6) SBO_CASE(7)
 #undef SBO_CASE
@@ -438,13 +670,13 @@ hipError_t launch_ps(const float* Y, int64_t m, int K, int s0, int32_t* blk, flo
 
 template <int P>
 hipError_t launch_p(int s0, const float* Y, int64_t m, int K, int32_t* blk, float* energy,
-                    const float* dsw, int32_t* chunk_count, float* part_E, int32_t* part_j,
-                    LdsRaised* raised, hipStream_t st) {
-    if (s0 <= 1) return launch_ps<P, 1>(Y, m, K, s0, blk, energy, dsw, chunk_count, part_E, part_j, raised, st);
-    if (s0 <= 2) return launch_ps<P, 2>(Y, m, K, s0, blk, energy, dsw, chunk_count, part_E, part_j, raised, st);
-    if (s0 <= 4) return launch_ps<P, 4>(Y, m, K, s0, blk, energy, dsw, chunk_count, part_E, part_j, raised, st);
-    if (s0 <= 8) return launch_ps<P, 8>(Y, m, K, s0, blk, energy, dsw, chunk_count, part_E, part_j, raised, st);
-    return launch_ps<P, 16>(Y, m, K, s0, blk, energy, dsw, chunk_count, part_E, part_j, raised, st);
+                    const float* dsw, const unsigned* dsb, int32_t* chunk_count, float* part_E,
+                    int32_t* part_j, LdsRaised* raised, hipStream_t st) {
+    if (s0 <= 1) return launch_ps<P, 1>(Y, m, K, s0, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, st);
+    if (s0 <= 2) return launch_ps<P, 2>(Y, m, K, s0, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, st);
+    if (s0 <= 4) return launch_ps<P, 4>(Y, m, K, s0, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, st);
+    if (s0 <= 8) return launch_ps<P, 8>(Y, m, K, s0, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, st);
+    return launch_ps<P, 16>(Y, m, K, s0, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, st);
 }
 
 }  // namespace
@@ -462,14 +694,26 @@ hipError_t launch_dict_swizzle(int p, int K, const float* D, float* dsw, hipStre
     return hipGetLastError();
 }
 
-hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const float* dsw,
-                         int32_t* blk, float* energy, int32_t* chunk_count, float* part_E,
-                         int32_t* part_j, LdsRaised* raised, hipStream_t st) {
+hipError_t launch_dict_swizzle_split(int p, int K, const float* D, unsigned* dsb, hipStream_t st) {
+    u32x4* out = reinterpret_cast<u32x4*>(dsb);
+    const dim3 grid((K * p + 63) / 64);
     switch (p) {
-        case 16: return launch_p<16>(s0, Y, m, K, blk, energy, dsw, chunk_count, part_E, part_j, raised, st);
-        case 32: return launch_p<32>(s0, Y, m, K, blk, energy, dsw, chunk_count, part_E, part_j, raised, st);
-        case 64: return launch_p<64>(s0, Y, m, K, blk, energy, dsw, chunk_count, part_E, part_j, raised, st);
-        case 256: return launch_p<256>(s0, Y, m, K, blk, energy, dsw, chunk_count, part_E, part_j, raised, st);
+        case 16: hipLaunchKernelGGL((dict_swizzle_split_kernel<16>), grid, dim3(256), 0, st, D, K, out); break;
+        case 32: hipLaunchKernelGGL((dict_swizzle_split_kernel<32>), grid, dim3(256), 0, st, D, K, out); break;
+        case 64: hipLaunchKernelGGL((dict_swizzle_split_kernel<64>), grid, dim3(256), 0, st, D, K, out); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const float* dsw,
+                         const unsigned* dsb, int32_t* blk, float* energy, int32_t* chunk_count,
+                         float* part_E, int32_t* part_j, LdsRaised* raised, hipStream_t st) {
+    switch (p) {
+        case 16: return launch_p<16>(s0, Y, m, K, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, st);
+        case 32: return launch_p<32>(s0, Y, m, K, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, st);
+        case 64: return launch_p<64>(s0, Y, m, K, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, st);
+        case 256: return launch_p<256>(s0, Y, m, K, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -8,6 +8,10 @@ namespace sbo {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 
@@ -35,6 +39,61 @@ __device__ __forceinline__ float group_sum(float x) {
     if constexpr (G >= 8) x += dpp_f<kDppHalfMirror>(x);
     if constexpr (G == 16) x += dpp_f<kDppRowMirror>(x);
     return x;
+}
+
+// ---- fp32 as a sum of three bf16 -------------------------------------------------------
+// v = hi + mid + lo exactly: each part is the bf16 nearest to what the parts before it leave
+// (3 x 8 significand bits plus the signs of the remainders cover the 24 bits of fp32; the two
+// subtractions are exact).  Two values at a time, packed as the matrix cores take them
+// (first value in the low half of the word).  With a = a_hi + a_mid + a_lo and likewise b,
+// a * b = hi*hi + (hi*mid + mid*hi) + (hi*lo + mid*mid + lo*hi) + terms below 2^-24 |a b|,
+// every product of two bf16 being exact in fp32: six bf16 matrix products with fp32
+// accumulation reproduce an fp32 contraction to fp32 accuracy.
+struct Bf16x3Pair {
+    unsigned hi, mid, lo;
+};
+__device__ __forceinline__ unsigned pack_bf16(float v0, float v1) {
+    const bf16x2 t = {(__bf16)v0, (__bf16)v1};           // v_cvt_pk_bf16_f32: round to nearest even
+    return __builtin_bit_cast(unsigned, t);
+}
+__device__ __forceinline__ Bf16x3Pair split_bf16x3(float v0, float v1) {
+    Bf16x3Pair r;
+    r.hi = pack_bf16(v0, v1);
+    const float a0 = v0 - __builtin_bit_cast(float, r.hi << 16);
+    const float a1 = v1 - __builtin_bit_cast(float, r.hi & 0xffff0000u);
+    r.mid = pack_bf16(a0, a1);
+    const float b0 = a0 - __builtin_bit_cast(float, r.mid << 16);
+    const float b1 = a1 - __builtin_bit_cast(float, r.mid & 0xffff0000u);
+    r.lo = pack_bf16(b0, b1);
+    return r;
+}
+
+// ---- the dictionary in the coding kernels' operand orders --------------------------------
+// Rows = atoms of all blocks (row j*P + k = atom k of Q_j), in stages of 64 rows, each stage a
+// run of 16-byte units in exactly the order the lanes of a wavefront consume the MFMA A operand
+// (row = stage*64 + mt*32 + nn, lane = hh*32 + nn):
+//   fp32 order : unit (mt*(P/8) + q)*64 + lane        = dims hh*P/2 + 4q .. +3 of the row
+//   split order: unit ((mt*(P/16) + ks)*3 + pl)*64 + lane = the 8 bf16 of part pl (0 hi, 1 mid,
+//                2 lo) of dims ks*16 + hh*8 .. +7 of the row
+// These store the four dims 4*d4 .. 4*d4+3 of row `grow`.
+template <int P>
+__device__ __forceinline__ void store_operand_f32(float* __restrict__ dsw, int grow, int d4, f32x4 row) {
+    constexpr int QN = P / 8;
+    const int st = grow >> 6, mt = (grow >> 5) & 1, nn = grow & 31;
+    const int hh = d4 / QN, q = d4 % QN;
+    reinterpret_cast<f32x4*>(dsw)[(int64_t)st * (2 * QN * 64) + (mt * QN + q) * 64 + hh * 32 + nn] = row;
+}
+template <int P>
+__device__ __forceinline__ void store_operand_split(unsigned* __restrict__ dsb, int grow, int d4, f32x4 row) {
+    constexpr int KS16 = P / 16;
+    const int st = grow >> 6, mt = (grow >> 5) & 1, nn = grow & 31;
+    const int ks = d4 >> 2, hh = (d4 >> 1) & 1, half = d4 & 1;
+    const Bf16x3Pair a = split_bf16x3(row.x, row.y), b = split_bf16x3(row.z, row.w);
+    u32x2* out = reinterpret_cast<u32x2*>(dsb) +
+                 ((int64_t)st * (2 * KS16 * 3 * 64) + (int64_t)((mt * KS16 + ks) * 3) * 64 + hh * 32 + nn) * 2 + half;
+    out[0] = u32x2{a.hi, b.hi};
+    out[2 * 64] = u32x2{a.mid, b.mid};
+    out[4 * 64] = u32x2{a.lo, b.lo};
 }
 
 // Workgroup-wide exclusive scan of n <= 4 * blockDim.x integers produced by f(idx).

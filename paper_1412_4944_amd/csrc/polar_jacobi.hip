@@ -30,6 +30,7 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
                                                              float* __restrict__ D,
                                                              float* __restrict__ eig_sv, float done,
                                                              float* __restrict__ dsw,
+                                                             unsigned* __restrict__ dsb,
                                                              int32_t* __restrict__ sweeps_out,
                                                              const int32_t* __restrict__ only) {
     constexpr int LD = P + 4;
@@ -296,15 +297,9 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
         for (int a = 0; a < 4; ++a) {
             f32x4 row = {o[a][0], o[a][1], o[a][2], o[a][3]};
             *reinterpret_cast<f32x4*>(&Dj[(k0 + a) * P + q0]) = row;
-            // the same four values in the coding kernel's operand order (see dict_swizzle_kernel:
-            // stage of 64 dictionary rows, unit (mt*QN + q)*64 + hh*32 + nn)
-            if (dsw != nullptr) {
-                constexpr int QN = P / 8;
-                const int grow = j * P + k0 + a, d4 = q0 >> 2;
-                const int st = grow >> 6, mt = (grow >> 5) & 1, nn = grow & 31;
-                const int hh = d4 / QN, q = d4 % QN;
-                reinterpret_cast<f32x4*>(dsw)[(int64_t)st * (2 * QN * 64) + (mt * QN + q) * 64 + hh * 32 + nn] = row;
-            }
+            // the same four values in the coding kernel's operand orders
+            if (dsw != nullptr) store_operand_f32<P>(dsw, j * P + k0 + a, q0 >> 2, row);
+            if (dsb != nullptr) store_operand_split<P>(dsb, j * P + k0 + a, q0 >> 2, row);
         }
     }
 }
@@ -313,25 +308,25 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
 
 // TPP = 16 lanes per column pair (4 and 8 were measured slower at every p).
 static hipError_t launch_jacobi(int p, int K, const float* M, const int32_t* counts, float* D,
-                                float* eig_sv, float* dsw, int32_t* sweeps, const int32_t* only,
-                                hipStream_t st) {
+                                float* eig_sv, float* dsw, unsigned* dsb, int32_t* sweeps,
+                                const int32_t* only, hipStream_t st) {
     constexpr int TPP = 16;
     const float done = kPolarDone;
     switch (p) {
-        case 16: hipLaunchKernelGGL((polar_kernel<16, TPP>), dim3(K), dim3(8 * TPP), 0, st, M, counts, D, eig_sv, done, dsw, sweeps, only); break;
-        case 32: hipLaunchKernelGGL((polar_kernel<32, TPP>), dim3(K), dim3(16 * TPP), 0, st, M, counts, D, eig_sv, done, dsw, sweeps, only); break;
-        case 64: hipLaunchKernelGGL((polar_kernel<64, TPP>), dim3(K), dim3(32 * TPP), 0, st, M, counts, D, eig_sv, done, dsw, sweeps, only); break;
+        case 16: hipLaunchKernelGGL((polar_kernel<16, TPP>), dim3(K), dim3(8 * TPP), 0, st, M, counts, D, eig_sv, done, dsw, dsb, sweeps, only); break;
+        case 32: hipLaunchKernelGGL((polar_kernel<32, TPP>), dim3(K), dim3(16 * TPP), 0, st, M, counts, D, eig_sv, done, dsw, dsb, sweeps, only); break;
+        case 64: hipLaunchKernelGGL((polar_kernel<64, TPP>), dim3(K), dim3(32 * TPP), 0, st, M, counts, D, eig_sv, done, dsw, dsb, sweeps, only); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
 hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
-                        const Workspace& ws, int jacobi_only, float* eig_sv, bool write_dsw,
+                        const Workspace& ws, int jacobi_only, float* eig_sv, int write_ops,
                         hipStream_t st) {
     const bool ns = eig_sv == nullptr && !jacobi_only;
     if (p == 256) {
-        if (write_dsw) return hipErrorInvalidValue;   // p = 256 rewrites the operand order itself
+        if (write_ops) return hipErrorInvalidValue;   // p = 256 rewrites the operand order itself
         if (!ns)
             return launch_polar_wide(K, M, counts, D, ws.vwork, ws.jac_a, eig_sv, ws.sweeps, nullptr,
                                      ws.raised, st);
@@ -341,12 +336,13 @@ hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, flo
         return launch_polar_wide(K, M, counts, D, ws.vwork, ws.jac_a, nullptr, ws.sweeps,
                                  ws.ns_fallback, ws.raised, st);
     }
-    float* dsw = write_dsw ? ws.dsw : nullptr;
-    if (!ns) return launch_jacobi(p, K, M, counts, D, eig_sv, dsw, ws.sweeps, nullptr, st);
+    float* dsw = write_ops == 1 ? ws.dsw : nullptr;
+    unsigned* dsb = write_ops == 2 ? ws.dsb : nullptr;
+    if (!ns) return launch_jacobi(p, K, M, counts, D, eig_sv, dsw, dsb, ws.sweeps, nullptr, st);
     // Newton-Schulz for every block; the Jacobi SVD only for the ones it flags.
-    hipError_t e = launch_polar_ns(p, K, M, counts, D, dsw, ws.ns_fallback, ws.sweeps, st);
+    hipError_t e = launch_polar_ns(p, K, M, counts, D, dsw, dsb, ws.ns_fallback, ws.sweeps, st);
     if (e != hipSuccess) return e;
-    return launch_jacobi(p, K, M, counts, D, nullptr, dsw, ws.sweeps, ws.ns_fallback, st);
+    return launch_jacobi(p, K, M, counts, D, nullptr, dsw, dsb, ws.sweeps, ws.ns_fallback, st);
 }
 
 }  // namespace sbo

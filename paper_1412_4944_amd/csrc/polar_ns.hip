@@ -23,8 +23,8 @@ namespace {
 template <int P>
 __global__ __launch_bounds__(P == 64 ? 256 : 64) void polar_ns_kernel(
     const float* __restrict__ M, const int32_t* __restrict__ counts, float* __restrict__ D,
-    float* __restrict__ dsw, int32_t* __restrict__ fallback, int32_t* __restrict__ iters_out,
-    int max_iters) {
+    float* __restrict__ dsw, unsigned* __restrict__ dsb, int32_t* __restrict__ fallback,
+    int32_t* __restrict__ iters_out, int max_iters) {
     constexpr int T = P == 64 ? 2 : 1;         // 32-wide tiles per side
     constexpr int NTH = T * T * 64;
     constexpr int PAD = T * 32;                // padded dimension (p = 16 sits in one tile)
@@ -197,21 +197,15 @@ __global__ __launch_bounds__(P == 64 ? 256 : 64) void polar_ns_kernel(
         if (iters_out != nullptr) iters_out[j] = -it;   // negative: Newton-Schulz steps, not sweeps
     }
 
-    // D[j][k][:] = row k of X; the same 16-byte units in the coding kernel's operand order
-    // (see dict_swizzle_kernel: stage of 64 dictionary rows, unit (mt*QN + q)*64 + hh*32 + nn)
+    // D[j][k][:] = row k of X; the same values in the coding kernel's operand orders
     float* Dj = D + (int64_t)j * P * P;
     for (int u = tid; u < P * P / 4; u += NTH) {
         const int k = u / (P / 4), d4 = u % (P / 4);
         const f32x4 row = {X[k * LD + 4 * d4], X[k * LD + 4 * d4 + 1], X[k * LD + 4 * d4 + 2],
                            X[k * LD + 4 * d4 + 3]};
         *reinterpret_cast<f32x4*>(&Dj[k * P + 4 * d4]) = row;
-        if (dsw != nullptr) {
-            constexpr int QN = P / 8;
-            const int grow = j * P + k;
-            const int st = grow >> 6, mt = (grow >> 5) & 1, nn = grow & 31;
-            const int hh = d4 / QN, q = d4 % QN;
-            reinterpret_cast<f32x4*>(dsw)[(int64_t)st * (2 * QN * 64) + (mt * QN + q) * 64 + hh * 32 + nn] = row;
-        }
+        if (dsw != nullptr) store_operand_f32<P>(dsw, j * P + k, d4, row);
+        if (dsb != nullptr) store_operand_split<P>(dsb, j * P + k, d4, row);
     }
 }
 
@@ -219,12 +213,12 @@ __global__ __launch_bounds__(P == 64 ? 256 : 64) void polar_ns_kernel(
 
 // fallback[j] = 1 for every block this kernel leaves to the Jacobi SVD, 0 otherwise.
 hipError_t launch_polar_ns(int p, int K, const float* M, const int32_t* counts, float* D, float* dsw,
-                           int32_t* fallback, int32_t* iters, hipStream_t st) {
+                           unsigned* dsb, int32_t* fallback, int32_t* iters, hipStream_t st) {
     constexpr int kMaxIters = 26;
     switch (p) {
-        case 16: hipLaunchKernelGGL((polar_ns_kernel<16>), dim3(K), dim3(64), 0, st, M, counts, D, dsw, fallback, iters, kMaxIters); break;
-        case 32: hipLaunchKernelGGL((polar_ns_kernel<32>), dim3(K), dim3(64), 0, st, M, counts, D, dsw, fallback, iters, kMaxIters); break;
-        case 64: hipLaunchKernelGGL((polar_ns_kernel<64>), dim3(K), dim3(256), 0, st, M, counts, D, dsw, fallback, iters, kMaxIters); break;
+        case 16: hipLaunchKernelGGL((polar_ns_kernel<16>), dim3(K), dim3(64), 0, st, M, counts, D, dsw, dsb, fallback, iters, kMaxIters); break;
+        case 32: hipLaunchKernelGGL((polar_ns_kernel<32>), dim3(K), dim3(64), 0, st, M, counts, D, dsw, dsb, fallback, iters, kMaxIters); break;
+        case 64: hipLaunchKernelGGL((polar_ns_kernel<64>), dim3(K), dim3(256), 0, st, M, counts, D, dsw, dsb, fallback, iters, kMaxIters); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -33,6 +33,7 @@ size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char
     w.perm = (int32_t*)take((size_t)m_max * 4);
     w.energy = (float*)take((size_t)m_max * 4);
     w.dsw = (float*)take((size_t)((K * p + 63) / 64) * 64 * p * 4);
+    w.dsb = (unsigned*)take(p <= 64 ? (size_t)((K * p + 63) / 64) * 64 * p * 6 : 0);
     const size_t split_m = (size_t)(m_max < kEnergySplitSignals ? m_max : kEnergySplitSignals);
     w.part_E = (float*)take((size_t)kEnergySplitRows * split_m * 4);
     w.part_j = (int32_t*)take((size_t)kEnergySplitRows * split_m * 4);
@@ -118,18 +119,34 @@ static int run_group(sbo_ctx* c, const int32_t* blk, int64_t m, bool have_hist =
     return SBO_OK;
 }
 
+// The coding kernel reads the split dictionary (bf16 matrix cores) or the fp32 one.
+static bool use_split(const sbo_ctx* c) { return c->coding_arith == SBO_ARITH_BF16X3 && c->p <= 64; }
+
+// D in the operand order(s) the coding kernels of this context read (tiny; outside the stages).
+static int run_swizzle(sbo_ctx* c, const float* D) {
+    if (use_split(c)) SBO_HIP(launch_dict_swizzle_split(c->p, c->K, D, c->ws.dsb, c->stream));
+    else SBO_HIP(launch_dict_swizzle(c->p, c->K, D, c->ws.dsw, c->stream));
+    return SBO_OK;
+}
+
+static int run_energy(sbo_ctx* c, const float* Y, int64_t m, int32_t* blk) {
+    StageTimer t(c, SBO_STAGE_ENERGY);     // also leaves the chunk histograms of the grouping
+    SBO_HIP(launch_energy(c->p, c->K, c->s0, Y, m, c->ws.dsw, use_split(c) ? c->ws.dsb : nullptr, blk,
+                          c->ws.energy, c->ws.chunk_count, c->ws.part_E, c->ws.part_j, &c->raised,
+                          c->stream));
+    return SBO_OK;
+}
+
 static int run_code(sbo_ctx* c, const float* Y, int64_t m, const float* D, int32_t* blk,
                     int32_t* supp, float* coef, float* err) {
-    SBO_HIP(launch_dict_swizzle(c->p, c->K, D, c->ws.dsw, c->stream));   // tiny; outside the stages
-    {
-        StageTimer t(c, SBO_STAGE_ENERGY);
-        SBO_HIP(launch_energy(c->p, c->K, c->s0, Y, m, c->ws.dsw, blk, c->ws.energy,
-                              c->ws.chunk_count, c->ws.part_E, c->ws.part_j, &c->raised, c->stream));
-    }
-    int rc = run_group(c, blk, m, true);       // the energy kernel left the chunk histograms
+    int rc = run_swizzle(c, D);
+    if (rc) return rc;
+    rc = run_energy(c, Y, m, blk);
+    if (rc) return rc;
+    rc = run_group(c, blk, m, true);           // the energy kernel left the chunk histograms
     if (rc) return rc;
     {
-        StageTimer t(c, SBO_STAGE_SELECT);
+        StageTimer t(c, SBO_STAGE_SELECT);         // p = 256 reads ws.dsw, which run_swizzle wrote
         SBO_HIP(launch_select(c->p, c->K, c->s0, Y, m, D, c->ws, supp, coef, err, true, c->stream));
     }
     return SBO_OK;
@@ -144,7 +161,7 @@ static int run_update_grouped(sbo_ctx* c, const float* Y, int64_t m, const int32
     }
     {
         StageTimer t(c, SBO_STAGE_SVD);
-        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws, c->svd_method, nullptr, false,
+        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws, c->svd_method, nullptr, 0,
                              c->stream));
     }
     return SBO_OK;
@@ -172,6 +189,7 @@ int sbo_create(sbo_ctx** out, int p, int K, int s0, int64_t m_max, void* hip_str
     c->m_max = m_max;
     c->stream = (hipStream_t)hip_stream;
     c->svd_method = SBO_SVD_AUTO;
+    c->coding_arith = SBO_ARITH_BF16X3;      // p = 256 has the fp32 kernel only (use_split)
     c->timing = 0;
     c->n_spans = 0;
     const size_t bytes = workspace_layout(p, K, s0, m_max, nullptr, nullptr);
@@ -270,7 +288,7 @@ int sbo_polar(sbo_ctx* c, const float* M, const int32_t* counts, float* D) {
     if (!c || !M || !D) return SBO_EINVAL;
     c->n_spans = 0;
     StageTimer t(c, SBO_STAGE_SVD);
-    SBO_HIP(launch_polar(c->p, c->K, M, counts, D, c->ws, c->svd_method, nullptr, false, c->stream));
+    SBO_HIP(launch_polar(c->p, c->K, M, counts, D, c->ws, c->svd_method, nullptr, 0, c->stream));
     return SBO_OK;
 }
 
@@ -308,12 +326,12 @@ int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter, int
         }
         // The dictionary in the coding kernel's operand order: rewritten from D at the start
         // of the call, kept up to date by the SVD kernel afterwards.
-        if (it == 0) SBO_HIP(launch_dict_swizzle(c->p, c->K, D, c->ws.dsw, c->stream));
-        {
-            StageTimer t(c, SBO_STAGE_ENERGY);  // also leaves the chunk histograms of the grouping
-            SBO_HIP(launch_energy(c->p, c->K, c->s0, Y, m, c->ws.dsw, blk, c->ws.energy,
-                                  c->ws.chunk_count, c->ws.part_E, c->ws.part_j, &c->raised, c->stream));
+        if (it == 0) {
+            rc = run_swizzle(c, D);
+            if (rc) return rc;
         }
+        rc = run_energy(c, Y, m, blk);
+        if (rc) return rc;
         rc = run_group(c, blk, m, true);
         if (rc) return rc;
         {
@@ -327,8 +345,8 @@ int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter, int
         }
         {
             StageTimer t(c, SBO_STAGE_SVD);
-            SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws, c->svd_method, nullptr, true,
-                                 c->stream));
+            SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws, c->svd_method, nullptr,
+                                 use_split(c) ? 2 : 1, c->stream));
         }
     }
     return SBO_OK;
@@ -357,7 +375,7 @@ static int run_train_rounds(sbo_ctx* c, const float* Y, int64_t m, const int32_t
             SBO_HIP(launch_accumulate(c->p, c->K, c->s0, Y, m, supp, coef, c->ws, c->ws.M, c->stream));
         }
         StageTimer t(c, SBO_STAGE_SVD);
-        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws, c->svd_method, nullptr, false,
+        SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws, c->svd_method, nullptr, 0,
                              c->stream));
     }
     return SBO_OK;
@@ -397,7 +415,7 @@ int sbo_worst(sbo_ctx* c, const float* err, int64_t m, int64_t W, int32_t* ids) 
 // Gram matrix of the set -> its eigenvectors by descending eigenvalue (ws.perm etc. hold the set).
 static int run_init_base(sbo_ctx* c, const float* Y, int64_t n, float* Q, float* sv) {
     SBO_HIP(launch_gram(c->p, 1, Y, n, c->ws, c->ws.M, c->stream));
-    SBO_HIP(launch_polar(c->p, 1, c->ws.M, nullptr, Q, c->ws, 0, sv ? sv : c->ws.energy, false,
+    SBO_HIP(launch_polar(c->p, 1, c->ws.M, nullptr, Q, c->ws, 0, sv ? sv : c->ws.energy, 0,
                          c->stream));              // energy[m_max >= p] as a sink
     return SBO_OK;
 }
@@ -430,7 +448,7 @@ static int run_new_base(sbo_ctx* c, const float* Y, int64_t n, int R, int have_q
         }
         if (sqerr_per_round)
             SBO_HIP(launch_sqerr(err, c->ws.perm, n, c->ws, sqerr_per_round + r, c->stream));
-        SBO_HIP(launch_polar(c->p, 1, c->ws.M, c->ws.counts, Q, c->ws, c->svd_method, nullptr, false,
+        SBO_HIP(launch_polar(c->p, 1, c->ws.M, c->ws.counts, Q, c->ws, c->svd_method, nullptr, 0,
                              c->stream));
     }
     return SBO_OK;
@@ -486,11 +504,11 @@ int sbo_learn(sbo_ctx* c, const float* Y, int64_t m, float* D, const int32_t* in
     if (c->p <= 64 && n_init <= c->m_max && (int64_t)K0 * c->p <= c->m_max) {
         SBO_HIP(launch_equal_blocks(init_ids, K0, P0, m, c->ws, c->stream));
         SBO_HIP(launch_gram(c->p, K0, Y, n_init, c->ws, c->ws.M, c->stream));
-        SBO_HIP(launch_polar(c->p, K0, c->ws.M, nullptr, D, c->ws, 0, c->ws.energy, false, c->stream));
+        SBO_HIP(launch_polar(c->p, K0, c->ws.M, nullptr, D, c->ws, 0, c->ws.energy, 0, c->stream));
         for (int r = 0; r < R; ++r) {
             SBO_HIP(launch_select_accum(c->p, K0, c->s0, Y, n_init, D, c->ws, supp, coef, err, c->stream));
             SBO_HIP(launch_accum_reduce(c->p, K0, n_init, c->ws, c->ws.M, nullptr, nullptr, c->stream));
-            SBO_HIP(launch_polar(c->p, K0, c->ws.M, c->ws.counts, D, c->ws, c->svd_method, nullptr, false,
+            SBO_HIP(launch_polar(c->p, K0, c->ws.M, c->ws.counts, D, c->ws, c->svd_method, nullptr, 0,
                                  c->stream));
         }
     } else {
@@ -547,6 +565,10 @@ int sbo_set_option(sbo_ctx* c, int option, int value) {
         case SBO_OPT_SVD_METHOD:
             if (value != SBO_SVD_AUTO && value != SBO_SVD_JACOBI) return SBO_EINVAL;
             c->svd_method = value;
+            return SBO_OK;
+        case SBO_OPT_CODING_ARITH:
+            if (value != SBO_ARITH_F32 && value != SBO_ARITH_BF16X3) return SBO_EINVAL;
+            c->coding_arith = value;
             return SBO_OK;
         default: return SBO_EINVAL;
     }

@@ -17,13 +17,13 @@ constexpr int kWave = 64;
 // One wavefront owns one chunk of consecutive signals; a chunk is a multiple of
 // 64 signals, sized so that there are at most ~1024 chunks.
 struct GroupGeom {
-    int chunk;     // signals per chunk (multiple of 256)
+    int chunk;     // signals per chunk (multiple of 512)
     int n_chunks;  // ceil(m / chunk)
 };
 inline GroupGeom group_geom(int64_t m) {
     int64_t c = (m + 1023) / 1024;
-    c = ((c + 255) / 256) * 256;           // whole workgroups of the coding kernel (256 or 128 signals)
-    if (c < 256) c = 256;
+    c = ((c + 511) / 512) * 512;           // whole workgroups of the coding kernels (128, 256 or 512 signals)
+    if (c < 512) c = 512;
     GroupGeom g;
     g.chunk = (int)c;
     g.n_chunks = (int)((m + c - 1) / c);
@@ -92,6 +92,7 @@ struct Workspace {
     // coding
     float* energy;         // [m_max] kept energy in the winning block
     float* dsw;            // [ceil(K*p/64)*64][p] dictionary in MFMA operand order
+    unsigned* dsb;         // p <= 64: the same rows as three bf16 parts in the split operand order (6 bytes per entry)
     float* part_E;         // [kEnergySplitRows][min(m_max, kEnergySplitSignals)] split coding: best energy per row
     int32_t* part_j;       // same shape: its block
     // accumulation
@@ -138,6 +139,7 @@ struct sbo_ctx {
     char* ws_base;
     sbo::Workspace ws;
     int svd_method;                  // SBO_SVD_AUTO or SBO_SVD_JACOBI (sbo_set_option)
+    int coding_arith;                // SBO_ARITH_F32 or SBO_ARITH_BF16X3 (sbo_set_option)
     sbo::LdsRaised raised;
     int timing;
     std::vector<sbo_span> spans;     // event pool; the first n_spans are in use
@@ -149,13 +151,17 @@ namespace sbo {
 
 // dsw = D rewritten by launch_dict_swizzle into the energy kernel's operand order.
 hipError_t launch_dict_swizzle(int p, int K, const float* D, float* dsw, hipStream_t st);
+// dsb = D as three bf16 parts per entry in the split operand order (p <= 64).
+hipError_t launch_dict_swizzle_split(int p, int K, const float* D, unsigned* dsb, hipStream_t st);
 // chunk_count != nullptr: also add the per-chunk histograms of the chosen blocks into it (the
 // first step of launch_group; the array must be zero on entry, launch_group leaves it so).
 // part_E / part_j ([kEnergySplitRows][min(m_max, kEnergySplitSignals)], may be nullptr): scratch
 // for small m, where the blocks are split over several workgroup rows to fill the chip.
+// dsb != nullptr and p <= 64: the projection runs on the bf16 matrix cores from the split
+// dictionary (dsw is then not read); otherwise on the fp32 matrix instruction from dsw.
 hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const float* dsw,
-                         int32_t* blk, float* energy, int32_t* chunk_count, float* part_E,
-                         int32_t* part_j, LdsRaised* raised, hipStream_t st);
+                         const unsigned* dsb, int32_t* blk, float* energy, int32_t* chunk_count,
+                         float* part_E, int32_t* part_j, LdsRaised* raised, hipStream_t st);
 
 hipError_t launch_group(int K, const int32_t* blk, int64_t m, const Workspace& ws, bool have_hist,
                         hipStream_t st);
@@ -193,14 +199,15 @@ hipError_t launch_accum_reduce(int p, int K, int64_t m, const Workspace& ws, flo
 // eig_sv != nullptr switches to eigen mode (always Jacobi): M[j] symmetric positive
 // semidefinite, D[j] receives its eigenvectors as atoms by descending eigenvalue and
 // eig_sv[j][p] the square roots of the eigenvalues.
-// write_dsw (p <= 64): the rows of every updated block are also written into ws.dsw, the coding
-// kernel's operand order (what launch_dict_swizzle would produce from the new D).
+// write_ops (p <= 64): the rows of every updated block are also written in the coding kernel's
+// operand order: 1 = into ws.dsw (what launch_dict_swizzle would produce from the new D), 2 = into
+// ws.dsb (launch_dict_swizzle_split), 0 = neither.
 hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
-                        const Workspace& ws, int jacobi_only, float* eig_sv, bool write_dsw,
+                        const Workspace& ws, int jacobi_only, float* eig_sv, int write_ops,
                         hipStream_t st);
 
 hipError_t launch_polar_ns(int p, int K, const float* M, const int32_t* counts, float* D, float* dsw,
-                           int32_t* fallback, int32_t* iters, hipStream_t st);
+                           unsigned* dsb, int32_t* fallback, int32_t* iters, hipStream_t st);
 
 // p = 256 variant of launch_polar (polar_wide.hip) and the size of its scratch (working
 // copy of P_j, rotation log, sweep counts).

@@ -17,7 +17,7 @@ ORTHO_TOL = 1e-5     # max |Q^T Q - I| of every block written by the GPU
 class Sbo:
     """One libsbo context plus device copies; everything returned is numpy."""
 
-    def __init__(self, p, K, s0, m_max, jacobi_only=False):
+    def __init__(self, p, K, s0, m_max, jacobi_only=False, arith=None):
         import torch
         self.torch = torch
         self.dev = torch.device("cuda:0")
@@ -25,6 +25,13 @@ class Sbo:
         self.ctx = sbo.sbo_create(p, K, s0, m_max)
         if jacobi_only:
             self.svd_jacobi(True)
+        if arith is not None:
+            self.coding_arith(arith)
+
+    def coding_arith(self, name):
+        """"f32": fp32 matrix instruction; "bf16x3": three-part bf16 split on the bf16 matrix cores."""
+        sbo.sbo_set_option(self.ctx, sbo.SBO_OPT_CODING_ARITH,
+                           {"f32": sbo.SBO_ARITH_F32, "bf16x3": sbo.SBO_ARITH_BF16X3}[name])
 
     def svd_jacobi(self, on):
         """Jacobi SVD for every orthobase (on) or the default Newton-Schulz + Jacobi fallback."""

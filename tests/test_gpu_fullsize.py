@@ -13,6 +13,30 @@ from gpu_util import Sbo, compare_assigned_code, compare_code, compare_Q
 pytestmark = pytest.mark.gpu
 
 
+# The oracle's results do not depend on how the GPU multiplies: computed once per workload and
+# shared by the parametrized cases below.
+import functools
+
+
+@functools.lru_cache(maxsize=2)
+def _problem_of(name):
+    return synth.generate(synth.CONFIGS[name])
+
+
+@functools.lru_cache(maxsize=4)
+def _oracle_code_of(name, n_sample):
+    pr = _problem_of(name)
+    cfg = pr.cfg
+    ids = _sample_ids(pr.Y.shape[0], n_sample, cfg.number)
+    return ids, orc.o_code(pr.Y[ids], pr.D_init, cfg.s0)
+
+
+@functools.lru_cache(maxsize=4)
+def _oracle_curve_of(name):
+    pr = _problem_of(name)
+    return orc.o_iterate(pr.Y, pr.D_init, pr.cfg.s0, pr.cfg.iters)[2]
+
+
 def _sample_ids(m, n, seed):
     if n >= m:
         return np.arange(m)
@@ -22,17 +46,18 @@ def _sample_ids(m, n, seed):
     return ids
 
 
-@pytest.mark.parametrize("name,n_sample", [("headline", 262144), ("skew", 110000), ("patch16", 14000)])
-def test_full_size_iteration_against_oracle(name, n_sample):
+@pytest.mark.parametrize("name,n_sample,arith", [("headline", 262144, "f32"), ("headline", 262144, "bf16x3"),
+                                                 ("skew", 110000, "f32"), ("skew", 110000, "bf16x3"),
+                                                 ("patch16", 14000, "f32")])
+def test_full_size_iteration_against_oracle(name, n_sample, arith):
     cfg = synth.CONFIGS[name]
-    print(f"case {name}: p={cfg.p} K={cfg.K} m={cfg.m} s0={cfg.s0}: generating", flush=True)
-    pr = synth.generate(cfg)
+    print(f"case {name} {arith}: p={cfg.p} K={cfg.K} m={cfg.m} s0={cfg.s0}: generating", flush=True)
+    pr = _problem_of(name)
     m = pr.Y.shape[0]
-    ids = _sample_ids(m, n_sample, cfg.number)
-    with Sbo(cfg.p, cfg.K, cfg.s0, m) as g:
+    ids, o = _oracle_code_of(name, n_sample)
+    with Sbo(cfg.p, cfg.K, cfg.s0, m, arith=arith) as g:
         print("  coding on the GPU", flush=True)
         blk, supp, coef, err = g.code(pr.Y, pr.D_init)
-        o = orc.o_code(pr.Y[ids], pr.D_init, cfg.s0)
         frac = compare_code(pr.Y[ids], pr.D_init, cfg.s0, o, (blk[ids], supp[ids], coef[ids], err[ids]))
         print(f"  coding parity on {len(ids)} of {m} signals, exempt fraction {frac:.5f}", flush=True)
         # properties that hold at any size
@@ -71,21 +96,22 @@ def test_full_size_iteration_against_oracle(name, n_sample):
         compare_code(pr.Y[ids], Dg, cfg.s0, o2, (b2[ids], s2[ids], c2[ids], e2[ids]))
 
 
+@pytest.mark.parametrize("arith", ["f32", "bf16x3"])
 @pytest.mark.parametrize("name", ["patch8", "headline"])
-def test_full_size_configured_iterations(name):
+def test_full_size_configured_iterations(name, arith):
     """The configured number of iterations (10) at the stated size, free-running on both sides:
     the squared-error curve never increases and stays within 1e-3 of the oracle's (Section 4
     RMSE); then the last coding pass, element by element, against the oracle coding with the
     dictionary that pass used."""
     cfg = synth.CONFIGS[name]
-    pr = synth.generate(cfg)
+    pr = _problem_of(name)
     m, iters = pr.Y.shape[0], cfg.iters
-    print(f"case {name}: p={cfg.p} K={cfg.K} m={m} s0={cfg.s0} iterations={iters}", flush=True)
-    with Sbo(cfg.p, cfg.K, cfg.s0, m) as g:
+    print(f"case {name} {arith}: p={cfg.p} K={cfg.K} m={m} s0={cfg.s0} iterations={iters}", flush=True)
+    with Sbo(cfg.p, cfg.K, cfg.s0, m, arith=arith) as g:
         Dg, blk, supp, coef, err, sq = g.iterate(pr.Y, pr.D_init, iters)
         Dprev, *_r = g.iterate(pr.Y, pr.D_init, iters - 1)     # the dictionary the last pass coded with
     print("  oracle", flush=True)
-    sq_o = orc.o_iterate(pr.Y, pr.D_init, cfg.s0, iters)[2]
+    sq_o = _oracle_curve_of(name)
     print(f"  oracle sqerr {sq_o}\n  gpu    sqerr {sq}", flush=True)
     assert (np.diff(sq) <= 1e-6 * sq[0]).all(), "error increased"
     np.testing.assert_allclose(sq, sq_o, rtol=1e-3)
