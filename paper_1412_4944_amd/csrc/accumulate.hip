@@ -7,8 +7,9 @@
 // pairwise in a fixed order), and a second kernel adds the piece results of a block in piece order.
 // No floating-point atomics are used anywhere.
 //
-// The piece kernel (p <= 64: one workgroup of 8 wavefronts per piece, about one piece per
-// CU, each wavefront keeping the operands of several steps in flight) forms the product on the matrix cores: with atoms on the M axis, the
+// The piece kernel (p <= 64: one workgroup of 8 wavefronts per piece, as few pieces as keep
+// every CU busy in one round (accum_tall_piece), each wavefront keeping the operands of several
+// steps in flight) forms the product on the matrix cores: with atoms on the M axis, the
 // dimensions on the N axis and the signal index as the contraction index, one fp32 MFMA
 // 32x32x2 adds two signals to a 32x32 tile of P_j.  Its A operand is the dense x_i, which
 // each signal's s0 (atom, coefficient) pairs are scattered into through a 64-float row of
@@ -18,6 +19,7 @@
 // additions is fixed by the program.
 #include "sbo_internal.h"
 #include "device_utils.h"
+#include "sq_total.h"
 
 namespace sbo {
 
@@ -362,10 +364,7 @@ __global__ __launch_bounds__(256) void accum_wide_kernel(const float* __restrict
 }
 
 // Besides the sums over pieces (blockIdx.x < K), nb workgroups in the grid columns from K on form
-// the total squared error sum_i err[i] (sq_out != nullptr): every workgroup of the column sums
-// a contiguous share in a fixed order, and the one that finishes last adds the shares in
-// index order (it is identified by an integer counter, which it sets back to zero; nobody
-// waits for anybody).
+// the total squared error sum_i err[i] (sq_out != nullptr; see sq_total.h).
 template <int P>
 __global__ __launch_bounds__(256) void accum_reduce_kernel(int K, int piece,
                                                            const int32_t* __restrict__ offsets,
@@ -380,46 +379,8 @@ __global__ __launch_bounds__(256) void accum_reduce_kernel(int K, int piece,
         // the nb workgroups of the squared-error sum occupy the grid columns from K on
         const int b = ((int)blockIdx.x - K) * (int)gridDim.y + (int)blockIdx.y;
         if (sq_out == nullptr || b >= nb) return;
-        __shared__ double red[256];
-        __shared__ int is_last;
-        const int tid = threadIdx.x;
-        const int64_t per = (m + nb - 1) / nb;
-        const int64_t beg = b * per, end = beg + per < m ? beg + per : m;
-        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;   // four loads in flight per thread
-        int64_t i = beg + tid;
-        for (; i + 768 < end; i += 1024) {
-            const float a = err[i], b2 = err[i + 256], c2 = err[i + 512], d2 = err[i + 768];
-            s0 += (double)a;
-            s1 += (double)b2;
-            s2 += (double)c2;
-            s3 += (double)d2;
-        }
-        for (; i < end; i += 256) s0 += (double)err[i];
-        red[tid] = (s0 + s1) + (s2 + s3);
-        __syncthreads();
-        for (int o = 128; o > 0; o >>= 1) {
-            if (tid < o) red[tid] += red[tid + o];
-            __syncthreads();
-        }
-        if (tid == 0) {
-            __hip_atomic_store(&sq_part[b], red[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __threadfence();
-            is_last = atomicAdd(sq_counter, 1) == nb - 1;
-        }
-        __syncthreads();
-        if (!is_last) return;
-        __threadfence();
-        red[tid] = tid < nb ? __hip_atomic_load(&sq_part[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                            : 0.0;
-        __syncthreads();
-        for (int o = 128; o > 0; o >>= 1) {
-            if (tid < o) red[tid] += red[tid + o];
-            __syncthreads();
-        }
-        if (tid == 0) {
-            *sq_out = red[0];
-            *sq_counter = 0;
-        }
+        __shared__ double sq_lds[256 + 1];
+        sq_total_part<256>(err, m, b, nb, sq_part, sq_counter, sq_out, sq_lds);
         return;
     }
     int* piece_start = lds;

@@ -167,6 +167,26 @@ static int run_update_grouped(sbo_ctx* c, const float* Y, int64_t m, const int32
     return SBO_OK;
 }
 
+// The SVD update from the piece results of launch_select_accum (p <= 64); err / sq_out: also
+// the squared-error total of the coding pass.  One launch on the default path; with the Jacobi
+// SVD for every block the pieces are summed by their own launch first.
+static int run_polar_pieces(sbo_ctx* c, int64_t m, float* D, int write_ops, const float* err, double* sq_out,
+                            int K = -1) {
+    if (K < 0) K = c->K;
+    if (c->svd_method == SBO_SVD_JACOBI) {
+        {
+            StageTimer t(c, SBO_STAGE_ACCUM);
+            SBO_HIP(launch_accum_reduce(c->p, K, m, c->ws, c->ws.M, err, sq_out, c->stream));
+        }
+        StageTimer t(c, SBO_STAGE_SVD);
+        SBO_HIP(launch_polar(c->p, K, c->ws.M, c->ws.counts, D, c->ws, 1, nullptr, write_ops, c->stream));
+        return SBO_OK;
+    }
+    StageTimer t(c, SBO_STAGE_SVD);
+    SBO_HIP(launch_polar_from_pieces(c->p, K, m, D, c->ws, write_ops, err, sq_out, c->stream));
+    return SBO_OK;
+}
+
 }  // namespace sbo
 
 using namespace sbo;
@@ -338,16 +358,8 @@ int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter, int
             StageTimer t(c, SBO_STAGE_SELECT);  // includes the per-piece accumulation
             SBO_HIP(launch_select_accum(c->p, c->K, c->s0, Y, m, D, c->ws, supp, coef, err, c->stream));
         }
-        {
-            StageTimer t(c, SBO_STAGE_ACCUM);   // the sum over pieces, and the squared-error total
-            SBO_HIP(launch_accum_reduce(c->p, c->K, m, c->ws, c->ws.M, err,
-                                        sqerr_per_iter ? sqerr_per_iter + it : nullptr, c->stream));
-        }
-        {
-            StageTimer t(c, SBO_STAGE_SVD);
-            SBO_HIP(launch_polar(c->p, c->K, c->ws.M, c->ws.counts, D, c->ws, c->svd_method, nullptr,
-                                 use_split(c) ? 2 : 1, c->stream));
-        }
+        rc = run_polar_pieces(c, m, D, use_split(c) ? 2 : 1, err, sqerr_per_iter ? sqerr_per_iter + it : nullptr);
+        if (rc) return rc;
     }
     return SBO_OK;
 }
@@ -363,8 +375,9 @@ static int run_train_rounds(sbo_ctx* c, const float* Y, int64_t m, const int32_t
                 SBO_HIP(launch_select_accum(c->p, c->K, c->s0, Y, m, D, c->ws, supp, coef, err,
                                             c->stream));
             }
-            StageTimer t(c, SBO_STAGE_ACCUM);
-            SBO_HIP(launch_accum_reduce(c->p, c->K, m, c->ws, c->ws.M, nullptr, nullptr, c->stream));
+            rc = run_polar_pieces(c, m, D, 0, nullptr, nullptr);
+            if (rc) return rc;
+            continue;
         } else {
             {
                 StageTimer t(c, SBO_STAGE_SELECT);
@@ -441,15 +454,19 @@ static int run_new_base(sbo_ctx* c, const float* Y, int64_t n, int R, int have_q
     for (int r = 0; r < R; ++r) {
         if (c->p <= 64) {
             SBO_HIP(launch_select_accum(c->p, 1, c->s0, Y, n, Q, c->ws, supp, coef, err, c->stream));
-            SBO_HIP(launch_accum_reduce(c->p, 1, n, c->ws, c->ws.M, nullptr, nullptr, c->stream));
         } else {
             SBO_HIP(launch_select(c->p, 1, c->s0, Y, n, Q, c->ws, supp, coef, err, false, c->stream));
             SBO_HIP(launch_accumulate(c->p, 1, c->s0, Y, n, supp, coef, c->ws, c->ws.M, c->stream));
         }
         if (sqerr_per_round)
             SBO_HIP(launch_sqerr(err, c->ws.perm, n, c->ws, sqerr_per_round + r, c->stream));
-        SBO_HIP(launch_polar(c->p, 1, c->ws.M, c->ws.counts, Q, c->ws, c->svd_method, nullptr, 0,
-                             c->stream));
+        if (c->p <= 64) {
+            int rc = run_polar_pieces(c, n, Q, 0, nullptr, nullptr, 1);
+            if (rc) return rc;
+        } else {
+            SBO_HIP(launch_polar(c->p, 1, c->ws.M, c->ws.counts, Q, c->ws, c->svd_method, nullptr, 0,
+                                 c->stream));
+        }
     }
     return SBO_OK;
 }
@@ -507,9 +524,8 @@ int sbo_learn(sbo_ctx* c, const float* Y, int64_t m, float* D, const int32_t* in
         SBO_HIP(launch_polar(c->p, K0, c->ws.M, nullptr, D, c->ws, 0, c->ws.energy, 0, c->stream));
         for (int r = 0; r < R; ++r) {
             SBO_HIP(launch_select_accum(c->p, K0, c->s0, Y, n_init, D, c->ws, supp, coef, err, c->stream));
-            SBO_HIP(launch_accum_reduce(c->p, K0, n_init, c->ws, c->ws.M, nullptr, nullptr, c->stream));
-            SBO_HIP(launch_polar(c->p, K0, c->ws.M, c->ws.counts, D, c->ws, c->svd_method, nullptr, 0,
-                                 c->stream));
+            rc = run_polar_pieces(c, n_init, D, 0, nullptr, nullptr, K0);
+            if (rc) return fail(rc);
         }
     } else {
         for (int j = 0; j < K0; ++j) {

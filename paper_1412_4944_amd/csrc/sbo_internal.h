@@ -206,8 +206,27 @@ hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, flo
                         const Workspace& ws, int jacobi_only, float* eig_sv, int write_ops,
                         hipStream_t st);
 
-hipError_t launch_polar_ns(int p, int K, const float* M, const int32_t* counts, float* D, float* dsw,
-                           unsigned* dsb, int32_t* fallback, int32_t* iters, hipStream_t st);
+// Total squared error riding along in a launch (sq_total.h): out == nullptr = none.
+struct SqTotalArgs {
+    const float* err = nullptr;
+    int64_t m = 0;
+    double* part = nullptr;     // ws.sq_partial
+    int* counter = nullptr;     // ws.sq_counter (zero between launches)
+    double* out = nullptr;
+    int nb = 0;                 // workgroups (<= kSqBlocks)
+};
+// Newton-Schulz for p <= 64 with the Jacobi SVD in the same workgroup for a block that does not
+// converge.  M == nullptr: P_j = the sum of block j's pieces in `partial` (fused select +
+// accumulate, cut from `offsets` with `piece` signals per piece).
+hipError_t launch_polar_ns(int p, int K, const float* M, const float* partial, const int32_t* offsets,
+                           int piece, const int32_t* counts, float* D, float* dsw, unsigned* dsb,
+                           int32_t* fallback, int32_t* iters, const SqTotalArgs& sq, LdsRaised* raised,
+                           hipStream_t st);
+// The SVD update straight from the piece results of launch_select_accum (p <= 64, Newton-Schulz
+// path): what launch_accum_reduce + launch_polar do, in one launch.  err / sq_out as for
+// launch_accum_reduce.
+hipError_t launch_polar_from_pieces(int p, int K, int64_t m, float* D, const Workspace& ws, int write_ops,
+                                    const float* err, double* sq_out, hipStream_t st);
 
 // p = 256 variant of launch_polar (polar_wide.hip) and the size of its scratch (working
 // copy of P_j, rotation log, sweep counts).
