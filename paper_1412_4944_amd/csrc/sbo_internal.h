@@ -35,13 +35,11 @@ inline GroupGeom group_geom(int64_t m) {
 // workgroup reduces one piece into a partial p x p matrix.
 constexpr int kNumCU = 256;
 inline int accum_piece(int64_t m, int K, int p) {
-    // p <= 64: two workgroups fit a CU, and all pieces should be resident in one round
-    // (pieces <= 2 * CUs where K allows)
-    const int slots = 2 * kNumCU;
-    const int target = K < slots / 2 ? slots - K : slots / 2;
-    // p = 256: one workgroup per CU (512 registers per lane), so all pieces fit one round
-    const int target_wide = K < kNumCU / 2 ? kNumCU - K : kNumCU / 2;
-    int64_t c = p <= 64 ? (m + target - 1) / target : (m + target_wide - 1) / target_wide;
+    // One workgroup per CU for every p (8 wavefronts with 150 KiB of LDS for p <= 64, 512
+    // registers per lane for p = 256), and all pieces resident in one round: pieces <= CUs where
+    // K allows.
+    const int target = K < kNumCU / 2 ? kNumCU - K : kNumCU / 2;
+    int64_t c = (m + target - 1) / target;
     c = ((c + 63) / 64) * 64;
     if (c < (p <= 64 ? 64 : 256)) c = p <= 64 ? 64 : 256;
     if (c > 4096) c = 4096;

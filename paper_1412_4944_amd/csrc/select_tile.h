@@ -18,14 +18,25 @@ namespace sbo {
 // because scattered 4-byte stores to rows in original signal order are what this step
 // would otherwise wait on.
 // KEEP_X: on return ct[n][atom] holds the sparse code x of every signal of the tile
-// (kept coefficients, zeros elsewhere).
+// (kept coefficients, zeros elsewhere).  Without KEEP_X ct is touched only on the tie path
+// (*used_ct is then set).  On return the compacted rows are still in `stage`: entry pos of
+// signal n at stage_idx(n, 0, pos) (atom) and stage_idx(n, 1, pos) (coefficient bits).
 constexpr int kSelectStageWords = 32 * 2 * 16;
+
+// Word index of entry `pos` (< 16) of signal row n in the stage area; kind 0 = atom, 1 =
+// coefficient bits.  A row is 32 words = 8 groups of 4 (groups 0-3 atoms, 4-7 coefficients);
+// the group index is XORed with the row number so that lanes writing the same entry of
+// different rows do not all land in one LDS bank (a plain [n][32] layout would put them there),
+// while the four words of a group stay together for the 16-byte copy out.
+__device__ __forceinline__ int stage_idx(int n, int kind, int pos) {
+    return n * 32 + ((((kind << 2) | (pos >> 2)) ^ (n & 7)) << 2) + (pos & 3);
+}
 
 template <int P, int S, bool KEEP_X>
 __device__ __forceinline__ void tile_select(const f32x16* acc, int h, int n, bool active, int64_t i,
                                             int s0, float* ct, int* stage,
                                             int32_t* __restrict__ supp, float* __restrict__ coef,
-                                            float* __restrict__ err) {
+                                            float* __restrict__ err, bool* used_ct = nullptr) {
     constexpr int MT = P >= 32 ? P / 32 : 1;
     constexpr int NVL = MT * 16;
     constexpr int LDC = P + 1;
@@ -78,8 +89,8 @@ __device__ __forceinline__ void tile_select(const f32x16* acc, int h, int n, boo
                 const int atom = (f >> 4) * 32 + ((f & 15) >> 2) * 8 + h * 4 + (f & 3);
                 if (mag[f] >= tau) {
                     if (active) {             // (a lane without a signal keeps "everything")
-                        stage[n * 32 + pos] = atom;
-                        stage[n * 32 + 16 + pos] = __builtin_bit_cast(int, c[f]);
+                        stage[stage_idx(n, 0, pos)] = atom;
+                        stage[stage_idx(n, 1, pos)] = __builtin_bit_cast(int, c[f]);
                     }
                     ++pos;
                 } else if (atom < P) {
@@ -93,6 +104,7 @@ __device__ __forceinline__ void tile_select(const f32x16* acc, int h, int n, boo
         if (active && h == 0) err[i] = dropped;
     } else {
         // Exact magnitude ties: walk each signal's coefficients in atom order.
+        if (used_ct != nullptr) *used_ct = true;
 #pragma unroll
         for (int f = 0; f < NVL; ++f) {
             const int atom = (f >> 4) * 32 + ((f & 15) >> 2) * 8 + h * 4 + (f & 3);
@@ -118,8 +130,8 @@ __device__ __forceinline__ void tile_select(const f32x16* acc, int h, int n, boo
                     ++taken_eq;
                 }
                 if (take && pos < s0) {
-                    stage[n * 32 + pos] = k;
-                    stage[n * 32 + 16 + pos] = __builtin_bit_cast(int, v);
+                    stage[stage_idx(n, 0, pos)] = k;
+                    stage[stage_idx(n, 1, pos)] = __builtin_bit_cast(int, v);
                     ++pos;
                 } else {
                     dropped += v * v;
@@ -135,18 +147,17 @@ __device__ __forceinline__ void tile_select(const f32x16* acc, int h, int n, boo
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     if (active) {
-        const int* src = stage + n * 32 + h * 16;
         int* dst = (h ? reinterpret_cast<int*>(coef) : supp) + i * s0;
         typedef int i32x4 __attribute__((ext_vector_type(4)));
         typedef int i32x2 __attribute__((ext_vector_type(2)));
         if ((s0 & 3) == 0) {
             for (int t = 0; t < s0; t += 4)
-                *reinterpret_cast<i32x4*>(dst + t) = *reinterpret_cast<const i32x4*>(src + t);
+                *reinterpret_cast<i32x4*>(dst + t) = *reinterpret_cast<const i32x4*>(stage + stage_idx(n, h, t));
         } else if ((s0 & 1) == 0) {
             for (int t = 0; t < s0; t += 2)
-                *reinterpret_cast<i32x2*>(dst + t) = *reinterpret_cast<const i32x2*>(src + t);
+                *reinterpret_cast<i32x2*>(dst + t) = *reinterpret_cast<const i32x2*>(stage + stage_idx(n, h, t));
         } else {
-            for (int t = 0; t < s0; ++t) dst[t] = src[t];
+            for (int t = 0; t < s0; ++t) dst[t] = stage[stage_idx(n, h, t)];
         }
     }
     __builtin_amdgcn_wave_barrier();           // stage is reused by the caller's next tile
