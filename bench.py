@@ -5,9 +5,10 @@ block accumulation + SVD update) on one MI355X, through the C-ABI of libsbo.
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload headline]
 
 A step is one full iteration over the whole synthetic signal set, inputs resident in
-HBM.  Prints ONE JSON line: whole-job signals/s, the roofline entry of the dominant
-kernel (the fused MFMA energy/argmax kernel, timed with HIP events on its own stream
-by the library), per-stage times, and the CPU oracle timed on a bounded sample.
+HBM.  Prints ONE JSON line: whole-job signals/s on the headline workload, the roofline
+entry of the dominant kernel (the fused projection / top-s0 energy / block argmax kernel,
+timed with HIP events on its own stream by the library), per-stage times, the other four
+configurations (`configs`), and the CPU oracle timed on a bounded sample.
 """
 from __future__ import annotations
 
@@ -22,12 +23,18 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_MFMA_F32_TFLOPS = 157.3
+PEAK_MFMA_BF16_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
+# An fp32-accurate product on the bf16 matrix cores = six bf16 partial products (operands as
+# exact sums of three bf16): the matrix roof for algorithmic fp32 flops computed that way.
+SPLIT_PRODUCTS = 6
 
-ROOFLINE_KERNEL = "energy_kernel"
+
+def roofline_kernel_name(p: int, arith: str) -> str:
+    return "energy_split_kernel" if arith == "bf16x3" else "energy_kernel"
 
 
-def measured_traffic_bytes(workload: str):
+def measured_traffic_bytes(workload: str, kernel: str):
     """HBM bytes per launch of the roofline kernel from the tracked rocprofv3 --pmc summary
     profiles/<workload>_hbm_traffic_pmc.txt (its line `roofline_kernel_hbm_bytes_per_launch:
     <bytes> kernel=<name>`); None when there is no summary for this workload or it is for
@@ -38,7 +45,7 @@ def measured_traffic_bytes(workload: str):
             for line in f:
                 if line.startswith("roofline_kernel_hbm_bytes_per_launch:"):
                     parts = line.split()
-                    if f"kernel={ROOFLINE_KERNEL}" in parts:
+                    if f"kernel={kernel}" in parts:
                         return float(parts[1])
     except OSError:
         pass
@@ -52,33 +59,33 @@ class Probes:
         import ctypes
         path = os.path.join(ROOT, "paper_1412_4944_amd", "lib", "libsbo_benchprobe.so")
         self.L = ctypes.CDLL(path)
-        self.L.bench_probe_mfma.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
-        self.L.bench_probe_copy.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_double)]
+        dp = ctypes.POINTER(ctypes.c_double)
+        self.L.bench_probe_mfma.argtypes = [ctypes.c_void_p, ctypes.c_int, dp]
+        self.L.bench_probe_mfma_bf16.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, dp]
+        self.L.bench_probe_copy.argtypes = [ctypes.c_void_p, dp]
         self.ct = ctypes
 
-    def _stream(self):
+    def _call(self, fn, *args):
         import torch
-        return self.ct.c_void_p(torch.cuda.current_stream().cuda_stream)
+        v = self.ct.c_double(0.0)
+        rc = fn(self.ct.c_void_p(torch.cuda.current_stream().cuda_stream), *args, self.ct.byref(v))
+        if rc != 0:
+            raise RuntimeError(f"bench probe: HIP error {rc}")
+        return v.value
 
     def mfma(self, iters):
-        v = self.ct.c_double(0.0)
-        rc = self.L.bench_probe_mfma(self._stream(), int(iters), self.ct.byref(v))
-        if rc != 0:
-            raise RuntimeError(f"bench_probe_mfma: HIP error {rc}")
-        return v.value
+        return self._call(self.L.bench_probe_mfma, int(iters))
+
+    def mfma_bf16(self, iters, random_operands):
+        return self._call(self.L.bench_probe_mfma_bf16, int(iters), 1 if random_operands else 0)
 
     def copy(self):
-        v = self.ct.c_double(0.0)
-        rc = self.L.bench_probe_copy(self._stream(), self.ct.byref(v))
-        if rc != 0:
-            raise RuntimeError(f"bench_probe_copy: HIP error {rc}")
-        return v.value
+        return self._call(self.L.bench_probe_copy)
 
 
 def cpu_baseline(pr, sample_m: int) -> dict:
     """The fp64 oracle as it stands, one iteration (coding + update) on the first
     sample_m signals of the same workload, on the host cores."""
-    import numpy as np
     from oracle import sbo_oracle as orc
     try:
         from threadpoolctl import threadpool_info
@@ -99,6 +106,69 @@ def cpu_baseline(pr, sample_m: int) -> dict:
             "seconds": t2 - t0}
 
 
+def roofline_entry(p, K, m, energy_ms, arith, workload):
+    """The energy kernel against the matrix roof of the instruction it runs on."""
+    flops = 2.0 * K * p * p * m                 # algorithmic: projection onto all K orthobases
+    achieved = flops / (energy_ms * 1e-3) / 1e12
+    kernel = roofline_kernel_name(p, arith)
+    if kernel == "energy_split_kernel":
+        peak = PEAK_MFMA_BF16_TFLOPS / SPLIT_PRODUCTS
+        extra = {"kernel": "energy_split_kernel (fused Q^T y on the bf16 matrix cores, fp32 operands as exact "
+                           "sums of three bf16, six partial products + top-s0 energy + block argmax)",
+                 "peak_note": "2500 TFLOP/s dense bf16 MFMA / 6 partial products per fp32-accurate product",
+                 "executed_bf16_tflops": achieved * SPLIT_PRODUCTS, "peak_bf16_tflops": PEAK_MFMA_BF16_TFLOPS,
+                 "vs_fp32_mfma_peak": achieved / PEAK_MFMA_F32_TFLOPS}
+    else:
+        peak = PEAK_MFMA_F32_TFLOPS
+        extra = {"kernel": "energy_kernel (fused Q^T y on the fp32 matrix instruction + top-s0 energy + block argmax)"}
+    return {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+            "traffic": measured_traffic_bytes(workload, kernel), **extra}
+
+
+def run_config(sbo, synth, torch, name, steps, warmup, arith):
+    """One of the other configurations: ms per iteration, stage times, the energy kernel
+    against its roof, the update stages against HBM."""
+    cfg = synth.CONFIGS[name]
+    pr = synth.generate(cfg)
+    p, K, s0, m = cfg.p, cfg.K, cfg.s0, pr.Y.shape[0]
+    dev = torch.device("cuda:0")
+    Y = torch.from_numpy(pr.Y).to(dev)
+    D = torch.from_numpy(pr.D_init).to(dev)
+    blk = torch.empty(m, dtype=torch.int32, device=dev)
+    supp = torch.empty((m, s0), dtype=torch.int32, device=dev)
+    coef = torch.empty((m, s0), dtype=torch.float32, device=dev)
+    err = torch.empty(m, dtype=torch.float32, device=dev)
+    sq = torch.zeros(max(steps, warmup, 1), dtype=torch.float64, device=dev)
+    ctx = sbo.sbo_create(p, K, s0, m)
+    sbo.sbo_set_option(ctx, sbo.SBO_OPT_CODING_ARITH,
+                       sbo.SBO_ARITH_BF16X3 if arith == "bf16x3" else sbo.SBO_ARITH_F32)
+    sbo.sbo_set_timing(ctx, 2)
+    sbo.sbo_iterate(ctx, Y, D, warmup, blk, supp, coef, err, sq)
+    torch.cuda.synchronize()
+    D0 = D.clone()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    sbo.sbo_iterate(ctx, Y, D, steps, blk, supp, coef, err, sq)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    energy_ms = sbo.sbo_stage_ms(ctx)["energy"] / steps
+    sbo.sbo_set_timing(ctx, 1)
+    sbo.sbo_iterate(ctx, Y, D0, steps, blk, supp, coef, err, sq)
+    torch.cuda.synchronize()
+    st = {k: v / steps for k, v in sbo.sbo_stage_ms(ctx).items()}
+    sbo.sbo_destroy(ctx)
+    ms = 1e3 * (t1 - t0) / steps
+    upd_bytes = m * (4 + 4 + 4 + 4 * p + 8 * s0 + 4) + 4 * K * p * p
+    t_upd = (st["group"] + st["select"] + st["accum"]) * 1e-3
+    rf = roofline_entry(p, K, m, energy_ms, arith, name)
+    return {"workload": f"{name}: p={p} K={K} m={m} s0={s0}", "steps": steps, "warmup": warmup,
+            "ms_per_step": ms, "signals_per_s": m / (ms * 1e-3), "stage_ms": st,
+            "energy_ms_timed_region": energy_ms, "energy_kernel": rf["kernel"].split(" ")[0],
+            "energy_tflops": rf["achieved"], "energy_frac": rf["frac"], "energy_peak_tflops": rf["peak"],
+            "update_GBps": upd_bytes / t_upd / 1e9, "update_frac_hbm": upd_bytes / t_upd / 1e9 / PEAK_HBM_GBS,
+            "svd_ms": st["svd"]}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -111,11 +181,13 @@ def main() -> int:
     ap.add_argument("--cpu-sample", type=int, default=262144)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-probe", action="store_true",
-                    help="skip the fp32 MFMA loop / device copy probes (achievable peaks)")
+                    help="skip the bare MFMA loop / device copy probes (achievable peaks)")
     ap.add_argument("--no-learn", action="store_true",
                     help="skip the timing of Algorithm 2 as a whole in the shape of the paper's Table 2")
     ap.add_argument("--no-next", action="store_true",
                     help="skip the (untimed-region) measurement of worst-W / base initialisation / new base")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the four other configurations (tiny, patch8, patch16, skew)")
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run one plain 256 MiB device copy (a dispatch of known HBM traffic, used "
                          "to scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -153,21 +225,23 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    # Achievable peaks on this GPU (bare fp32 MFMA loop, plain device copy), measured first;
+    # Achievable peaks on this GPU (bare MFMA loops, plain device copy), measured first;
     # they also bring the clocks up.
     measured = None
     if not args.no_probe:
         pb = Probes()
-        measured = {"mfma_f32_tflops": pb.mfma(150),            # launches of ~0.6 ms, like the kernel's
+        measured = {"mfma_f32_tflops": pb.mfma(150),             # launches of ~0.6 ms
                     "mfma_f32_tflops_sustained": pb.mfma(4000),  # ~17 ms launches: power-limited
+                    "mfma_bf16_tflops_constant_operands": pb.mfma_bf16(600, False),
+                    "mfma_bf16_tflops_random_operands": pb.mfma_bf16(600, True),
                     "hbm_copy_GBps": pb.copy()}
 
     ctx = sbo.sbo_create(p, K, s0, m)
     sbo.sbo_set_option(ctx, sbo.SBO_OPT_CODING_ARITH,
                        sbo.SBO_ARITH_BF16X3 if args.arith == "bf16x3" else sbo.SBO_ARITH_F32)
     # Timed region: HIP events around the roofline kernel only (an event pair per stage costs
-    # several microseconds on the stream, 4 % of a step here); the full per-stage breakdown comes
-    # from a second, untimed pass over the same number of iterations.
+    # several microseconds on the stream); the full per-stage breakdown comes from a second,
+    # untimed pass over the same number of iterations.
     sbo.sbo_set_timing(ctx, 2)
     for _ in range(args.warmup):
         sbo.sbo_iterate(ctx, Y, D, 1, blk, supp, coef, err, sq)
@@ -189,18 +263,40 @@ def main() -> int:
     sbo.sbo_iterate(ctx, Y, D_start, args.steps, blk, supp, coef, err, sq)
     torch.cuda.synchronize()
     stage_sum = sbo.sbo_stage_ms(ctx)           # summed over the K iterations
-    sweeps_warm = sbo.sbo_svd_sweeps(ctx, K)    # last iteration of the pass (warm-started Jacobi)
+    sweeps_iter = sbo.sbo_svd_sweeps(ctx, K)    # last iteration of the pass
 
     # a-2 and a-3 on their own (sbo_update: grouping of a given blk, accumulation from given
-    # codes, cold SVD), from the codes of the last pass; outside the timed region.
+    # codes, SVD), from the codes of the last pass; outside the timed region.
     D_upd = D.clone()
     sbo.sbo_update(ctx, Y, blk, supp, coef, D_upd)
     D_upd.copy_(D)
     sbo.sbo_update(ctx, Y, blk, supp, coef, D_upd)
     torch.cuda.synchronize()
     upd = sbo.sbo_stage_ms(ctx)
-    sweeps_cold = sbo.sbo_svd_sweeps(ctx, K)
+    sweeps_upd = sbo.sbo_svd_sweeps(ctx, K)
     del D_upd
+
+    # The same coding pass on the fp32 matrix instruction (the alternative arithmetic), for
+    # comparison: its energy kernel against the fp32 MFMA peak.  Outside the timed region.
+    other = None
+    if True:
+        alt = "f32" if args.arith == "bf16x3" else "bf16x3"
+        sbo.sbo_set_option(ctx, sbo.SBO_OPT_CODING_ARITH,
+                           sbo.SBO_ARITH_F32 if alt == "f32" else sbo.SBO_ARITH_BF16X3)
+        sbo.sbo_set_timing(ctx, 2)
+        b2, s2, c2, e2 = blk.clone(), supp.clone(), coef.clone(), err.clone()
+        sbo.sbo_code(ctx, Y, D, b2, s2, c2, e2)
+        sbo.sbo_code(ctx, Y, D, b2, s2, c2, e2)
+        best = float("inf")
+        for _ in range(5):
+            sbo.sbo_code(ctx, Y, D, b2, s2, c2, e2)
+            best = min(best, sbo.sbo_stage_ms(ctx)["energy"])
+        rf = roofline_entry(p, K, m, best, alt, cfg.name)
+        other = {"arith": alt, "energy_ms": best, "achieved_tflops": rf["achieved"], "peak_tflops": rf["peak"],
+                 "frac": rf["frac"], "kernel": rf["kernel"].split(" ")[0]}
+        del b2, s2, c2, e2
+        sbo.sbo_set_option(ctx, sbo.SBO_OPT_CODING_ARITH,
+                           sbo.SBO_ARITH_BF16X3 if args.arith == "bf16x3" else sbo.SBO_ARITH_F32)
 
     # Representation only (sbo_code with a fixed dictionary: the paper's t_rep operation).
     sbo.sbo_set_timing(ctx, 0)
@@ -287,18 +383,26 @@ def main() -> int:
             learn["K"].append(Kf)
             learn["seconds"].append(best)
             learn["rmse"].append(hist[-1])
+        del Yl, lb, ls, lc, le
+
+    # The other four configurations (a few steps each).
+    configs = None
+    if not args.no_configs:
+        del Y, D, blk, supp, coef, err
+        torch.cuda.empty_cache()
+        configs = []
+        for name, steps, warm in (("tiny", 50, 20), ("patch8", 50, 20), ("patch16", 10, 5), ("skew", 5, 3)):
+            if name != cfg.name:
+                configs.append(run_config(sbo, synth, torch, name, steps, warm, args.arith))
 
     total_s = t1 - t0
     ms_per_step = 1e3 * total_s / args.steps
     stage_ms = {k: v / args.steps for k, v in stage_sum.items()}
 
-    flops = 2.0 * K * p * p * m                 # projection onto all K orthobases
-    t_energy = energy_ms * 1e-3                 # from the timed region
-    achieved = flops / t_energy / 1e12
     # Everything after the energy/argmax kernel that is bound by memory rather than by the
     # matrix pipe: grouping, support selection (fused with the per-piece accumulation for
-    # p <= 64) and the sum over pieces.  Algorithmic bytes: blk in, perm out and in, Y once,
-    # supp/coef/err out, P_j out.
+    # p <= 64) and the sum over pieces (folded into the SVD launch on the default path).
+    # Algorithmic bytes: blk in, perm out and in, Y once, supp/coef/err out, P_j out.
     upd_bytes = m * (4 + 4 + 4 + 4 * p + 8 * s0 + 4) + 4 * K * p * p
     t_upd = (stage_ms["group"] + stage_ms["select"] + stage_ms["accum"]) * 1e-3
 
@@ -317,38 +421,44 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: p={p} K={K} m={m} s0={s0}, planted ONBs, "
                                f"{cfg.snr_db} dB SNR, random ONB init",
-                   "p": p, "K": K, "m": m, "s0": s0},
-        "roofline": {"kernel": "energy_kernel (fused Q^T y MFMA + top-s0 energy + block argmax)",
-                     "bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_F32_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_MFMA_F32_TFLOPS,
-                     "traffic": measured_traffic_bytes(cfg.name)},
+                   "p": p, "K": K, "m": m, "s0": s0, "coding_arith": args.arith},
+        "roofline": roofline_entry(p, K, m, energy_ms, args.arith, cfg.name),
         "energy_ms_timed_region": energy_ms,
         "stage_ms": stage_ms,
+        "launch_gaps_ms": ms_per_step - sum(stage_ms.values()),
         "update_hbm": {"stages": "group + select (fused with accumulate for p<=64) + accum",
                        "algorithmic_bytes": upd_bytes,
                        "achieved_GBps": upd_bytes / t_upd / 1e9, "peak_GBps": PEAK_HBM_GBS,
                        "frac": upd_bytes / t_upd / 1e9 / PEAK_HBM_GBS},
-        "update_standalone": {"what": "sbo_update: a-2 grouping + a-3 accumulation (+ cold SVD) from given codes",
-                              "group_ms": upd["group"], "accum_ms": upd["accum"], "svd_cold_ms": upd["svd"],
+        "update_standalone": {"what": "sbo_update: a-2 grouping + a-3 accumulation (+ SVD) from given codes",
+                              "group_ms": upd["group"], "accum_ms": upd["accum"], "svd_ms": upd["svd"],
                               "algorithmic_bytes": m * (4 * p + 8 * s0 + 8) + 4 * K * p * p,
                               "a2_a3_GBps": (m * (4 * p + 8 * s0 + 8) + 4 * K * p * p) /
                                             ((upd["group"] + upd["accum"]) * 1e-3) / 1e9,
                               "a3_GBps": (m * (4 * p + 8 * s0 + 8) + 4 * K * p * p) / (upd["accum"] * 1e-3) / 1e9},
         "code_only_ms": code_ms,
         "svd_work": {"note": "per block: Jacobi sweeps (> 0) or minus the Newton-Schulz steps (< 0)",
-                     "iterate_last_mean": sum(sweeps_warm) / K, "iterate_last_min": min(sweeps_warm),
-                     "iterate_last_max": max(sweeps_warm), "update_mean": sum(sweeps_cold) / K,
-                     "update_min": min(sweeps_cold), "update_max": max(sweeps_cold)},
+                     "iterate_last_mean": sum(sweeps_iter) / K, "iterate_last_min": min(sweeps_iter),
+                     "iterate_last_max": max(sweeps_iter), "update_mean": sum(sweeps_upd) / K,
+                     "update_min": min(sweeps_upd), "update_max": max(sweeps_upd)},
         "rmse_first_last": [float(np.sqrt(first_sq / (p * m))), float(np.sqrt(last_sq / (p * m)))],
     }
+    if other is not None:
+        out["other_coding_arith"] = other
     if measured is not None:
         out["measured_peaks"] = measured
-        out["roofline"]["frac_of_measured_peak"] = achieved / measured["mfma_f32_tflops"]
         out["update_hbm"]["frac_of_measured_copy"] = out["update_hbm"]["achieved_GBps"] / measured["hbm_copy_GBps"]
+        if out["roofline"]["kernel"].startswith("energy_split"):
+            out["roofline"]["frac_of_measured_random_operand_rate"] = \
+                out["roofline"]["executed_bf16_tflops"] / measured["mfma_bf16_tflops_random_operands"]
+        else:
+            out["roofline"]["frac_of_measured_peak"] = out["roofline"]["achieved"] / measured["mfma_f32_tflops"]
     if next_rows is not None:
         out["next_rows"] = next_rows
     if learn is not None:
         out["learn_table2_shape"] = learn
+    if configs is not None:
+        out["configs"] = configs
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(pr, min(args.cpu_sample, m))
     print(json.dumps(out))

@@ -221,11 +221,11 @@ enum {
 
 enum {
     SBO_ARITH_F32    = 0,  /* the fp32 matrix instruction (v_mfma_f32_32x32x2_f32) */
-    SBO_ARITH_BF16X3 = 1   /* default.  p <= 64: every fp32 operand entry written as the exact sum of
+    SBO_ARITH_BF16X3 = 1   /* default: every fp32 operand entry written as the exact sum of
                               three bf16 numbers; the six partial products that matter at fp32 accuracy
                               run on the bf16 matrix cores with fp32 accumulation (same fp32 inputs and
                               outputs, rounding at the fp32 level: the dropped partial products are below
-                              2^-24 of |a||b|).  p = 256 uses the fp32 instruction either way. */
+                              2^-24 of |a||b|). */
 };
 
 /* Set an option for every later call on this context (Algorithm 1 steps 6-7 leave the SVD

@@ -7,6 +7,11 @@
 //       rate of a bare v_mfma_f32_32x32x2_f32 loop (TFLOP/s; 1024 workgroups of 4 wavefronts,
 //       each issuing 32 * iters MFMAs: iters = 150 is a launch of about 0.6 ms, iters = 4000
 //       one of about 17 ms, long enough for the power limit to show)
+//   int bench_probe_mfma_bf16(void* hip_stream, int iters, int random_operands, double* tflops)
+//       rate of a bare v_mfma_f32_32x32x16_bf16 loop (the same launch shape); with
+//       random_operands != 0 every lane's operands are random bit patterns of moderate
+//       magnitude instead of two constants: the matrix cores then draw far more power and the
+//       sustained rate drops, which is the rate a kernel working on real data can reach
 //   int bench_probe_copy(void* hip_stream, double* gbps)
 //       rate of a plain 256 MiB device copy (GB/s, bytes read + bytes written)
 // Both allocate and free their own scratch and synchronise the stream; tflops / gbps are host
@@ -33,6 +38,46 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(float* __restrict__ out
 #pragma unroll
             for (int i = 0; i < 4; ++i)
                 acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[i], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[i][r];
+    out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+// the same loop on the bf16 matrix cores; eight operand pairs per lane, constant or random
+__global__ __launch_bounds__(256) void probe_mfma_bf16_kernel(float* __restrict__ out, int iters, int random_operands) {
+    f32x16 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    u32x4 a[8], b[8];
+    unsigned x = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            x = x * 1664525u + 1013904223u;
+            const unsigned ra = random_operands ? x : 0u;
+            x = x * 1664525u + 1013904223u;
+            const unsigned rb = random_operands ? x : 0u;
+            // two bf16 per word, sign and mantissa free, exponent kept near 1 (0x3c00..0x3fff)
+            a[u][c] = (ra & 0x83ff83ffu) | 0x3c003c00u;
+            b[u][c] = (rb & 0x83ff83ffu) | 0x3c003c00u;
+        }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[u]),
+                                                                 __builtin_bit_cast(bf16x8, b[(u + i) & 7]), acc[i], 0, 0, 0);
     }
     float s = 0.f;
 #pragma unroll
@@ -87,6 +132,32 @@ hipError_t probe_mfma(hipStream_t st, int iters, double* tflops) {
     return e;
 }
 
+hipError_t probe_mfma_bf16(hipStream_t st, int iters, int random_operands, double* tflops) {
+    constexpr int kWgs = 1024;
+    float* out = nullptr;
+    hipError_t e = hipMalloc(&out, (size_t)kWgs * 256 * sizeof(float));
+    if (e != hipSuccess) return e;
+    EventPair ev;
+    e = ev.init();
+    float best = 0.f;
+    for (int rep = 0; rep < 3 && e == hipSuccess; ++rep) {
+        hipLaunchKernelGGL(probe_mfma_bf16_kernel, dim3(kWgs), dim3(256), 0, st, out, rep == 0 ? 200 : iters,
+                           random_operands);
+        if (rep == 0) continue;                 // warm-up
+        (void)hipEventRecord(ev.a, st);
+        hipLaunchKernelGGL(probe_mfma_bf16_kernel, dim3(kWgs), dim3(256), 0, st, out, iters, random_operands);
+        (void)hipEventRecord(ev.b, st);
+        e = hipEventSynchronize(ev.b);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev.a, ev.b);
+        const float rate = (float)((double)kWgs * 4 * iters * 8 * 4 * 32768.0 / (ms * 1e-3) / 1e12);
+        if (rate > best) best = rate;
+    }
+    (void)hipFree(out);
+    *tflops = best;
+    return e;
+}
+
 hipError_t probe_copy(hipStream_t st, double* gbps) {
     const int64_t n = (int64_t)16 * 1024 * 1024;               // 16-byte units: 256 MiB each way
     f32x4 *src = nullptr, *dst = nullptr;
@@ -117,6 +188,11 @@ hipError_t probe_copy(hipStream_t st, double* gbps) {
 extern "C" int bench_probe_mfma(void* hip_stream, int iters, double* tflops) {
     if (!tflops || iters < 1 || iters > 100000) return (int)hipErrorInvalidValue;
     return (int)probe_mfma((hipStream_t)hip_stream, iters, tflops);
+}
+
+extern "C" int bench_probe_mfma_bf16(void* hip_stream, int iters, int random_operands, double* tflops) {
+    if (!tflops || iters < 1 || iters > 100000) return (int)hipErrorInvalidValue;
+    return (int)probe_mfma_bf16((hipStream_t)hip_stream, iters, random_operands, tflops);
 }
 
 extern "C" int bench_probe_copy(void* hip_stream, double* gbps) {

@@ -362,42 +362,58 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
     }
 }
 
-// The same kernel with the projection on the bf16 matrix cores (p <= 64): every fp32 operand
-// entry is the exact sum of three bf16 parts (device_utils.h), and the six partial products
-// that matter at fp32 accuracy are accumulated in fp32 by v_mfma_f32_32x32x16_bf16.  Per
-// 32 x 32 x 16 step that is six matrix instructions of 8 passes each where the fp32 instruction
-// needs 8 x 16 passes for the same 16 dims, and, unlike the fp32 matrix instruction, they run
-// beside the vector ALU.  To use that, a workgroup is two teams of four wavefronts, one
-// wavefront of each team per SIMD, half a stage apart: while team 0 multiplies stage s, team 1
-// runs the selection networks on its stage s - 1 results, then the roles swap; both read the
-// same LDS stage, and the one barrier per stage keeps them in this order.  The signals' three
-// parts stay in registers for the whole kernel (B operand, 8 bf16 per lane and step); the
-// dictionary arrives pre-split (Dsb) and is staged through LDS as in the fp32 kernel (24 KiB
-// per 64-row stage at p = 64).
-constexpr int kSplitWaves = 8;
+// The same kernel with the projection on the bf16 matrix cores: every fp32 operand entry is
+// the exact sum of three bf16 parts (device_utils.h), and the six partial products that matter
+// at fp32 accuracy are accumulated in fp32 by v_mfma_f32_32x32x16_bf16.  Per 32 x 32 x 16 step
+// that is six matrix instructions of 8 passes each where the fp32 instruction needs 8 x 16
+// passes for the same 16 dims, and, unlike the fp32 matrix instruction, they run beside the
+// vector ALU.  The signals' three parts stay in registers for the whole kernel (B operand, 8
+// bf16 per lane and step); the dictionary arrives pre-split (Dsb) and is staged through LDS,
+// double-buffered, one barrier per stage.
+//   p <= 64: a stage is 64 dictionary rows (24 KiB at p = 64), a wavefront owns 64 signals, and a
+//            workgroup is two teams of four wavefronts, one wavefront of each team per SIMD, half
+//            a stage apart: while team 0 multiplies stage s, team 1 runs the selection networks
+//            on its stage s - 1 results, then the roles swap; both read the same LDS stage.
+//   p = 256: the split signals alone take 192 registers per lane for 32 signals, so a
+//            wavefront owns 32 signals, has its SIMD to itself (4 wavefronts per workgroup, no
+//            teams), and a stage is 32 rows (48 KiB); a block spans 8 stages, across which the
+//            lane keeps a running sorted top-S (as the fp32 kernel does).
+template <int P>
+struct SplitGeom {
+    static constexpr int MTS = P <= 64 ? 2 : 1;          // 32-row tiles per stage
+    static constexpr int NT = P <= 64 ? 2 : 1;           // 32-signal tile columns per wavefront
+    static constexpr int WAVES = P <= 64 ? 8 : 4;
+    static constexpr bool TEAMS = P <= 64;
+    static constexpr int KS16 = P / 16;                  // contraction steps of 16 dims
+    static constexpr int STAGE_ROWS = 32 * MTS;
+    static constexpr int STAGE_U = MTS * KS16 * 3 * 64;  // 16-byte units per stage
+    static constexpr size_t LDS = (size_t)2 * STAGE_U * 16;
+};
 
-template <int P, int S, int NT, int SX>
-__global__ __launch_bounds__(64 * kSplitWaves) void energy_split_kernel(
+template <int P, int S, int SX>
+__global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
     const float* __restrict__ Y, int m, const u32x4* __restrict__ Dsb, int K, int s0,
     int32_t* __restrict__ blk, float* __restrict__ energy, int32_t* __restrict__ chunk_count, int chunk,
     int units_per_y) {
-    constexpr int NTH = 64 * kSplitWaves;
-    constexpr int KS16 = P / 16;         // contraction steps of 16 dims (a lane half covers 8 of them)
-    constexpr int NB = 64 / P;           // blocks per 64-row stage
-    constexpr int NV = P / 2;            // coefficients per lane per block
-    constexpr int STAGE_U = 2 * KS16 * 3 * 64;
-    constexpr int FPT = (STAGE_U + NTH - 1) / NTH;   // 16-byte units each thread moves per stage
+    using G = SplitGeom<P>;
+    constexpr int MTS = G::MTS, NT = G::NT, KS16 = G::KS16, STAGE_U = G::STAGE_U;
+    constexpr int NTH = 64 * G::WAVES;
+    constexpr int NB = P <= 64 ? 64 / P : 1;   // blocks per stage (p <= 64)
+    constexpr int SPB = P <= 64 ? 1 : P / G::STAGE_ROWS;   // stages per block (p > 64)
+    constexpr int NV = P <= 64 ? P / 2 : 16 * MTS;         // coefficients per lane per block and stage
+    constexpr int FPT = (STAGE_U + NTH - 1) / NTH;         // 16-byte units each thread moves per stage
     constexpr bool kWhole = STAGE_U % NTH == 0;
-    static_assert(P == 16 || P == 32 || P == 64, "the split kernel covers p <= 64");
+    static_assert(P == 16 || P == 32 || P == 64 || P == 256, "unsupported p");
+    static_assert(P <= 64 || S <= NV, "sort width");
 
     extern __shared__ u32x4 Qb_raw[];    // [2][STAGE_U]
     u32x4(*Qs)[STAGE_U] = reinterpret_cast<u32x4(*)[STAGE_U]>(Qb_raw);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int team = wave >> 2;          // wavefronts w and w + 4 share a SIMD
+    const int team = G::TEAMS ? wave >> 2 : 0;           // wavefronts w and w + 4 share a SIMD
     const int h = lane >> 5, n = lane & 31;
-    const int64_t sig0 = ((int64_t)blockIdx.x * kSplitWaves + wave) * (32 * NT);
+    const int64_t sig0 = ((int64_t)blockIdx.x * G::WAVES + wave) * (32 * NT);
 
     // B operand: the three bf16 parts of this lane's dims (ks*16 + h*8 .. +7) of NT signals.
     u32x4 yq[NT][KS16][3];
@@ -420,12 +436,13 @@ __global__ __launch_bounds__(64 * kSplitWaves) void energy_split_kernel(
         }
     }
 
-    // Small m: the stages are split over blockIdx.y exactly as in energy_kernel.
-    const int n_stage = (K * P + 63) / 64;
+    // Small m: the stages (p <= 64) or blocks (p = 256) are split over blockIdx.y exactly as in
+    // energy_kernel.
+    const int n_stage = (K * P + G::STAGE_ROWS - 1) / G::STAGE_ROWS;
     int s_beg = 0, s_end = n_stage;
     if (units_per_y > 0) {
-        s_beg = min(n_stage, (int)blockIdx.y * units_per_y);
-        s_end = min(n_stage, s_beg + units_per_y);
+        s_beg = min(n_stage, (int)blockIdx.y * units_per_y * SPB);
+        s_end = min(n_stage, s_beg + units_per_y * SPB);
         blk += (int64_t)blockIdx.y * m;
         energy += (int64_t)blockIdx.y * m;
     }
@@ -444,10 +461,13 @@ __global__ __launch_bounds__(64 * kSplitWaves) void energy_split_kernel(
 
     int best[NT];
     float bestE[NT];
+    float run[NT][S];                    // p > 64: lane's top-S magnitudes of the current block
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         best[nt] = 0;
         bestE[nt] = -1.f;
+#pragma unroll
+        for (int i = 0; i < S; ++i) run[nt][i] = 0.f;
     }
 
     // the six partial products, smallest first: (A part, B part)
@@ -455,22 +475,22 @@ __global__ __launch_bounds__(64 * kSplitWaves) void energy_split_kernel(
     constexpr int TB[6] = {0, 2, 1, 0, 1, 0};
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
                          0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    f32x16 acc[NT][2];
+    f32x16 acc[NT][MTS];
 
-    // Projection of the wavefront's signals onto the 64 rows staged in buffer buf:
-    // NT x 2 x KS16 x 6 matrix instructions into acc.
+    // Projection of the wavefront's signals onto the rows staged in buffer buf:
+    // NT x MTS x KS16 x 6 matrix instructions into acc.
     auto project = [&](int buf) {
 #pragma unroll
         for (int ks = 0; ks < KS16; ++ks) {
-            u32x4 a[2][3];
+            u32x4 a[MTS][3];
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
+            for (int mt = 0; mt < MTS; ++mt)
 #pragma unroll
                 for (int pl = 0; pl < 3; ++pl) a[mt][pl] = Qs[buf][((mt * KS16 + ks) * 3 + pl) * 64 + lane];
 #pragma unroll
             for (int t = 0; t < 6; ++t)
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
+                for (int mt = 0; mt < MTS; ++mt)
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt)
                         acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
@@ -482,21 +502,50 @@ __global__ __launch_bounds__(64 * kSplitWaves) void energy_split_kernel(
     // Kept energy of the wavefront's signals in the blocks of stage s (from acc) against the
     // running best.
     auto select = [&](int s) {
+        if constexpr (P <= 64) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
+            for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                float x[NV];
+                for (int b = 0; b < NB; ++b) {
+                    float x[NV];
 #pragma unroll
-                for (int v = 0; v < NV; ++v) {
-                    const int f = b * NV + v;      // flattened (tile, register)
-                    x[v] = fabsf(acc[nt][f >> 4][f & 15]);
+                    for (int v = 0; v < NV; ++v) {
+                        const int f = b * NV + v;      // flattened (tile, register)
+                        x[v] = fabsf(acc[nt][f >> 4][f & 15]);
+                    }
+                    const float e = pair_top_energy<NV, S, SX>(x, s0, h != 0);
+                    const int j = s * NB + b;
+                    if (j < K && e > bestE[nt]) {
+                        bestE[nt] = e;
+                        best[nt] = j;
+                    }
                 }
-                const float e = pair_top_energy<NV, S, SX>(x, s0, h != 0);
-                const int j = s * NB + b;
-                if (j < K && e > bestE[nt]) {
-                    bestE[nt] = e;
-                    best[nt] = j;
+            }
+        } else {
+            // A block spans SPB stages: keep the lane's sorted top-S across them and combine
+            // the lane pair after the block's last stage.
+            const int part = s % SPB;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                float x[NV], a[S];
+#pragma unroll
+                for (int f = 0; f < NV; ++f) x[f] = fabsf(acc[nt][f >> 4][f & 15]);
+                top_sorted<NV, S>(x, a);
+                if (part == 0) {
+#pragma unroll
+                    for (int i = 0; i < S; ++i) run[nt][i] = a[i];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < S; ++i) run[nt][i] = fmaxf(run[nt][i], a[S - 1 - i]);
+                    bitonic_merge_desc<S>(run[nt]);
+                }
+                if (part == SPB - 1) {
+                    const float e = pair_list_energy<S, SX>(run[nt], s0, h != 0);
+                    const int j = s / SPB;
+                    if (j < K && e > bestE[nt]) {
+                        bestE[nt] = e;
+                        best[nt] = j;
+                    }
                 }
             }
         }
@@ -545,7 +594,7 @@ __global__ __launch_bounds__(64 * kSplitWaves) void energy_split_kernel(
                 if (sig0 + nt * 32 + n < m) atomicAdd(&lh[best[nt]], 1);
         }
         __syncthreads();
-        const int64_t c = ((int64_t)blockIdx.x * (kSplitWaves * 32 * NT)) / chunk;
+        const int64_t c = ((int64_t)blockIdx.x * (G::WAVES * 32 * NT)) / chunk;
         for (int j = tid; j < K; j += NTH)
             if (lh[j] != 0) atomicAdd(&chunk_count[c * K + j], lh[j]);
     }
@@ -589,7 +638,7 @@ __global__ __launch_bounds__(256) void energy_merge_kernel(const float* __restri
     }
 }
 
-// Dsb != nullptr (p <= 64): the projection on the bf16 matrix cores from the split dictionary.
+// Dsb != nullptr: the projection on the bf16 matrix cores from the split dictionary.
 template <int P, int S, int SX>
 hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, float* energy,
                       const f32x4* Dsw, const u32x4* Dsb, int32_t* chunk_count, float* part_E,
@@ -597,13 +646,18 @@ hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, fl
     constexpr int NT = P <= 64 ? 2 : 1;
     constexpr int QN = P / 8;
     constexpr size_t lds = (size_t)2 * (2 * QN * 64) * sizeof(f32x4);
-    constexpr size_t lds_split = (size_t)2 * (2 * (P / 16) * 3 * 64) * sizeof(u32x4);
-    const bool split = Dsb != nullptr && P <= 64;
-    const int per_wg = (split ? kSplitWaves : 4) * 32 * NT;
+    using G = SplitGeom<P>;
+    const bool split = Dsb != nullptr;
+    const int per_wg = split ? G::WAVES * 32 * G::NT : 4 * 32 * NT;
     dim3 grid((unsigned)((m + per_wg - 1) / per_wg));
+    if (raised == nullptr) return hipErrorInvalidValue;
     if (!split && lds > 64 * 1024) {
-        if (raised == nullptr) return hipErrorInvalidValue;
         if (hipError_t e = raised->ensure(reinterpret_cast<const void*>(&energy_kernel<P, S, NT, SX>), lds);
+            e != hipSuccess)
+            return e;
+    }
+    if (split && G::LDS > 64 * 1024) {
+        if (hipError_t e = raised->ensure(reinterpret_cast<const void*>(&energy_split_kernel<P, S, SX>), G::LDS);
             e != hipSuccess)
             return e;
     }
@@ -626,9 +680,8 @@ hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, fl
     float* out_E = by_rows ? part_E : energy;
     int32_t* hist = by_rows ? nullptr : chunk_count;
     if (split) {
-        if constexpr (P <= 64)
-            hipLaunchKernelGGL((energy_split_kernel<P, S, NT, SX>), grid, dim3(64 * kSplitWaves), lds_split, st, Y, (int)m,
-                               Dsb, K, s0, out_j, out_E, hist, chunk, units_per_y);
+        hipLaunchKernelGGL((energy_split_kernel<P, S, SX>), grid, dim3(64 * G::WAVES), G::LDS, st, Y, (int)m, Dsb,
+                           K, s0, out_j, out_E, hist, chunk, units_per_y);
     } else {
         hipLaunchKernelGGL((energy_kernel<P, S, NT, SX>), grid, dim3(256), lds, st, Y, (int)m, Dsw, K, s0,
                            out_j, out_E, hist, chunk, units_per_y);
@@ -701,6 +754,7 @@ hipError_t launch_dict_swizzle_split(int p, int K, const float* D, unsigned* dsb
         case 16: hipLaunchKernelGGL((dict_swizzle_split_kernel<16>), grid, dim3(256), 0, st, D, K, out); break;
         case 32: hipLaunchKernelGGL((dict_swizzle_split_kernel<32>), grid, dim3(256), 0, st, D, K, out); break;
         case 64: hipLaunchKernelGGL((dict_swizzle_split_kernel<64>), grid, dim3(256), 0, st, D, K, out); break;
+        case 256: hipLaunchKernelGGL((dict_swizzle_split_kernel<256>), grid, dim3(256), 0, st, D, K, out); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -33,7 +33,7 @@ size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char
     w.perm = (int32_t*)take((size_t)m_max * 4);
     w.energy = (float*)take((size_t)m_max * 4);
     w.dsw = (float*)take((size_t)((K * p + 63) / 64) * 64 * p * 4);
-    w.dsb = (unsigned*)take(p <= 64 ? (size_t)((K * p + 63) / 64) * 64 * p * 6 : 0);
+    w.dsb = (unsigned*)take((size_t)((K * p + 63) / 64) * 64 * p * 6);
     const size_t split_m = (size_t)(m_max < kEnergySplitSignals ? m_max : kEnergySplitSignals);
     w.part_E = (float*)take((size_t)kEnergySplitRows * split_m * 4);
     w.part_j = (int32_t*)take((size_t)kEnergySplitRows * split_m * 4);
@@ -120,12 +120,13 @@ static int run_group(sbo_ctx* c, const int32_t* blk, int64_t m, bool have_hist =
 }
 
 // The coding kernel reads the split dictionary (bf16 matrix cores) or the fp32 one.
-static bool use_split(const sbo_ctx* c) { return c->coding_arith == SBO_ARITH_BF16X3 && c->p <= 64; }
+static bool use_split(const sbo_ctx* c) { return c->coding_arith == SBO_ARITH_BF16X3; }
 
 // D in the operand order(s) the coding kernels of this context read (tiny; outside the stages).
+// The p = 256 select kernel reads the fp32 order whatever the energy kernel reads.
 static int run_swizzle(sbo_ctx* c, const float* D) {
     if (use_split(c)) SBO_HIP(launch_dict_swizzle_split(c->p, c->K, D, c->ws.dsb, c->stream));
-    else SBO_HIP(launch_dict_swizzle(c->p, c->K, D, c->ws.dsw, c->stream));
+    if (!use_split(c) || c->p > 64) SBO_HIP(launch_dict_swizzle(c->p, c->K, D, c->ws.dsw, c->stream));
     return SBO_OK;
 }
 
@@ -209,7 +210,7 @@ int sbo_create(sbo_ctx** out, int p, int K, int s0, int64_t m_max, void* hip_str
     c->m_max = m_max;
     c->stream = (hipStream_t)hip_stream;
     c->svd_method = SBO_SVD_AUTO;
-    c->coding_arith = SBO_ARITH_BF16X3;      // p = 256 has the fp32 kernel only (use_split)
+    c->coding_arith = SBO_ARITH_BF16X3;
     c->timing = 0;
     c->n_spans = 0;
     const size_t bytes = workspace_layout(p, K, s0, m_max, nullptr, nullptr);

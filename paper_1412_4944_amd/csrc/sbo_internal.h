@@ -90,7 +90,7 @@ struct Workspace {
     // coding
     float* energy;         // [m_max] kept energy in the winning block
     float* dsw;            // [ceil(K*p/64)*64][p] dictionary in MFMA operand order
-    unsigned* dsb;         // p <= 64: the same rows as three bf16 parts in the split operand order (6 bytes per entry)
+    unsigned* dsb;         // the same rows as three bf16 parts in the split operand order (6 bytes per entry)
     float* part_E;         // [kEnergySplitRows][min(m_max, kEnergySplitSignals)] split coding: best energy per row
     int32_t* part_j;       // same shape: its block
     // accumulation
@@ -149,13 +149,13 @@ namespace sbo {
 
 // dsw = D rewritten by launch_dict_swizzle into the energy kernel's operand order.
 hipError_t launch_dict_swizzle(int p, int K, const float* D, float* dsw, hipStream_t st);
-// dsb = D as three bf16 parts per entry in the split operand order (p <= 64).
+// dsb = D as three bf16 parts per entry in the split operand order.
 hipError_t launch_dict_swizzle_split(int p, int K, const float* D, unsigned* dsb, hipStream_t st);
 // chunk_count != nullptr: also add the per-chunk histograms of the chosen blocks into it (the
 // first step of launch_group; the array must be zero on entry, launch_group leaves it so).
 // part_E / part_j ([kEnergySplitRows][min(m_max, kEnergySplitSignals)], may be nullptr): scratch
 // for small m, where the blocks are split over several workgroup rows to fill the chip.
-// dsb != nullptr and p <= 64: the projection runs on the bf16 matrix cores from the split
+// dsb != nullptr: the projection runs on the bf16 matrix cores from the split
 // dictionary (dsw is then not read); otherwise on the fp32 matrix instruction from dsw.
 hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const float* dsw,
                          const unsigned* dsb, int32_t* blk, float* energy, int32_t* chunk_count,

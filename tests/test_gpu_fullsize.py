@@ -48,7 +48,7 @@ def _sample_ids(m, n, seed):
 
 @pytest.mark.parametrize("name,n_sample,arith", [("headline", 262144, "f32"), ("headline", 262144, "bf16x3"),
                                                  ("skew", 110000, "f32"), ("skew", 110000, "bf16x3"),
-                                                 ("patch16", 14000, "f32")])
+                                                 ("patch16", 14000, "f32"), ("patch16", 14000, "bf16x3")])
 def test_full_size_iteration_against_oracle(name, n_sample, arith):
     cfg = synth.CONFIGS[name]
     print(f"case {name} {arith}: p={cfg.p} K={cfg.K} m={cfg.m} s0={cfg.s0}: generating", flush=True)

@@ -45,8 +45,6 @@ ARITH = ["f32", "bf16x3"]     # the two ways the projection onto all K orthobase
 def test_code_matches_oracle(name, kw, arith):
     pr = _problem(name, **kw)
     cfg = pr.cfg
-    if arith == "bf16x3" and cfg.p > 64:
-        pytest.skip("p = 256 has one projection kernel (fp32 matrix instruction): covered by the f32 case")
     print(f"case {name} {arith}: p={cfg.p} K={cfg.K} m={pr.Y.shape[0]} s0={cfg.s0}", flush=True)
     with Sbo(cfg.p, cfg.K, cfg.s0, pr.Y.shape[0], arith=arith) as g:
         for D in (pr.D_init, pr.D_planted):
@@ -167,8 +165,6 @@ def test_polar_rank_deficient_and_empty_blocks():
 def test_iterate_free_running(name, kw, iters, arith):
     pr = _problem(name, **kw)
     cfg = pr.cfg
-    if arith == "bf16x3" and cfg.p > 64:
-        pytest.skip("p = 256 has one projection kernel: covered by the f32 case")
     print(f"case {name} {arith}: p={cfg.p} K={cfg.K} m={pr.Y.shape[0]} s0={cfg.s0}", flush=True)
     Do, last, sq_o = orc.o_iterate(pr.Y, pr.D_init, cfg.s0, iters)
     with Sbo(cfg.p, cfg.K, cfg.s0, pr.Y.shape[0], arith=arith) as g:
@@ -193,8 +189,6 @@ def test_iterate_one_step_matches_oracle(name, kw, arith):
     the coding outputs element by element, the updated dictionary teacher-forced."""
     pr = _problem(name, **kw)
     cfg = pr.cfg
-    if arith == "bf16x3" and cfg.p > 64:
-        pytest.skip("p = 256 has one projection kernel: covered by the f32 case")
     print(f"case {name} {arith}: p={cfg.p} K={cfg.K} m={pr.Y.shape[0]} s0={cfg.s0}", flush=True)
     o = orc.o_code(pr.Y, pr.D_init, cfg.s0)
     with Sbo(cfg.p, cfg.K, cfg.s0, pr.Y.shape[0], arith=arith) as g:
