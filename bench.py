@@ -63,6 +63,7 @@ class Probes:
         self.L.bench_probe_mfma.argtypes = [ctypes.c_void_p, ctypes.c_int, dp]
         self.L.bench_probe_mfma_bf16.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, dp]
         self.L.bench_probe_copy.argtypes = [ctypes.c_void_p, dp]
+        self.L.bench_probe_overlap.argtypes = [ctypes.c_void_p, ctypes.c_int, dp]
         self.ct = ctypes
 
     def _call(self, fn, *args):
@@ -81,6 +82,16 @@ class Probes:
 
     def copy(self):
         return self._call(self.L.bench_probe_copy)
+
+    def overlap(self, bf16):
+        """ms of [a bare MFMA loop, a vector-ALU loop, both at once on the two wavefronts of each SIMD]."""
+        import torch
+        v = (self.ct.c_double * 3)()
+        rc = self.L.bench_probe_overlap(self.ct.c_void_p(torch.cuda.current_stream().cuda_stream),
+                                        1 if bf16 else 0, v)
+        if rc != 0:
+            raise RuntimeError(f"bench probe: HIP error {rc}")
+        return [v[0], v[1], v[2]]
 
 
 def cpu_baseline(pr, sample_m: int) -> dict:
@@ -234,7 +245,8 @@ def main() -> int:
                     "mfma_f32_tflops_sustained": pb.mfma(4000),  # ~17 ms launches: power-limited
                     "mfma_bf16_tflops_constant_operands": pb.mfma_bf16(600, False),
                     "mfma_bf16_tflops_random_operands": pb.mfma_bf16(600, True),
-                    "hbm_copy_GBps": pb.copy()}
+                    "hbm_copy_GBps": pb.copy(),
+                    "overlap_ms_mfma_valu_both": {"bf16_mfma": pb.overlap(True), "f32_mfma": pb.overlap(False)}}
 
     ctx = sbo.sbo_create(p, K, s0, m)
     sbo.sbo_set_option(ctx, sbo.SBO_OPT_CODING_ARITH,

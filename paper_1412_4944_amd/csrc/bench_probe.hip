@@ -14,6 +14,13 @@
 //       sustained rate drops, which is the rate a kernel working on real data can reach
 //   int bench_probe_copy(void* hip_stream, double* gbps)
 //       rate of a plain 256 MiB device copy (GB/s, bytes read + bytes written)
+//   int bench_probe_overlap(void* hip_stream, int bf16, double* ms3)
+//       does matrix work of one wavefront run beside vector-ALU work of another wavefront on the
+//       same SIMD?  256 workgroups of 8 wavefronts (two per SIMD: one issues a bare MFMA loop,
+//       the other a loop of dependent min/max/multiply); ms3[0] = the MFMA loop alone, ms3[1] = the
+//       vector loop alone, ms3[2] = both.  bf16 != 0: v_mfma_f32_32x32x16_bf16, else
+//       v_mfma_f32_32x32x2_f32.  both ~ max(alone) means they overlap, both ~ sum means they share
+//       the pipe.
 // Both allocate and free their own scratch and synchronise the stream; tflops / gbps are host
 // pointers; the return value is a hipError_t (0 = success).
 #include <hip/hip_runtime.h>
@@ -158,6 +165,88 @@ hipError_t probe_mfma_bf16(hipStream_t st, int iters, int random_operands, doubl
     return e;
 }
 
+// Wavefronts 0-3 of a workgroup (one per SIMD) issue MFMAs, wavefronts 4-7 (their SIMD
+// partners) vector-ALU work.
+template <bool BF16>
+__global__ __launch_bounds__(512) void probe_overlap_kernel(float* __restrict__ out, int mfma_iters,
+                                                            int valu_iters) {
+    typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+    float res = 0.f;
+    if (threadIdx.x < 256) {
+        f32x16 acc[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+        const float a = threadIdx.x * 1e-3f, b = blockIdx.x * 1e-3f;
+        bf16x8 av, bv;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            av[e] = (__bf16)(a + e);
+            bv[e] = (__bf16)(b - e);
+        }
+        for (int it = 0; it < mfma_iters; ++it) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if constexpr (BF16) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[i], 0, 0, 0);
+                    else acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[i], 0, 0, 0);
+                }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) res += acc[i][r];
+    } else {
+        float x[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = threadIdx.x * 0.37f + i;
+        for (int it = 0; it < valu_iters; ++it) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int i = 0; i < 15; ++i) {
+                    const float hi = fmaxf(x[i], x[i + 1]), lo = fminf(x[i], x[i + 1]);
+                    x[i] = hi;
+                    x[i + 1] = lo * 1.0001f;
+                }
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) res += x[i];
+    }
+    out[blockIdx.x * 512 + threadIdx.x] = res;
+}
+
+template <bool BF16>
+hipError_t probe_overlap(hipStream_t st, double* ms3) {
+    // per loop iteration: 32 MFMAs (bf16: 8 passes, fp32: 16 passes of 4 clocks) against 180
+    // vector instructions of 4 clocks; the counts make the two loops alone take about the same time
+    const int mfma_iters = BF16 ? 6000 : 3000, valu_iters = 8000;
+    float* out = nullptr;
+    hipError_t e = hipMalloc(&out, (size_t)256 * 512 * sizeof(float));
+    if (e != hipSuccess) return e;
+    EventPair ev;
+    e = ev.init();
+    const int mi[3] = {mfma_iters, 0, mfma_iters}, vi[3] = {0, valu_iters, valu_iters};
+    hipLaunchKernelGGL((probe_overlap_kernel<BF16>), dim3(256), dim3(512), 0, st, out, 100, 100);   // warm-up
+    for (int c = 0; c < 3 && e == hipSuccess; ++c) {
+        float best = 1e30f;
+        for (int rep = 0; rep < 2 && e == hipSuccess; ++rep) {
+            (void)hipEventRecord(ev.a, st);
+            hipLaunchKernelGGL((probe_overlap_kernel<BF16>), dim3(256), dim3(512), 0, st, out, mi[c], vi[c]);
+            (void)hipEventRecord(ev.b, st);
+            e = hipEventSynchronize(ev.b);
+            float ms = 0.f;
+            if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev.a, ev.b);
+            if (ms < best) best = ms;
+        }
+        ms3[c] = best;
+    }
+    (void)hipFree(out);
+    return e;
+}
+
 hipError_t probe_copy(hipStream_t st, double* gbps) {
     const int64_t n = (int64_t)16 * 1024 * 1024;               // 16-byte units: 256 MiB each way
     f32x4 *src = nullptr, *dst = nullptr;
@@ -193,6 +282,12 @@ extern "C" int bench_probe_mfma(void* hip_stream, int iters, double* tflops) {
 extern "C" int bench_probe_mfma_bf16(void* hip_stream, int iters, int random_operands, double* tflops) {
     if (!tflops || iters < 1 || iters > 100000) return (int)hipErrorInvalidValue;
     return (int)probe_mfma_bf16((hipStream_t)hip_stream, iters, random_operands, tflops);
+}
+
+extern "C" int bench_probe_overlap(void* hip_stream, int bf16, double* ms3) {
+    if (!ms3) return (int)hipErrorInvalidValue;
+    return (int)(bf16 ? probe_overlap<true>((hipStream_t)hip_stream, ms3)
+                      : probe_overlap<false>((hipStream_t)hip_stream, ms3));
 }
 
 extern "C" int bench_probe_copy(void* hip_stream, double* gbps) {

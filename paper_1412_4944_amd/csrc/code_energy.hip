@@ -370,20 +370,16 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
 // vector ALU.  The signals' three parts stay in registers for the whole kernel (B operand, 8
 // bf16 per lane and step); the dictionary arrives pre-split (Dsb) and is staged through LDS,
 // double-buffered, one barrier per stage.
-//   p <= 64: a stage is 64 dictionary rows (24 KiB at p = 64), a wavefront owns 64 signals, and a
-//            workgroup is two teams of four wavefronts, one wavefront of each team per SIMD, half
-//            a stage apart: while team 0 multiplies stage s, team 1 runs the selection networks
-//            on its stage s - 1 results, then the roles swap; both read the same LDS stage.
-//   p = 256: the split signals alone take 192 registers per lane for 32 signals, so a
-//            wavefront owns 32 signals, has its SIMD to itself (4 wavefronts per workgroup, no
-//            teams), and a stage is 32 rows (48 KiB); a block spans 8 stages, across which the
-//            lane keeps a running sorted top-S (as the fp32 kernel does).
+// A stage is 64 dictionary rows (24 KiB at p = 64), a wavefront owns 64 signals, and a
+// workgroup is two teams of four wavefronts, one wavefront of each team per SIMD, half a stage
+// apart: while team 0 multiplies stage s, team 1 runs the selection networks on its stage s - 1
+// results, then the roles swap; both read the same LDS stage.  (p = 256: energy_split_wide_kernel.)
 template <int P>
 struct SplitGeom {
-    static constexpr int MTS = P <= 64 ? 2 : 1;          // 32-row tiles per stage
-    static constexpr int NT = P <= 64 ? 2 : 1;           // 32-signal tile columns per wavefront
-    static constexpr int WAVES = P <= 64 ? 8 : 4;
-    static constexpr bool TEAMS = P <= 64;
+    static constexpr int MTS = 2;                        // 32-row tiles per stage
+    static constexpr int NT = 2;                         // 32-signal tile columns per wavefront
+    static constexpr int WAVES = 8;
+    static constexpr bool TEAMS = true;
     static constexpr int KS16 = P / 16;                  // contraction steps of 16 dims
     static constexpr int STAGE_ROWS = 32 * MTS;
     static constexpr int STAGE_U = MTS * KS16 * 3 * 64;  // 16-byte units per stage
@@ -398,13 +394,12 @@ __global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
     using G = SplitGeom<P>;
     constexpr int MTS = G::MTS, NT = G::NT, KS16 = G::KS16, STAGE_U = G::STAGE_U;
     constexpr int NTH = 64 * G::WAVES;
-    constexpr int NB = P <= 64 ? 64 / P : 1;   // blocks per stage (p <= 64)
-    constexpr int SPB = P <= 64 ? 1 : P / G::STAGE_ROWS;   // stages per block (p > 64)
-    constexpr int NV = P <= 64 ? P / 2 : 16 * MTS;         // coefficients per lane per block and stage
+    constexpr int NB = 64 / P;                 // blocks per stage
+    constexpr int SPB = 1;
+    constexpr int NV = P / 2;                  // coefficients per lane per block and stage
     constexpr int FPT = (STAGE_U + NTH - 1) / NTH;         // 16-byte units each thread moves per stage
     constexpr bool kWhole = STAGE_U % NTH == 0;
-    static_assert(P == 16 || P == 32 || P == 64 || P == 256, "unsupported p");
-    static_assert(P <= 64 || S <= NV, "sort width");
+    static_assert(P == 16 || P == 32 || P == 64, "unsupported p");
 
     extern __shared__ u32x4 Qb_raw[];    // [2][STAGE_U]
     u32x4(*Qs)[STAGE_U] = reinterpret_cast<u32x4(*)[STAGE_U]>(Qb_raw);
@@ -436,8 +431,7 @@ __global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
         }
     }
 
-    // Small m: the stages (p <= 64) or blocks (p = 256) are split over blockIdx.y exactly as in
-    // energy_kernel.
+    // Small m: the stages are split over blockIdx.y exactly as in energy_kernel.
     const int n_stage = (K * P + G::STAGE_ROWS - 1) / G::STAGE_ROWS;
     int s_beg = 0, s_end = n_stage;
     if (units_per_y > 0) {
@@ -461,13 +455,10 @@ __global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
 
     int best[NT];
     float bestE[NT];
-    float run[NT][S];                    // p > 64: lane's top-S magnitudes of the current block
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         best[nt] = 0;
         bestE[nt] = -1.f;
-#pragma unroll
-        for (int i = 0; i < S; ++i) run[nt][i] = 0.f;
     }
 
     // the six partial products, smallest first: (A part, B part)
@@ -502,7 +493,7 @@ __global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
     // Kept energy of the wavefront's signals in the blocks of stage s (from acc) against the
     // running best.
     auto select = [&](int s) {
-        if constexpr (P <= 64) {
+        {
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
@@ -515,33 +506,6 @@ __global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
                     }
                     const float e = pair_top_energy<NV, S, SX>(x, s0, h != 0);
                     const int j = s * NB + b;
-                    if (j < K && e > bestE[nt]) {
-                        bestE[nt] = e;
-                        best[nt] = j;
-                    }
-                }
-            }
-        } else {
-            // A block spans SPB stages: keep the lane's sorted top-S across them and combine
-            // the lane pair after the block's last stage.
-            const int part = s % SPB;
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                float x[NV], a[S];
-#pragma unroll
-                for (int f = 0; f < NV; ++f) x[f] = fabsf(acc[nt][f >> 4][f & 15]);
-                top_sorted<NV, S>(x, a);
-                if (part == 0) {
-#pragma unroll
-                    for (int i = 0; i < S; ++i) run[nt][i] = a[i];
-                } else {
-#pragma unroll
-                    for (int i = 0; i < S; ++i) run[nt][i] = fmaxf(run[nt][i], a[S - 1 - i]);
-                    bitonic_merge_desc<S>(run[nt]);
-                }
-                if (part == SPB - 1) {
-                    const float e = pair_list_energy<S, SX>(run[nt], s0, h != 0);
-                    const int j = s / SPB;
                     if (j < K && e > bestE[nt]) {
                         bestE[nt] = e;
                         best[nt] = j;
@@ -600,6 +564,194 @@ __global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
     }
 }
 
+// p = 256 on the bf16 matrix cores.  The three bf16 parts of 32 signals take 192 registers per
+// lane, too many for two wavefronts per SIMD, and with one wavefront per SIMD the selection
+// networks would run while the matrix cores idle.  So the CONTRACTION is halved instead: the
+// two wavefronts of a SIMD (w and w + 4) share one tile of 32 signals, each holds one half of the
+// dims (96 registers) and multiplies the staged rows (32 atoms a stage, 48 KiB, double-buffered)
+// by its half.  For every block one of the two is the selector (even blocks: the wavefront with
+// the lower dims, odd blocks: the other): its partner leaves its partial products in LDS, the
+// selector adds them to its own one stage later and runs the selection networks on the sums
+// while the partner already multiplies the next stage.  A block spans 8 stages, across which the
+// selector keeps the lane's running sorted top-S; the two wavefronts' best blocks are compared
+// at the end.
+constexpr int kWideWaves = 8;
+
+template <int P, int S, int SX>
+__global__ __launch_bounds__(64 * kWideWaves) void energy_split_wide_kernel(
+    const float* __restrict__ Y, int m, const u32x4* __restrict__ Dsb, int K, int s0,
+    int32_t* __restrict__ blk, float* __restrict__ energy, int32_t* __restrict__ chunk_count, int chunk,
+    int units_per_y) {
+    constexpr int KS16 = P / 16, KH = KS16 / 2;            // contraction steps: all, per wavefront
+    constexpr int SPB = P / 32;                            // stages per block
+    constexpr int STAGE_U = KS16 * 3 * 64;                 // 16-byte units per stage of 32 rows
+    constexpr int NTH = 64 * kWideWaves;
+    constexpr int FPT = STAGE_U / NTH;
+    static_assert(P == 256 && STAGE_U % NTH == 0 && S <= 16, "shape");
+
+    extern __shared__ u32x4 Qw_raw[];    // Qs[2][STAGE_U] | xch[2][4 SIMDs][4][64] (f32x4)
+    u32x4(*Qs)[STAGE_U] = reinterpret_cast<u32x4(*)[STAGE_U]>(Qw_raw);
+    f32x4* xch = reinterpret_cast<f32x4*>(Qw_raw + 2 * STAGE_U);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int simd = wave & 3, half = wave >> 2;           // wavefronts w and w + 4 share a SIMD
+    const int h = lane >> 5, n = lane & 31;
+    const int64_t i = ((int64_t)blockIdx.x * 4 + simd) * 32 + n;
+
+    // B operand: the three bf16 parts of dims (half*KH + ks)*16 + h*8 .. +7 of signal i
+    u32x4 yq[KH][3];
+#pragma unroll
+    for (int ks = 0; ks < KH; ++ks) {
+        f32x4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = v0;
+        if (i < m) {
+            const f32x4* src = reinterpret_cast<const f32x4*>(Y + i * P + (half * KH + ks) * 16 + h * 8);
+            v0 = src[0];
+            v1 = src[1];
+        }
+        const Bf16x3Pair a = split_bf16x3(v0.x, v0.y), b = split_bf16x3(v0.z, v0.w);
+        const Bf16x3Pair c = split_bf16x3(v1.x, v1.y), d = split_bf16x3(v1.z, v1.w);
+        yq[ks][0] = u32x4{a.hi, b.hi, c.hi, d.hi};
+        yq[ks][1] = u32x4{a.mid, b.mid, c.mid, d.mid};
+        yq[ks][2] = u32x4{a.lo, b.lo, c.lo, d.lo};
+    }
+
+    // Small m: the blocks are split over blockIdx.y exactly as in energy_kernel.
+    const int n_stage = K * SPB;
+    int s_beg = 0, s_end = n_stage;
+    if (units_per_y > 0) {
+        s_beg = min(n_stage, (int)blockIdx.y * units_per_y * SPB);
+        s_end = min(n_stage, s_beg + units_per_y * SPB);
+        blk += (int64_t)blockIdx.y * m;
+        energy += (int64_t)blockIdx.y * m;
+    }
+
+    u32x4 pre[FPT];
+    auto fetch = [&](int s) {
+#pragma unroll
+        for (int r = 0; r < FPT; ++r) pre[r] = Dsb[(int64_t)s * STAGE_U + tid + NTH * r];
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int r = 0; r < FPT; ++r) Qs[buf][tid + NTH * r] = pre[r];
+    };
+
+    int best = 0;
+    float bestE = -1.f;
+    float run[S];                        // selector: lane's top-S magnitudes of the current block
+#pragma unroll
+    for (int t = 0; t < S; ++t) run[t] = 0.f;
+
+    // the six partial products, smallest first: (A part, B part)
+    constexpr int TA[6] = {2, 0, 1, 1, 0, 0};
+    constexpr int TB[6] = {0, 2, 1, 0, 1, 0};
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
+                         0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x16 acc = zero;
+    auto selects = [&](int s) { return (((s / SPB) & 1) == half); };   // uniform over the wavefront
+
+    // This wavefront's half of the products of the rows staged in buffer buf.
+    auto project = [&](int buf) {
+#pragma unroll
+        for (int ks = 0; ks < KH; ++ks) {
+            u32x4 a[3];
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl) a[pl] = Qs[buf][((half * KH + ks) * 3 + pl) * 64 + lane];
+#pragma unroll
+            for (int t = 0; t < 6; ++t)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[TA[t]]),
+                                                              __builtin_bit_cast(bf16x8, yq[ks][TB[t]]),
+                                                              (ks == 0 && t == 0) ? zero : acc, 0, 0, 0);
+        }
+    };
+    // Selector of stage s: own partial (still in acc) + the partner's (exchange buffer buf), then
+    // the lane's running top-S and, after the block's last stage, the kept energy of the lane pair.
+    auto select = [&](int s, int buf) {
+        float x[16], a[S];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 o = xch[((buf * 4 + simd) * 4 + q) * 64 + lane];
+            x[4 * q + 0] = fabsf(acc[4 * q + 0] + o.x);
+            x[4 * q + 1] = fabsf(acc[4 * q + 1] + o.y);
+            x[4 * q + 2] = fabsf(acc[4 * q + 2] + o.z);
+            x[4 * q + 3] = fabsf(acc[4 * q + 3] + o.w);
+        }
+        top_sorted<16, S>(x, a);
+        const int part = s % SPB;
+        if (part == 0) {                 // uniform
+#pragma unroll
+            for (int t = 0; t < S; ++t) run[t] = a[t];
+        } else {
+#pragma unroll
+            for (int t = 0; t < S; ++t) run[t] = fmaxf(run[t], a[S - 1 - t]);
+            bitonic_merge_desc<S>(run);
+        }
+        if (part == SPB - 1) {           // uniform
+            const float e = pair_list_energy<S, SX>(run, s0, h != 0);
+            const int j = s / SPB;
+            if (e > bestE) {
+                bestE = e;
+                best = j;
+            }
+        }
+    };
+
+    if (s_beg < s_end) {                 // uniform
+        fetch(s_beg);
+        stash(0);
+    }
+    __syncthreads();
+    for (int s = s_beg; s < s_end; ++s) {
+        const int cur = (s - s_beg) & 1;
+        if (s + 1 < s_end) fetch(s + 1);
+        if (s > s_beg && selects(s - 1)) select(s - 1, cur ^ 1);
+        project(cur);
+        if (!selects(s)) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                xch[((cur * 4 + simd) * 4 + q) * 64 + lane] =
+                    f32x4{acc[4 * q + 0], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        }
+        if (s + 1 < s_end) stash(cur ^ 1);
+        __syncthreads();
+    }
+    if (s_beg < s_end && selects(s_end - 1)) select(s_end - 1, (s_end - 1 - s_beg) & 1);
+
+    // the better of the two wavefronts' best blocks (equal energies: the lower block)
+    __syncthreads();                     // the exchange buffers are free
+    float* mrgE = reinterpret_cast<float*>(xch);           // [4][64]
+    int* mrgJ = reinterpret_cast<int*>(xch) + 4 * 64;
+    if (half == 1) {
+        mrgE[simd * 64 + lane] = bestE;
+        mrgJ[simd * 64 + lane] = best;
+    }
+    __syncthreads();
+    if (half == 0) {
+        const float e = mrgE[simd * 64 + lane];
+        const int j = mrgJ[simd * 64 + lane];
+        if (e > bestE || (e == bestE && j < best)) {
+            bestE = e;
+            best = j;
+        }
+        if (h == 0 && i < m) {
+            blk[i] = best;
+            energy[i] = bestE;
+        }
+    }
+
+    // the grouping's chunk histograms (see energy_kernel)
+    if (chunk_count != nullptr) {        // uniform
+        int* lh = reinterpret_cast<int*>(Qw_raw);          // the stage buffers are dead
+        for (int j = tid; j < K; j += NTH) lh[j] = 0;
+        __syncthreads();
+        if (half == 0 && h == 0 && i < m) atomicAdd(&lh[best], 1);
+        __syncthreads();
+        const int64_t c = ((int64_t)blockIdx.x * 128) / chunk;
+        for (int j = tid; j < K; j += NTH)
+            if (lh[j] != 0) atomicAdd(&chunk_count[c * K + j], lh[j]);
+    }
+}
+
 // Winner over the rows of a split launch: part_E / part_j hold, per row y, the best energy
 // and block of the row's share of the blocks (rows in ascending block order, so the strict
 // comparison keeps the lowest block among equal energies).  Also the grouping histogram
@@ -646,9 +798,12 @@ hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, fl
     constexpr int NT = P <= 64 ? 2 : 1;
     constexpr int QN = P / 8;
     constexpr size_t lds = (size_t)2 * (2 * QN * 64) * sizeof(f32x4);
-    using G = SplitGeom<P>;
+    constexpr bool wide = P > 64;
+    using G = SplitGeom<wide ? 64 : P>;
+    // p = 256: two 48 KiB stages + the partial-product exchange (2 x 4 SIMDs x 4 KiB)
+    constexpr size_t lds_split = wide ? (size_t)2 * (P / 16) * 3 * 64 * 16 + (size_t)2 * 4 * 4 * 64 * 16 : G::LDS;
     const bool split = Dsb != nullptr;
-    const int per_wg = split ? G::WAVES * 32 * G::NT : 4 * 32 * NT;
+    const int per_wg = split ? (wide ? 128 : G::WAVES * 32 * G::NT) : 4 * 32 * NT;
     dim3 grid((unsigned)((m + per_wg - 1) / per_wg));
     if (raised == nullptr) return hipErrorInvalidValue;
     if (!split && lds > 64 * 1024) {
@@ -656,10 +811,13 @@ hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, fl
             e != hipSuccess)
             return e;
     }
-    if (split && G::LDS > 64 * 1024) {
-        if (hipError_t e = raised->ensure(reinterpret_cast<const void*>(&energy_split_kernel<P, S, SX>), G::LDS);
-            e != hipSuccess)
-            return e;
+    if constexpr (wide) {
+        if (split) {
+            if (hipError_t e = raised->ensure(
+                    reinterpret_cast<const void*>(&energy_split_wide_kernel<P, S, SX>), lds_split);
+                e != hipSuccess)
+                return e;
+        }
     }
     const int chunk = group_geom(m).chunk;
     if (chunk % per_wg != 0) return hipErrorInvalidValue;
@@ -680,8 +838,12 @@ hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, fl
     float* out_E = by_rows ? part_E : energy;
     int32_t* hist = by_rows ? nullptr : chunk_count;
     if (split) {
-        hipLaunchKernelGGL((energy_split_kernel<P, S, SX>), grid, dim3(64 * G::WAVES), G::LDS, st, Y, (int)m, Dsb,
-                           K, s0, out_j, out_E, hist, chunk, units_per_y);
+        if constexpr (wide)
+            hipLaunchKernelGGL((energy_split_wide_kernel<P, S, SX>), grid, dim3(64 * kWideWaves), lds_split, st,
+                               Y, (int)m, Dsb, K, s0, out_j, out_E, hist, chunk, units_per_y);
+        else
+            hipLaunchKernelGGL((energy_split_kernel<P, S, SX>), grid, dim3(64 * G::WAVES), lds_split, st, Y,
+                               (int)m, Dsb, K, s0, out_j, out_E, hist, chunk, units_per_y);
     } else {
         hipLaunchKernelGGL((energy_kernel<P, S, NT, SX>), grid, dim3(256), lds, st, Y, (int)m, Dsw, K, s0,
                            out_j, out_E, hist, chunk, units_per_y);

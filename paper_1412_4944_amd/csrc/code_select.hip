@@ -262,17 +262,137 @@ __global__ __launch_bounds__(256) void select_wide_kernel(const float* __restric
     if (active && h == 0) err[i] = dropped;
 }
 
+// p = 256 on the bf16 matrix cores (see energy_split_kernel for the arithmetic): the four
+// wavefronts of a workgroup take four 32-signal tiles of ONE block and share its rows, staged
+// through LDS 32 atoms at a time (48 KiB in the split operand order, double-buffered); each
+// wavefront keeps its signals' three bf16 parts (192 registers) and the whole projection
+// (8 accumulator tiles, 128 registers) in registers and selects from there.  Dsb is the whole
+// dictionary in the split operand order (dict_swizzle_split_kernel).
+// Workgroup ids are dealt out so that the workgroups of one XCD (ids equal modulo 8) take a
+// contiguous run of tiles, that is, few blocks, whose rows then stay in that XCD's L2.
+template <int P, int S>
+__global__ __launch_bounds__(256) void select_wide_split_kernel(const float* __restrict__ Y,
+                                                                const u32x4* __restrict__ Dsb, int K, int s0,
+                                                                const int32_t* __restrict__ offsets,
+                                                                const int32_t* __restrict__ perm,
+                                                                int32_t* __restrict__ supp,
+                                                                float* __restrict__ coef,
+                                                                float* __restrict__ err) {
+    constexpr int KS16 = P / 16;
+    constexpr int MT = P / 32;
+    constexpr int STAGE_U = KS16 * 3 * 64;     // 16-byte units of 32 rows
+    constexpr int FPT = STAGE_U / 256;
+    static_assert(STAGE_U % 256 == 0 && S <= 16, "shape");
+
+    extern __shared__ int lds[];               // unit_start[K+1] | tmp[16] | pad | Qs[2][STAGE_U] | stage[4][..]
+    int* unit_start = lds;
+    int* tmp = lds + (K + 1);
+    const int head = ((K + 1 + 16) + 3) & ~3;
+    u32x4(*Qs)[STAGE_U] = reinterpret_cast<u32x4(*)[STAGE_U]>(lds + head);
+    int* stage_all = reinterpret_cast<int*>(Qs + 2);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int h = lane >> 5, n = lane & 31;
+
+    // units of four tiles per block
+    wg_exclusive_scan4([&](int j) { return (((offsets[j + 1] - offsets[j] + 31) >> 5) + 3) >> 2; }, K,
+                       unit_start, tmp);
+    const int per_xcd = gridDim.x >> 3;        // the grid is a multiple of 8 (launcher)
+    const int id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (id >= unit_start[K]) return;           // uniform over the workgroup
+
+    const int j = upper_slot(unit_start, K, id);
+    const int pos0 = offsets[j] + ((id - unit_start[j]) * 4 + wave) * 32;
+    const int cnt = min(32, offsets[j + 1] - pos0);        // <= 0: this wavefront has no tile (it still
+    const bool active = n < cnt;                           // takes part in the staging and the barriers)
+    const int64_t i = active ? perm[pos0 + n] : -1;
+
+    u32x4 pre[FPT];
+    const u32x4* Qj = Dsb + (int64_t)j * MT * STAGE_U;
+    auto fetch = [&](int s) {
+#pragma unroll
+        for (int r = 0; r < FPT; ++r) pre[r] = Qj[(int64_t)s * STAGE_U + tid + 256 * r];
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int r = 0; r < FPT; ++r) Qs[buf][tid + 256 * r] = pre[r];
+    };
+    fetch(0);
+
+    // B operand: the three bf16 parts of this lane's dims (ks*16 + h*8 .. +7) of its signal
+    u32x4 yq[KS16][3];
+#pragma unroll
+    for (int ks = 0; ks < KS16; ++ks) {
+        f32x4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = v0;
+        if (active) {
+            const f32x4* src = reinterpret_cast<const f32x4*>(Y + i * P + ks * 16 + h * 8);
+            v0 = src[0];
+            v1 = src[1];
+        }
+        const Bf16x3Pair a = split_bf16x3(v0.x, v0.y), b = split_bf16x3(v0.z, v0.w);
+        const Bf16x3Pair c = split_bf16x3(v1.x, v1.y), d = split_bf16x3(v1.z, v1.w);
+        yq[ks][0] = u32x4{a.hi, b.hi, c.hi, d.hi};
+        yq[ks][1] = u32x4{a.mid, b.mid, c.mid, d.mid};
+        yq[ks][2] = u32x4{a.lo, b.lo, c.lo, d.lo};
+    }
+    stash(0);
+    __syncthreads();
+
+    // the six partial products, smallest first: (A part, B part)
+    constexpr int TA[6] = {2, 0, 1, 1, 0, 0};
+    constexpr int TB[6] = {0, 2, 1, 0, 1, 0};
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
+                         0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x16 acc[MT];
+#pragma unroll
+    for (int s = 0; s < MT; ++s) {
+        const int cur = s & 1;
+        if (s + 1 < MT) fetch(s + 1);
+#pragma unroll
+        for (int ks = 0; ks < KS16; ++ks) {
+            u32x4 a[3];
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl) a[pl] = Qs[cur][(ks * 3 + pl) * 64 + lane];
+#pragma unroll
+            for (int t = 0; t < 6; ++t)
+                acc[s] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[TA[t]]),
+                                                                 __builtin_bit_cast(bf16x8, yq[ks][TB[t]]),
+                                                                 (ks == 0 && t == 0) ? zero : acc[s], 0, 0, 0);
+        }
+        if (s + 1 < MT) stash(cur ^ 1);
+        __syncthreads();
+    }
+
+    tile_select<P, S, false>(acc, h, n, active, i, s0, nullptr, stage_all + wave * kSelectStageWords, supp, coef,
+                             err);
+}
+
 template <int P, int S>
 hipError_t launch_wide_ps(const float* Y, int64_t m, const float* D, int K, int s0,
-                          const Workspace& ws, int32_t* supp, float* coef, float* err,
+                          const Workspace& ws, int32_t* supp, float* coef, float* err, bool split,
                           hipStream_t st) {
+    (void)D;                                   // the kernels read ws.dsb / ws.dsw, the same Q in operand order
+    if (split) {
+        // a multiple of 8, so that the kernel's dealing of ids over the XCDs covers every unit
+        const int64_t max_units = (((m + 127) / 128 + K) + 7) & ~(int64_t)7;
+        const int head = ((K + 1 + 16) + 3) & ~3;
+        const size_t lds = (size_t)head * sizeof(int) + (size_t)2 * (P / 16) * 3 * 64 * 16 +
+                           (size_t)4 * kSelectStageWords * sizeof(int);
+        if (hipError_t e =
+                ws.raised->ensure(reinterpret_cast<const void*>(&select_wide_split_kernel<P, S>), lds);
+            e != hipSuccess)
+            return e;
+        hipLaunchKernelGGL((select_wide_split_kernel<P, S>), dim3((unsigned)max_units), dim3(256), lds, st, Y,
+                           reinterpret_cast<const u32x4*>(ws.dsb), K, s0, ws.offsets, ws.perm, supp, coef, err);
+        return hipGetLastError();
+    }
     const int64_t max_tiles = (m + 31) / 32 + K;
     dim3 grid((unsigned)((max_tiles + 3) / 4));
     const size_t lds = (K + 1 + 16) * sizeof(int) + 4 * 32 * (P + 1) * sizeof(float);
     if (hipError_t e = ws.raised->ensure(reinterpret_cast<const void*>(&select_wide_kernel<P, S>), lds);
         e != hipSuccess)
         return e;
-    (void)D;                                   // the kernel reads ws.dsw, the same Q in operand order
     hipLaunchKernelGGL((select_wide_kernel<P, S>), grid, dim3(256), lds, st, Y,
                        reinterpret_cast<const f32x4*>(ws.dsw), K, s0, ws.offsets, ws.perm, supp, coef, err);
     return hipGetLastError();
@@ -280,13 +400,13 @@ hipError_t launch_wide_ps(const float* Y, int64_t m, const float* D, int K, int 
 
 template <int P>
 hipError_t launch_wide_p(int s0, const float* Y, int64_t m, const float* D, int K,
-                         const Workspace& ws, int32_t* supp, float* coef, float* err,
+                         const Workspace& ws, int32_t* supp, float* coef, float* err, bool split,
                          hipStream_t st) {
-    if (s0 <= 1) return launch_wide_ps<P, 1>(Y, m, D, K, s0, ws, supp, coef, err, st);
-    if (s0 <= 2) return launch_wide_ps<P, 2>(Y, m, D, K, s0, ws, supp, coef, err, st);
-    if (s0 <= 4) return launch_wide_ps<P, 4>(Y, m, D, K, s0, ws, supp, coef, err, st);
-    if (s0 <= 8) return launch_wide_ps<P, 8>(Y, m, D, K, s0, ws, supp, coef, err, st);
-    return launch_wide_ps<P, 16>(Y, m, D, K, s0, ws, supp, coef, err, st);
+    if (s0 <= 1) return launch_wide_ps<P, 1>(Y, m, D, K, s0, ws, supp, coef, err, split, st);
+    if (s0 <= 2) return launch_wide_ps<P, 2>(Y, m, D, K, s0, ws, supp, coef, err, split, st);
+    if (s0 <= 4) return launch_wide_ps<P, 4>(Y, m, D, K, s0, ws, supp, coef, err, split, st);
+    if (s0 <= 8) return launch_wide_ps<P, 8>(Y, m, D, K, s0, ws, supp, coef, err, split, st);
+    return launch_wide_ps<P, 16>(Y, m, D, K, s0, ws, supp, coef, err, split, st);
 }
 
 template <int P, int S>
@@ -314,17 +434,18 @@ hipError_t launch_p(int s0, const float* Y, int64_t m, const float* D, int K, co
 }  // namespace
 
 hipError_t launch_select(int p, int K, int s0, const float* Y, int64_t m, const float* D,
-                         const Workspace& ws, int32_t* supp, float* coef, float* err, bool dsw_valid,
-                         hipStream_t st) {
-    if (p == 256 && !dsw_valid) {              // the p = 256 kernel reads Q in operand order
-        hipError_t e = launch_dict_swizzle(p, K, D, ws.dsw, st);
+                         const Workspace& ws, int32_t* supp, float* coef, float* err, bool ops_valid,
+                         bool split, hipStream_t st) {
+    if (p == 256 && !ops_valid) {              // the p = 256 kernels read Q in operand order
+        hipError_t e = split ? launch_dict_swizzle_split(p, K, D, ws.dsb, st)
+                             : launch_dict_swizzle(p, K, D, ws.dsw, st);
         if (e != hipSuccess) return e;
     }
     switch (p) {
         case 16: return launch_p<16>(s0, Y, m, D, K, ws, supp, coef, err, st);
         case 32: return launch_p<32>(s0, Y, m, D, K, ws, supp, coef, err, st);
         case 64: return launch_p<64>(s0, Y, m, D, K, ws, supp, coef, err, st);
-        case 256: return launch_wide_p<256>(s0, Y, m, D, K, ws, supp, coef, err, st);
+        case 256: return launch_wide_p<256>(s0, Y, m, D, K, ws, supp, coef, err, split, st);
         default: return hipErrorInvalidValue;
     }
 }

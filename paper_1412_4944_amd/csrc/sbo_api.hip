@@ -123,10 +123,9 @@ static int run_group(sbo_ctx* c, const int32_t* blk, int64_t m, bool have_hist =
 static bool use_split(const sbo_ctx* c) { return c->coding_arith == SBO_ARITH_BF16X3; }
 
 // D in the operand order(s) the coding kernels of this context read (tiny; outside the stages).
-// The p = 256 select kernel reads the fp32 order whatever the energy kernel reads.
 static int run_swizzle(sbo_ctx* c, const float* D) {
     if (use_split(c)) SBO_HIP(launch_dict_swizzle_split(c->p, c->K, D, c->ws.dsb, c->stream));
-    if (!use_split(c) || c->p > 64) SBO_HIP(launch_dict_swizzle(c->p, c->K, D, c->ws.dsw, c->stream));
+    else SBO_HIP(launch_dict_swizzle(c->p, c->K, D, c->ws.dsw, c->stream));
     return SBO_OK;
 }
 
@@ -147,8 +146,8 @@ static int run_code(sbo_ctx* c, const float* Y, int64_t m, const float* D, int32
     rc = run_group(c, blk, m, true);           // the energy kernel left the chunk histograms
     if (rc) return rc;
     {
-        StageTimer t(c, SBO_STAGE_SELECT);         // p = 256 reads ws.dsw, which run_swizzle wrote
-        SBO_HIP(launch_select(c->p, c->K, c->s0, Y, m, D, c->ws, supp, coef, err, true, c->stream));
+        StageTimer t(c, SBO_STAGE_SELECT);         // p = 256 reads the operand order run_swizzle wrote
+        SBO_HIP(launch_select(c->p, c->K, c->s0, Y, m, D, c->ws, supp, coef, err, true, use_split(c), c->stream));
     }
     return SBO_OK;
 }
@@ -383,7 +382,7 @@ static int run_train_rounds(sbo_ctx* c, const float* Y, int64_t m, const int32_t
             {
                 StageTimer t(c, SBO_STAGE_SELECT);
                 SBO_HIP(launch_select(c->p, c->K, c->s0, Y, m, D, c->ws, supp, coef, err, false,
-                                      c->stream));
+                                      use_split(c), c->stream));
             }
             StageTimer t(c, SBO_STAGE_ACCUM);
             SBO_HIP(launch_accumulate(c->p, c->K, c->s0, Y, m, supp, coef, c->ws, c->ws.M, c->stream));
@@ -456,7 +455,7 @@ static int run_new_base(sbo_ctx* c, const float* Y, int64_t n, int R, int have_q
         if (c->p <= 64) {
             SBO_HIP(launch_select_accum(c->p, 1, c->s0, Y, n, Q, c->ws, supp, coef, err, c->stream));
         } else {
-            SBO_HIP(launch_select(c->p, 1, c->s0, Y, n, Q, c->ws, supp, coef, err, false, c->stream));
+            SBO_HIP(launch_select(c->p, 1, c->s0, Y, n, Q, c->ws, supp, coef, err, false, use_split(c), c->stream));
             SBO_HIP(launch_accumulate(c->p, 1, c->s0, Y, n, supp, coef, c->ws, c->ws.M, c->stream));
         }
         if (sqerr_per_round)

@@ -169,11 +169,12 @@ constexpr int64_t kGroupStaticMaxM = (int64_t)1 << 20;
 hipError_t launch_group_static(int K, const int32_t* blk, int64_t m, int32_t* counts, int32_t* offsets,
                                int32_t* perm, hipStream_t st);
 
-// dsw_valid: ws.dsw already holds this D in operand order (launch_dict_swizzle); p = 256 reads
-// it and rewrites it first otherwise.
+// p = 256 reads Q in operand order: ws.dsb (split: the bf16 matrix cores) or ws.dsw (fp32 matrix
+// instruction).  ops_valid: that buffer already holds this D (launch_dict_swizzle[_split]);
+// otherwise it is rewritten first.  p <= 64 reads D itself and ignores both flags.
 hipError_t launch_select(int p, int K, int s0, const float* Y, int64_t m, const float* D,
-                         const Workspace& ws, int32_t* supp, float* coef, float* err, bool dsw_valid,
-                         hipStream_t st);
+                         const Workspace& ws, int32_t* supp, float* coef, float* err, bool ops_valid,
+                         bool split, hipStream_t st);
 
 hipError_t launch_accumulate(int p, int K, int s0, const float* Y, int64_t m, const int32_t* supp,
                              const float* coef, const Workspace& ws, float* M, hipStream_t st);

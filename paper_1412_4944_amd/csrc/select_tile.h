@@ -1,4 +1,4 @@
-// Per-tile support selection shared by the select kernels (p <= 64).
+// Per-tile support selection shared by the select kernels.
 #pragma once
 
 #include "device_utils.h"
@@ -12,7 +12,8 @@ namespace sbo {
 // lowest-index entries equal to tau in ascending atom order, the coefficients and the
 // residual (sum of the dropped c^2) of signal i (original index; active = lane has a
 // signal).  Exact magnitude ties beyond the trivial one are resolved by a sequential
-// per-signal pass through the wave-private LDS tile ct[32][P+1].  The (atom, coefficient)
+// per-signal pass through the wave-private LDS tile ct[32][P+1] (p <= 64; for larger p by
+// running counts over the registers, and ct is not used: pass nullptr).  The (atom, coefficient)
 // rows are first compacted in the wave-private LDS area stage[32][2][16] (words) and then
 // written with one or a few wide stores per lane (lane half 0: supp row, half 1: coef row),
 // because scattered 4-byte stores to rows in original signal order are what this step
@@ -98,6 +99,57 @@ __device__ __forceinline__ void tile_select(const f32x16* acc, int h, int n, boo
                 }
                 if constexpr (KEEP_X)
                     if (atom < P) ct[n * LDC + atom] = mag[f] >= tau ? c[f] : 0.f;
+            }
+        }
+        dropped += other_half(dropped);
+        if (active && h == 0) err[i] = dropped;
+    } else if constexpr (P > 64) {
+        // Exact magnitude ties, in registers (a [32][P] scratch tile per wavefront would not fit
+        // beside the staged dictionary): entries above tau are kept, entries equal to tau in
+        // ascending atom order until s0 are reached.  Atom order = group order, and within a
+        // group the lane of half 0 comes first, so the running counts cross the lane pair once
+        // per group.
+        if (used_ct != nullptr) *used_ct = true;
+        int gt = 0;
+#pragma unroll
+        for (int f = 0; f < NVL; ++f) gt += mag[f] > tau;
+        gt += other_half(gt);
+        const int need = s0 - gt;              // entries equal to tau still to take (>= 1)
+        int run_eq = 0, run_keep = 0;
+        float dropped = 0.f;
+#pragma unroll
+        for (int g = 0; g < NVL / 4; ++g) {
+            int eq_own = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) eq_own += mag[4 * g + e] == tau;
+            const int eq_par = other_half(eq_own);
+            int eq_rank = run_eq + (h ? eq_par : 0);
+            run_eq += eq_own + eq_par;
+            bool keep[4];
+            int keep_own = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool is_eq = mag[4 * g + e] == tau;
+                keep[e] = mag[4 * g + e] > tau || (is_eq && eq_rank < need);
+                eq_rank += is_eq;
+                keep_own += keep[e];
+            }
+            const int keep_par = other_half(keep_own);
+            int pos = run_keep + (h ? keep_par : 0);
+            run_keep += keep_own + keep_par;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int f = 4 * g + e;
+                const int atom = (f >> 4) * 32 + ((f & 15) >> 2) * 8 + h * 4 + (f & 3);
+                if (keep[e]) {
+                    if (active && pos < s0) {
+                        stage[stage_idx(n, 0, pos)] = atom;
+                        stage[stage_idx(n, 1, pos)] = __builtin_bit_cast(int, c[f]);
+                    }
+                    ++pos;
+                } else if (atom < P) {
+                    dropped += c[f] * c[f];
+                }
             }
         }
         dropped += other_half(dropped);

@@ -56,18 +56,19 @@ def test_code_matches_oracle(name, kw, arith):
             print(f"  exempt fraction {frac:.5f}", flush=True)
 
 
+@pytest.mark.parametrize("p", [16, 64, 256])
 @pytest.mark.parametrize("arith", ARITH)
-def test_code_ties_zero_signal_and_duplicates(arith):
+def test_code_ties_zero_signal_and_duplicates(arith, p):
     # identical blocks (block tie -> lowest index), equal magnitudes (atom tie -> lowest
     # index), an all-zero signal; every expected value follows from the tie rules alone
-    p, K, s0 = 16, 4, 3
+    K, s0 = 4, 3
     rng = np.random.default_rng(3)
     Q = synth.random_onb(rng, p).T.astype(np.float32)
     D = np.stack([np.eye(p, dtype=np.float32), Q, np.eye(p, dtype=np.float32), Q])
     Y = np.zeros((70, p), np.float32)
     Y[0, [2, 5, 7, 9]] = [1.0, -1.0, 1.0, 1.0]          # four equal magnitudes, keep 2,5,7
     Y[1] = 0.0
-    Y[2, [0, 15]] = [3.0, -3.0]                          # fewer non-zeros than s0
+    Y[2, [0, p - 1]] = [3.0, -3.0]                       # fewer non-zeros than s0
     Y[3:] = rng.standard_normal((67, p)).astype(np.float32)
     Y[40] = Y[39]                                        # duplicate signals
     o = orc.o_code(Y, D, s0)
@@ -76,7 +77,7 @@ def test_code_ties_zero_signal_and_duplicates(arith):
     assert blk[0] == 0 and supp[0].tolist() == [2, 5, 7] and coef[0].tolist() == [1.0, -1.0, 1.0]
     assert err[0] == 1.0
     assert blk[1] == 0 and supp[1].tolist() == [0, 1, 2] and (coef[1] == 0).all() and err[1] == 0
-    assert blk[2] == 0 and supp[2].tolist() == [0, 1, 15] and coef[2].tolist() == [3.0, 0.0, -3.0]
+    assert blk[2] == 0 and supp[2].tolist() == [0, 1, p - 1] and coef[2].tolist() == [3.0, 0.0, -3.0]
     assert (blk[40], supp[40].tolist(), coef[40].tolist()) == (blk[39], supp[39].tolist(), coef[39].tolist())
     assert (blk < 2).all()                               # blocks 2,3 duplicate 0,1: lowest index wins
     compare_code(Y, D, s0, o, (blk, supp, coef, err), max_exempt_frac=0.05)
