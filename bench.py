@@ -31,7 +31,17 @@ SPLIT_PRODUCTS = 6
 
 
 def roofline_kernel_name(p: int, arith: str) -> str:
-    return "energy_split_kernel" if arith == "bf16x3" else "energy_kernel"
+    return "energy_kernel" if arith == "f32" else "energy_split_kernel"
+
+
+def arith_value(sbo, arith: str) -> int:
+    return {"f32": sbo.SBO_ARITH_F32, "bf16x3": sbo.SBO_ARITH_BF16X3, "screen": sbo.SBO_ARITH_BF16X3_SCREEN}[arith]
+
+
+def screening_applies(p: int, m: int) -> bool:
+    """SBO_ARITH_BF16X3_SCREEN screens only for p <= 64 and when the signals fill the chip (the
+    library's rule: at least 192 workgroups of 512 signals); otherwise it is SBO_ARITH_BF16X3."""
+    return p <= 64 and (m + 511) // 512 >= 192
 
 
 def measured_traffic_bytes(workload: str, kernel: str):
@@ -122,7 +132,18 @@ def roofline_entry(p, K, m, energy_ms, arith, workload):
     flops = 2.0 * K * p * p * m                 # algorithmic: projection onto all K orthobases
     achieved = flops / (energy_ms * 1e-3) / 1e12
     kernel = roofline_kernel_name(p, arith)
-    if kernel == "energy_split_kernel":
+    if arith == "screen" and screening_applies(p, m):
+        # two launches: three partial products for every signal, then six for the undecided ones
+        peak = PEAK_MFMA_BF16_TFLOPS / 3
+        extra = {"kernel": "energy_split_kernel MODE 1 + MODE 2 (fused Q^T y on the bf16 matrix cores: the three "
+                           "largest bf16 partial products for every signal + top-s0 energy + block argmax, then "
+                           "all six products for the signals that pass leaves undecided)",
+                 "peak_note": "2500 TFLOP/s dense bf16 MFMA / 3 partial products per screened product; the time "
+                              "is that of both launches",
+                 "peak_bf16_tflops": PEAK_MFMA_BF16_TFLOPS,
+                 "vs_six_product_roof": achieved / (PEAK_MFMA_BF16_TFLOPS / SPLIT_PRODUCTS),
+                 "vs_fp32_mfma_peak": achieved / PEAK_MFMA_F32_TFLOPS}
+    elif kernel == "energy_split_kernel":
         peak = PEAK_MFMA_BF16_TFLOPS / SPLIT_PRODUCTS
         extra = {"kernel": "energy_split_kernel (fused Q^T y on the bf16 matrix cores, fp32 operands as exact "
                            "sums of three bf16, six partial products + top-s0 energy + block argmax)",
@@ -151,8 +172,7 @@ def run_config(sbo, synth, torch, name, steps, warmup, arith):
     err = torch.empty(m, dtype=torch.float32, device=dev)
     sq = torch.zeros(max(steps, warmup, 1), dtype=torch.float64, device=dev)
     ctx = sbo.sbo_create(p, K, s0, m)
-    sbo.sbo_set_option(ctx, sbo.SBO_OPT_CODING_ARITH,
-                       sbo.SBO_ARITH_BF16X3 if arith == "bf16x3" else sbo.SBO_ARITH_F32)
+    sbo.sbo_set_option(ctx, sbo.SBO_OPT_CODING_ARITH, arith_value(sbo, arith))
     sbo.sbo_set_timing(ctx, 2)
     sbo.sbo_iterate(ctx, Y, D, warmup, blk, supp, coef, err, sq)
     torch.cuda.synchronize()
@@ -187,7 +207,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=30,
                     help="untimed iterations first (the clocks of an idle GPU take some tens of ms to settle)")
     ap.add_argument("--workload", default="headline")
-    ap.add_argument("--arith", default="bf16x3", choices=["f32", "bf16x3"],
+    ap.add_argument("--arith", default="bf16x3", choices=["f32", "bf16x3", "screen"],
                     help="how the projection onto all K orthobases is multiplied out (SBO_OPT_CODING_ARITH)")
     ap.add_argument("--cpu-sample", type=int, default=262144)
     ap.add_argument("--no-cpu", action="store_true")
@@ -249,8 +269,7 @@ def main() -> int:
                     "overlap_ms_mfma_valu_both": {"bf16_mfma": pb.overlap(True), "f32_mfma": pb.overlap(False)}}
 
     ctx = sbo.sbo_create(p, K, s0, m)
-    sbo.sbo_set_option(ctx, sbo.SBO_OPT_CODING_ARITH,
-                       sbo.SBO_ARITH_BF16X3 if args.arith == "bf16x3" else sbo.SBO_ARITH_F32)
+    sbo.sbo_set_option(ctx, sbo.SBO_OPT_CODING_ARITH, arith_value(sbo, args.arith))
     # Timed region: HIP events around the roofline kernel only (an event pair per stage costs
     # several microseconds on the stream); the full per-stage breakdown comes from a second,
     # untimed pass over the same number of iterations.
@@ -290,11 +309,11 @@ def main() -> int:
 
     # The same coding pass on the fp32 matrix instruction (the alternative arithmetic), for
     # comparison: its energy kernel against the fp32 MFMA peak.  Outside the timed region.
-    other = None
-    if True:
-        alt = "f32" if args.arith == "bf16x3" else "bf16x3"
-        sbo.sbo_set_option(ctx, sbo.SBO_OPT_CODING_ARITH,
-                           sbo.SBO_ARITH_F32 if alt == "f32" else sbo.SBO_ARITH_BF16X3)
+    other = []
+    for alt in ("f32", "bf16x3", "screen"):
+        if alt == args.arith or (alt == "screen" and not screening_applies(p, m)):
+            continue
+        sbo.sbo_set_option(ctx, sbo.SBO_OPT_CODING_ARITH, arith_value(sbo, alt))
         sbo.sbo_set_timing(ctx, 2)
         b2, s2, c2, e2 = blk.clone(), supp.clone(), coef.clone(), err.clone()
         sbo.sbo_code(ctx, Y, D, b2, s2, c2, e2)
@@ -304,11 +323,10 @@ def main() -> int:
             sbo.sbo_code(ctx, Y, D, b2, s2, c2, e2)
             best = min(best, sbo.sbo_stage_ms(ctx)["energy"])
         rf = roofline_entry(p, K, m, best, alt, cfg.name)
-        other = {"arith": alt, "energy_ms": best, "achieved_tflops": rf["achieved"], "peak_tflops": rf["peak"],
-                 "frac": rf["frac"], "kernel": rf["kernel"].split(" ")[0]}
+        other.append({"arith": alt, "energy_ms": best, "achieved_tflops": rf["achieved"],
+                      "peak_tflops": rf["peak"], "frac": rf["frac"], "kernel": rf["kernel"].split(" ")[0]})
         del b2, s2, c2, e2
-        sbo.sbo_set_option(ctx, sbo.SBO_OPT_CODING_ARITH,
-                           sbo.SBO_ARITH_BF16X3 if args.arith == "bf16x3" else sbo.SBO_ARITH_F32)
+    sbo.sbo_set_option(ctx, sbo.SBO_OPT_CODING_ARITH, arith_value(sbo, args.arith))
 
     # Representation only (sbo_code with a fixed dictionary: the paper's t_rep operation).
     sbo.sbo_set_timing(ctx, 0)
@@ -460,9 +478,11 @@ def main() -> int:
     if measured is not None:
         out["measured_peaks"] = measured
         out["update_hbm"]["frac_of_measured_copy"] = out["update_hbm"]["achieved_GBps"] / measured["hbm_copy_GBps"]
-        if out["roofline"]["kernel"].startswith("energy_split"):
+        if "executed_bf16_tflops" in out["roofline"]:
             out["roofline"]["frac_of_measured_random_operand_rate"] = \
                 out["roofline"]["executed_bf16_tflops"] / measured["mfma_bf16_tflops_random_operands"]
+        elif out["roofline"]["kernel"].startswith("energy_split"):
+            pass
         else:
             out["roofline"]["frac_of_measured_peak"] = out["roofline"]["achieved"] / measured["mfma_f32_tflops"]
     if next_rows is not None:

@@ -211,7 +211,7 @@ int sbo_svd_sweeps(sbo_ctx* c, int32_t* sweeps);
 enum {
     SBO_OPT_SVD_METHOD   = 0,  /* how Q_j = U V^T is computed: SBO_SVD_AUTO or SBO_SVD_JACOBI */
     SBO_OPT_CODING_ARITH = 1   /* how the projection Q_j^T y onto all K orthobases is multiplied out:
-                                  SBO_ARITH_F32 or SBO_ARITH_BF16X3 */
+                                  SBO_ARITH_F32, SBO_ARITH_BF16X3 or SBO_ARITH_BF16X3_SCREEN */
 };
 enum {
     SBO_SVD_AUTO   = 0,  /* default: Newton-Schulz polar factor on the matrix cores, the one-sided
@@ -221,11 +221,20 @@ enum {
 
 enum {
     SBO_ARITH_F32    = 0,  /* the fp32 matrix instruction (v_mfma_f32_32x32x2_f32) */
-    SBO_ARITH_BF16X3 = 1   /* default: every fp32 operand entry written as the exact sum of
-                              three bf16 numbers; the six partial products that matter at fp32 accuracy
-                              run on the bf16 matrix cores with fp32 accumulation (same fp32 inputs and
-                              outputs, rounding at the fp32 level: the dropped partial products are below
-                              2^-24 of |a||b|). */
+    SBO_ARITH_BF16X3 = 1,  /* default: every fp32 operand entry written as the exact sum of three bf16 numbers;
+                              the six partial products that matter at fp32 accuracy run on the bf16
+                              matrix cores with fp32 accumulation (same fp32 inputs and outputs, rounding
+                              at the fp32 level: the dropped partial products are below 2^-24 of |a||b|) */
+    SBO_ARITH_BF16X3_SCREEN = 2  /* as SBO_ARITH_BF16X3, but the choice of the orthobase (eq. (4))
+                              first runs with the three largest partial products only, for all signals; that
+                              decides every signal whose two best kept energies are further apart than twice
+                              the error bound of the shortened product, 2 (2 sqrt(s0) c + s0 c^2) ||y||^2 with
+                              c = 3.01 * 2^-16 + 2e-6, and only the remaining signals get the six products
+                              over all orthobases.  The chosen orthobases are those of SBO_ARITH_BF16X3;
+                              supports and coefficients always come from the six products.  Used for
+                              p <= 64 when the signals fill the chip; otherwise as SBO_ARITH_BF16X3.
+                              Pays when the orthobases are well separated (few undecided signals); with
+                              near-random orthobases it is about as fast as SBO_ARITH_BF16X3. */
 };
 
 /* Set an option for every later call on this context (Algorithm 1 steps 6-7 leave the SVD

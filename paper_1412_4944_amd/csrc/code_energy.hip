@@ -374,6 +374,52 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
 // workgroup is two teams of four wavefronts, one wavefront of each team per SIMD, half a stage
 // apart: while team 0 multiplies stage s, team 1 runs the selection networks on its stage s - 1
 // results, then the roles swap; both read the same LDS stage.  (p = 256: energy_split_wide_kernel.)
+//
+// MODE 0: as described, for every signal.
+// MODE 1 (screening): only the three largest partial products (hi*hi, hi*mid, mid*hi) are formed.
+//   With round-to-nearest parts |mid| <= 2^-8 |a| and |lo| <= 2^-16 |a|, so the dropped terms are
+//   below 3.01 * 2^-16 |a||b|, a coefficient is off by at most kScreenCoef * ||y|| (Cauchy-Schwarz
+//   over the unit atom), and a block's kept energy by at most eps = (2 sqrt(s0) kScreenCoef +
+//   s0 kScreenCoef^2) ||y||^2.  A block whose screened energy lies more than 2 eps below the best
+//   screened energy cannot be the true winner, so a signal whose two best screened energies are
+//   more than 2 eps apart has its block decided; every other signal is appended to a list
+//   (flag_ids, flag_count) and left out of the chunk histograms.
+// MODE 2 (resolution): MODE 0 for the signals of that list only (ids, *count read from device
+//   memory; workgroups past the end return at once): the full six products over all K blocks.  The
+//   list is short, so the stages are always split over blockIdx.y (as for small m); row y leaves
+//   its best (energy, block) of list entry t at blk / energy [y * m + t], and
+//   energy_resolve_merge_kernel picks the winners, writes them at the listed signals and
+//   completes the chunk histograms.
+// Half the matrix work for all signals and the full work for the few undecided ones give the same
+// blocks as the full work for all.
+// Winners of the resolution pass (energy_split_kernel MODE 2): entry t of the list has one
+// (energy, block) per row at part_* [y * m + t], rows in ascending block order; the winner goes to
+// blk / energy of signal ids[t] and into the grouping's chunk histograms.
+__global__ __launch_bounds__(256) void energy_resolve_merge_kernel(
+    const float* __restrict__ part_E, const int32_t* __restrict__ part_j, int rows, int m, int K,
+    const int32_t* __restrict__ ids, const int32_t* __restrict__ count, int32_t* __restrict__ blk,
+    float* __restrict__ energy, int32_t* __restrict__ chunk_count, int chunk) {
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= min(m, *count)) return;
+    int best = 0;
+    float bestE = -1.f;
+    for (int y = 0; y < rows; ++y) {
+        const float e = part_E[(int64_t)y * m + t];
+        if (e > bestE) {
+            bestE = e;
+            best = part_j[(int64_t)y * m + t];
+        }
+    }
+    const int i = ids[t];
+    blk[i] = best;
+    energy[i] = bestE;
+    if (chunk_count != nullptr) atomicAdd(&chunk_count[(int64_t)(i / chunk) * K + best], 1);
+}
+
+// Bound on a screened coefficient's error relative to ||y||: the three dropped partial products
+// (3.01 * 2^-16) plus the fp32 accumulation of up to 256 terms.
+constexpr float kScreenCoef = 3.01f / 65536.f + 2e-6f;
+
 template <int P>
 struct SplitGeom {
     static constexpr int MTS = 2;                        // 32-row tiles per stage
@@ -386,11 +432,11 @@ struct SplitGeom {
     static constexpr size_t LDS = (size_t)2 * STAGE_U * 16;
 };
 
-template <int P, int S, int SX>
+template <int P, int S, int SX, int MODE>
 __global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
     const float* __restrict__ Y, int m, const u32x4* __restrict__ Dsb, int K, int s0,
     int32_t* __restrict__ blk, float* __restrict__ energy, int32_t* __restrict__ chunk_count, int chunk,
-    int units_per_y) {
+    int units_per_y, int32_t* __restrict__ flag_ids, int32_t* __restrict__ flag_count, float margin_rel) {
     using G = SplitGeom<P>;
     constexpr int MTS = G::MTS, NT = G::NT, KS16 = G::KS16, STAGE_U = G::STAGE_U;
     constexpr int NTH = 64 * G::WAVES;
@@ -409,20 +455,35 @@ __global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
     const int team = G::TEAMS ? wave >> 2 : 0;           // wavefronts w and w + 4 share a SIMD
     const int h = lane >> 5, n = lane & 31;
     const int64_t sig0 = ((int64_t)blockIdx.x * G::WAVES + wave) * (32 * NT);
+    const int m_all = m;
+    if constexpr (MODE == 2) {
+        m = min(m, *flag_count);                           // the listed signals only
+        if ((int64_t)blockIdx.x * (G::WAVES * 32 * NT) >= m) return;   // uniform over the workgroup
+    }
 
     // B operand: the three bf16 parts of this lane's dims (ks*16 + h*8 .. +7) of NT signals.
     u32x4 yq[NT][KS16][3];
+    int64_t sig[NT];                     // the signal of this lane in tile column nt (-1: none)
+    int64_t tpos[NT];                    // where its result goes (MODE 2: its place in the list)
+    float yn2[NT];                       // MODE 1: this lane's share of ||y||^2
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        const int64_t i = sig0 + nt * 32 + n;
+        const int64_t t = sig0 + nt * 32 + n;
+        sig[nt] = t < m ? (MODE == 2 ? (int64_t)flag_ids[t] : t) : -1;
+        tpos[nt] = t;
+        const int64_t i = sig[nt];
+        yn2[nt] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < KS16; ++ks) {
             f32x4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = v0;
-            if (i < m) {
+            if (i >= 0) {
                 const f32x4* src = reinterpret_cast<const f32x4*>(Y + i * P + ks * 16 + h * 8);
                 v0 = src[0];
                 v1 = src[1];
             }
+            if constexpr (MODE == 1)
+                yn2[nt] += v0.x * v0.x + v0.y * v0.y + v0.z * v0.z + v0.w * v0.w + v1.x * v1.x + v1.y * v1.y +
+                           v1.z * v1.z + v1.w * v1.w;
             const Bf16x3Pair a = split_bf16x3(v0.x, v0.y), b = split_bf16x3(v0.z, v0.w);
             const Bf16x3Pair c = split_bf16x3(v1.x, v1.y), d = split_bf16x3(v1.z, v1.w);
             yq[nt][ks][0] = u32x4{a.hi, b.hi, c.hi, d.hi};
@@ -437,8 +498,8 @@ __global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
     if (units_per_y > 0) {
         s_beg = min(n_stage, (int)blockIdx.y * units_per_y * SPB);
         s_end = min(n_stage, s_beg + units_per_y * SPB);
-        blk += (int64_t)blockIdx.y * m;
-        energy += (int64_t)blockIdx.y * m;
+        blk += (int64_t)blockIdx.y * m_all;
+        energy += (int64_t)blockIdx.y * m_all;
     }
 
     u32x4 pre[FPT];
@@ -454,16 +515,18 @@ __global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
     };
 
     int best[NT];
-    float bestE[NT];
+    float bestE[NT], secondE[NT];        // secondE (MODE 1): the second-best screened energy
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         best[nt] = 0;
         bestE[nt] = -1.f;
+        secondE[nt] = -1.f;
     }
 
-    // the six partial products, smallest first: (A part, B part)
+    // the partial products, smallest first: (A part, B part); screening forms the last three
     constexpr int TA[6] = {2, 0, 1, 1, 0, 0};
     constexpr int TB[6] = {0, 2, 1, 0, 1, 0};
+    constexpr int T0 = MODE == 1 ? 3 : 0;
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
                          0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     f32x16 acc[NT][MTS];
@@ -479,7 +542,7 @@ __global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
 #pragma unroll
                 for (int pl = 0; pl < 3; ++pl) a[mt][pl] = Qs[buf][((mt * KS16 + ks) * 3 + pl) * 64 + lane];
 #pragma unroll
-            for (int t = 0; t < 6; ++t)
+            for (int t = T0; t < 6; ++t)
 #pragma unroll
                 for (int mt = 0; mt < MTS; ++mt)
 #pragma unroll
@@ -487,7 +550,7 @@ __global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
                         acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                             __builtin_bit_cast(bf16x8, a[mt][TA[t]]),
                             __builtin_bit_cast(bf16x8, yq[nt][ks][TB[t]]),
-                            (ks == 0 && t == 0) ? zero : acc[nt][mt], 0, 0, 0);
+                            (ks == 0 && t == T0) ? zero : acc[nt][mt], 0, 0, 0);
         }
     };
     // Kept energy of the wavefront's signals in the blocks of stage s (from acc) against the
@@ -506,6 +569,9 @@ __global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
                     }
                     const float e = pair_top_energy<NV, S, SX>(x, s0, h != 0);
                     const int j = s * NB + b;
+                    if constexpr (MODE == 1) {
+                        if (j < K) secondE[nt] = fmaxf(secondE[nt], fminf(e, bestE[nt]));
+                    }
                     if (j < K && e > bestE[nt]) {
                         bestE[nt] = e;
                         best[nt] = j;
@@ -535,32 +601,74 @@ __global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
     }
     if (team == 1 && s_beg < s_end) select(s_end - 1);
 
+    bool undecided[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        undecided[nt] = false;
+        if constexpr (MODE == 1) {
+            const float y2 = yn2[nt] + other_half(yn2[nt]);
+            undecided[nt] = !(bestE[nt] - secondE[nt] > margin_rel * y2);       // also for NaN
+        }
+    }
     if (h == 0) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            const int64_t i = sig0 + nt * 32 + n;
-            if (i < m) {
-                blk[i] = best[nt];
-                energy[i] = bestE[nt];
+            if (sig[nt] >= 0) {
+                blk[tpos[nt]] = best[nt];
+                energy[tpos[nt]] = bestE[nt];
             }
         }
     }
-
-    // the grouping's chunk histograms (see energy_kernel)
-    if (chunk_count != nullptr) {        // uniform
-        int* lh = reinterpret_cast<int*>(Qb_raw);          // the stage buffers are dead (>= 12 KiB): the
-                                                           // loop's last barrier follows the last read
-        for (int j = tid; j < K; j += NTH) lh[j] = 0;
-        __syncthreads();
-        if (h == 0) {
+    if constexpr (MODE == 1) {
+        // The undecided signals of the workgroup -> the list: one reservation per workgroup (a
+        // returning atomic per wavefront on the one counter would serialise thousands of them).
+        // The stage buffers are dead; the words used here lie beyond the histogram below.
+        int* fl = reinterpret_cast<int*>(Qb_raw) + 2048;   // [2 * WAVES] counts | [1] base
+        unsigned long long mask[NT];
+        bool put[NT];
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                if (sig0 + nt * 32 + n < m) atomicAdd(&lh[best[nt]], 1);
+        for (int nt = 0; nt < NT; ++nt) {
+            put[nt] = h == 0 && sig[nt] >= 0 && undecided[nt];
+            mask[nt] = __ballot(put[nt]);
+            if (lane == 0) fl[wave * NT + nt] = __popcll(mask[nt]);
         }
         __syncthreads();
-        const int64_t c = ((int64_t)blockIdx.x * (G::WAVES * 32 * NT)) / chunk;
-        for (int j = tid; j < K; j += NTH)
-            if (lh[j] != 0) atomicAdd(&chunk_count[c * K + j], lh[j]);
+        if (tid == 0) {
+            int total = 0;
+            for (int e = 0; e < G::WAVES * NT; ++e) {
+                const int c = fl[e];
+                fl[e] = total;
+                total += c;
+            }
+            fl[G::WAVES * NT] = total > 0 ? atomicAdd(flag_count, total) : 0;
+        }
+        __syncthreads();
+        const int base = fl[G::WAVES * NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            if (put[nt])
+                flag_ids[base + fl[wave * NT + nt] + __popcll(mask[nt] & ((1ull << lane) - 1ull))] =
+                    (int32_t)sig[nt];
+    }
+
+    // the grouping's chunk histograms (see energy_kernel); the undecided signals of a screening
+    // pass are added by the resolution pass
+    if (chunk_count != nullptr) {        // uniform (MODE 2: the merge kernel does this)
+        if constexpr (MODE != 2) {
+            int* lh = reinterpret_cast<int*>(Qb_raw);      // the stage buffers are dead (>= 12 KiB): the
+                                                           // loop's last barrier follows the last read
+            for (int j = tid; j < K; j += NTH) lh[j] = 0;
+            __syncthreads();
+            if (h == 0) {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    if (sig[nt] >= 0 && !undecided[nt]) atomicAdd(&lh[best[nt]], 1);
+            }
+            __syncthreads();
+            const int64_t c = ((int64_t)blockIdx.x * (G::WAVES * 32 * NT)) / chunk;
+            for (int j = tid; j < K; j += NTH)
+                if (lh[j] != 0) atomicAdd(&chunk_count[c * K + j], lh[j]);
+        }
     }
 }
 
@@ -794,7 +902,7 @@ __global__ __launch_bounds__(256) void energy_merge_kernel(const float* __restri
 template <int P, int S, int SX>
 hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, float* energy,
                       const f32x4* Dsw, const u32x4* Dsb, int32_t* chunk_count, float* part_E,
-                      int32_t* part_j, LdsRaised* raised, hipStream_t st) {
+                      int32_t* part_j, LdsRaised* raised, const EnergyScreen* scr, hipStream_t st) {
     constexpr int NT = P <= 64 ? 2 : 1;
     constexpr int QN = P / 8;
     constexpr size_t lds = (size_t)2 * (2 * QN * 64) * sizeof(f32x4);
@@ -841,9 +949,25 @@ hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, fl
         if constexpr (wide)
             hipLaunchKernelGGL((energy_split_wide_kernel<P, S, SX>), grid, dim3(64 * kWideWaves), lds_split, st,
                                Y, (int)m, Dsb, K, s0, out_j, out_E, hist, chunk, units_per_y);
-        else
-            hipLaunchKernelGGL((energy_split_kernel<P, S, SX>), grid, dim3(64 * G::WAVES), lds_split, st, Y,
-                               (int)m, Dsb, K, s0, out_j, out_E, hist, chunk, units_per_y);
+        else if (scr != nullptr && !by_rows && K > 1 && part_E != nullptr && part_j != nullptr) {
+            // screening pass over all signals, then the full products for the undecided ones
+            const float kc = kScreenCoef;
+            const float margin = 2.f * (2.f * sqrtf((float)s0) * kc + (float)s0 * kc * kc) * 1.05f;
+            hipLaunchKernelGGL((energy_split_kernel<P, S, SX, 1>), grid, dim3(64 * G::WAVES), lds_split, st, Y,
+                               (int)m, Dsb, K, s0, out_j, out_E, hist, chunk, 0, scr->ids, scr->count, margin);
+            int r_rows = units < kEnergySplitRows ? units : kEnergySplitRows;
+            const int r_upy = (units + r_rows - 1) / r_rows;
+            r_rows = (units + r_upy - 1) / r_upy;
+            hipLaunchKernelGGL((energy_split_kernel<P, S, SX, 2>), dim3(grid.x, r_rows), dim3(64 * G::WAVES),
+                               lds_split, st, Y, (int)m, Dsb, K, s0, part_j, part_E, nullptr, chunk, r_upy,
+                               scr->ids, scr->count, 0.f);
+            hipLaunchKernelGGL(energy_resolve_merge_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, st,
+                               part_E, part_j, r_rows, (int)m, K, scr->ids, scr->count, blk, energy, chunk_count,
+                               chunk);
+        } else
+            hipLaunchKernelGGL((energy_split_kernel<P, S, SX, 0>), grid, dim3(64 * G::WAVES), lds_split, st, Y,
+                               (int)m, Dsb, K, s0, out_j, out_E, hist, chunk, units_per_y, nullptr, nullptr,
+                               0.f);
     } else {
         hipLaunchKernelGGL((energy_kernel<P, S, NT, SX>), grid, dim3(256), lds, st, Y, (int)m, Dsw, K, s0,
                            out_j, out_E, hist, chunk, units_per_y);
@@ -861,19 +985,19 @@ hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, fl
 template <int P, int S>
 hipError_t launch_ps(const float* Y, int64_t m, int K, int s0, int32_t* blk, float* energy,
                      const float* dsw, const unsigned* dsb, int32_t* chunk_count, float* part_E,
-                     int32_t* part_j, LdsRaised* raised, hipStream_t st) {
+                     int32_t* part_j, LdsRaised* raised, const EnergyScreen* scr, hipStream_t st) {
     const f32x4* Dsw = reinterpret_cast<const f32x4*>(dsw);
     const u32x4* Dsb = reinterpret_cast<const u32x4*>(dsb);
     constexpr int NV = P <= 64 ? P / 2 : 32;
     if constexpr (S > NV) {
-        return launch_pse<P, S, 0>(Y, m, K, s0, blk, energy, Dsw, Dsb, chunk_count, part_E, part_j, raised, st);
+        return launch_pse<P, S, 0>(Y, m, K, s0, blk, energy, Dsw, Dsb, chunk_count, part_E, part_j, raised, scr, st);
     } else {
         switch (S - s0) {
 #define SBO_CASE(DELTA)                                                                          \
     case DELTA:                                                                                  \
         if constexpr (S - DELTA > S / 2 || S == 1)                                               \
             return launch_pse<P, S, S - DELTA>(Y, m, K, s0, blk, energy, Dsw, Dsb, chunk_count,  \
-                                               part_E, part_j, raised, st);                      \
+                                               part_E, part_j, raised, scr, st);                      \
         break;
             SBO_CASE(0) SBO_CASE(1) SBO_CASE(2) SBO_CASE(3) SBO_CASE(4) SBO_CASE(5) SBO_CASE(6) SBO_CASE(7)
 #undef SBO_CASE
@@ -886,12 +1010,12 @@ hipError_t launch_ps(const float* Y, int64_t m, int K, int s0, int32_t* blk, flo
 template <int P>
 hipError_t launch_p(int s0, const float* Y, int64_t m, int K, int32_t* blk, float* energy,
                     const float* dsw, const unsigned* dsb, int32_t* chunk_count, float* part_E,
-                    int32_t* part_j, LdsRaised* raised, hipStream_t st) {
-    if (s0 <= 1) return launch_ps<P, 1>(Y, m, K, s0, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, st);
-    if (s0 <= 2) return launch_ps<P, 2>(Y, m, K, s0, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, st);
-    if (s0 <= 4) return launch_ps<P, 4>(Y, m, K, s0, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, st);
-    if (s0 <= 8) return launch_ps<P, 8>(Y, m, K, s0, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, st);
-    return launch_ps<P, 16>(Y, m, K, s0, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, st);
+                    int32_t* part_j, LdsRaised* raised, const EnergyScreen* scr, hipStream_t st) {
+    if (s0 <= 1) return launch_ps<P, 1>(Y, m, K, s0, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, scr, st);
+    if (s0 <= 2) return launch_ps<P, 2>(Y, m, K, s0, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, scr, st);
+    if (s0 <= 4) return launch_ps<P, 4>(Y, m, K, s0, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, scr, st);
+    if (s0 <= 8) return launch_ps<P, 8>(Y, m, K, s0, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, scr, st);
+    return launch_ps<P, 16>(Y, m, K, s0, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, scr, st);
 }
 
 }  // namespace
@@ -924,12 +1048,12 @@ hipError_t launch_dict_swizzle_split(int p, int K, const float* D, unsigned* dsb
 
 hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const float* dsw,
                          const unsigned* dsb, int32_t* blk, float* energy, int32_t* chunk_count,
-                         float* part_E, int32_t* part_j, LdsRaised* raised, hipStream_t st) {
+                         float* part_E, int32_t* part_j, LdsRaised* raised, const EnergyScreen* scr, hipStream_t st) {
     switch (p) {
-        case 16: return launch_p<16>(s0, Y, m, K, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, st);
-        case 32: return launch_p<32>(s0, Y, m, K, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, st);
-        case 64: return launch_p<64>(s0, Y, m, K, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, st);
-        case 256: return launch_p<256>(s0, Y, m, K, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, st);
+        case 16: return launch_p<16>(s0, Y, m, K, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, scr, st);
+        case 32: return launch_p<32>(s0, Y, m, K, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, scr, st);
+        case 64: return launch_p<64>(s0, Y, m, K, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, scr, st);
+        case 256: return launch_p<256>(s0, Y, m, K, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, scr, st);
         default: return hipErrorInvalidValue;
     }
 }

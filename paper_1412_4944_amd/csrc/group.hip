@@ -74,7 +74,8 @@ __global__ __launch_bounds__(256) void group_hist_kernel(const int32_t* __restri
 __global__ __launch_bounds__(256) void group_scan_kernel(int32_t* __restrict__ chunk_count,
                                                          int K, int n_chunks,
                                                          int32_t* __restrict__ chunk_base,
-                                                         int32_t* __restrict__ counts) {
+                                                         int32_t* __restrict__ counts,
+                                                         int32_t* __restrict__ clear_word) {
     __shared__ int out[4 * 256 + 1];
     __shared__ int tmp[16];
     const int j = blockIdx.x;
@@ -91,6 +92,8 @@ __global__ __launch_bounds__(256) void group_scan_kernel(int32_t* __restrict__ c
         __syncthreads();
     }
     if (threadIdx.x == 0) counts[j] = carry;
+    // the coding kernel's count of undecided signals has been consumed by now
+    if (clear_word != nullptr && j == 0 && threadIdx.x == 0) *clear_word = 0;
 }
 
 // 3. perm[offsets[j] + chunk_base[c][j] + rank inside the chunk] = signal id.
@@ -157,7 +160,7 @@ hipError_t launch_group(int K, const int32_t* blk, int64_t m, const Workspace& w
         hipLaunchKernelGGL(group_hist_kernel, dim3(wgs), dim3(256), 4 * K * sizeof(int), st, blk,
                            (int)m, K, g.chunk, g.n_chunks, ws.chunk_count);
     hipLaunchKernelGGL(group_scan_kernel, dim3(K), dim3(256), 0, st, ws.chunk_count, K,
-                       g.n_chunks, ws.chunk_base, ws.counts);
+                       g.n_chunks, ws.chunk_base, ws.counts, ws.flag_count);
     hipLaunchKernelGGL(group_scatter_kernel, dim3(wgs), dim3(256),
                        (K + 1 + 16 + 4 * K) * sizeof(int), st, blk, (int)m, K, g.chunk, g.n_chunks,
                        ws.chunk_base, ws.counts, ws.offsets, ws.perm);
@@ -182,7 +185,7 @@ hipError_t launch_group_static(int K, const int32_t* blk, int64_t m, int32_t* co
     hipLaunchKernelGGL(group_hist_kernel, dim3(wgs), dim3(256), 4 * K * sizeof(int), st, blk, (int)m, K,
                        g.chunk, g.n_chunks, chunk_count);
     hipLaunchKernelGGL(group_scan_kernel, dim3(K), dim3(256), 0, st, chunk_count, K, g.n_chunks,
-                       chunk_base, counts);
+                       chunk_base, counts, nullptr);
     hipLaunchKernelGGL(group_scatter_kernel, dim3(wgs), dim3(256), (K + 1 + 16 + 4 * K) * sizeof(int), st,
                        blk, (int)m, K, g.chunk, g.n_chunks, chunk_base, counts, offsets, perm);
     return hipGetLastError();

@@ -34,7 +34,7 @@ size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char
     w.energy = (float*)take((size_t)m_max * 4);
     w.dsw = (float*)take((size_t)((K * p + 63) / 64) * 64 * p * 4);
     w.dsb = (unsigned*)take((size_t)((K * p + 63) / 64) * 64 * p * 6);
-    const size_t split_m = (size_t)(m_max < kEnergySplitSignals ? m_max : kEnergySplitSignals);
+    const size_t split_m = (size_t)m_max;      // small m: one entry per signal; resolution pass: per list entry
     w.part_E = (float*)take((size_t)kEnergySplitRows * split_m * 4);
     w.part_j = (int32_t*)take((size_t)kEnergySplitRows * split_m * 4);
     w.partial = (float*)take((size_t)max_pieces_bound(m_max, K, p) * p * p * 4);
@@ -50,6 +50,8 @@ size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char
     w.sel_ids = (int32_t*)take((size_t)m_max * 4);
     w.sq_out = (double*)take(8);
     w.sq_counter = (int32_t*)take(4);
+    w.flag_ids = (int32_t*)take((size_t)m_max * 4);
+    w.flag_count = (int32_t*)take(4);
     w.sweeps = (int32_t*)take((size_t)K * 4);
     w.ns_fallback = (int32_t*)take((size_t)K * 4);
     w.sq_partial = (double*)take((size_t)kSqBlocks * 8);
@@ -120,7 +122,7 @@ static int run_group(sbo_ctx* c, const int32_t* blk, int64_t m, bool have_hist =
 }
 
 // The coding kernel reads the split dictionary (bf16 matrix cores) or the fp32 one.
-static bool use_split(const sbo_ctx* c) { return c->coding_arith == SBO_ARITH_BF16X3; }
+static bool use_split(const sbo_ctx* c) { return c->coding_arith != SBO_ARITH_F32; }
 
 // D in the operand order(s) the coding kernels of this context read (tiny; outside the stages).
 static int run_swizzle(sbo_ctx* c, const float* D) {
@@ -131,9 +133,10 @@ static int run_swizzle(sbo_ctx* c, const float* D) {
 
 static int run_energy(sbo_ctx* c, const float* Y, int64_t m, int32_t* blk) {
     StageTimer t(c, SBO_STAGE_ENERGY);     // also leaves the chunk histograms of the grouping
+    const EnergyScreen scr{c->ws.flag_ids, c->ws.flag_count};
     SBO_HIP(launch_energy(c->p, c->K, c->s0, Y, m, c->ws.dsw, use_split(c) ? c->ws.dsb : nullptr, blk,
                           c->ws.energy, c->ws.chunk_count, c->ws.part_E, c->ws.part_j, &c->raised,
-                          c->stream));
+                          c->coding_arith == SBO_ARITH_BF16X3_SCREEN ? &scr : nullptr, c->stream));
     return SBO_OK;
 }
 
@@ -227,6 +230,7 @@ int sbo_create(sbo_ctx** out, int p, int K, int s0, int64_t m_max, void* hip_str
     // finished-workgroup counter are zero whenever no call is in flight.
     e = hipMemsetAsync(c->ws.chunk_count, 0, (size_t)max_chunks() * K * 4, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->ws.sq_counter, 0, 4, c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(c->ws.flag_count, 0, 4, c->stream);
     if (e != hipSuccess) {
         (void)hipFree(c->ws_base);
         delete c;
@@ -583,7 +587,8 @@ int sbo_set_option(sbo_ctx* c, int option, int value) {
             c->svd_method = value;
             return SBO_OK;
         case SBO_OPT_CODING_ARITH:
-            if (value != SBO_ARITH_F32 && value != SBO_ARITH_BF16X3) return SBO_EINVAL;
+            if (value != SBO_ARITH_F32 && value != SBO_ARITH_BF16X3 && value != SBO_ARITH_BF16X3_SCREEN)
+                return SBO_EINVAL;
             c->coding_arith = value;
             return SBO_OK;
         default: return SBO_EINVAL;

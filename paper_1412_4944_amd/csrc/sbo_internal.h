@@ -91,7 +91,7 @@ struct Workspace {
     float* energy;         // [m_max] kept energy in the winning block
     float* dsw;            // [ceil(K*p/64)*64][p] dictionary in MFMA operand order
     unsigned* dsb;         // the same rows as three bf16 parts in the split operand order (6 bytes per entry)
-    float* part_E;         // [kEnergySplitRows][min(m_max, kEnergySplitSignals)] split coding: best energy per row
+    float* part_E;         // [kEnergySplitRows][m_max] split coding / resolution pass: best energy per row
     int32_t* part_j;       // same shape: its block
     // accumulation
     float* partial;        // [max_pieces][p][p]
@@ -108,6 +108,8 @@ struct Workspace {
     int32_t* sweeps;       // [K] most recent SVD stage: Jacobi sweeps, or minus the Newton-Schulz steps
     int32_t* ns_fallback;  // [K] 1 = Newton-Schulz left the block to the Jacobi kernel
     int32_t* sq_counter;   // [1] workgroups of the fused squared-error sum that have finished (0 between launches)
+    int32_t* flag_ids;     // [m_max] signals whose block the screening pass of the coding kernel left undecided
+    int32_t* flag_count;   // [1] how many (0 between calls: the grouping's scan kernel clears it)
     // iterate
     double* sq_partial;    // [kSqBlocks]
     size_t bytes;
@@ -137,7 +139,7 @@ struct sbo_ctx {
     char* ws_base;
     sbo::Workspace ws;
     int svd_method;                  // SBO_SVD_AUTO or SBO_SVD_JACOBI (sbo_set_option)
-    int coding_arith;                // SBO_ARITH_F32 or SBO_ARITH_BF16X3 (sbo_set_option)
+    int coding_arith;                // SBO_ARITH_* (sbo_set_option)
     sbo::LdsRaised raised;
     int timing;
     std::vector<sbo_span> spans;     // event pool; the first n_spans are in use
@@ -153,13 +155,24 @@ hipError_t launch_dict_swizzle(int p, int K, const float* D, float* dsw, hipStre
 hipError_t launch_dict_swizzle_split(int p, int K, const float* D, unsigned* dsb, hipStream_t st);
 // chunk_count != nullptr: also add the per-chunk histograms of the chosen blocks into it (the
 // first step of launch_group; the array must be zero on entry, launch_group leaves it so).
-// part_E / part_j ([kEnergySplitRows][min(m_max, kEnergySplitSignals)], may be nullptr): scratch
-// for small m, where the blocks are split over several workgroup rows to fill the chip.
+// part_E / part_j ([kEnergySplitRows][m_max], may be nullptr): scratch for small m (at most
+// kEnergySplitSignals), where the blocks are split over several workgroup rows to fill the chip,
+// and for the resolution pass of the screening (scr), which is always split that way.
 // dsb != nullptr: the projection runs on the bf16 matrix cores from the split
 // dictionary (dsw is then not read); otherwise on the fp32 matrix instruction from dsw.
+// scr != nullptr (with dsb, p <= 64, enough signals to fill the chip): a screening pass with half
+// the matrix work decides the block of every signal whose two best energies are further apart
+// than the screening error allows, and the full products are formed only for the rest, listed in
+// scr->ids ([m]) / scr->count ([1], zero on entry; launch_group sets it back to zero).  The
+// energies written for decided signals are then the screened ones.
+struct EnergyScreen {
+    int32_t* ids;
+    int32_t* count;
+};
 hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const float* dsw,
                          const unsigned* dsb, int32_t* blk, float* energy, int32_t* chunk_count,
-                         float* part_E, int32_t* part_j, LdsRaised* raised, hipStream_t st);
+                         float* part_E, int32_t* part_j, LdsRaised* raised, const EnergyScreen* scr,
+                         hipStream_t st);
 
 hipError_t launch_group(int K, const int32_t* blk, int64_t m, const Workspace& ws, bool have_hist,
                         hipStream_t st);

@@ -29,9 +29,11 @@ class Sbo:
             self.coding_arith(arith)
 
     def coding_arith(self, name):
-        """"f32": fp32 matrix instruction; "bf16x3": three-part bf16 split on the bf16 matrix cores."""
+        """"f32": fp32 matrix instruction; "bf16x3": three-part bf16 split on the bf16 matrix cores;
+        "screen": the same with the block choice screened by the three largest partial products."""
         sbo.sbo_set_option(self.ctx, sbo.SBO_OPT_CODING_ARITH,
-                           {"f32": sbo.SBO_ARITH_F32, "bf16x3": sbo.SBO_ARITH_BF16X3}[name])
+                           {"f32": sbo.SBO_ARITH_F32, "bf16x3": sbo.SBO_ARITH_BF16X3,
+                            "screen": sbo.SBO_ARITH_BF16X3_SCREEN}[name])
 
     def svd_jacobi(self, on):
         """Jacobi SVD for every orthobase (on) or the default Newton-Schulz + Jacobi fallback."""

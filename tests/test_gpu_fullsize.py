@@ -47,6 +47,7 @@ def _sample_ids(m, n, seed):
 
 
 @pytest.mark.parametrize("name,n_sample,arith", [("headline", 262144, "f32"), ("headline", 262144, "bf16x3"),
+                                                 ("headline", 262144, "screen"), ("skew", 110000, "screen"),
                                                  ("skew", 110000, "f32"), ("skew", 110000, "bf16x3"),
                                                  ("patch16", 14000, "f32"), ("patch16", 14000, "bf16x3")])
 def test_full_size_iteration_against_oracle(name, n_sample, arith):
@@ -96,7 +97,7 @@ def test_full_size_iteration_against_oracle(name, n_sample, arith):
         compare_code(pr.Y[ids], Dg, cfg.s0, o2, (b2[ids], s2[ids], c2[ids], e2[ids]))
 
 
-@pytest.mark.parametrize("arith", ["f32", "bf16x3"])
+@pytest.mark.parametrize("arith", ["f32", "bf16x3", "screen"])
 @pytest.mark.parametrize("name", ["patch8", "headline"])
 def test_full_size_configured_iterations(name, arith):
     """The configured number of iterations (10) at the stated size, free-running on both sides:
@@ -228,3 +229,25 @@ def test_full_size_learn_patch8():
         Dg = D.cpu().numpy().astype(np.float64)
         for j in range(Kf):
             assert np.abs(Dg[j] @ Dg[j].T - np.eye(p)).max() <= 1e-5
+
+
+@pytest.mark.parametrize("name", ["headline", "skew"])
+def test_screened_block_choice_equals_the_full_products(name):
+    """SBO_ARITH_BF16X3_SCREEN decides most signals' orthobase from the three largest partial
+    products and forms all six only for the undecided ones: every output must be bit-identical to
+    SBO_ARITH_BF16X3, which forms all six for every signal (random initial dictionary: the
+    energies of the orthobases are close, many signals are undecided; planted dictionary: few)."""
+    cfg = synth.CONFIGS[name]
+    pr = _problem_of(name)
+    m = pr.Y.shape[0]
+    print(f"case {name}: p={cfg.p} K={cfg.K} m={m} s0={cfg.s0}", flush=True)
+    with Sbo(cfg.p, cfg.K, cfg.s0, m) as g:
+        for D in (pr.D_init, pr.D_planted):
+            g.coding_arith("bf16x3")
+            ref = g.code(pr.Y, D)
+            g.coding_arith("screen")
+            out = g.code(pr.Y, D)
+            out2 = g.code(pr.Y, D)
+            for a, b, c in zip(ref, out, out2):
+                assert np.array_equal(a, b), "screened coding differs from the full products"
+                assert np.array_equal(b, c), "screened coding is not repeatable"
