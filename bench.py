@@ -35,7 +35,8 @@ def roofline_kernel_name(p: int, arith: str) -> str:
 
 
 def arith_value(sbo, arith: str) -> int:
-    return {"f32": sbo.SBO_ARITH_F32, "bf16x3": sbo.SBO_ARITH_BF16X3, "screen": sbo.SBO_ARITH_BF16X3_SCREEN}[arith]
+    return {"f32": sbo.SBO_ARITH_F32, "bf16x3": sbo.SBO_ARITH_BF16X3, "screen": sbo.SBO_ARITH_BF16X3_SCREEN,
+            "f16x2": sbo.SBO_ARITH_F16X2}[arith]
 
 
 def screening_applies(p: int, m: int) -> bool:
@@ -143,6 +144,23 @@ def roofline_entry(p, K, m, energy_ms, arith, workload):
                  "peak_bf16_tflops": PEAK_MFMA_BF16_TFLOPS,
                  "vs_six_product_roof": achieved / (PEAK_MFMA_BF16_TFLOPS / SPLIT_PRODUCTS),
                  "vs_fp32_mfma_peak": achieved / PEAK_MFMA_F32_TFLOPS}
+    elif arith == "f16x2" and p <= 64:
+        peak = PEAK_MFMA_BF16_TFLOPS / 3          # fp16 and bf16 MFMA share the 2500 TFLOP/s peak
+        # the selection networks: 276 vector instructions per tile of 32 signals and block (counted in
+        # the kernel's ISA), one lane-operation per lane and instruction, against 256 CUs x 64 lanes x 2.4 GHz
+        sel_ops = 276.0 * 64.0 * (K * m / 32.0)
+        sel_peak = 256 * 64 * 2.4e9
+        extra = {"kernel": "energy_split_kernel MODE 3 (fused Q^T y on the fp16 matrix cores, fp32 operands scaled "
+                           "and written as hi + lo in fp16, three partial products + top-s0 energy + block argmax)",
+                 "peak_note": "2500 TFLOP/s dense fp16 MFMA / 3 partial products per product; the kernel's time is "
+                              "0.70 x (matrix part + selection networks on the vector ALU), see selection_alu",
+                 "executed_f16_tflops": achieved * 3, "peak_f16_tflops": PEAK_MFMA_BF16_TFLOPS,
+                 "vs_six_product_roof": achieved / (PEAK_MFMA_BF16_TFLOPS / SPLIT_PRODUCTS),
+                 "vs_fp32_mfma_peak": achieved / PEAK_MFMA_F32_TFLOPS,
+                 "selection_alu": {"lane_ops_per_launch": sel_ops,
+                                   "achieved_Tops": sel_ops / (energy_ms * 1e-3) / 1e12,
+                                   "peak_Tops": sel_peak / 1e12,
+                                   "frac": sel_ops / (energy_ms * 1e-3) / sel_peak}}
     elif kernel == "energy_split_kernel":
         peak = PEAK_MFMA_BF16_TFLOPS / SPLIT_PRODUCTS
         extra = {"kernel": "energy_split_kernel (fused Q^T y on the bf16 matrix cores, fp32 operands as exact "
@@ -207,7 +225,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=30,
                     help="untimed iterations first (the clocks of an idle GPU take some tens of ms to settle)")
     ap.add_argument("--workload", default="headline")
-    ap.add_argument("--arith", default="bf16x3", choices=["f32", "bf16x3", "screen"],
+    ap.add_argument("--arith", default="f16x2", choices=["f32", "bf16x3", "screen", "f16x2"],
                     help="how the projection onto all K orthobases is multiplied out (SBO_OPT_CODING_ARITH)")
     ap.add_argument("--cpu-sample", type=int, default=262144)
     ap.add_argument("--no-cpu", action="store_true")
@@ -310,7 +328,7 @@ def main() -> int:
     # The same coding pass on the fp32 matrix instruction (the alternative arithmetic), for
     # comparison: its energy kernel against the fp32 MFMA peak.  Outside the timed region.
     other = []
-    for alt in ("f32", "bf16x3", "screen"):
+    for alt in ("f32", "bf16x3", "screen", "f16x2"):
         if alt == args.arith or (alt == "screen" and not screening_applies(p, m)):
             continue
         sbo.sbo_set_option(ctx, sbo.SBO_OPT_CODING_ARITH, arith_value(sbo, alt))
@@ -478,9 +496,9 @@ def main() -> int:
     if measured is not None:
         out["measured_peaks"] = measured
         out["update_hbm"]["frac_of_measured_copy"] = out["update_hbm"]["achieved_GBps"] / measured["hbm_copy_GBps"]
-        if "executed_bf16_tflops" in out["roofline"]:
-            out["roofline"]["frac_of_measured_random_operand_rate"] = \
-                out["roofline"]["executed_bf16_tflops"] / measured["mfma_bf16_tflops_random_operands"]
+        if "executed_bf16_tflops" in out["roofline"] or "executed_f16_tflops" in out["roofline"]:
+            ex = out["roofline"].get("executed_bf16_tflops", out["roofline"].get("executed_f16_tflops"))
+            out["roofline"]["frac_of_measured_random_operand_rate"] = ex / measured["mfma_bf16_tflops_random_operands"]
         elif out["roofline"]["kernel"].startswith("energy_split"):
             pass
         else:

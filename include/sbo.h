@@ -211,7 +211,7 @@ int sbo_svd_sweeps(sbo_ctx* c, int32_t* sweeps);
 enum {
     SBO_OPT_SVD_METHOD   = 0,  /* how Q_j = U V^T is computed: SBO_SVD_AUTO or SBO_SVD_JACOBI */
     SBO_OPT_CODING_ARITH = 1   /* how the projection Q_j^T y onto all K orthobases is multiplied out:
-                                  SBO_ARITH_F32, SBO_ARITH_BF16X3 or SBO_ARITH_BF16X3_SCREEN */
+                                  SBO_ARITH_F32, SBO_ARITH_BF16X3, SBO_ARITH_BF16X3_SCREEN or SBO_ARITH_F16X2 */
 };
 enum {
     SBO_SVD_AUTO   = 0,  /* default: Newton-Schulz polar factor on the matrix cores, the one-sided
@@ -221,10 +221,20 @@ enum {
 
 enum {
     SBO_ARITH_F32    = 0,  /* the fp32 matrix instruction (v_mfma_f32_32x32x2_f32) */
-    SBO_ARITH_BF16X3 = 1,  /* default: every fp32 operand entry written as the exact sum of three bf16 numbers;
+    SBO_ARITH_BF16X3 = 1,  /* every fp32 operand entry written as the exact sum of three bf16 numbers;
                               the six partial products that matter at fp32 accuracy run on the bf16
                               matrix cores with fp32 accumulation (same fp32 inputs and outputs, rounding
                               at the fp32 level: the dropped partial products are below 2^-24 of |a||b|) */
+    SBO_ARITH_F16X2 = 3,   /* default: the choice of the orthobase (eq. (4)) on the fp16 matrix cores: every signal
+                              scaled by a power of two, signal and dictionary entries each written as
+                              hi + lo in fp16 (22 significand bits), three partial products with fp32
+                              accumulation: per-term error 3 * 2^-22 |a||b|, below the p * 2^-24 sum |a||b|
+                              an fp32 dot product of p terms guarantees; half the matrix work of
+                              SBO_ARITH_BF16X3.  Supports and coefficients still come from the six bf16
+                              products.  p <= 64; p = 256 runs as SBO_ARITH_BF16X3.  Dictionary entries
+                              must be below 8 in magnitude (orthonormal atoms: at most 1); a signal whose
+                              largest magnitude is below 2^-63 is coded as a zero signal (its energies
+                              underflow in fp32 under any arithmetic). */
     SBO_ARITH_BF16X3_SCREEN = 2  /* as SBO_ARITH_BF16X3, but the choice of the orthobase (eq. (4))
                               first runs with the three largest partial products only, for all signals; that
                               decides every signal whose two best kept energies are further apart than twice

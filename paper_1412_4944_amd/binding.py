@@ -220,7 +220,7 @@ def sbo_svd_sweeps(ctx, K: int) -> list:
 
 SBO_OPT_SVD_METHOD, SBO_OPT_CODING_ARITH = 0, 1
 SBO_SVD_AUTO, SBO_SVD_JACOBI = 0, 1
-SBO_ARITH_F32, SBO_ARITH_BF16X3, SBO_ARITH_BF16X3_SCREEN = 0, 1, 2
+SBO_ARITH_F32, SBO_ARITH_BF16X3, SBO_ARITH_BF16X3_SCREEN, SBO_ARITH_F16X2 = 0, 1, 2, 3
 
 
 def sbo_set_option(ctx, option: int, value: int) -> None:

@@ -144,11 +144,11 @@ __global__ __launch_bounds__(256) void dict_swizzle_kernel(const float* __restri
 
 // The same dictionary in the split operand order (see device_utils.h): every entry as three
 // bf16 parts, 8 consecutive dims of a row per 16-byte unit and part.
-template <int P>
+template <int P, int NPL>
 __global__ __launch_bounds__(256) void dict_swizzle_split_kernel(const float* __restrict__ D, int K,
                                                                  u32x4* __restrict__ Dsb) {
     constexpr int KS16 = P / 16;
-    constexpr int STAGE_U = 2 * KS16 * 3 * 64;
+    constexpr int STAGE_U = 2 * KS16 * NPL * 64;
     const f32x4* D4 = reinterpret_cast<const f32x4*>(D);
     const int rows = K * P;
     const int s = blockIdx.x;
@@ -161,12 +161,20 @@ __global__ __launch_bounds__(256) void dict_swizzle_split_kernel(const float* __
             v0 = D4[(int64_t)grow * (P / 4) + ks * 4 + hh * 2];
             v1 = D4[(int64_t)grow * (P / 4) + ks * 4 + hh * 2 + 1];
         }
-        const Bf16x3Pair a = split_bf16x3(v0.x, v0.y), b = split_bf16x3(v0.z, v0.w);
-        const Bf16x3Pair c = split_bf16x3(v1.x, v1.y), d = split_bf16x3(v1.z, v1.w);
-        u32x4* out = Dsb + (int64_t)s * STAGE_U + (mk * 3) * 64 + lane;
-        out[0] = u32x4{a.hi, b.hi, c.hi, d.hi};
-        out[64] = u32x4{a.mid, b.mid, c.mid, d.mid};
-        out[128] = u32x4{a.lo, b.lo, c.lo, d.lo};
+        u32x4* out = Dsb + (int64_t)s * STAGE_U + (mk * NPL) * 64 + lane;
+        if constexpr (NPL == 3) {
+            const Bf16x3Pair a = split_bf16x3(v0.x, v0.y), b = split_bf16x3(v0.z, v0.w);
+            const Bf16x3Pair c = split_bf16x3(v1.x, v1.y), d = split_bf16x3(v1.z, v1.w);
+            out[0] = u32x4{a.hi, b.hi, c.hi, d.hi};
+            out[64] = u32x4{a.mid, b.mid, c.mid, d.mid};
+            out[128] = u32x4{a.lo, b.lo, c.lo, d.lo};
+        } else {
+            constexpr float sc = kF16DictScale;
+            const F16x2Pair a = split_f16x2(v0.x * sc, v0.y * sc), b = split_f16x2(v0.z * sc, v0.w * sc);
+            const F16x2Pair c = split_f16x2(v1.x * sc, v1.y * sc), d = split_f16x2(v1.z * sc, v1.w * sc);
+            out[0] = u32x4{a.hi, b.hi, c.hi, d.hi};
+            out[64] = u32x4{a.lo, b.lo, c.lo, d.lo};
+        }
     }
 }
 
@@ -392,6 +400,14 @@ __global__ __launch_bounds__(256) void energy_kernel(const float* __restrict__ Y
 //   completes the chunk histograms.
 // Half the matrix work for all signals and the full work for the few undecided ones give the same
 // blocks as the full work for all.
+//
+// MODE 3 (two fp16 parts, device_utils.h): the signals are scaled by a power of two each (largest
+//   magnitude into [2^13, 2^14)), the dictionary by kF16DictScale, both split into hi + lo in fp16,
+//   and the three products hi*lo, lo*hi, hi*hi run on v_mfma_f32_32x32x16_f16 into the one fp32
+//   accumulator: half the matrix work and two thirds of the operand traffic of MODE 0, with a
+//   per-term error of 3 * 2^-22 |a b| (an fp32 dot product of p terms guarantees p * 2^-24 sum |a b|).
+//   The choice of the block does not see the scales (common to all blocks of a signal); the
+//   energy written out is scaled back.
 // Winners of the resolution pass (energy_split_kernel MODE 2): entry t of the list has one
 // (energy, block) per row at part_* [y * m + t], rows in ascending block order; the winner goes to
 // blk / energy of signal ids[t] and into the grouping's chunk histograms.
@@ -420,24 +436,28 @@ __global__ __launch_bounds__(256) void energy_resolve_merge_kernel(
 // (3.01 * 2^-16) plus the fp32 accumulation of up to 256 terms.
 constexpr float kScreenCoef = 3.01f / 65536.f + 2e-6f;
 
-template <int P>
+constexpr int kSplitWgWaves = 8;
+
+template <int P, int NPL = 3>
 struct SplitGeom {
     static constexpr int MTS = 2;                        // 32-row tiles per stage
     static constexpr int NT = 2;                         // 32-signal tile columns per wavefront
-    static constexpr int WAVES = 8;
+    static constexpr int WAVES = kSplitWgWaves;
     static constexpr bool TEAMS = true;
     static constexpr int KS16 = P / 16;                  // contraction steps of 16 dims
     static constexpr int STAGE_ROWS = 32 * MTS;
-    static constexpr int STAGE_U = MTS * KS16 * 3 * 64;  // 16-byte units per stage
+    static constexpr int STAGE_U = MTS * KS16 * NPL * 64;   // 16-byte units per stage
     static constexpr size_t LDS = (size_t)2 * STAGE_U * 16;
 };
 
 template <int P, int S, int SX, int MODE>
-__global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
+__global__ __launch_bounds__(64 * kSplitWgWaves) void energy_split_kernel(
     const float* __restrict__ Y, int m, const u32x4* __restrict__ Dsb, int K, int s0,
     int32_t* __restrict__ blk, float* __restrict__ energy, int32_t* __restrict__ chunk_count, int chunk,
     int units_per_y, int32_t* __restrict__ flag_ids, int32_t* __restrict__ flag_count, float margin_rel) {
-    using G = SplitGeom<P>;
+    constexpr bool F16 = MODE == 3;
+    constexpr int NPL = F16 ? 2 : 3;           // operand parts
+    using G = SplitGeom<P, NPL>;
     constexpr int MTS = G::MTS, NT = G::NT, KS16 = G::KS16, STAGE_U = G::STAGE_U;
     constexpr int NTH = 64 * G::WAVES;
     constexpr int NB = 64 / P;                 // blocks per stage
@@ -461,11 +481,12 @@ __global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
         if ((int64_t)blockIdx.x * (G::WAVES * 32 * NT) >= m) return;   // uniform over the workgroup
     }
 
-    // B operand: the three bf16 parts of this lane's dims (ks*16 + h*8 .. +7) of NT signals.
-    u32x4 yq[NT][KS16][3];
+    // B operand: the parts of this lane's dims (ks*16 + h*8 .. +7) of NT signals.
+    u32x4 yq[NT][KS16][NPL];
     int64_t sig[NT];                     // the signal of this lane in tile column nt (-1: none)
     int64_t tpos[NT];                    // where its result goes (MODE 2: its place in the list)
     float yn2[NT];                       // MODE 1: this lane's share of ||y||^2
+    float unscale[NT];                   // MODE 3: 1 / (scale of the signal * scale of the dictionary)^2
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         const int64_t t = sig0 + nt * 32 + n;
@@ -473,22 +494,50 @@ __global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
         tpos[nt] = t;
         const int64_t i = sig[nt];
         yn2[nt] = 0.f;
+        unscale[nt] = 1.f;
+        f32x4 raw[KS16][2];
 #pragma unroll
         for (int ks = 0; ks < KS16; ++ks) {
-            f32x4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = v0;
+            raw[ks][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+            raw[ks][1] = raw[ks][0];
             if (i >= 0) {
                 const f32x4* src = reinterpret_cast<const f32x4*>(Y + i * P + ks * 16 + h * 8);
-                v0 = src[0];
-                v1 = src[1];
+                raw[ks][0] = src[0];
+                raw[ks][1] = src[1];
             }
+        }
+        float scale = 1.f;
+        if constexpr (F16) {
+            float vmax = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KS16; ++ks)
+#pragma unroll
+                for (int e = 0; e < 2; ++e)
+                    vmax = fmaxf(fmaxf(fmaxf(vmax, fabsf(raw[ks][e].x)), fmaxf(fabsf(raw[ks][e].y), fabsf(raw[ks][e].z))),
+                                 fabsf(raw[ks][e].w));
+            vmax = fmaxf(vmax, other_half(vmax));
+            scale = f16_signal_scale(vmax);
+            const float inv = 1.f / (scale * kF16DictScale);       // a power of two: exact
+            unscale[nt] = inv * inv;
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS16; ++ks) {
+            const f32x4 v0 = raw[ks][0], v1 = raw[ks][1];
             if constexpr (MODE == 1)
                 yn2[nt] += v0.x * v0.x + v0.y * v0.y + v0.z * v0.z + v0.w * v0.w + v1.x * v1.x + v1.y * v1.y +
                            v1.z * v1.z + v1.w * v1.w;
-            const Bf16x3Pair a = split_bf16x3(v0.x, v0.y), b = split_bf16x3(v0.z, v0.w);
-            const Bf16x3Pair c = split_bf16x3(v1.x, v1.y), d = split_bf16x3(v1.z, v1.w);
-            yq[nt][ks][0] = u32x4{a.hi, b.hi, c.hi, d.hi};
-            yq[nt][ks][1] = u32x4{a.mid, b.mid, c.mid, d.mid};
-            yq[nt][ks][2] = u32x4{a.lo, b.lo, c.lo, d.lo};
+            if constexpr (F16) {
+                const F16x2Pair a = split_f16x2(v0.x * scale, v0.y * scale), b = split_f16x2(v0.z * scale, v0.w * scale);
+                const F16x2Pair c = split_f16x2(v1.x * scale, v1.y * scale), d = split_f16x2(v1.z * scale, v1.w * scale);
+                yq[nt][ks][0] = u32x4{a.hi, b.hi, c.hi, d.hi};
+                yq[nt][ks][1] = u32x4{a.lo, b.lo, c.lo, d.lo};
+            } else {
+                const Bf16x3Pair a = split_bf16x3(v0.x, v0.y), b = split_bf16x3(v0.z, v0.w);
+                const Bf16x3Pair c = split_bf16x3(v1.x, v1.y), d = split_bf16x3(v1.z, v1.w);
+                yq[nt][ks][0] = u32x4{a.hi, b.hi, c.hi, d.hi};
+                yq[nt][ks][1] = u32x4{a.mid, b.mid, c.mid, d.mid};
+                yq[nt][ks][2] = u32x4{a.lo, b.lo, c.lo, d.lo};
+            }
         }
     }
 
@@ -523,10 +572,12 @@ __global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
         secondE[nt] = -1.f;
     }
 
-    // the partial products, smallest first: (A part, B part); screening forms the last three
-    constexpr int TA[6] = {2, 0, 1, 1, 0, 0};
-    constexpr int TB[6] = {0, 2, 1, 0, 1, 0};
+    // the partial products, smallest first: (A part, B part); screening forms the last three of
+    // the bf16 list, the fp16 parts have three in all
+    constexpr int TA[6] = {F16 ? 0 : 2, F16 ? 1 : 0, F16 ? 0 : 1, 1, 0, 0};
+    constexpr int TB[6] = {F16 ? 1 : 0, F16 ? 0 : 2, F16 ? 0 : 1, 0, 1, 0};
     constexpr int T0 = MODE == 1 ? 3 : 0;
+    constexpr int T1 = F16 ? 3 : 6;
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
                          0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     f32x16 acc[NT][MTS];
@@ -536,21 +587,27 @@ __global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
     auto project = [&](int buf) {
 #pragma unroll
         for (int ks = 0; ks < KS16; ++ks) {
-            u32x4 a[MTS][3];
+            u32x4 a[MTS][NPL];
 #pragma unroll
             for (int mt = 0; mt < MTS; ++mt)
 #pragma unroll
-                for (int pl = 0; pl < 3; ++pl) a[mt][pl] = Qs[buf][((mt * KS16 + ks) * 3 + pl) * 64 + lane];
+                for (int pl = 0; pl < NPL; ++pl) a[mt][pl] = Qs[buf][((mt * KS16 + ks) * NPL + pl) * 64 + lane];
 #pragma unroll
-            for (int t = T0; t < 6; ++t)
+            for (int t = T0; t < T1; ++t)
 #pragma unroll
                 for (int mt = 0; mt < MTS; ++mt)
 #pragma unroll
-                    for (int nt = 0; nt < NT; ++nt)
-                        acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, a[mt][TA[t]]),
-                            __builtin_bit_cast(bf16x8, yq[nt][ks][TB[t]]),
-                            (ks == 0 && t == T0) ? zero : acc[nt][mt], 0, 0, 0);
+                    for (int nt = 0; nt < NT; ++nt) {
+                        const f32x16 c_in = (ks == 0 && t == T0) ? zero : acc[nt][mt];
+                        if constexpr (F16)
+                            acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                                __builtin_bit_cast(f16x8, a[mt][TA[t]]), __builtin_bit_cast(f16x8, yq[nt][ks][TB[t]]),
+                                c_in, 0, 0, 0);
+                        else
+                            acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                __builtin_bit_cast(bf16x8, a[mt][TA[t]]),
+                                __builtin_bit_cast(bf16x8, yq[nt][ks][TB[t]]), c_in, 0, 0, 0);
+                    }
         }
     };
     // Kept energy of the wavefront's signals in the blocks of stage s (from acc) against the
@@ -615,7 +672,7 @@ __global__ __launch_bounds__(64 * SplitGeom<P>::WAVES) void energy_split_kernel(
         for (int nt = 0; nt < NT; ++nt) {
             if (sig[nt] >= 0) {
                 blk[tpos[nt]] = best[nt];
-                energy[tpos[nt]] = bestE[nt];
+                energy[tpos[nt]] = bestE[nt] * unscale[nt];
             }
         }
     }
@@ -901,13 +958,15 @@ __global__ __launch_bounds__(256) void energy_merge_kernel(const float* __restri
 // Dsb != nullptr: the projection on the bf16 matrix cores from the split dictionary.
 template <int P, int S, int SX>
 hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, float* energy,
-                      const f32x4* Dsw, const u32x4* Dsb, int32_t* chunk_count, float* part_E,
+                      const f32x4* Dsw, const u32x4* Dsb, int dsb_kind, int32_t* chunk_count, float* part_E,
                       int32_t* part_j, LdsRaised* raised, const EnergyScreen* scr, hipStream_t st) {
     constexpr int NT = P <= 64 ? 2 : 1;
     constexpr int QN = P / 8;
     constexpr size_t lds = (size_t)2 * (2 * QN * 64) * sizeof(f32x4);
     constexpr bool wide = P > 64;
     using G = SplitGeom<wide ? 64 : P>;
+    constexpr size_t lds_f16 = SplitGeom<wide ? 64 : P, 2>::LDS;
+    const bool f16 = Dsb != nullptr && dsb_kind == 3 && !wide;
     // p = 256: two 48 KiB stages + the partial-product exchange (2 x 4 SIMDs x 4 KiB)
     constexpr size_t lds_split = wide ? (size_t)2 * (P / 16) * 3 * 64 * 16 + (size_t)2 * 4 * 4 * 64 * 16 : G::LDS;
     const bool split = Dsb != nullptr;
@@ -949,7 +1008,7 @@ hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, fl
         if constexpr (wide)
             hipLaunchKernelGGL((energy_split_wide_kernel<P, S, SX>), grid, dim3(64 * kWideWaves), lds_split, st,
                                Y, (int)m, Dsb, K, s0, out_j, out_E, hist, chunk, units_per_y);
-        else if (scr != nullptr && !by_rows && K > 1 && part_E != nullptr && part_j != nullptr) {
+        else if (scr != nullptr && !f16 && !by_rows && K > 1 && part_E != nullptr && part_j != nullptr) {
             // screening pass over all signals, then the full products for the undecided ones
             const float kc = kScreenCoef;
             const float margin = 2.f * (2.f * sqrtf((float)s0) * kc + (float)s0 * kc * kc) * 1.05f;
@@ -964,6 +1023,10 @@ hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, fl
             hipLaunchKernelGGL(energy_resolve_merge_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, st,
                                part_E, part_j, r_rows, (int)m, K, scr->ids, scr->count, blk, energy, chunk_count,
                                chunk);
+        } else if (f16) {
+            if constexpr (!wide)
+                hipLaunchKernelGGL((energy_split_kernel<P, S, SX, 3>), grid, dim3(64 * G::WAVES), lds_f16, st, Y, (int)m, Dsb, K, s0, out_j, out_E, hist, chunk,
+                                   units_per_y, nullptr, nullptr, 0.f);
         } else
             hipLaunchKernelGGL((energy_split_kernel<P, S, SX, 0>), grid, dim3(64 * G::WAVES), lds_split, st, Y,
                                (int)m, Dsb, K, s0, out_j, out_E, hist, chunk, units_per_y, nullptr, nullptr,
@@ -984,19 +1047,19 @@ hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, fl
 // s0 > 8), which takes the run-time path.
 template <int P, int S>
 hipError_t launch_ps(const float* Y, int64_t m, int K, int s0, int32_t* blk, float* energy,
-                     const float* dsw, const unsigned* dsb, int32_t* chunk_count, float* part_E,
+                     const float* dsw, const unsigned* dsb, int dsb_kind, int32_t* chunk_count, float* part_E,
                      int32_t* part_j, LdsRaised* raised, const EnergyScreen* scr, hipStream_t st) {
     const f32x4* Dsw = reinterpret_cast<const f32x4*>(dsw);
     const u32x4* Dsb = reinterpret_cast<const u32x4*>(dsb);
     constexpr int NV = P <= 64 ? P / 2 : 32;
     if constexpr (S > NV) {
-        return launch_pse<P, S, 0>(Y, m, K, s0, blk, energy, Dsw, Dsb, chunk_count, part_E, part_j, raised, scr, st);
+        return launch_pse<P, S, 0>(Y, m, K, s0, blk, energy, Dsw, Dsb, dsb_kind, chunk_count, part_E, part_j, raised, scr, st);
     } else {
         switch (S - s0) {
 #define SBO_CASE(DELTA)                                                                          \
     case DELTA:                                                                                  \
         if constexpr (S - DELTA > S / 2 || S == 1)                                               \
-            return launch_pse<P, S, S - DELTA>(Y, m, K, s0, blk, energy, Dsw, Dsb, chunk_count,  \
+            return launch_pse<P, S, S - DELTA>(Y, m, K, s0, blk, energy, Dsw, Dsb, dsb_kind, chunk_count,  \
                                                part_E, part_j, raised, scr, st);                      \
         break;
             SBO_CASE(0) SBO_CASE(1) SBO_CASE(2) SBO_CASE(3) SBO_CASE(4) SBO_CASE(5) SBO_CASE(6) SBO_CASE(7)
@@ -1009,13 +1072,13 @@ hipError_t launch_ps(const float* Y, int64_t m, int K, int s0, int32_t* blk, flo
 
 template <int P>
 hipError_t launch_p(int s0, const float* Y, int64_t m, int K, int32_t* blk, float* energy,
-                    const float* dsw, const unsigned* dsb, int32_t* chunk_count, float* part_E,
+                    const float* dsw, const unsigned* dsb, int dsb_kind, int32_t* chunk_count, float* part_E,
                     int32_t* part_j, LdsRaised* raised, const EnergyScreen* scr, hipStream_t st) {
-    if (s0 <= 1) return launch_ps<P, 1>(Y, m, K, s0, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, scr, st);
-    if (s0 <= 2) return launch_ps<P, 2>(Y, m, K, s0, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, scr, st);
-    if (s0 <= 4) return launch_ps<P, 4>(Y, m, K, s0, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, scr, st);
-    if (s0 <= 8) return launch_ps<P, 8>(Y, m, K, s0, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, scr, st);
-    return launch_ps<P, 16>(Y, m, K, s0, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, scr, st);
+    if (s0 <= 1) return launch_ps<P, 1>(Y, m, K, s0, blk, energy, dsw, dsb, dsb_kind, chunk_count, part_E, part_j, raised, scr, st);
+    if (s0 <= 2) return launch_ps<P, 2>(Y, m, K, s0, blk, energy, dsw, dsb, dsb_kind, chunk_count, part_E, part_j, raised, scr, st);
+    if (s0 <= 4) return launch_ps<P, 4>(Y, m, K, s0, blk, energy, dsw, dsb, dsb_kind, chunk_count, part_E, part_j, raised, scr, st);
+    if (s0 <= 8) return launch_ps<P, 8>(Y, m, K, s0, blk, energy, dsw, dsb, dsb_kind, chunk_count, part_E, part_j, raised, scr, st);
+    return launch_ps<P, 16>(Y, m, K, s0, blk, energy, dsw, dsb, dsb_kind, chunk_count, part_E, part_j, raised, scr, st);
 }
 
 }  // namespace
@@ -1033,27 +1096,36 @@ hipError_t launch_dict_swizzle(int p, int K, const float* D, float* dsw, hipStre
     return hipGetLastError();
 }
 
-hipError_t launch_dict_swizzle_split(int p, int K, const float* D, unsigned* dsb, hipStream_t st) {
+hipError_t launch_dict_swizzle_split(int p, int K, const float* D, unsigned* dsb, int kind, hipStream_t st) {
     u32x4* out = reinterpret_cast<u32x4*>(dsb);
     const dim3 grid((K * p + 63) / 64);
+    if (kind == 3) {
+        switch (p) {
+            case 16: hipLaunchKernelGGL((dict_swizzle_split_kernel<16, 2>), grid, dim3(256), 0, st, D, K, out); break;
+            case 32: hipLaunchKernelGGL((dict_swizzle_split_kernel<32, 2>), grid, dim3(256), 0, st, D, K, out); break;
+            case 64: hipLaunchKernelGGL((dict_swizzle_split_kernel<64, 2>), grid, dim3(256), 0, st, D, K, out); break;
+            default: return hipErrorInvalidValue;
+        }
+        return hipGetLastError();
+    }
     switch (p) {
-        case 16: hipLaunchKernelGGL((dict_swizzle_split_kernel<16>), grid, dim3(256), 0, st, D, K, out); break;
-        case 32: hipLaunchKernelGGL((dict_swizzle_split_kernel<32>), grid, dim3(256), 0, st, D, K, out); break;
-        case 64: hipLaunchKernelGGL((dict_swizzle_split_kernel<64>), grid, dim3(256), 0, st, D, K, out); break;
-        case 256: hipLaunchKernelGGL((dict_swizzle_split_kernel<256>), grid, dim3(256), 0, st, D, K, out); break;
+        case 16: hipLaunchKernelGGL((dict_swizzle_split_kernel<16, 3>), grid, dim3(256), 0, st, D, K, out); break;
+        case 32: hipLaunchKernelGGL((dict_swizzle_split_kernel<32, 3>), grid, dim3(256), 0, st, D, K, out); break;
+        case 64: hipLaunchKernelGGL((dict_swizzle_split_kernel<64, 3>), grid, dim3(256), 0, st, D, K, out); break;
+        case 256: hipLaunchKernelGGL((dict_swizzle_split_kernel<256, 3>), grid, dim3(256), 0, st, D, K, out); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
 hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const float* dsw,
-                         const unsigned* dsb, int32_t* blk, float* energy, int32_t* chunk_count,
+                         const unsigned* dsb, int dsb_kind, int32_t* blk, float* energy, int32_t* chunk_count,
                          float* part_E, int32_t* part_j, LdsRaised* raised, const EnergyScreen* scr, hipStream_t st) {
     switch (p) {
-        case 16: return launch_p<16>(s0, Y, m, K, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, scr, st);
-        case 32: return launch_p<32>(s0, Y, m, K, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, scr, st);
-        case 64: return launch_p<64>(s0, Y, m, K, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, scr, st);
-        case 256: return launch_p<256>(s0, Y, m, K, blk, energy, dsw, dsb, chunk_count, part_E, part_j, raised, scr, st);
+        case 16: return launch_p<16>(s0, Y, m, K, blk, energy, dsw, dsb, dsb_kind, chunk_count, part_E, part_j, raised, scr, st);
+        case 32: return launch_p<32>(s0, Y, m, K, blk, energy, dsw, dsb, dsb_kind, chunk_count, part_E, part_j, raised, scr, st);
+        case 64: return launch_p<64>(s0, Y, m, K, blk, energy, dsw, dsb, dsb_kind, chunk_count, part_E, part_j, raised, scr, st);
+        case 256: return launch_p<256>(s0, Y, m, K, blk, energy, dsw, dsb, dsb_kind, chunk_count, part_E, part_j, raised, scr, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -437,7 +437,7 @@ hipError_t launch_select(int p, int K, int s0, const float* Y, int64_t m, const 
                          const Workspace& ws, int32_t* supp, float* coef, float* err, bool ops_valid,
                          bool split, hipStream_t st) {
     if (p == 256 && !ops_valid) {              // the p = 256 kernels read Q in operand order
-        hipError_t e = split ? launch_dict_swizzle_split(p, K, D, ws.dsb, st)
+        hipError_t e = split ? launch_dict_swizzle_split(p, K, D, ws.dsb, 2, st)
                              : launch_dict_swizzle(p, K, D, ws.dsw, st);
         if (e != hipSuccess) return e;
     }

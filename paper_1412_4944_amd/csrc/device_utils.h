@@ -12,6 +12,7 @@ typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 
@@ -68,6 +69,42 @@ __device__ __forceinline__ Bf16x3Pair split_bf16x3(float v0, float v1) {
     return r;
 }
 
+// ---- fp32 as a sum of two fp16 ------------------------------------------------------------
+// For v scaled by a power of two so that |v| < 2^15: v = hi + lo + r with hi the fp16 nearest
+// to v, lo the fp16 nearest to v - hi (exact in fp32) and |r| <= 2^-22 |v| (11 + 11 significand
+// bits; lo is a normal fp16 unless |v| < 2^-3, where its absolute error 2^-25 is below 2^-39 of
+// the largest entry).  a * b = hi*hi + hi*lo + lo*hi + terms below 3 * 2^-22 |a b|, every
+// product of two fp16 being exact in fp32: three fp16 matrix products with fp32 accumulation
+// give a contraction whose error per term, 3 * 2^-22 |a b|, is below the p * 2^-24 sum |a b|
+// that an fp32 dot product of p >= 16 terms guarantees.
+struct F16x2Pair {
+    unsigned hi, lo;
+};
+__device__ __forceinline__ unsigned pack_f16(float v0, float v1) {
+    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+    const f16x2 t = {(_Float16)v0, (_Float16)v1};        // round to nearest even
+    return __builtin_bit_cast(unsigned, t);
+}
+__device__ __forceinline__ F16x2Pair split_f16x2(float v0, float v1) {
+    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+    F16x2Pair r;
+    r.hi = pack_f16(v0, v1);
+    const f16x2 h = __builtin_bit_cast(f16x2, r.hi);
+    r.lo = pack_f16(v0 - (float)h[0], v1 - (float)h[1]);
+    return r;
+}
+// Dictionary entries (|q| <= 1 for orthonormal atoms; anything below 8 is representable) are
+// scaled by this before the split.
+constexpr float kF16DictScale = 8192.f;
+// Power of two that brings a signal whose largest magnitude is vmax into [2^13, 2^14).  1 for a
+// zero or non-finite signal and for one below 2^-63: its energies (squares of its coefficients)
+// underflow in fp32 whatever the arithmetic, and all its parts then round to zero.
+__device__ __forceinline__ float f16_signal_scale(float vmax) {
+    const unsigned e = (__builtin_bit_cast(unsigned, vmax) >> 23) & 0xffu;      // biased exponent
+    if (e < 64u || e == 0xffu) return 1.f;
+    return __builtin_bit_cast(float, (unsigned)(127 + 13 + 127 - (int)e) << 23);   // 2^(13 - (e - 127))
+}
+
 // ---- the dictionary in the coding kernels' operand orders --------------------------------
 // Rows = atoms of all blocks (row j*P + k = atom k of Q_j), in stages of 64 rows, each stage a
 // run of 16-byte units in exactly the order the lanes of a wavefront consume the MFMA A operand
@@ -75,6 +112,8 @@ __device__ __forceinline__ Bf16x3Pair split_bf16x3(float v0, float v1) {
 //   fp32 order : unit (mt*(P/8) + q)*64 + lane        = dims hh*P/2 + 4q .. +3 of the row
 //   split order: unit ((mt*(P/16) + ks)*3 + pl)*64 + lane = the 8 bf16 of part pl (0 hi, 1 mid,
 //                2 lo) of dims ks*16 + hh*8 .. +7 of the row
+//   fp16 order : unit ((mt*(P/16) + ks)*2 + pl)*64 + lane = the 8 fp16 of part pl (0 hi, 1 lo) of
+//                the same dims, entries scaled by kF16DictScale
 // These store the four dims 4*d4 .. 4*d4+3 of row `grow`.
 template <int P>
 __device__ __forceinline__ void store_operand_f32(float* __restrict__ dsw, int grow, int d4, f32x4 row) {
@@ -94,6 +133,26 @@ __device__ __forceinline__ void store_operand_split(unsigned* __restrict__ dsb, 
     out[0] = u32x2{a.hi, b.hi};
     out[2 * 64] = u32x2{a.mid, b.mid};
     out[4 * 64] = u32x2{a.lo, b.lo};
+}
+
+template <int P>
+__device__ __forceinline__ void store_operand_f16x2(unsigned* __restrict__ dsb, int grow, int d4, f32x4 row) {
+    constexpr int KS16 = P / 16;
+    const int st = grow >> 6, mt = (grow >> 5) & 1, nn = grow & 31;
+    const int ks = d4 >> 2, hh = (d4 >> 1) & 1, half = d4 & 1;
+    const F16x2Pair a = split_f16x2(row.x * kF16DictScale, row.y * kF16DictScale);
+    const F16x2Pair b = split_f16x2(row.z * kF16DictScale, row.w * kF16DictScale);
+    u32x2* out = reinterpret_cast<u32x2*>(dsb) +
+                 ((int64_t)st * (2 * KS16 * 2 * 64) + (int64_t)((mt * KS16 + ks) * 2) * 64 + hh * 32 + nn) * 2 + half;
+    out[0] = u32x2{a.hi, b.hi};
+    out[2 * 64] = u32x2{a.lo, b.lo};
+}
+// kind: 2 = the three-bf16 split order, 3 = the two-fp16 order
+template <int P>
+__device__ __forceinline__ void store_operand_parts(unsigned* __restrict__ dsb, int kind, int grow, int d4,
+                                                    f32x4 row) {
+    if (kind == 3) store_operand_f16x2<P>(dsb, grow, d4, row);
+    else store_operand_split<P>(dsb, grow, d4, row);
 }
 
 // Workgroup-wide exclusive scan of n <= 4 * blockDim.x integers produced by f(idx).

@@ -50,7 +50,7 @@ constexpr int jacobi_lds_floats() {
 template <int P, int TPP>
 __device__ __forceinline__ void jacobi_block(const BlockMatrixSource& src, float* __restrict__ Dj,
                                              float* __restrict__ eig_sv, float done,
-                                             float* __restrict__ dsw, unsigned* __restrict__ dsb, int j,
+                                             float* __restrict__ dsw, unsigned* __restrict__ dsb, int dsb_kind, int j,
                                              int32_t* __restrict__ sweeps_out, float* lds) {
     constexpr int LD = P + 4;
     constexpr int NT = (P / 2) * TPP;          // threads: TPP lanes per column pair
@@ -310,7 +310,7 @@ __device__ __forceinline__ void jacobi_block(const BlockMatrixSource& src, float
             *reinterpret_cast<f32x4*>(&Dj[(k0 + a) * P + q0]) = row;
             // the same four values in the coding kernel's operand orders
             if (dsw != nullptr) store_operand_f32<P>(dsw, j * P + k0 + a, q0 >> 2, row);
-            if (dsb != nullptr) store_operand_split<P>(dsb, j * P + k0 + a, q0 >> 2, row);
+            if (dsb != nullptr) store_operand_parts<P>(dsb, dsb_kind, j * P + k0 + a, q0 >> 2, row);
         }
     }
 }

@@ -18,7 +18,7 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
                                                              float* __restrict__ D,
                                                              float* __restrict__ eig_sv, float done,
                                                              float* __restrict__ dsw,
-                                                             unsigned* __restrict__ dsb,
+                                                             unsigned* __restrict__ dsb, int dsb_kind,
                                                              int32_t* __restrict__ sweeps_out,
                                                              const int32_t* __restrict__ only) {
     __shared__ __attribute__((aligned(16))) float lds[jacobi_lds_floats<P>()];
@@ -31,21 +31,21 @@ __global__ __launch_bounds__((P / 2) * TPP) void polar_kernel(const float* __res
     }
     const BlockMatrixSource src = {M + (int64_t)j * P * P, nullptr, 0, 0, P * P};
     jacobi_block<P, TPP>(src, D + (int64_t)j * P * P, eig_sv ? eig_sv + (int64_t)j * P : nullptr, done, dsw,
-                         dsb, j, sweeps_out ? sweeps_out + j : nullptr, lds);
+                         dsb, dsb_kind, j, sweeps_out ? sweeps_out + j : nullptr, lds);
 }
 
 }  // namespace
 
 // TPP = 16 lanes per column pair (4 and 8 were measured slower at every p).
 static hipError_t launch_jacobi(int p, int K, const float* M, const int32_t* counts, float* D,
-                                float* eig_sv, float* dsw, unsigned* dsb, int32_t* sweeps,
+                                float* eig_sv, float* dsw, unsigned* dsb, int dsb_kind, int32_t* sweeps,
                                 const int32_t* only, hipStream_t st) {
     constexpr int TPP = 16;
     const float done = kPolarDone;
     switch (p) {
-        case 16: hipLaunchKernelGGL((polar_kernel<16, TPP>), dim3(K), dim3(8 * TPP), 0, st, M, counts, D, eig_sv, done, dsw, dsb, sweeps, only); break;
-        case 32: hipLaunchKernelGGL((polar_kernel<32, TPP>), dim3(K), dim3(16 * TPP), 0, st, M, counts, D, eig_sv, done, dsw, dsb, sweeps, only); break;
-        case 64: hipLaunchKernelGGL((polar_kernel<64, TPP>), dim3(K), dim3(32 * TPP), 0, st, M, counts, D, eig_sv, done, dsw, dsb, sweeps, only); break;
+        case 16: hipLaunchKernelGGL((polar_kernel<16, TPP>), dim3(K), dim3(8 * TPP), 0, st, M, counts, D, eig_sv, done, dsw, dsb, dsb_kind, sweeps, only); break;
+        case 32: hipLaunchKernelGGL((polar_kernel<32, TPP>), dim3(K), dim3(16 * TPP), 0, st, M, counts, D, eig_sv, done, dsw, dsb, dsb_kind, sweeps, only); break;
+        case 64: hipLaunchKernelGGL((polar_kernel<64, TPP>), dim3(K), dim3(32 * TPP), 0, st, M, counts, D, eig_sv, done, dsw, dsb, dsb_kind, sweeps, only); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -67,11 +67,11 @@ hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, flo
                                  ws.ns_fallback, ws.raised, st);
     }
     float* dsw = write_ops == 1 ? ws.dsw : nullptr;
-    unsigned* dsb = write_ops == 2 ? ws.dsb : nullptr;
-    if (!ns) return launch_jacobi(p, K, M, counts, D, eig_sv, dsw, dsb, ws.sweeps, nullptr, st);
+    unsigned* dsb = write_ops >= 2 ? ws.dsb : nullptr;
+    if (!ns) return launch_jacobi(p, K, M, counts, D, eig_sv, dsw, dsb, write_ops, ws.sweeps, nullptr, st);
     // Newton-Schulz for every block; a block on which it does not converge gets the Jacobi SVD in
     // the same workgroup.
-    return launch_polar_ns(p, K, M, nullptr, nullptr, 0, counts, D, dsw, dsb, ws.ns_fallback, ws.sweeps,
+    return launch_polar_ns(p, K, M, nullptr, nullptr, 0, counts, D, dsw, dsb, write_ops, ws.ns_fallback, ws.sweeps,
                            SqTotalArgs{}, ws.raised, st);
 }
 
@@ -88,7 +88,7 @@ hipError_t launch_polar_from_pieces(int p, int K, int64_t m, float* D, const Wor
         sq.nb = 128;                           // <= kSqBlocks shares of err
     }
     return launch_polar_ns(p, K, nullptr, ws.partial, ws.offsets, accum_piece(m, K, p), ws.counts, D,
-                           write_ops == 1 ? ws.dsw : nullptr, write_ops == 2 ? ws.dsb : nullptr,
+                           write_ops == 1 ? ws.dsw : nullptr, write_ops >= 2 ? ws.dsb : nullptr, write_ops,
                            ws.ns_fallback, ws.sweeps, sq, ws.raised, st);
 }
 

@@ -59,6 +59,7 @@ struct NsArgs {
     float* D;
     float* dsw;
     unsigned* dsb;
+    int dsb_kind;              // 2 = three bf16 parts, 3 = two fp16 parts (device_utils.h)
     int32_t* fallback;         // [K] 1 = the block went to the Jacobi SVD
     int32_t* iters_out;        // [K] minus the Newton-Schulz steps, or the Jacobi sweeps
     int max_iters;
@@ -372,7 +373,7 @@ __global__ __launch_bounds__(ns_threads<P>()) void polar_ns_kernel(NsArgs g) {
     if (!converged) {                          // uniform: the Jacobi SVD of this block, right here
         __syncthreads();
         if (tid == 0) g.fallback[j] = 1;
-        jacobi_block<P, TPP_FALLBACK>(src, g.D + (int64_t)j * P * P, nullptr, kPolarDone, g.dsw, g.dsb, j,
+        jacobi_block<P, TPP_FALLBACK>(src, g.D + (int64_t)j * P * P, nullptr, kPolarDone, g.dsw, g.dsb, g.dsb_kind, j,
                                       g.iters_out ? g.iters_out + j : nullptr,
                                       reinterpret_cast<float*>(lds_raw));
         return;
@@ -393,7 +394,7 @@ __global__ __launch_bounds__(ns_threads<P>()) void polar_ns_kernel(NsArgs g) {
         const f32x4 row = *reinterpret_cast<const f32x4*>(&F[k * LDF + 4 * d4]);
         *reinterpret_cast<f32x4*>(&Dj[k * P + 4 * d4]) = row;
         if (g.dsw != nullptr) store_operand_f32<P>(g.dsw, j * P + k, d4, row);
-        if (g.dsb != nullptr) store_operand_split<P>(g.dsb, j * P + k, d4, row);
+        if (g.dsb != nullptr) store_operand_parts<P>(g.dsb, g.dsb_kind, j * P + k, d4, row);
     }
 }
 
@@ -416,7 +417,7 @@ hipError_t launch_ns_p(const NsArgs& a, LdsRaised* raised, hipStream_t st) {
 // M == nullptr: P_j = the sum of block j's pieces in partial (cut from offsets with `piece`
 // signals per piece).  sq.out != nullptr: extra workgroups form *sq.out = sum of sq.err[0..m).
 hipError_t launch_polar_ns(int p, int K, const float* M, const float* partial, const int32_t* offsets,
-                           int piece, const int32_t* counts, float* D, float* dsw, unsigned* dsb,
+                           int piece, const int32_t* counts, float* D, float* dsw, unsigned* dsb, int dsb_kind,
                            int32_t* fallback, int32_t* iters, const SqTotalArgs& sq, LdsRaised* raised,
                            hipStream_t st) {
     constexpr int kMaxIters = 26;
@@ -429,6 +430,7 @@ hipError_t launch_polar_ns(int p, int K, const float* M, const float* partial, c
     a.D = D;
     a.dsw = dsw;
     a.dsb = dsb;
+    a.dsb_kind = dsb_kind;
     a.fallback = fallback;
     a.iters_out = iters;
     a.max_iters = kMaxIters;

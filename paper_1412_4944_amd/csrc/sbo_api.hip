@@ -123,10 +123,16 @@ static int run_group(sbo_ctx* c, const int32_t* blk, int64_t m, bool have_hist =
 
 // The coding kernel reads the split dictionary (bf16 matrix cores) or the fp32 one.
 static bool use_split(const sbo_ctx* c) { return c->coding_arith != SBO_ARITH_F32; }
+// Which operand order the coding kernel of this context reads (the write_ops / kind values of
+// launch_polar and launch_dict_swizzle_split): 1 fp32, 2 three bf16 parts, 3 two fp16 parts.
+static int ops_kind(const sbo_ctx* c) {
+    if (c->coding_arith == SBO_ARITH_F32) return 1;
+    return c->coding_arith == SBO_ARITH_F16X2 && c->p <= 64 ? 3 : 2;
+}
 
 // D in the operand order(s) the coding kernels of this context read (tiny; outside the stages).
 static int run_swizzle(sbo_ctx* c, const float* D) {
-    if (use_split(c)) SBO_HIP(launch_dict_swizzle_split(c->p, c->K, D, c->ws.dsb, c->stream));
+    if (use_split(c)) SBO_HIP(launch_dict_swizzle_split(c->p, c->K, D, c->ws.dsb, ops_kind(c), c->stream));
     else SBO_HIP(launch_dict_swizzle(c->p, c->K, D, c->ws.dsw, c->stream));
     return SBO_OK;
 }
@@ -134,7 +140,7 @@ static int run_swizzle(sbo_ctx* c, const float* D) {
 static int run_energy(sbo_ctx* c, const float* Y, int64_t m, int32_t* blk) {
     StageTimer t(c, SBO_STAGE_ENERGY);     // also leaves the chunk histograms of the grouping
     const EnergyScreen scr{c->ws.flag_ids, c->ws.flag_count};
-    SBO_HIP(launch_energy(c->p, c->K, c->s0, Y, m, c->ws.dsw, use_split(c) ? c->ws.dsb : nullptr, blk,
+    SBO_HIP(launch_energy(c->p, c->K, c->s0, Y, m, c->ws.dsw, use_split(c) ? c->ws.dsb : nullptr, ops_kind(c), blk,
                           c->ws.energy, c->ws.chunk_count, c->ws.part_E, c->ws.part_j, &c->raised,
                           c->coding_arith == SBO_ARITH_BF16X3_SCREEN ? &scr : nullptr, c->stream));
     return SBO_OK;
@@ -212,7 +218,7 @@ int sbo_create(sbo_ctx** out, int p, int K, int s0, int64_t m_max, void* hip_str
     c->m_max = m_max;
     c->stream = (hipStream_t)hip_stream;
     c->svd_method = SBO_SVD_AUTO;
-    c->coding_arith = SBO_ARITH_BF16X3;
+    c->coding_arith = SBO_ARITH_F16X2;
     c->timing = 0;
     c->n_spans = 0;
     const size_t bytes = workspace_layout(p, K, s0, m_max, nullptr, nullptr);
@@ -362,7 +368,7 @@ int sbo_iterate(sbo_ctx* c, const float* Y, int64_t m, float* D, int n_iter, int
             StageTimer t(c, SBO_STAGE_SELECT);  // includes the per-piece accumulation
             SBO_HIP(launch_select_accum(c->p, c->K, c->s0, Y, m, D, c->ws, supp, coef, err, c->stream));
         }
-        rc = run_polar_pieces(c, m, D, use_split(c) ? 2 : 1, err, sqerr_per_iter ? sqerr_per_iter + it : nullptr);
+        rc = run_polar_pieces(c, m, D, ops_kind(c), err, sqerr_per_iter ? sqerr_per_iter + it : nullptr);
         if (rc) return rc;
     }
     return SBO_OK;
@@ -587,7 +593,8 @@ int sbo_set_option(sbo_ctx* c, int option, int value) {
             c->svd_method = value;
             return SBO_OK;
         case SBO_OPT_CODING_ARITH:
-            if (value != SBO_ARITH_F32 && value != SBO_ARITH_BF16X3 && value != SBO_ARITH_BF16X3_SCREEN)
+            if (value != SBO_ARITH_F32 && value != SBO_ARITH_BF16X3 && value != SBO_ARITH_BF16X3_SCREEN &&
+                value != SBO_ARITH_F16X2)
                 return SBO_EINVAL;
             c->coding_arith = value;
             return SBO_OK;

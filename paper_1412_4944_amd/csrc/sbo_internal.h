@@ -151,15 +151,17 @@ namespace sbo {
 
 // dsw = D rewritten by launch_dict_swizzle into the energy kernel's operand order.
 hipError_t launch_dict_swizzle(int p, int K, const float* D, float* dsw, hipStream_t st);
-// dsb = D as three bf16 parts per entry in the split operand order.
-hipError_t launch_dict_swizzle_split(int p, int K, const float* D, unsigned* dsb, hipStream_t st);
+// dsb = D in the operand order of the split coding kernels; kind 2: three bf16 parts per entry,
+// kind 3 (p <= 64): two fp16 parts per entry (device_utils.h).
+hipError_t launch_dict_swizzle_split(int p, int K, const float* D, unsigned* dsb, int kind, hipStream_t st);
 // chunk_count != nullptr: also add the per-chunk histograms of the chosen blocks into it (the
 // first step of launch_group; the array must be zero on entry, launch_group leaves it so).
 // part_E / part_j ([kEnergySplitRows][m_max], may be nullptr): scratch for small m (at most
 // kEnergySplitSignals), where the blocks are split over several workgroup rows to fill the chip,
 // and for the resolution pass of the screening (scr), which is always split that way.
-// dsb != nullptr: the projection runs on the bf16 matrix cores from the split
-// dictionary (dsw is then not read); otherwise on the fp32 matrix instruction from dsw.
+// dsb != nullptr: the projection runs on the bf16 (dsb_kind 2) or fp16 (dsb_kind 3, p <= 64) matrix
+// cores from the split dictionary (dsw is then not read); otherwise on the fp32 matrix instruction
+// from dsw.
 // scr != nullptr (with dsb, p <= 64, enough signals to fill the chip): a screening pass with half
 // the matrix work decides the block of every signal whose two best energies are further apart
 // than the screening error allows, and the full products are formed only for the rest, listed in
@@ -170,7 +172,7 @@ struct EnergyScreen {
     int32_t* count;
 };
 hipError_t launch_energy(int p, int K, int s0, const float* Y, int64_t m, const float* dsw,
-                         const unsigned* dsb, int32_t* blk, float* energy, int32_t* chunk_count,
+                         const unsigned* dsb, int dsb_kind, int32_t* blk, float* energy, int32_t* chunk_count,
                          float* part_E, int32_t* part_j, LdsRaised* raised, const EnergyScreen* scr,
                          hipStream_t st);
 
@@ -212,8 +214,8 @@ hipError_t launch_accum_reduce(int p, int K, int64_t m, const Workspace& ws, flo
 // semidefinite, D[j] receives its eigenvectors as atoms by descending eigenvalue and
 // eig_sv[j][p] the square roots of the eigenvalues.
 // write_ops (p <= 64): the rows of every updated block are also written in the coding kernel's
-// operand order: 1 = into ws.dsw (what launch_dict_swizzle would produce from the new D), 2 = into
-// ws.dsb (launch_dict_swizzle_split), 0 = neither.
+// operand order: 1 = into ws.dsw (what launch_dict_swizzle would produce from the new D), 2 / 3 =
+// into ws.dsb (launch_dict_swizzle_split with kind 2: three bf16 parts / 3: two fp16 parts), 0 = neither.
 hipError_t launch_polar(int p, int K, const float* M, const int32_t* counts, float* D,
                         const Workspace& ws, int jacobi_only, float* eig_sv, int write_ops,
                         hipStream_t st);
@@ -231,7 +233,7 @@ struct SqTotalArgs {
 // converge.  M == nullptr: P_j = the sum of block j's pieces in `partial` (fused select +
 // accumulate, cut from `offsets` with `piece` signals per piece).
 hipError_t launch_polar_ns(int p, int K, const float* M, const float* partial, const int32_t* offsets,
-                           int piece, const int32_t* counts, float* D, float* dsw, unsigned* dsb,
+                           int piece, const int32_t* counts, float* D, float* dsw, unsigned* dsb, int dsb_kind,
                            int32_t* fallback, int32_t* iters, const SqTotalArgs& sq, LdsRaised* raised,
                            hipStream_t st);
 // The SVD update straight from the piece results of launch_select_accum (p <= 64, Newton-Schulz

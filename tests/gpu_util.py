@@ -33,7 +33,7 @@ class Sbo:
         "screen": the same with the block choice screened by the three largest partial products."""
         sbo.sbo_set_option(self.ctx, sbo.SBO_OPT_CODING_ARITH,
                            {"f32": sbo.SBO_ARITH_F32, "bf16x3": sbo.SBO_ARITH_BF16X3,
-                            "screen": sbo.SBO_ARITH_BF16X3_SCREEN}[name])
+                            "screen": sbo.SBO_ARITH_BF16X3_SCREEN, "f16x2": sbo.SBO_ARITH_F16X2}[name])
 
     def svd_jacobi(self, on):
         """Jacobi SVD for every orthobase (on) or the default Newton-Schulz + Jacobi fallback."""

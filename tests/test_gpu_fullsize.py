@@ -48,6 +48,7 @@ def _sample_ids(m, n, seed):
 
 @pytest.mark.parametrize("name,n_sample,arith", [("headline", 262144, "f32"), ("headline", 262144, "bf16x3"),
                                                  ("headline", 262144, "screen"), ("skew", 110000, "screen"),
+                                                 ("headline", 262144, "f16x2"), ("skew", 110000, "f16x2"),
                                                  ("skew", 110000, "f32"), ("skew", 110000, "bf16x3"),
                                                  ("patch16", 14000, "f32"), ("patch16", 14000, "bf16x3")])
 def test_full_size_iteration_against_oracle(name, n_sample, arith):
@@ -97,7 +98,7 @@ def test_full_size_iteration_against_oracle(name, n_sample, arith):
         compare_code(pr.Y[ids], Dg, cfg.s0, o2, (b2[ids], s2[ids], c2[ids], e2[ids]))
 
 
-@pytest.mark.parametrize("arith", ["f32", "bf16x3", "screen"])
+@pytest.mark.parametrize("arith", ["f32", "bf16x3", "screen", "f16x2"])
 @pytest.mark.parametrize("name", ["patch8", "headline"])
 def test_full_size_configured_iterations(name, arith):
     """The configured number of iterations (10) at the stated size, free-running on both sides:

@@ -37,7 +37,7 @@ CODE_CASES = [
 ]
 
 
-ARITH = ["f32", "bf16x3", "screen"]     # the two ways the projection onto all K orthobases is multiplied out
+ARITH = ["f32", "bf16x3", "screen", "f16x2"]     # the two ways the projection onto all K orthobases is multiplied out
 
 
 @pytest.mark.parametrize("arith", ARITH)
