@@ -144,7 +144,7 @@ def roofline_entry(p, K, m, energy_ms, arith, workload):
                  "peak_bf16_tflops": PEAK_MFMA_BF16_TFLOPS,
                  "vs_six_product_roof": achieved / (PEAK_MFMA_BF16_TFLOPS / SPLIT_PRODUCTS),
                  "vs_fp32_mfma_peak": achieved / PEAK_MFMA_F32_TFLOPS}
-    elif arith == "f16x2" and p <= 64:
+    elif arith == "f16x2":
         peak = PEAK_MFMA_BF16_TFLOPS / 3          # fp16 and bf16 MFMA share the 2500 TFLOP/s peak
         # the selection networks: 276 vector instructions per tile of 32 signals and block (counted in
         # the kernel's ISA), one lane-operation per lane and instruction, against 256 CUs x 64 lanes x 2.4 GHz
@@ -161,6 +161,10 @@ def roofline_entry(p, K, m, energy_ms, arith, workload):
                                    "achieved_Tops": sel_ops / (energy_ms * 1e-3) / 1e12,
                                    "peak_Tops": sel_peak / 1e12,
                                    "frac": sel_ops / (energy_ms * 1e-3) / sel_peak}}
+        if p > 64:
+            extra["kernel"] = ("energy_split_wide_kernel (the same on the fp16 matrix cores for p = 256: the two "
+                               "wavefronts of a SIMD each multiply half of the dims)")
+            del extra["selection_alu"]
     elif kernel == "energy_split_kernel":
         peak = PEAK_MFMA_BF16_TFLOPS / SPLIT_PRODUCTS
         extra = {"kernel": "energy_split_kernel (fused Q^T y on the bf16 matrix cores, fp32 operands as exact "

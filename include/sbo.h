@@ -231,7 +231,7 @@ enum {
                               accumulation: per-term error 3 * 2^-22 |a||b|, below the p * 2^-24 sum |a||b|
                               an fp32 dot product of p terms guarantees; half the matrix work of
                               SBO_ARITH_BF16X3.  Supports and coefficients still come from the six bf16
-                              products.  p <= 64; p = 256 runs as SBO_ARITH_BF16X3.  Dictionary entries
+                              products.  Dictionary entries
                               must be below 8 in magnitude (orthonormal atoms: at most 1); a signal whose
                               largest magnitude is below 2^-63 is coded as a zero signal (its energies
                               underflow in fp32 under any arithmetic). */

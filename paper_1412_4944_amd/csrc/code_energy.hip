@@ -729,12 +729,15 @@ __global__ __launch_bounds__(64 * kSplitWgWaves) void energy_split_kernel(
     }
 }
 
-// p = 256 on the bf16 matrix cores.  The three bf16 parts of 32 signals take 192 registers per
-// lane, too many for two wavefronts per SIMD, and with one wavefront per SIMD the selection
+// p = 256 on the bf16 / fp16 matrix cores.  The three bf16 parts of 32 signals take 192 registers
+// per lane, too many for two wavefronts per SIMD, and with one wavefront per SIMD the selection
 // networks would run while the matrix cores idle.  So the CONTRACTION is halved instead: the
-// two wavefronts of a SIMD (w and w + 4) share one tile of 32 signals, each holds one half of the
-// dims (96 registers) and multiplies the staged rows (32 atoms a stage, 48 KiB, double-buffered)
-// by its half.  For every block one of the two is the selector (even blocks: the wavefront with
+// two wavefronts of a SIMD (w and w + 4) share their signals, each holds one half of the dims and
+// multiplies the staged rows (32 atoms a stage, double-buffered) by its half.  With three bf16
+// parts (F16 = false) that is one tile of 32 signals per pair (96 registers); with two fp16 parts
+// (F16 = true, scaling and products as in energy_split_kernel MODE 3) two tiles (128 registers), so
+// that an A operand read from LDS feeds twice as many matrix instructions and a stage is 32 KiB
+// instead of 48.  For every block one of the two is the selector (even blocks: the wavefront with
 // the lower dims, odd blocks: the other): its partner leaves its partial products in LDS, the
 // selector adds them to its own one stage later and runs the selection networks on the sums
 // while the partner already multiplies the next stage.  A block spans 8 stages, across which the
@@ -742,19 +745,21 @@ __global__ __launch_bounds__(64 * kSplitWgWaves) void energy_split_kernel(
 // at the end.
 constexpr int kWideWaves = 8;
 
-template <int P, int S, int SX>
+template <int P, int S, int SX, bool F16>
 __global__ __launch_bounds__(64 * kWideWaves) void energy_split_wide_kernel(
     const float* __restrict__ Y, int m, const u32x4* __restrict__ Dsb, int K, int s0,
     int32_t* __restrict__ blk, float* __restrict__ energy, int32_t* __restrict__ chunk_count, int chunk,
     int units_per_y) {
     constexpr int KS16 = P / 16, KH = KS16 / 2;            // contraction steps: all, per wavefront
     constexpr int SPB = P / 32;                            // stages per block
-    constexpr int STAGE_U = KS16 * 3 * 64;                 // 16-byte units per stage of 32 rows
+    constexpr int NPL = F16 ? 2 : 3;                       // operand parts
+    constexpr int NT = F16 ? 2 : 1;                        // 32-signal tiles per pair of wavefronts
+    constexpr int STAGE_U = KS16 * NPL * 64;               // 16-byte units per stage of 32 rows
     constexpr int NTH = 64 * kWideWaves;
     constexpr int FPT = STAGE_U / NTH;
     static_assert(P == 256 && STAGE_U % NTH == 0 && S <= 16, "shape");
 
-    extern __shared__ u32x4 Qw_raw[];    // Qs[2][STAGE_U] | xch[2][4 SIMDs][4][64] (f32x4)
+    extern __shared__ u32x4 Qw_raw[];    // Qs[2][STAGE_U] | xch[2][4 SIMDs][NT][4][64] (f32x4)
     u32x4(*Qs)[STAGE_U] = reinterpret_cast<u32x4(*)[STAGE_U]>(Qw_raw);
     f32x4* xch = reinterpret_cast<f32x4*>(Qw_raw + 2 * STAGE_U);
 
@@ -762,23 +767,63 @@ __global__ __launch_bounds__(64 * kWideWaves) void energy_split_wide_kernel(
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int simd = wave & 3, half = wave >> 2;           // wavefronts w and w + 4 share a SIMD
     const int h = lane >> 5, n = lane & 31;
-    const int64_t i = ((int64_t)blockIdx.x * 4 + simd) * 32 + n;
-
-    // B operand: the three bf16 parts of dims (half*KH + ks)*16 + h*8 .. +7 of signal i
-    u32x4 yq[KH][3];
+    // B operand: the parts of dims (half*KH + ks)*16 + h*8 .. +7 of this lane's signal in tile nt
+    u32x4 yq[NT][KH][NPL];
+    int64_t sig[NT];
+    float unscale[NT];                   // F16: 1 / (scale of the signal * scale of the dictionary)^2
 #pragma unroll
-    for (int ks = 0; ks < KH; ++ks) {
-        f32x4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = v0;
-        if (i < m) {
-            const f32x4* src = reinterpret_cast<const f32x4*>(Y + i * P + (half * KH + ks) * 16 + h * 8);
-            v0 = src[0];
-            v1 = src[1];
+    for (int nt = 0; nt < NT; ++nt) {
+        const int64_t i = (((int64_t)blockIdx.x * 4 + simd) * NT + nt) * 32 + n;
+        sig[nt] = i < m ? i : -1;
+        unscale[nt] = 1.f;
+        f32x4 raw[KH][2];
+#pragma unroll
+        for (int ks = 0; ks < KH; ++ks) {
+            raw[ks][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+            raw[ks][1] = raw[ks][0];
+            if (i < m) {
+                const f32x4* src = reinterpret_cast<const f32x4*>(Y + i * P + (half * KH + ks) * 16 + h * 8);
+                raw[ks][0] = src[0];
+                raw[ks][1] = src[1];
+            }
         }
-        const Bf16x3Pair a = split_bf16x3(v0.x, v0.y), b = split_bf16x3(v0.z, v0.w);
-        const Bf16x3Pair c = split_bf16x3(v1.x, v1.y), d = split_bf16x3(v1.z, v1.w);
-        yq[ks][0] = u32x4{a.hi, b.hi, c.hi, d.hi};
-        yq[ks][1] = u32x4{a.mid, b.mid, c.mid, d.mid};
-        yq[ks][2] = u32x4{a.lo, b.lo, c.lo, d.lo};
+        float scale = 1.f;
+        if constexpr (F16) {
+            // the largest magnitude of the whole signal: this lane's dims, the other lane half's,
+            // and the partner wavefront's half of the dims (through LDS, before the stages use it)
+            float vmax = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KH; ++ks)
+#pragma unroll
+                for (int e = 0; e < 2; ++e)
+                    vmax = fmaxf(fmaxf(fmaxf(vmax, fabsf(raw[ks][e].x)), fmaxf(fabsf(raw[ks][e].y), fabsf(raw[ks][e].z))),
+                                 fabsf(raw[ks][e].w));
+            vmax = fmaxf(vmax, other_half(vmax));
+            float* vx = reinterpret_cast<float*>(Qw_raw);  // [2 halves][4 SIMDs][64]
+            vx[(half * 4 + simd) * 64 + lane] = vmax;
+            __syncthreads();
+            vmax = fmaxf(vmax, vx[((half ^ 1) * 4 + simd) * 64 + lane]);
+            __syncthreads();
+            scale = f16_signal_scale(vmax);
+            const float inv = 1.f / (scale * kF16DictScale);
+            unscale[nt] = inv * inv;
+        }
+#pragma unroll
+        for (int ks = 0; ks < KH; ++ks) {
+            const f32x4 v0 = raw[ks][0], v1 = raw[ks][1];
+            if constexpr (F16) {
+                const F16x2Pair a = split_f16x2(v0.x * scale, v0.y * scale), b = split_f16x2(v0.z * scale, v0.w * scale);
+                const F16x2Pair c = split_f16x2(v1.x * scale, v1.y * scale), d = split_f16x2(v1.z * scale, v1.w * scale);
+                yq[nt][ks][0] = u32x4{a.hi, b.hi, c.hi, d.hi};
+                yq[nt][ks][1] = u32x4{a.lo, b.lo, c.lo, d.lo};
+            } else {
+                const Bf16x3Pair a = split_bf16x3(v0.x, v0.y), b = split_bf16x3(v0.z, v0.w);
+                const Bf16x3Pair c = split_bf16x3(v1.x, v1.y), d = split_bf16x3(v1.z, v1.w);
+                yq[nt][ks][0] = u32x4{a.hi, b.hi, c.hi, d.hi};
+                yq[nt][ks][1] = u32x4{a.mid, b.mid, c.mid, d.mid};
+                yq[nt][ks][2] = u32x4{a.lo, b.lo, c.lo, d.lo};
+            }
+        }
     }
 
     // Small m: the blocks are split over blockIdx.y exactly as in energy_kernel.
@@ -801,62 +846,83 @@ __global__ __launch_bounds__(64 * kWideWaves) void energy_split_wide_kernel(
         for (int r = 0; r < FPT; ++r) Qs[buf][tid + NTH * r] = pre[r];
     };
 
-    int best = 0;
-    float bestE = -1.f;
-    float run[S];                        // selector: lane's top-S magnitudes of the current block
+    int best[NT];
+    float bestE[NT];
+    float run[NT][S];                    // selector: lane's top-S magnitudes of the current block
 #pragma unroll
-    for (int t = 0; t < S; ++t) run[t] = 0.f;
+    for (int nt = 0; nt < NT; ++nt) {
+        best[nt] = 0;
+        bestE[nt] = -1.f;
+#pragma unroll
+        for (int t = 0; t < S; ++t) run[nt][t] = 0.f;
+    }
 
-    // the six partial products, smallest first: (A part, B part)
-    constexpr int TA[6] = {2, 0, 1, 1, 0, 0};
-    constexpr int TB[6] = {0, 2, 1, 0, 1, 0};
+    // the partial products, smallest first: (A part, B part): six of three bf16 parts, three of
+    // two fp16 parts
+    constexpr int TA[6] = {F16 ? 0 : 2, F16 ? 1 : 0, F16 ? 0 : 1, 1, 0, 0};
+    constexpr int TB[6] = {F16 ? 1 : 0, F16 ? 0 : 2, F16 ? 0 : 1, 0, 1, 0};
+    constexpr int T1 = F16 ? 3 : 6;
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
                          0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    f32x16 acc = zero;
+    f32x16 acc[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[nt] = zero;
     auto selects = [&](int s) { return (((s / SPB) & 1) == half); };   // uniform over the wavefront
 
     // This wavefront's half of the products of the rows staged in buffer buf.
     auto project = [&](int buf) {
 #pragma unroll
         for (int ks = 0; ks < KH; ++ks) {
-            u32x4 a[3];
+            u32x4 a[NPL];
 #pragma unroll
-            for (int pl = 0; pl < 3; ++pl) a[pl] = Qs[buf][((half * KH + ks) * 3 + pl) * 64 + lane];
+            for (int pl = 0; pl < NPL; ++pl) a[pl] = Qs[buf][((half * KH + ks) * NPL + pl) * 64 + lane];
 #pragma unroll
-            for (int t = 0; t < 6; ++t)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[TA[t]]),
-                                                              __builtin_bit_cast(bf16x8, yq[ks][TB[t]]),
-                                                              (ks == 0 && t == 0) ? zero : acc, 0, 0, 0);
+            for (int t = 0; t < T1; ++t)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const f32x16 c_in = (ks == 0 && t == 0) ? zero : acc[nt];
+                    if constexpr (F16)
+                        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a[TA[t]]),
+                                                                         __builtin_bit_cast(f16x8, yq[nt][ks][TB[t]]),
+                                                                         c_in, 0, 0, 0);
+                    else
+                        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[TA[t]]),
+                                                                          __builtin_bit_cast(bf16x8, yq[nt][ks][TB[t]]),
+                                                                          c_in, 0, 0, 0);
+                }
         }
     };
     // Selector of stage s: own partial (still in acc) + the partner's (exchange buffer buf), then
     // the lane's running top-S and, after the block's last stage, the kept energy of the lane pair.
     auto select = [&](int s, int buf) {
-        float x[16], a[S];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const f32x4 o = xch[((buf * 4 + simd) * 4 + q) * 64 + lane];
-            x[4 * q + 0] = fabsf(acc[4 * q + 0] + o.x);
-            x[4 * q + 1] = fabsf(acc[4 * q + 1] + o.y);
-            x[4 * q + 2] = fabsf(acc[4 * q + 2] + o.z);
-            x[4 * q + 3] = fabsf(acc[4 * q + 3] + o.w);
-        }
-        top_sorted<16, S>(x, a);
         const int part = s % SPB;
-        if (part == 0) {                 // uniform
 #pragma unroll
-            for (int t = 0; t < S; ++t) run[t] = a[t];
-        } else {
+        for (int nt = 0; nt < NT; ++nt) {
+            float x[16], a[S];
 #pragma unroll
-            for (int t = 0; t < S; ++t) run[t] = fmaxf(run[t], a[S - 1 - t]);
-            bitonic_merge_desc<S>(run);
-        }
-        if (part == SPB - 1) {           // uniform
-            const float e = pair_list_energy<S, SX>(run, s0, h != 0);
-            const int j = s / SPB;
-            if (e > bestE) {
-                bestE = e;
-                best = j;
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 o = xch[(((buf * 4 + simd) * NT + nt) * 4 + q) * 64 + lane];
+                x[4 * q + 0] = fabsf(acc[nt][4 * q + 0] + o.x);
+                x[4 * q + 1] = fabsf(acc[nt][4 * q + 1] + o.y);
+                x[4 * q + 2] = fabsf(acc[nt][4 * q + 2] + o.z);
+                x[4 * q + 3] = fabsf(acc[nt][4 * q + 3] + o.w);
+            }
+            top_sorted<16, S>(x, a);
+            if (part == 0) {             // uniform
+#pragma unroll
+                for (int t = 0; t < S; ++t) run[nt][t] = a[t];
+            } else {
+#pragma unroll
+                for (int t = 0; t < S; ++t) run[nt][t] = fmaxf(run[nt][t], a[S - 1 - t]);
+                bitonic_merge_desc<S>(run[nt]);
+            }
+            if (part == SPB - 1) {       // uniform
+                const float e = pair_list_energy<S, SX>(run[nt], s0, h != 0);
+                const int j = s / SPB;
+                if (e > bestE[nt]) {
+                    bestE[nt] = e;
+                    best[nt] = j;
+                }
             }
         }
     };
@@ -873,9 +939,11 @@ __global__ __launch_bounds__(64 * kWideWaves) void energy_split_wide_kernel(
         project(cur);
         if (!selects(s)) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                xch[((cur * 4 + simd) * 4 + q) * 64 + lane] =
-                    f32x4{acc[4 * q + 0], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    xch[(((cur * 4 + simd) * NT + nt) * 4 + q) * 64 + lane] =
+                        f32x4{acc[nt][4 * q + 0], acc[nt][4 * q + 1], acc[nt][4 * q + 2], acc[nt][4 * q + 3]};
         }
         if (s + 1 < s_end) stash(cur ^ 1);
         __syncthreads();
@@ -884,23 +952,29 @@ __global__ __launch_bounds__(64 * kWideWaves) void energy_split_wide_kernel(
 
     // the better of the two wavefronts' best blocks (equal energies: the lower block)
     __syncthreads();                     // the exchange buffers are free
-    float* mrgE = reinterpret_cast<float*>(xch);           // [4][64]
-    int* mrgJ = reinterpret_cast<int*>(xch) + 4 * 64;
+    float* mrgE = reinterpret_cast<float*>(xch);           // [4][NT][64]
+    int* mrgJ = reinterpret_cast<int*>(xch) + 4 * NT * 64;
     if (half == 1) {
-        mrgE[simd * 64 + lane] = bestE;
-        mrgJ[simd * 64 + lane] = best;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            mrgE[(simd * NT + nt) * 64 + lane] = bestE[nt];
+            mrgJ[(simd * NT + nt) * 64 + lane] = best[nt];
+        }
     }
     __syncthreads();
     if (half == 0) {
-        const float e = mrgE[simd * 64 + lane];
-        const int j = mrgJ[simd * 64 + lane];
-        if (e > bestE || (e == bestE && j < best)) {
-            bestE = e;
-            best = j;
-        }
-        if (h == 0 && i < m) {
-            blk[i] = best;
-            energy[i] = bestE;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const float e = mrgE[(simd * NT + nt) * 64 + lane];
+            const int j = mrgJ[(simd * NT + nt) * 64 + lane];
+            if (e > bestE[nt] || (e == bestE[nt] && j < best[nt])) {
+                bestE[nt] = e;
+                best[nt] = j;
+            }
+            if (h == 0 && sig[nt] >= 0) {
+                blk[sig[nt]] = best[nt];
+                energy[sig[nt]] = bestE[nt] * unscale[nt];
+            }
         }
     }
 
@@ -909,9 +983,13 @@ __global__ __launch_bounds__(64 * kWideWaves) void energy_split_wide_kernel(
         int* lh = reinterpret_cast<int*>(Qw_raw);          // the stage buffers are dead
         for (int j = tid; j < K; j += NTH) lh[j] = 0;
         __syncthreads();
-        if (half == 0 && h == 0 && i < m) atomicAdd(&lh[best], 1);
+        if (half == 0 && h == 0) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                if (sig[nt] >= 0) atomicAdd(&lh[best[nt]], 1);
+        }
         __syncthreads();
-        const int64_t c = ((int64_t)blockIdx.x * 128) / chunk;
+        const int64_t c = ((int64_t)blockIdx.x * (128 * NT)) / chunk;
         for (int j = tid; j < K; j += NTH)
             if (lh[j] != 0) atomicAdd(&chunk_count[c * K + j], lh[j]);
     }
@@ -966,11 +1044,12 @@ hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, fl
     constexpr bool wide = P > 64;
     using G = SplitGeom<wide ? 64 : P>;
     constexpr size_t lds_f16 = SplitGeom<wide ? 64 : P, 2>::LDS;
-    const bool f16 = Dsb != nullptr && dsb_kind == 3 && !wide;
-    // p = 256: two 48 KiB stages + the partial-product exchange (2 x 4 SIMDs x 4 KiB)
+    const bool f16 = Dsb != nullptr && dsb_kind == 3;
+    // p = 256: two stages of 32 rows + the partial-product exchange (2 x 4 SIMDs x 4 KiB per signal tile)
     constexpr size_t lds_split = wide ? (size_t)2 * (P / 16) * 3 * 64 * 16 + (size_t)2 * 4 * 4 * 64 * 16 : G::LDS;
+    constexpr size_t lds_wide16 = (size_t)2 * (P / 16) * 2 * 64 * 16 + (size_t)2 * 2 * 4 * 4 * 64 * 16;
     const bool split = Dsb != nullptr;
-    const int per_wg = split ? (wide ? 128 : G::WAVES * 32 * G::NT) : 4 * 32 * NT;
+    const int per_wg = split ? (wide ? (f16 ? 256 : 128) : G::WAVES * 32 * G::NT) : 4 * 32 * NT;
     dim3 grid((unsigned)((m + per_wg - 1) / per_wg));
     if (raised == nullptr) return hipErrorInvalidValue;
     if (!split && lds > 64 * 1024) {
@@ -980,10 +1059,11 @@ hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, fl
     }
     if constexpr (wide) {
         if (split) {
-            if (hipError_t e = raised->ensure(
-                    reinterpret_cast<const void*>(&energy_split_wide_kernel<P, S, SX>), lds_split);
-                e != hipSuccess)
-                return e;
+            hipError_t e = f16 ? raised->ensure(reinterpret_cast<const void*>(
+                                                    &energy_split_wide_kernel<P, S, SX, true>), lds_wide16)
+                               : raised->ensure(reinterpret_cast<const void*>(
+                                                    &energy_split_wide_kernel<P, S, SX, false>), lds_split);
+            if (e != hipSuccess) return e;
         }
     }
     const int chunk = group_geom(m).chunk;
@@ -1005,10 +1085,14 @@ hipError_t launch_pse(const float* Y, int64_t m, int K, int s0, int32_t* blk, fl
     float* out_E = by_rows ? part_E : energy;
     int32_t* hist = by_rows ? nullptr : chunk_count;
     if (split) {
-        if constexpr (wide)
-            hipLaunchKernelGGL((energy_split_wide_kernel<P, S, SX>), grid, dim3(64 * kWideWaves), lds_split, st,
-                               Y, (int)m, Dsb, K, s0, out_j, out_E, hist, chunk, units_per_y);
-        else if (scr != nullptr && !f16 && !by_rows && K > 1 && part_E != nullptr && part_j != nullptr) {
+        if constexpr (wide) {
+            if (f16)
+                hipLaunchKernelGGL((energy_split_wide_kernel<P, S, SX, true>), grid, dim3(64 * kWideWaves),
+                                   lds_wide16, st, Y, (int)m, Dsb, K, s0, out_j, out_E, hist, chunk, units_per_y);
+            else
+                hipLaunchKernelGGL((energy_split_wide_kernel<P, S, SX, false>), grid, dim3(64 * kWideWaves),
+                                   lds_split, st, Y, (int)m, Dsb, K, s0, out_j, out_E, hist, chunk, units_per_y);
+        } else if (scr != nullptr && !f16 && !by_rows && K > 1 && part_E != nullptr && part_j != nullptr) {
             // screening pass over all signals, then the full products for the undecided ones
             const float kc = kScreenCoef;
             const float margin = 2.f * (2.f * sqrtf((float)s0) * kc + (float)s0 * kc * kc) * 1.05f;
@@ -1104,6 +1188,7 @@ hipError_t launch_dict_swizzle_split(int p, int K, const float* D, unsigned* dsb
             case 16: hipLaunchKernelGGL((dict_swizzle_split_kernel<16, 2>), grid, dim3(256), 0, st, D, K, out); break;
             case 32: hipLaunchKernelGGL((dict_swizzle_split_kernel<32, 2>), grid, dim3(256), 0, st, D, K, out); break;
             case 64: hipLaunchKernelGGL((dict_swizzle_split_kernel<64, 2>), grid, dim3(256), 0, st, D, K, out); break;
+            case 256: hipLaunchKernelGGL((dict_swizzle_split_kernel<256, 2>), grid, dim3(256), 0, st, D, K, out); break;
             default: return hipErrorInvalidValue;
         }
         return hipGetLastError();

@@ -34,6 +34,7 @@ size_t workspace_layout(int p, int K, int s0, int64_t m_max, Workspace* ws, char
     w.energy = (float*)take((size_t)m_max * 4);
     w.dsw = (float*)take((size_t)((K * p + 63) / 64) * 64 * p * 4);
     w.dsb = (unsigned*)take((size_t)((K * p + 63) / 64) * 64 * p * 6);
+    w.dsh = (unsigned*)take(p > 64 ? (size_t)((K * p + 63) / 64) * 64 * p * 4 : 0);
     const size_t split_m = (size_t)m_max;      // small m: one entry per signal; resolution pass: per list entry
     w.part_E = (float*)take((size_t)kEnergySplitRows * split_m * 4);
     w.part_j = (int32_t*)take((size_t)kEnergySplitRows * split_m * 4);
@@ -127,12 +128,21 @@ static bool use_split(const sbo_ctx* c) { return c->coding_arith != SBO_ARITH_F3
 // launch_polar and launch_dict_swizzle_split): 1 fp32, 2 three bf16 parts, 3 two fp16 parts.
 static int ops_kind(const sbo_ctx* c) {
     if (c->coding_arith == SBO_ARITH_F32) return 1;
-    return c->coding_arith == SBO_ARITH_F16X2 && c->p <= 64 ? 3 : 2;
+    return c->coding_arith == SBO_ARITH_F16X2 ? 3 : 2;
+}
+// The buffer the energy kernel reads: at p = 256 the fp16 order has a buffer of its own, because
+// the select kernel there reads the three-bf16 order from ws.dsb.
+static unsigned* energy_parts(const sbo_ctx* c) {
+    return c->p > 64 && ops_kind(c) == 3 ? c->ws.dsh : c->ws.dsb;
 }
 
 // D in the operand order(s) the coding kernels of this context read (tiny; outside the stages).
 static int run_swizzle(sbo_ctx* c, const float* D) {
-    if (use_split(c)) SBO_HIP(launch_dict_swizzle_split(c->p, c->K, D, c->ws.dsb, ops_kind(c), c->stream));
+    if (use_split(c)) {
+        SBO_HIP(launch_dict_swizzle_split(c->p, c->K, D, energy_parts(c), ops_kind(c), c->stream));
+        if (energy_parts(c) != c->ws.dsb)       // p = 256: the select kernel's order as well
+            SBO_HIP(launch_dict_swizzle_split(c->p, c->K, D, c->ws.dsb, 2, c->stream));
+    }
     else SBO_HIP(launch_dict_swizzle(c->p, c->K, D, c->ws.dsw, c->stream));
     return SBO_OK;
 }
@@ -140,7 +150,7 @@ static int run_swizzle(sbo_ctx* c, const float* D) {
 static int run_energy(sbo_ctx* c, const float* Y, int64_t m, int32_t* blk) {
     StageTimer t(c, SBO_STAGE_ENERGY);     // also leaves the chunk histograms of the grouping
     const EnergyScreen scr{c->ws.flag_ids, c->ws.flag_count};
-    SBO_HIP(launch_energy(c->p, c->K, c->s0, Y, m, c->ws.dsw, use_split(c) ? c->ws.dsb : nullptr, ops_kind(c), blk,
+    SBO_HIP(launch_energy(c->p, c->K, c->s0, Y, m, c->ws.dsw, use_split(c) ? energy_parts(c) : nullptr, ops_kind(c), blk,
                           c->ws.energy, c->ws.chunk_count, c->ws.part_E, c->ws.part_j, &c->raised,
                           c->coding_arith == SBO_ARITH_BF16X3_SCREEN ? &scr : nullptr, c->stream));
     return SBO_OK;

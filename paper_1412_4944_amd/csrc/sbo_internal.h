@@ -90,6 +90,7 @@ struct Workspace {
     // coding
     float* energy;         // [m_max] kept energy in the winning block
     float* dsw;            // [ceil(K*p/64)*64][p] dictionary in MFMA operand order
+    unsigned* dsh;         // p > 64 only: the same rows as two fp16 parts (the energy kernel's order there)
     unsigned* dsb;         // the same rows as three bf16 parts in the split operand order (6 bytes per entry)
     float* part_E;         // [kEnergySplitRows][m_max] split coding / resolution pass: best energy per row
     int32_t* part_j;       // same shape: its block

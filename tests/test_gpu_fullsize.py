@@ -50,7 +50,8 @@ def _sample_ids(m, n, seed):
                                                  ("headline", 262144, "screen"), ("skew", 110000, "screen"),
                                                  ("headline", 262144, "f16x2"), ("skew", 110000, "f16x2"),
                                                  ("skew", 110000, "f32"), ("skew", 110000, "bf16x3"),
-                                                 ("patch16", 14000, "f32"), ("patch16", 14000, "bf16x3")])
+                                                 ("patch16", 14000, "f32"), ("patch16", 14000, "bf16x3"),
+                                                 ("patch16", 14000, "f16x2")])
 def test_full_size_iteration_against_oracle(name, n_sample, arith):
     cfg = synth.CONFIGS[name]
     print(f"case {name} {arith}: p={cfg.p} K={cfg.K} m={cfg.m} s0={cfg.s0}: generating", flush=True)

@@ -83,6 +83,29 @@ def test_code_ties_zero_signal_and_duplicates(arith, p):
     compare_code(Y, D, s0, o, (blk, supp, coef, err), max_exempt_frac=0.05)
 
 
+@pytest.mark.parametrize("p,K,s0", [(64, 5, 8), (16, 3, 4), (256, 2, 12)])
+@pytest.mark.parametrize("arith", ARITH)
+def test_code_over_signal_scales_and_dynamic_range(arith, p, K, s0):
+    """Coding does not depend on the scale of a signal (the fp16 arithmetic rescales every signal by
+    a power of two, the others work on the values as they are): signals scaled by 1e-15 .. 1e15,
+    signals with one dimension 1e6 times the others, and a signal of a single non-zero entry."""
+    rng = np.random.default_rng(91 + p)
+    pr = _problem(f"scales_p{p}", p=p, K=K, m=700, s0=s0, snr_db=25.0)
+    Y = pr.Y.copy()
+    m = Y.shape[0]
+    Y *= (10.0 ** rng.uniform(-15, 15, size=(m, 1))).astype(np.float32)
+    Y[5::50, 3] *= 1e6
+    Y[7] = 0.0
+    Y[7, p - 2] = -2.5e-9
+    D = pr.D_planted
+    print(f"case {arith}: p={p} K={K} m={m} s0={s0}", flush=True)
+    o = orc.o_code(Y, D, s0)
+    with Sbo(p, K, s0, m, arith=arith) as g:
+        out = g.code(Y, D)
+    frac = compare_code(Y, D, s0, o, out, max_exempt_frac=0.01)
+    print(f"  exempt fraction {frac:.5f}", flush=True)
+
+
 @pytest.mark.parametrize("K,m", [(4, 1024), (32, 5000), (128, 70001), (1, 100), (1000, 3000), (7, 1)])
 def test_group_matches_oracle(K, m):
     rng = np.random.default_rng(K * 1000 + m)
