@@ -87,14 +87,15 @@ def test_code_ties_zero_signal_and_duplicates(arith, p):
 @pytest.mark.parametrize("arith", ARITH)
 def test_code_over_signal_scales_and_dynamic_range(arith, p, K, s0):
     """Coding does not depend on the scale of a signal (the fp16 arithmetic rescales every signal by
-    a power of two, the others work on the values as they are): signals scaled by 1e-15 .. 1e15,
-    signals with one dimension 1e6 times the others, and a signal of a single non-zero entry."""
+    a power of two, the others work on the values as they are): signals scaled by 1e-12 .. 1e12
+    (squares stay inside the fp32 range), signals with one dimension 1e4 times the others, and a
+    signal of a single non-zero entry."""
     rng = np.random.default_rng(91 + p)
     pr = _problem(f"scales_p{p}", p=p, K=K, m=700, s0=s0, snr_db=25.0)
     Y = pr.Y.copy()
     m = Y.shape[0]
-    Y *= (10.0 ** rng.uniform(-15, 15, size=(m, 1))).astype(np.float32)
-    Y[5::50, 3] *= 1e6
+    Y *= (10.0 ** rng.uniform(-12, 12, size=(m, 1))).astype(np.float32)
+    Y[5::50, 3] *= 1e4
     Y[7] = 0.0
     Y[7, p - 2] = -2.5e-9
     D = pr.D_planted
