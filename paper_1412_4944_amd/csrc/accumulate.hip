@@ -363,6 +363,185 @@ __global__ __launch_bounds__(256) void accum_wide_kernel(const float* __restrict
             }
 }
 
+// p = 256 on the bf16 matrix cores (three-part split of both operands, six partial products,
+// fp32 accumulation: device_utils.h).  Same division of the work as accum_wide_kernel (a piece per
+// workgroup, 64 atoms per wavefront, 256 accumulator registers), but a step covers 16 signals, the
+// contraction length of v_mfma_f32_32x32x16_bf16, and both operands go through LDS tiles with the
+// signals along the rows' 32 bytes, built by the whole workgroup while the matrix cores work on
+// the previous step's tiles (two sets of tiles):
+//   y tile [3 parts][256 dims][16 signals]: thread t loads dim t of the 16 signals (each load of a
+//          wavefront is 256 contiguous bytes), splits pairs of signals and stores two 16-byte units;
+//   x tile [3 parts][256 atoms + 1][16 signals]: zero-filled, then one thread per (signal, entry)
+//          scatters the three parts of a kept coefficient (entries that do not exist go to the
+//          extra row, which nobody reads).
+// The loads of a step are issued two steps ahead.
+constexpr int kAwsSignals = 16;
+
+template <int S0>
+__global__ __launch_bounds__(256) void accum_wide_split_kernel(const float* __restrict__ Y, int K, int piece,
+                                                               const int32_t* __restrict__ offsets,
+                                                               const int32_t* __restrict__ perm,
+                                                               const int32_t* __restrict__ supp,
+                                                               const float* __restrict__ coef,
+                                                               float* __restrict__ partial) {
+    constexpr int P = 256;
+    constexpr int NTL = 8;                     // 32-wide tiles along the dimensions
+    constexpr int G = kAwsSignals;
+    constexpr int YPLANE = P * 32;             // bytes of one part of the y tile
+    constexpr int XPLANE = (P + 1) * 32;       // bytes of one part of the x tile (+ the extra row)
+    constexpr int SET_B = 3 * YPLANE + 3 * XPLANE;
+    static_assert(G * S0 <= 256, "one thread per (signal, entry)");
+    // piece_start[K+1] | tmp[16] | pad | ids[kWideMaxPiece] | two sets of (y tile, x tile)
+    extern __shared__ int lds[];
+    int* piece_start = lds;
+    int* tmp = lds + (K + 1);
+    const int head = ((K + 1 + 16) + 3) & ~3;
+    int* ids = lds + head;
+    unsigned char* sets = reinterpret_cast<unsigned char*>(ids + kWideMaxPiece);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int h = lane >> 5, n = lane & 31;
+
+    wg_exclusive_scan4([&](int j) { return (offsets[j + 1] - offsets[j] + piece - 1) / piece; }, K,
+                       piece_start, tmp);
+    const int id = blockIdx.x;
+    if (id >= piece_start[K]) return;          // uniform over the workgroup
+
+    const int j = upper_slot(piece_start, K, id);
+    const int pos0 = offsets[j] + (id - piece_start[j]) * piece;
+    const int cnt = min(piece, offsets[j + 1] - pos0);   // <= kWideMaxPiece (launcher)
+    for (int q = tid; q < cnt; q += 256) ids[q] = perm[pos0 + q];
+    __syncthreads();
+
+    f32x16 acc[2][NTL];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < NTL; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    const int atom0 = 64 * wave;               // this wavefront's atoms: atom0 .. atom0+63
+    const int n_steps = (cnt + G - 1) / G;
+
+    // What a thread fetches for a step: dim `tid` of its 16 signals, and one (atom, coefficient)
+    // of one signal (threads below 16 * S0).  Positions past the end of the piece are clamped
+    // for the loads and masked when the tiles are built.
+    struct Fetched {
+        float y[G];
+        int k;
+        float c;
+    };
+    const int e_sig = tid / S0, e_ent = tid % S0;
+    auto fetch = [&](Fetched& f, int g) {
+#pragma unroll
+        for (int u = 0; u < G; ++u) {
+            const int64_t i = ids[min(g * G + u, cnt - 1)];
+            f.y[u] = Y[i * P + tid];
+        }
+        const int64_t i = ids[min(g * G + min(e_sig, G - 1), cnt - 1)];
+        f.k = supp[i * S0 + e_ent];
+        f.c = coef[i * S0 + e_ent];
+    };
+    auto zero_x = [&](int set) {
+        u32x4* xt = reinterpret_cast<u32x4*>(sets + (size_t)set * SET_B + 3 * YPLANE);
+        for (int e = tid; e < 3 * XPLANE / 16; e += 256) xt[e] = u32x4{0u, 0u, 0u, 0u};
+    };
+    auto build = [&](const Fetched& f, int g, int set) {
+        unsigned char* yt = sets + (size_t)set * SET_B;
+        unsigned char* xt = yt + 3 * YPLANE;
+        const int left = cnt - g * G;          // signals of this step (uniform)
+        unsigned w[3][8];
+#pragma unroll
+        for (int u = 0; u < G; u += 2) {
+            const Bf16x3Pair s = split_bf16x3(u < left ? f.y[u] : 0.f, u + 1 < left ? f.y[u + 1] : 0.f);
+            w[0][u >> 1] = s.hi;
+            w[1][u >> 1] = s.mid;
+            w[2][u >> 1] = s.lo;
+        }
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl) {
+            *reinterpret_cast<u32x4*>(yt + pl * YPLANE + tr_off(tid, 0)) = u32x4{w[pl][0], w[pl][1], w[pl][2], w[pl][3]};
+            *reinterpret_cast<u32x4*>(yt + pl * YPLANE + tr_off(tid, 8)) = u32x4{w[pl][4], w[pl][5], w[pl][6], w[pl][7]};
+        }
+        const bool have = tid < G * S0 && e_sig < left && (unsigned)f.k < (unsigned)P;
+        const TriWord t = split_trunc(f.c);
+        const int at = tr_off(have ? f.k : P, e_sig & (G - 1));
+        if (tid < G * S0) {
+            *reinterpret_cast<unsigned short*>(xt + at) = (unsigned short)(t.hi >> 16);
+            *reinterpret_cast<unsigned short*>(xt + XPLANE + at) = (unsigned short)(t.mid >> 16);
+            *reinterpret_cast<unsigned short*>(xt + 2 * XPLANE + at) = (unsigned short)(t.lo >> 16);
+        }
+    };
+    // the six partial products, smallest first: (A part, B part)
+    constexpr int TA[6] = {2, 0, 1, 1, 0, 0};
+    constexpr int TB[6] = {0, 2, 1, 0, 1, 0};
+    auto multiply = [&](int set) {
+        const unsigned char* yt = sets + (size_t)set * SET_B;
+        const unsigned char* xt = yt + 3 * YPLANE;
+        // operands: lane (h, n) takes signals 8h .. 8h+7 of atom resp. dim tile*32 + n
+        u32x4 xa[2][3];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl)
+                xa[mt][pl] = *reinterpret_cast<const u32x4*>(xt + pl * XPLANE + tr_off(atom0 + mt * 32 + n, 8 * h));
+#pragma unroll
+        for (int nt = 0; nt < NTL; ++nt) {
+            u32x4 yb[3];
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl)
+                yb[pl] = *reinterpret_cast<const u32x4*>(yt + pl * YPLANE + tr_off(nt * 32 + n, 8 * h));
+#pragma unroll
+            for (int t = 0; t < 6; ++t)
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        __builtin_bit_cast(bf16x8, xa[mt][TA[t]]), __builtin_bit_cast(bf16x8, yb[TB[t]]), acc[mt][nt],
+                        0, 0, 0);
+        }
+    };
+
+    // step g: its tiles are built during the multiplication of step g - 1 and its loads were issued
+    // during that of step g - 2
+    Fetched fa, fb;
+    fetch(fa, 0);
+    fetch(fb, 1);
+    zero_x(0);
+    __syncthreads();
+    build(fa, 0, 0);
+    fetch(fa, 2);
+    __syncthreads();
+    for (int g = 0; g < n_steps; g += 2) {
+        // even step g from set 0; meanwhile the tiles of step g + 1 in set 1
+        zero_x(1);
+        __syncthreads();
+        build(fb, g + 1, 1);
+        fetch(fb, g + 3);
+        multiply(0);
+        __syncthreads();
+        // odd step g + 1 from set 1; meanwhile the tiles of step g + 2 in set 0
+        zero_x(0);
+        __syncthreads();
+        build(fa, g + 2, 0);
+        fetch(fa, g + 4);
+        multiply(1);                           // past the end: its tiles hold zeros
+        __syncthreads();
+    }
+
+    float* out = partial + (int64_t)id * P * P;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NTL; ++nt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int atom = atom0 + mt * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+                out[atom * P + nt * 32 + n] = acc[mt][nt][r];
+            }
+}
+
 // Besides the sums over pieces (blockIdx.x < K), nb workgroups in the grid columns from K on form
 // the total squared error sum_i err[i] (sq_out != nullptr; see sq_total.h).
 template <int P>
@@ -419,13 +598,24 @@ hipError_t launch_ps(int K, const float* Y, int64_t m, const int32_t* supp, cons
 
 template <int S0>
 hipError_t launch_wide_s(int K, const float* Y, int64_t m, const int32_t* supp, const float* coef,
-                         const Workspace& ws, float* M, hipStream_t st) {
+                         const Workspace& ws, float* M, bool split, hipStream_t st) {
     constexpr int P = 256;
     const int piece = accum_piece(m, K, P);
     const int max_pieces = accum_max_pieces(m, K, P);
     const size_t lds1 = (K + 1 + 16 + kWideMaxPiece) * sizeof(int) + (size_t)4 * kWidePairs * 2 * 64 * sizeof(float);
-    hipLaunchKernelGGL((accum_wide_kernel<S0, false>), dim3(max_pieces), dim3(256), lds1, st, Y, K, piece,
-                       ws.offsets, ws.perm, supp, coef, ws.partial);
+    if (split) {
+        const int head = ((K + 1 + 16) + 3) & ~3;
+        const size_t lds = (size_t)(head + kWideMaxPiece) * sizeof(int) +
+                           (size_t)2 * (3 * P * 32 + 3 * (P + 1) * 32);
+        if (hipError_t e = ws.raised->ensure(reinterpret_cast<const void*>(&accum_wide_split_kernel<S0>), lds);
+            e != hipSuccess)
+            return e;
+        hipLaunchKernelGGL((accum_wide_split_kernel<S0>), dim3(max_pieces), dim3(256), lds, st, Y, K, piece,
+                           ws.offsets, ws.perm, supp, coef, ws.partial);
+    } else {
+        hipLaunchKernelGGL((accum_wide_kernel<S0, false>), dim3(max_pieces), dim3(256), lds1, st, Y, K, piece,
+                           ws.offsets, ws.perm, supp, coef, ws.partial);
+    }
     const size_t lds2 = (K + 1 + 16) * sizeof(int);
     hipLaunchKernelGGL((accum_reduce_kernel<P>), dim3(K, (P * P + 255) / 256), dim3(256), lds2, st,
                        K, piece, ws.offsets, ws.partial, M, nullptr, (int64_t)0, nullptr, nullptr, nullptr, 0);
@@ -433,10 +623,10 @@ hipError_t launch_wide_s(int K, const float* Y, int64_t m, const int32_t* supp, 
 }
 
 hipError_t launch_wide(int K, int s0, const float* Y, int64_t m, const int32_t* supp,
-                       const float* coef, const Workspace& ws, float* M, hipStream_t st) {
+                       const float* coef, const Workspace& ws, float* M, bool split, hipStream_t st) {
     switch (s0) {
 #define SBO_CASE(N) \
-    case N: return launch_wide_s<N>(K, Y, m, supp, coef, ws, M, st);
+    case N: return launch_wide_s<N>(K, Y, m, supp, coef, ws, M, split, st);
         SBO_CASE(1) SBO_CASE(2) SBO_CASE(3) SBO_CASE(4) SBO_CASE(5) SBO_CASE(6) SBO_CASE(7)
         SBO_CASE(8) SBO_CASE(9) SBO_CASE(10) SBO_CASE(11) SBO_CASE(12) SBO_CASE(13)
         SBO_CASE(14) SBO_CASE(15) SBO_CASE(16)
@@ -536,7 +726,7 @@ hipError_t launch_accumulate(int p, int K, int s0, const float* Y, int64_t m, co
         case 16: return launch_p<16>(K, s0, Y, m, supp, coef, ws, M, st);
         case 32: return launch_p<32>(K, s0, Y, m, supp, coef, ws, M, st);
         case 64: return launch_p<64>(K, s0, Y, m, supp, coef, ws, M, st);
-        case 256: return launch_wide(K, s0, Y, m, supp, coef, ws, M, st);
+        case 256: return launch_wide(K, s0, Y, m, supp, coef, ws, M, ws.parts_accum, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -69,6 +69,28 @@ __device__ __forceinline__ Bf16x3Pair split_bf16x3(float v0, float v1) {
     return r;
 }
 
+// The same decomposition by truncation (8 + 8 + 8 significand bits), one value at a time: three
+// words whose upper halves are bf16 numbers with hi + mid + lo = v exactly.
+struct TriWord {
+    unsigned hi, mid, lo;
+};
+__device__ __forceinline__ TriWord split_trunc(float v) {
+    TriWord t;
+    t.hi = __builtin_bit_cast(unsigned, v) & 0xffff0000u;
+    const float r1 = v - __builtin_bit_cast(float, t.hi);
+    t.mid = __builtin_bit_cast(unsigned, r1) & 0xffff0000u;
+    const float r2 = r1 - __builtin_bit_cast(float, t.mid);
+    t.lo = __builtin_bit_cast(unsigned, r2);             // at most 8 significant bits are left
+    return t;
+}
+
+// Byte offset of bf16 element (row, col) in a transposed MFMA operand tile [row][16 signals]: rows
+// of 32 bytes = two 16-byte units; the unit index is flipped on every other group of four rows so
+// that the eight rows a quarter-wavefront reads at once cover all LDS banks.
+__device__ __forceinline__ int tr_off(int row, int col) {
+    return row * 32 + ((((col >> 3) ^ (row >> 2)) & 1) << 4) + (col & 7) * 2;
+}
+
 // ---- fp32 as a sum of two fp16 ------------------------------------------------------------
 // For v scaled by a power of two so that |v| < 2^15: v = hi + lo + r with hi the fp16 nearest
 // to v, lo the fp16 nearest to v - hi (exact in fp32) and |r| <= 2^-22 |v| (11 + 11 significand

@@ -31,20 +31,6 @@ namespace sbo {
 
 namespace {
 
-// v as three words whose upper halves are bf16 numbers with hi + mid + lo = v exactly
-// (truncating split: 8 + 8 + 8 significand bits).
-struct TriWord {
-    unsigned hi, mid, lo;
-};
-__device__ __forceinline__ TriWord split_trunc(float v) {
-    TriWord t;
-    t.hi = __builtin_bit_cast(unsigned, v) & 0xffff0000u;
-    const float r1 = v - __builtin_bit_cast(float, t.hi);
-    t.mid = __builtin_bit_cast(unsigned, r1) & 0xffff0000u;
-    const float r2 = r1 - __builtin_bit_cast(float, t.mid);
-    t.lo = __builtin_bit_cast(unsigned, r2);             // at most 8 significant bits are left
-    return t;
-}
 // upper half of a -> low half of the result, upper half of b -> high half
 __device__ __forceinline__ unsigned pack_upper(unsigned a, unsigned b) {
     return __builtin_amdgcn_perm(b, a, 0x07060302u);

@@ -242,6 +242,7 @@ int sbo_create(sbo_ctx** out, int p, int K, int s0, int64_t m_max, void* hip_str
     c->ws_base = (char*)base;
     workspace_layout(p, K, s0, m_max, &c->ws, c->ws_base);
     c->ws.raised = &c->raised;
+    c->ws.parts_accum = c->coding_arith != SBO_ARITH_F32;
     // Two pieces of the workspace carry an invariant between calls: the chunk histograms and the
     // finished-workgroup counter are zero whenever no call is in flight.
     e = hipMemsetAsync(c->ws.chunk_count, 0, (size_t)max_chunks() * K * 4, c->stream);
@@ -607,6 +608,7 @@ int sbo_set_option(sbo_ctx* c, int option, int value) {
                 value != SBO_ARITH_F16X2)
                 return SBO_EINVAL;
             c->coding_arith = value;
+            c->ws.parts_accum = value != SBO_ARITH_F32;
             return SBO_OK;
         default: return SBO_EINVAL;
     }

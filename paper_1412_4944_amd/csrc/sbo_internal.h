@@ -109,6 +109,7 @@ struct Workspace {
     int32_t* sweeps;       // [K] most recent SVD stage: Jacobi sweeps, or minus the Newton-Schulz steps
     int32_t* ns_fallback;  // [K] 1 = Newton-Schulz left the block to the Jacobi kernel
     int32_t* sq_counter;   // [1] workgroups of the fused squared-error sum that have finished (0 between launches)
+    bool parts_accum = false;   // p = 256: the accumulation on the bf16 matrix cores (any coding arithmetic but fp32)
     int32_t* flag_ids;     // [m_max] signals whose block the screening pass of the coding kernel left undecided
     int32_t* flag_count;   // [1] how many (0 between calls: the grouping's scan kernel clears it)
     // iterate

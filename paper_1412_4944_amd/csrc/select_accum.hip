@@ -31,27 +31,6 @@ namespace {
 
 constexpr int kSaWaves = 8;
 
-// fp32 -> three words whose upper halves are bf16 parts with hi + mid + lo = v exactly
-// (truncating split: 8 + 8 + 8 significand bits)
-struct TriWord {
-    unsigned hi, mid, lo;
-};
-__device__ __forceinline__ TriWord split_trunc(float v) {
-    TriWord t;
-    t.hi = __builtin_bit_cast(unsigned, v) & 0xffff0000u;
-    const float r1 = v - __builtin_bit_cast(float, t.hi);
-    t.mid = __builtin_bit_cast(unsigned, r1) & 0xffff0000u;
-    const float r2 = r1 - __builtin_bit_cast(float, t.mid);
-    t.lo = __builtin_bit_cast(unsigned, r2);             // at most 8 significant bits are left
-    return t;
-}
-
-// Byte offset of bf16 element (row, col) in a transposed operand tile: rows of 16 signals
-// (32 bytes = two 16-byte units); the unit index is flipped on every other group of four rows
-// so that the eight rows a quarter-wavefront reads at once cover all LDS banks.
-__device__ __forceinline__ int tr_off(int row, int col) {
-    return row * 32 + ((((col >> 3) ^ (row >> 2)) & 1) << 4) + (col & 7) * 2;
-}
 
 template <int P, int S>
 __global__ __launch_bounds__(64 * kSaWaves) void select_accum_kernel(
