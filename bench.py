@@ -45,18 +45,18 @@ def screening_applies(p: int, m: int) -> bool:
     return p <= 64 and (m + 511) // 512 >= 192
 
 
-def measured_traffic_bytes(workload: str, kernel: str):
+def measured_traffic_bytes(workload: str, arith: str):
     """HBM bytes per launch of the roofline kernel from the tracked rocprofv3 --pmc summary
     profiles/<workload>_hbm_traffic_pmc.txt (its line `roofline_kernel_hbm_bytes_per_launch:
-    <bytes> kernel=<name>`); None when there is no summary for this workload or it is for
-    another kernel."""
+    <bytes> kernel=<name> arith=<coding arithmetic> ...`); None when there is no summary for this
+    workload and arithmetic."""
     path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic_pmc.txt")
     try:
         with open(path) as f:
             for line in f:
                 if line.startswith("roofline_kernel_hbm_bytes_per_launch:"):
                     parts = line.split()
-                    if f"kernel={kernel}" in parts:
+                    if f"arith={arith}" in parts:
                         return float(parts[1])
     except OSError:
         pass
@@ -176,7 +176,7 @@ def roofline_entry(p, K, m, energy_ms, arith, workload):
         peak = PEAK_MFMA_F32_TFLOPS
         extra = {"kernel": "energy_kernel (fused Q^T y on the fp32 matrix instruction + top-s0 energy + block argmax)"}
     return {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-            "traffic": measured_traffic_bytes(workload, kernel), **extra}
+            "traffic": measured_traffic_bytes(workload, arith), **extra}
 
 
 def run_config(sbo, synth, torch, name, steps, warmup, arith):
