@@ -142,18 +142,20 @@ __global__ __launch_bounds__(ns_threads<P>()) void polar_ns_kernel(NsArgs g) {
 
     // P_j -> the fp32 scratch, summed over the block's pieces in piece order (the order, and so
     // the bits, of accum_reduce_kernel; a finished matrix is a single piece).  16-byte loads,
-    // those of four pieces in flight at a time: one workgroup has to pull a few hundred KiB here.
+    // those of kInFlight pieces in flight at a time: one workgroup has to pull a few hundred KiB
+    // that other CUs have just written, and each round of loads is a trip to memory.
     {
         constexpr int U = (P * P / 4 + NTH - 1) / NTH;     // 16-byte units per thread
+        constexpr int kInFlight = 8;
         const f32x4* base = reinterpret_cast<const f32x4*>(src.M != nullptr ? src.M : src.partial);
         const int pc_beg = src.M != nullptr ? 0 : src.pc_beg, pc_end = src.M != nullptr ? 1 : src.pc_end;
         f32x4 sum[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) sum[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-        for (int pc = pc_beg; pc < pc_end; pc += 4) {
-            f32x4 v[4][U];
+        for (int pc = pc_beg; pc < pc_end; pc += kInFlight) {
+            f32x4 v[kInFlight][U];
 #pragma unroll
-            for (int k = 0; k < 4; ++k)
+            for (int k = 0; k < kInFlight; ++k)
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int e4 = tid + NTH * u;
@@ -161,7 +163,7 @@ __global__ __launch_bounds__(ns_threads<P>()) void polar_ns_kernel(NsArgs g) {
                     v[k][u] = e4 < P * P / 4 ? base[(int64_t)pcc * (P * P / 4) + e4] : f32x4{0.f, 0.f, 0.f, 0.f};
                 }
 #pragma unroll
-            for (int k = 0; k < 4; ++k)
+            for (int k = 0; k < kInFlight; ++k)
                 if (pc + k < pc_end) {                            // uniform
 #pragma unroll
                     for (int u = 0; u < U; ++u) sum[u] += v[k][u];
