@@ -128,7 +128,7 @@ def cpu_baseline(pr, sample_m: int) -> dict:
             "seconds": t2 - t0}
 
 
-def roofline_entry(p, K, m, energy_ms, arith, workload):
+def roofline_entry(p, K, m, energy_ms, arith, workload, s0=8):
     """The energy kernel against the matrix roof of the instruction it runs on."""
     flops = 2.0 * K * p * p * m                 # algorithmic: projection onto all K orthobases
     achieved = flops / (energy_ms * 1e-3) / 1e12
@@ -146,14 +146,15 @@ def roofline_entry(p, K, m, energy_ms, arith, workload):
                  "vs_fp32_mfma_peak": achieved / PEAK_MFMA_F32_TFLOPS}
     elif arith == "f16x2":
         peak = PEAK_MFMA_BF16_TFLOPS / 3          # fp16 and bf16 MFMA share the 2500 TFLOP/s peak
-        # the selection networks: 276 vector instructions per tile of 32 signals and block (counted in
-        # the kernel's ISA), one lane-operation per lane and instruction, against 256 CUs x 64 lanes x 2.4 GHz
+        # the selection networks: at least 276 min / max / median instructions per tile of 32 signals and
+        # block (the kernel's ISA has 1362 of them for its four copies of the network and the scale
+        # search), one lane-operation per lane and instruction, against 256 CUs x 64 lanes x 2.4 GHz
         sel_ops = 276.0 * 64.0 * (K * m / 32.0)
         sel_peak = 256 * 64 * 2.4e9
         extra = {"kernel": "energy_split_kernel MODE 3 (fused Q^T y on the fp16 matrix cores, fp32 operands scaled "
                            "and written as hi + lo in fp16, three partial products + top-s0 energy + block argmax)",
                  "peak_note": "2500 TFLOP/s dense fp16 MFMA / 3 partial products per product; the kernel's time is "
-                              "0.70 x (matrix part + selection networks on the vector ALU), see selection_alu",
+                              "0.70 x (matrix part + selection networks on the vector ALU)",
                  "executed_f16_tflops": achieved * 3, "peak_f16_tflops": PEAK_MFMA_BF16_TFLOPS,
                  "vs_six_product_roof": achieved / (PEAK_MFMA_BF16_TFLOPS / SPLIT_PRODUCTS),
                  "vs_fp32_mfma_peak": achieved / PEAK_MFMA_F32_TFLOPS,
@@ -164,6 +165,7 @@ def roofline_entry(p, K, m, energy_ms, arith, workload):
         if p > 64:
             extra["kernel"] = ("energy_split_wide_kernel (the same on the fp16 matrix cores for p = 256: the two "
                                "wavefronts of a SIMD each multiply half of the dims)")
+        if p != 64 or not 4 < s0 <= 8:         # the instruction count above is that of p = 64, sort width 8
             del extra["selection_alu"]
     elif kernel == "energy_split_kernel":
         peak = PEAK_MFMA_BF16_TFLOPS / SPLIT_PRODUCTS
@@ -175,8 +177,22 @@ def roofline_entry(p, K, m, energy_ms, arith, workload):
     else:
         peak = PEAK_MFMA_F32_TFLOPS
         extra = {"kernel": "energy_kernel (fused Q^T y on the fp32 matrix instruction + top-s0 energy + block argmax)"}
-    return {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-            "traffic": measured_traffic_bytes(workload, arith), **extra}
+    out = {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+           "traffic": measured_traffic_bytes(workload, arith), **extra}
+    sel = extra.get("selection_alu")
+    if sel is not None and sel["frac"] > out["frac"]:
+        # The roofline of a kernel is the highest of its floors.  With three fp16 products the
+        # vector-ALU floor (selection networks) lies above the matrix floor, so that is the roof
+        # the kernel is measured against; the matrix side stays in "mfma".
+        out = {"bound": "alu", "achieved": sel["achieved_Tops"], "peak": sel["peak_Tops"],
+               "unit": "Tops/s (vector lane operations: one min / max / median per lane and instruction; "
+                       "256 CUs x 64 lanes x 2.4 GHz)",
+               "frac": sel["frac"], "traffic": out["traffic"], "kernel": extra["kernel"],
+               "mfma": {"achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                        **{k: v for k, v in extra.items() if k not in ("kernel", "selection_alu")}},
+               "lane_ops_per_launch": sel["lane_ops_per_launch"],
+               "algorithmic_tflops": achieved, "vs_fp32_mfma_peak": achieved / PEAK_MFMA_F32_TFLOPS}
+    return out
 
 
 def run_config(sbo, synth, torch, name, steps, warmup, arith):
@@ -213,11 +229,13 @@ def run_config(sbo, synth, torch, name, steps, warmup, arith):
     ms = 1e3 * (t1 - t0) / steps
     upd_bytes = m * (4 + 4 + 4 + 4 * p + 8 * s0 + 4) + 4 * K * p * p
     t_upd = (st["group"] + st["select"] + st["accum"]) * 1e-3
-    rf = roofline_entry(p, K, m, energy_ms, arith, name)
+    rf = roofline_entry(p, K, m, energy_ms, arith, name, s0)
+    mf = rf.get("mfma", rf)                     # the matrix side, also where the vector ALU is the roof
     return {"workload": f"{name}: p={p} K={K} m={m} s0={s0}", "steps": steps, "warmup": warmup,
             "ms_per_step": ms, "signals_per_s": m / (ms * 1e-3), "stage_ms": st,
             "energy_ms_timed_region": energy_ms, "energy_kernel": rf["kernel"].split(" ")[0],
-            "energy_tflops": rf["achieved"], "energy_frac": rf["frac"], "energy_peak_tflops": rf["peak"],
+            "energy_bound": rf["bound"], "energy_frac": rf["frac"],
+            "energy_tflops": mf["achieved"], "energy_frac_mfma": mf["frac"], "energy_peak_tflops": mf["peak"],
             "update_GBps": upd_bytes / t_upd / 1e9, "update_frac_hbm": upd_bytes / t_upd / 1e9 / PEAK_HBM_GBS,
             "svd_ms": st["svd"]}
 
@@ -344,9 +362,10 @@ def main() -> int:
         for _ in range(5):
             sbo.sbo_code(ctx, Y, D, b2, s2, c2, e2)
             best = min(best, sbo.sbo_stage_ms(ctx)["energy"])
-        rf = roofline_entry(p, K, m, best, alt, cfg.name)
-        other.append({"arith": alt, "energy_ms": best, "achieved_tflops": rf["achieved"],
-                      "peak_tflops": rf["peak"], "frac": rf["frac"], "kernel": rf["kernel"].split(" ")[0]})
+        rf = roofline_entry(p, K, m, best, alt, cfg.name, s0)
+        mf = rf.get("mfma", rf)
+        other.append({"arith": alt, "energy_ms": best, "achieved_tflops": mf["achieved"],
+                      "peak_tflops": mf["peak"], "frac": mf["frac"], "kernel": rf["kernel"].split(" ")[0]})
         del b2, s2, c2, e2
     sbo.sbo_set_option(ctx, sbo.SBO_OPT_CODING_ARITH, arith_value(sbo, args.arith))
 
@@ -474,7 +493,7 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: p={p} K={K} m={m} s0={s0}, planted ONBs, "
                                f"{cfg.snr_db} dB SNR, random ONB init",
                    "p": p, "K": K, "m": m, "s0": s0, "coding_arith": args.arith},
-        "roofline": roofline_entry(p, K, m, energy_ms, args.arith, cfg.name),
+        "roofline": roofline_entry(p, K, m, energy_ms, args.arith, cfg.name, s0),
         "energy_ms_timed_region": energy_ms,
         "stage_ms": stage_ms,
         "launch_gaps_ms": ms_per_step - sum(stage_ms.values()),
@@ -500,9 +519,10 @@ def main() -> int:
     if measured is not None:
         out["measured_peaks"] = measured
         out["update_hbm"]["frac_of_measured_copy"] = out["update_hbm"]["achieved_GBps"] / measured["hbm_copy_GBps"]
-        if "executed_bf16_tflops" in out["roofline"] or "executed_f16_tflops" in out["roofline"]:
-            ex = out["roofline"].get("executed_bf16_tflops", out["roofline"].get("executed_f16_tflops"))
-            out["roofline"]["frac_of_measured_random_operand_rate"] = ex / measured["mfma_bf16_tflops_random_operands"]
+        mf = out["roofline"].get("mfma", out["roofline"])
+        if "executed_bf16_tflops" in mf or "executed_f16_tflops" in mf:
+            ex = mf.get("executed_bf16_tflops", mf.get("executed_f16_tflops"))
+            mf["frac_of_measured_random_operand_rate"] = ex / measured["mfma_bf16_tflops_random_operands"]
         elif out["roofline"]["kernel"].startswith("energy_split"):
             pass
         else:
