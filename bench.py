@@ -146,10 +146,12 @@ def roofline_entry(p, K, m, energy_ms, arith, workload, s0=8):
                  "vs_fp32_mfma_peak": achieved / PEAK_MFMA_F32_TFLOPS}
     elif arith == "f16x2":
         peak = PEAK_MFMA_BF16_TFLOPS / 3          # fp16 and bf16 MFMA share the 2500 TFLOP/s peak
-        # the selection networks: at least 276 min / max / median instructions per tile of 32 signals and
-        # block (the kernel's ISA has 1362 of them for its four copies of the network and the scale
-        # search), one lane-operation per lane and instruction, against 256 CUs x 64 lanes x 2.4 GHz
-        sel_ops = 276.0 * 64.0 * (K * m / 32.0)
+        # the selection networks, per tile of 32 signals and block (p = 64, sort width 8): 4 sorts of 8 by
+        # three-input insertion networks (33 instructions each), 3 half-cleaner + bitonic merges (32
+        # each), the lane-pair fold (8 maxima) and 8 squares = 244 vector instructions (the kernel's ISA
+        # agrees: 220 min / max / median per copy of the network + the squares and swaps); one
+        # lane-operation per lane and instruction, against 256 CUs x 64 lanes x 2.4 GHz
+        sel_ops = 244.0 * 64.0 * (K * m / 32.0)
         sel_peak = 256 * 64 * 2.4e9
         extra = {"kernel": "energy_split_kernel MODE 3 (fused Q^T y on the fp16 matrix cores, fp32 operands scaled "
                            "and written as hi + lo in fp16, three partial products + top-s0 energy + block argmax)",
