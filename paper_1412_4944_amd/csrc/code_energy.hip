@@ -1,18 +1,25 @@
 // Sparse-coding stage 1: for every signal, the kept energy in every orthobase and
 // the block where it is largest (Section 2, eq. (4); Section 3.1).
 //
-// c = Q_j^T y is a dense contraction: fp32 MFMA 32x32x2 with atoms on the M axis
-// and signals on the N axis, so that the 32x32 accumulator tile leaves every
+// c = Q_j^T y is a dense contraction for the matrix cores: 32 x 32 MFMA tiles with atoms
+// on the M axis and signals on the N axis, so that the accumulator tile leaves every
 // signal's coefficients in just two lanes (l and l^32).  The s0 largest magnitudes
 // are then found in registers by compare-exchange networks, merged across the lane
 // pair, squared and summed, and compared against the running best block.  The K*p x m
 // projection never leaves the register file.
 //
-// Dictionary rows (atom k of block j = row j*p + k, p floats) are streamed through
-// LDS in stages of 64 rows, double-buffered, in the exact per-lane order the MFMA
-// A operand wants, so every LDS read is one conflict-free 16-byte load per lane.  A
-// small kernel first rewrites D into that order (zero-padded to whole stages), which
-// makes the per-stage copy global -> registers -> LDS linear on both sides.
+// Dictionary rows (atom k of block j = row j*p + k) are streamed through LDS in stages of
+// 64 (p = 256: 32) rows, double-buffered, in the exact per-lane order the MFMA A operand
+// wants, so every LDS read is one conflict-free 16-byte load per lane.  A small kernel
+// first rewrites D into that order (zero-padded to whole stages), which makes the
+// per-stage copy global -> registers -> LDS linear on both sides.
+//
+// Three arithmetics, chosen per context (SBO_OPT_CODING_ARITH), each with its own kernels:
+//   energy_kernel                          the fp32 matrix instruction (32x32x2);
+//   energy_split_kernel MODE 0 / 1 / 2,    every fp32 operand as three bf16 parts, six (screening:
+//   energy_split_wide_kernel<false>        three) partial products on the bf16 matrix cores;
+//   energy_split_kernel MODE 3,            every (scaled) fp32 operand as two fp16 parts, three
+//   energy_split_wide_kernel<true>         partial products on the fp16 matrix cores (the default).
 #include "sbo_internal.h"
 #include "device_utils.h"
 

@@ -91,7 +91,8 @@ struct Workspace {
     float* energy;         // [m_max] kept energy in the winning block
     float* dsw;            // [ceil(K*p/64)*64][p] dictionary in MFMA operand order
     unsigned* dsh;         // p > 64 only: the same rows as two fp16 parts (the energy kernel's order there)
-    unsigned* dsb;         // the same rows as three bf16 parts in the split operand order (6 bytes per entry)
+    unsigned* dsb;         // the same rows in parts: three bf16 (6 bytes per entry) or, for the energy kernel at
+                           // p <= 64, two fp16 (4 bytes per entry), in the split operand orders
     float* part_E;         // [kEnergySplitRows][m_max] split coding / resolution pass: best energy per row
     int32_t* part_j;       // same shape: its block
     // accumulation
